@@ -1,0 +1,171 @@
+/*
+ * rnnt_joint_loss.h - C ABI of the MI355X (gfx950) transducer joint -> loss -> gradient library.
+ *
+ * One call computes, for a batch of already projected acoustic and label encodings, what the
+ * loop body of Algorithm 1 (arxiv 2211.16270, Section 4, lines 4-12) computes for every sample:
+ * joint network (Eq. 4), output layer (Eq. 6), transducer loss f^W_1..f^W_4 (Eqs. 7-10) and the
+ * gradients with respect to the output-layer parameters (line 8) and to both encodings
+ * (lines 10, 11).  Padding is never touched (Section 4.1.1) and several samples share one launch
+ * (Section 4.1.2); the [B,T,U+1,V] score tensor is never formed: scores live in MFMA
+ * accumulators one tile at a time and are recomputed for the backward pass.
+ *
+ * Conventions
+ *   - "dev" pointers are device memory of the current HIP device, "host" pointers are ordinary
+ *     host memory.  All arrays are dense, row-major, last index contiguous.
+ *   - The caller owns every buffer.  The library allocates no device memory, keeps no state
+ *     between calls, enqueues all work on the given stream and returns without waiting for it
+ *     (host arrays are consumed before the call returns).
+ *   - Outputs must not alias inputs or each other.
+ *   - Every entry point returns a status; nothing throws or aborts across this boundary.  All
+ *     argument checks happen on the host before anything is launched.
+ *   - Gradients are those of L = sum_b loss[b] (Section 2: L = -sum_b ln P(y_b|x_b)).
+ */
+#ifndef RNNT_JOINT_LOSS_H
+#define RNNT_JOINT_LOSS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RNNT_OK = 0,
+    RNNT_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+    RNNT_ERR_SHAPE = 2,       /* B, T_max, U_max, H, V or blank out of range                  */
+    RNNT_ERR_LENGTH = 3,      /* some T_len[b] not in [1,T_max] or U_len[b] not in [0,U_max]  */
+    RNNT_ERR_LABEL = 4,       /* a label outside [0,V) (only rnnt_validate_labels_host)       */
+    RNNT_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned (256 B) or too small              */
+    RNNT_ERR_UNSUPPORTED = 6, /* shape not supported by the kernels of the requested dtype    */
+    RNNT_ERR_HIP = 7          /* a HIP call or launch failed                                  */
+} rnnt_status;
+
+typedef enum {
+    RNNT_F32 = 0, /* enc, pred, W_out are float; everything is computed in fp32 (plain FMA)   */
+    RNNT_BF16 = 1 /* enc, pred, W_out are bfloat16; the three GEMMs run on bf16 MFMA with     */
+                  /* fp32 accumulation, tanh/softmax/lattice in fp32                          */
+} rnnt_dtype;
+
+/* Problem description.  Lattice of sample b: 0 <= t < T_len[b], 0 <= u <= U_len[b]. */
+typedef struct {
+    int32_t B;      /* samples, >= 1                                                         */
+    int32_t T_max;  /* rows of enc per sample, >= 1                                          */
+    int32_t U_max;  /* label slots per sample, >= 0; pred has U_max + 1 rows, U_max <= 1023  */
+    int32_t H;      /* joint size.  RNNT_BF16: multiple of 128, <= 1024.  RNNT_F32: 1..4096   */
+    int32_t V;      /* vocabulary incl. blank.  RNNT_BF16: multiple of 128.  RNNT_F32: 2..16384 */
+    int32_t blank;  /* index of the blank symbol, in [0,V)                                   */
+    int32_t dtype;  /* rnnt_dtype                                                            */
+    int32_t accumulate_params; /* 0: dW_out, db_out are overwritten; 1: added to (Alg. 1, line 3 / 8) */
+} rnnt_desc;
+
+/* What the host scheduler decided for a call (Section 4.1.2 analogue; see rnnt_joint_loss_plan). */
+typedef struct {
+    int64_t rows_total;       /* sum_b T_len[b] * (U_len[b] + 1): lattice nodes without padding */
+    int64_t rows_padded;      /* B * T_max * (U_max + 1)                                       */
+    int64_t tiles_total;      /* 8x8 lattice tiles over all samples                            */
+    int32_t n_groups;         /* launches of the forward/lattice stage; samples of a group run together */
+    int32_t n_chunks;         /* launches of the backward stage (row ranges of <= chunk_rows)  */
+    int64_t group_rows_cap;   /* lattice rows that fit one group                               */
+    int64_t chunk_rows;       /* tile-padded rows per backward chunk                           */
+    size_t  workspace_bytes;  /* bytes the plan uses                                           */
+    size_t  lattice_bytes;    /* part of it: lse, lpb, lpy, alpha, beta of one group           */
+    size_t  chunk_bytes;      /* part of it: bf16 score-gradient / joint chunk buffers         */
+} rnnt_plan_info;
+
+const char* rnnt_status_string(rnnt_status s);
+
+/*
+ * Workspace size for a call (host only, no GPU needed).
+ *   budget_bytes = 0: the library's default trade-off (never more than 1 GiB plus what the
+ *   largest single sample needs).  Otherwise the largest plan not exceeding budget_bytes; if
+ *   even the smallest workable plan (one sample per group, one tile row per chunk) exceeds it,
+ *   that smallest size is returned, so a result > budget_bytes means "budget too small".
+ * Returns 0 on invalid arguments.  The result does not depend on B beyond the largest sample
+ * once the default cap is reached (Section 5.2: memory almost independent of batch size).
+ */
+size_t rnnt_joint_loss_workspace_bytes(const rnnt_desc* desc, const int32_t* T_len_host,
+                                       const int32_t* U_len_host, size_t budget_bytes);
+
+/*
+ * The schedule a call with this workspace size would use (host only).  sample_group, if not NULL,
+ * receives for each of the B samples the index of the group it is processed in (every sample
+ * is in exactly one group; a group's lattice state fits the workspace).
+ */
+rnnt_status rnnt_joint_loss_plan(const rnnt_desc* desc, const int32_t* T_len_host,
+                                 const int32_t* U_len_host, size_t workspace_bytes,
+                                 rnnt_plan_info* info, int32_t* sample_group);
+
+/* Eq. (11): the paper's number of concurrently processed samples, 2^max(0,min(4,floor(log2(1e9/(4TUV))))).
+ * Kept for reference next to this library's own grouping rule; returns 0 on non-positive input. */
+int32_t rnnt_parallel_iterations(int64_t T, int64_t U, int64_t V);
+
+/* Host-side label check: RNNT_ERR_LABEL if some labels[b*U_max + u], u < U_len[b], is outside [0,V).
+ * The GPU path never indexes memory with a label; an out-of-range label there yields loss = +inf. */
+rnnt_status rnnt_validate_labels_host(const rnnt_desc* desc, const int32_t* labels_host,
+                                      const int32_t* U_len_host);
+
+/*
+ * Loss and gradients (Algorithm 1, lines 4-12, for all samples; Eqs. 4, 6, 7-10).
+ *
+ *   z[b,t,u,:] = tanh(enc[b,t,:] + pred[b,u,:])                (Eq. 4; the projections W^A, W^L, b^Z
+ *                                                               are applied by the caller beforehand)
+ *   h[b,t,u,:] = z[b,t,u,:] W_out + b_out                      (Eq. 6; W_out is the transpose of the
+ *                                                               paper's W^O in R^{V x H})
+ *   loss[b]    = -ln P(y_b | x_b), natural log                 (Eqs. 7-9)
+ *   dW_out, db_out, d_enc, d_pred: gradients of sum_b loss[b]  (Eq. 10; Alg. 1 lines 8, 10, 11)
+ *
+ * enc      dev  [B, T_max, H]      desc->dtype; rows t >= T_len[b] are never read
+ * pred     dev  [B, U_max+1, H]    desc->dtype; rows u >  U_len[b] are never read
+ * W_out    dev  [H, V]             desc->dtype
+ * b_out    dev  [V]                float
+ * labels   dev  [B, U_max]         int32, entries u >= U_len[b] are never read
+ * T_len    HOST [B]                1..T_max
+ * U_len    HOST [B]                0..U_max
+ * loss     dev  [B]                float, out
+ * d_enc    dev  [B, T_max, H]      float, out, fully overwritten (zeros in padded rows)
+ * d_pred   dev  [B, U_max+1, H]    float, out, fully overwritten (zeros in padded rows)
+ * dW_out   dev  [H, V]             float, out (overwritten or accumulated, see desc)
+ * db_out   dev  [V]                float, out (same)
+ * workspace dev, 256-byte aligned, workspace_bytes >= rnnt_joint_loss_workspace_bytes(...);
+ *          a larger workspace lets more samples share a launch
+ * hip_stream  a hipStream_t (NULL = the default stream)
+ *
+ * Floating-point sums into the gradient arrays use atomic adds, so results can differ in the
+ * last bits from run to run.  Calls that share a workspace must be ordered on one stream.
+ */
+rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc,
+                                    const void* enc, const void* pred, const void* W_out,
+                                    const float* b_out, const int32_t* labels,
+                                    const int32_t* T_len_host, const int32_t* U_len_host,
+                                    float* loss, float* d_enc, float* d_pred,
+                                    float* dW_out, float* db_out,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Loss only (Eqs. 4, 6, 7-9): same inputs, no gradient outputs, same workspace rule
+ * (the chunk buffers stay unused).
+ */
+rnnt_status rnnt_joint_loss_fwd(const rnnt_desc* desc,
+                                const void* enc, const void* pred, const void* W_out,
+                                const float* b_out, const int32_t* labels,
+                                const int32_t* T_len_host, const int32_t* U_len_host,
+                                float* loss, void* workspace, size_t workspace_bytes,
+                                void* hip_stream);
+
+/*
+ * Test hook: copies the forward/backward variables of sample b (as left in the workspace by the
+ * most recent call on this workspace, after the caller synchronised the stream) to host arrays
+ * alpha_host, beta_host [T_len[b] * (U_len[b]+1)], undoing the per-sample offset the lattice
+ * kernel works with, so they are the alpha, beta of Section 2 (f^W_2).  Only valid when the
+ * call used a single group (info.n_groups == 1).  Synchronous.
+ */
+rnnt_status rnnt_debug_read_lattice(const rnnt_desc* desc, const int32_t* T_len_host,
+                                    const int32_t* U_len_host, const void* workspace,
+                                    size_t workspace_bytes, int32_t b,
+                                    float* alpha_host, float* beta_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNNT_JOINT_LOSS_H */

@@ -1,0 +1,220 @@
+"""ctypes binding of include/rnnt_joint_loss.h: argument marshalling only.
+
+Functions carry the names of the C entry points.  Device arrays are torch tensors (torch is
+used for device memory and streams, nothing else); host arrays are numpy int32.  There is no
+fallback: if the shared library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "lib", "librnnt_joint_loss.so")
+
+RNNT_F32, RNNT_BF16 = 0, 1
+STATUS_NAMES = ["RNNT_OK", "RNNT_ERR_NULL", "RNNT_ERR_SHAPE", "RNNT_ERR_LENGTH", "RNNT_ERR_LABEL",
+                "RNNT_ERR_WORKSPACE", "RNNT_ERR_UNSUPPORTED", "RNNT_ERR_HIP"]
+EXPORTS = ["rnnt_status_string", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_loss_plan",
+           "rnnt_parallel_iterations", "rnnt_validate_labels_host", "rnnt_joint_loss_fwd_bwd",
+           "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice"]
+
+
+class RnntDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32), ("U_max", ctypes.c_int32),
+                ("H", ctypes.c_int32), ("V", ctypes.c_int32), ("blank", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("accumulate_params", ctypes.c_int32)]
+
+
+class RnntPlanInfo(ctypes.Structure):
+    _fields_ = [("rows_total", ctypes.c_int64), ("rows_padded", ctypes.c_int64),
+                ("tiles_total", ctypes.c_int64), ("n_groups", ctypes.c_int32),
+                ("n_chunks", ctypes.c_int32), ("group_rows_cap", ctypes.c_int64),
+                ("chunk_rows", ctypes.c_int64), ("workspace_bytes", ctypes.c_size_t),
+                ("lattice_bytes", ctypes.c_size_t), ("chunk_bytes", ctypes.c_size_t)]
+
+
+class RnntError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else str(status)
+        super().__init__(f"{where}: {name} ({lib().rnnt_status_string(status).decode()})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it was not built (there is no other code path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                           "(hipcc, gfx950) first; this package has no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32p, f32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p
+    dp = ctypes.POINTER(RnntDesc)
+    L.rnnt_status_string.restype = ctypes.c_char_p
+    L.rnnt_status_string.argtypes = [ctypes.c_int]
+    L.rnnt_joint_loss_workspace_bytes.restype = ctypes.c_size_t
+    L.rnnt_joint_loss_workspace_bytes.argtypes = [dp, i32p, i32p, ctypes.c_size_t]
+    L.rnnt_joint_loss_plan.restype = ctypes.c_int
+    L.rnnt_joint_loss_plan.argtypes = [dp, i32p, i32p, ctypes.c_size_t, ctypes.POINTER(RnntPlanInfo), i32p]
+    L.rnnt_parallel_iterations.restype = ctypes.c_int32
+    L.rnnt_parallel_iterations.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
+    L.rnnt_validate_labels_host.restype = ctypes.c_int
+    L.rnnt_validate_labels_host.argtypes = [dp, i32p, i32p]
+    L.rnnt_joint_loss_fwd_bwd.restype = ctypes.c_int
+    L.rnnt_joint_loss_fwd_bwd.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, f32p, f32p, f32p, f32p,
+                                          vp, ctypes.c_size_t, vp]
+    L.rnnt_joint_loss_fwd.restype = ctypes.c_int
+    L.rnnt_joint_loss_fwd.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
+    L.rnnt_debug_read_lattice.restype = ctypes.c_int
+    L.rnnt_debug_read_lattice.argtypes = [dp, i32p, i32p, vp, ctypes.c_size_t, ctypes.c_int32, vp, vp]
+    _lib = L
+    return L
+
+
+def make_desc(B, T_max, U_max, H, V, blank=0, dtype=RNNT_BF16, accumulate_params=0) -> RnntDesc:
+    return RnntDesc(int(B), int(T_max), int(U_max), int(H), int(V), int(blank), int(dtype),
+                    int(accumulate_params))
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ip(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def rnnt_joint_loss_workspace_bytes(desc: RnntDesc, T_len, U_len, budget_bytes: int = 0) -> int:
+    T, U = _i32(T_len), _i32(U_len)
+    return int(lib().rnnt_joint_loss_workspace_bytes(ctypes.byref(desc), _ip(T), _ip(U), int(budget_bytes)))
+
+
+def rnnt_joint_loss_plan(desc: RnntDesc, T_len, U_len, workspace_bytes: int = 0):
+    """Returns (status, info dict, sample_group int32[B])."""
+    T, U = _i32(T_len), _i32(U_len)
+    info = RnntPlanInfo()
+    groups = np.full(desc.B, -1, dtype=np.int32)
+    st = lib().rnnt_joint_loss_plan(ctypes.byref(desc), _ip(T), _ip(U), int(workspace_bytes),
+                                    ctypes.byref(info), _ip(groups))
+    d = {name: getattr(info, name) for name, _ in RnntPlanInfo._fields_}
+    return int(st), d, groups
+
+
+def rnnt_parallel_iterations(T: int, U: int, V: int) -> int:
+    return int(lib().rnnt_parallel_iterations(int(T), int(U), int(V)))
+
+
+def rnnt_validate_labels_host(desc: RnntDesc, labels, U_len) -> int:
+    lab, U = _i32(labels), _i32(U_len)
+    return int(lib().rnnt_validate_labels_host(ctypes.byref(desc), _ip(lab), _ip(U)))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    h = int(s.cuda_stream)
+    return h if h != 0 else None
+
+
+def rnnt_joint_loss_fwd_bwd(desc: RnntDesc, enc, pred, W_out, b_out, labels, T_len, U_len,
+                            loss, d_enc, d_pred, dW_out, db_out, workspace, stream=None) -> int:
+    """Raw call: every array argument is a torch CUDA tensor (or numpy for T_len/U_len) of the
+    layout the header states.  Returns the status code; enqueues on `stream` (default: torch's
+    current stream) without synchronising."""
+    T, U = _i32(T_len), _i32(U_len)
+    return int(lib().rnnt_joint_loss_fwd_bwd(
+        ctypes.byref(desc), _ptr(enc), _ptr(pred), _ptr(W_out), _ptr(b_out), _ptr(labels), _ip(T), _ip(U),
+        _ptr(loss), _ptr(d_enc), _ptr(d_pred), _ptr(dW_out), _ptr(db_out), _ptr(workspace),
+        int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
+        _stream_handle(stream)))
+
+
+def rnnt_joint_loss_fwd(desc: RnntDesc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, workspace,
+                        stream=None) -> int:
+    T, U = _i32(T_len), _i32(U_len)
+    return int(lib().rnnt_joint_loss_fwd(
+        ctypes.byref(desc), _ptr(enc), _ptr(pred), _ptr(W_out), _ptr(b_out), _ptr(labels), _ip(T), _ip(U),
+        _ptr(loss), _ptr(workspace),
+        int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
+        _stream_handle(stream)))
+
+
+def rnnt_debug_read_lattice(desc: RnntDesc, T_len, U_len, workspace, b: int):
+    """(status, alpha [T_b, U_b+1], beta [T_b, U_b+1]) of sample b after a single-group call."""
+    T, U = _i32(T_len), _i32(U_len)
+    n = int(T[b]) * (int(U[b]) + 1)
+    al = np.zeros(n, dtype=np.float32)
+    be = np.zeros(n, dtype=np.float32)
+    st = lib().rnnt_debug_read_lattice(ctypes.byref(desc), _ip(T), _ip(U), _ptr(workspace),
+                                       int(workspace.numel() * workspace.element_size()), int(b),
+                                       al.ctypes.data, be.ctypes.data)
+    shape = (int(T[b]), int(U[b]) + 1)
+    return int(st), al.reshape(shape), be.reshape(shape)
+
+
+# --------------------------------------------------------------------------------------------
+# Convenience on top of the raw calls (allocation of outputs and workspace with torch).
+# --------------------------------------------------------------------------------------------
+class Workspace:
+    """A reusable device workspace (torch uint8 tensor, 256-byte aligned by the allocator)."""
+
+    def __init__(self, nbytes: int, device="cuda:0"):
+        import torch
+        self.buf = torch.empty(int(nbytes), dtype=torch.uint8, device=device)
+        assert self.buf.data_ptr() % 256 == 0
+
+
+def to_device(batch, device="cuda:0"):
+    """synth.Batch -> dict of torch tensors in the storage types the library expects."""
+    import torch
+    bf16 = batch.wl.dtype == "bf16"
+    dt = torch.bfloat16 if bf16 else torch.float32
+
+    def cvt(x):
+        t = torch.from_numpy(np.ascontiguousarray(x))
+        return t.to(device=device, dtype=dt)
+
+    return dict(enc=cvt(batch.enc), pred=cvt(batch.pred), W_out=cvt(batch.W_out),
+                b_out=torch.from_numpy(batch.b_out).to(device),
+                labels=torch.from_numpy(np.ascontiguousarray(batch.labels)).to(device),
+                T_len=_i32(batch.T_len), U_len=_i32(batch.U_len))
+
+
+def run_fwd_bwd(dev: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optional[Workspace] = None,
+                budget_bytes: int = 0, accumulate_into=None, stream=None):
+    """Allocates outputs (and a workspace unless given), calls rnnt_joint_loss_fwd_bwd, raises on
+    a non-zero status.  Returns dict(loss, d_enc, d_pred, dW_out, db_out, workspace)."""
+    import torch
+    device = dev["enc"].device
+    desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1)
+    if workspace is None:
+        n = rnnt_joint_loss_workspace_bytes(desc, dev["T_len"], dev["U_len"], budget_bytes)
+        if n == 0:
+            raise RnntError(lib().rnnt_joint_loss_plan(ctypes.byref(desc), _ip(dev["T_len"]), _ip(dev["U_len"]),
+                                                       0, ctypes.byref(RnntPlanInfo()), None), "plan")
+        workspace = Workspace(n, device)
+    loss = torch.empty(B, dtype=torch.float32, device=device)
+    d_enc = torch.empty(B, T_max, H, dtype=torch.float32, device=device)
+    d_pred = torch.empty(B, U_max + 1, H, dtype=torch.float32, device=device)
+    if accumulate_into is None:
+        dW = torch.empty(H, V, dtype=torch.float32, device=device)
+        db = torch.empty(V, dtype=torch.float32, device=device)
+    else:
+        dW, db = accumulate_into
+    st = rnnt_joint_loss_fwd_bwd(desc, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                 dev["T_len"], dev["U_len"], loss, d_enc, d_pred, dW, db, workspace.buf, stream)
+    if st != 0:
+        raise RnntError(st, "rnnt_joint_loss_fwd_bwd")
+    return dict(loss=loss, d_enc=d_enc, d_pred=d_pred, dW_out=dW, db_out=db, workspace=workspace, desc=desc)

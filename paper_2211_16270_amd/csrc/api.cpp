@@ -1,0 +1,246 @@
+// C-ABI entry points (include/rnnt_joint_loss.h): argument checks, the host schedule, and the
+// launch sequence.  Compiled with hipcc as host code; the kernels live in the .hip files.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "../../include/rnnt_joint_loss.h"
+#include "kernels.h"
+#include "plan.h"
+
+using namespace rnnt;
+
+extern "C" const char* rnnt_status_string(rnnt_status s) {
+    switch (s) {
+        case RNNT_OK: return "ok";
+        case RNNT_ERR_NULL: return "null pointer argument";
+        case RNNT_ERR_SHAPE: return "shape or blank index out of range";
+        case RNNT_ERR_LENGTH: return "T_len or U_len out of range";
+        case RNNT_ERR_LABEL: return "label out of range";
+        case RNNT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case RNNT_ERR_UNSUPPORTED: return "shape not supported for this dtype";
+        case RNNT_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+extern "C" size_t rnnt_joint_loss_workspace_bytes(const rnnt_desc* desc, const int32_t* T_len,
+                                                  const int32_t* U_len, size_t budget_bytes) {
+    if (check_desc(desc) != RNNT_OK || check_lengths(desc, T_len, U_len) != RNNT_OK) return 0;
+    Plan p;
+    build_plan(*desc, T_len, U_len, budget_bytes, p);
+    return p.total_bytes;
+}
+
+extern "C" rnnt_status rnnt_joint_loss_plan(const rnnt_desc* desc, const int32_t* T_len, const int32_t* U_len,
+                                            size_t workspace_bytes, rnnt_plan_info* info, int32_t* sample_group) {
+    rnnt_status st = check_desc(desc);
+    if (st != RNNT_OK) return st;
+    st = check_lengths(desc, T_len, U_len);
+    if (st != RNNT_OK) return st;
+    if (!info) return RNNT_ERR_NULL;
+    Plan p;
+    build_plan(*desc, T_len, U_len, workspace_bytes, p);
+    if (workspace_bytes != 0 && p.total_bytes > workspace_bytes) return RNNT_ERR_WORKSPACE;
+    info->rows_total = p.rows_total;
+    info->rows_padded = (int64_t)desc->B * desc->T_max * (desc->U_max + 1);
+    info->tiles_total = p.tiles_total;
+    info->n_groups = (int32_t)p.groups.size();
+    info->n_chunks = (int32_t)p.chunks.size();
+    info->group_rows_cap = p.group_rows_cap;
+    info->chunk_rows = p.chunk_rows;
+    info->workspace_bytes = p.total_bytes;
+    info->lattice_bytes = p.lattice_bytes;
+    info->chunk_bytes = p.chunk_bytes;
+    if (sample_group)
+        for (int g = 0; g < (int)p.groups.size(); ++g)
+            for (int s = p.groups[g].s0; s < p.groups[g].s1; ++s) sample_group[s] = g;
+    return RNNT_OK;
+}
+
+extern "C" int32_t rnnt_parallel_iterations(int64_t T, int64_t U, int64_t V) {
+    if (T <= 0 || U <= 0 || V <= 0) return 0;
+    const double ratio = 1e9 / (4.0 * (double)T * (double)U * (double)V);
+    int e = (int)std::floor(std::log(ratio) / std::log(2.0));
+    if (e > 4) e = 4;
+    if (e < 0) e = 0;
+    return 1 << e;
+}
+
+extern "C" rnnt_status rnnt_validate_labels_host(const rnnt_desc* desc, const int32_t* labels,
+                                                 const int32_t* U_len) {
+    rnnt_status st = check_desc(desc);
+    if (st != RNNT_OK) return st;
+    if (!labels || !U_len) return RNNT_ERR_NULL;
+    for (int b = 0; b < desc->B; ++b) {
+        if (U_len[b] < 0 || U_len[b] > desc->U_max) return RNNT_ERR_LENGTH;
+        for (int u = 0; u < U_len[b]; ++u) {
+            const int32_t y = labels[(size_t)b * desc->U_max + u];
+            if (y < 0 || y >= desc->V) return RNNT_ERR_LABEL;
+        }
+    }
+    return RNNT_OK;
+}
+
+namespace {
+
+#define RNNT_HIP(expr)                           \
+    do {                                         \
+        if ((expr) != hipSuccess) {              \
+            (void)hipGetLastError();             \
+            return RNNT_ERR_HIP;                 \
+        }                                        \
+    } while (0)
+
+struct WsView {
+    SampleTable st;
+    LatticeState ls;   // row_base filled per group
+    void* wpack;
+    void* dH;
+    void* dHt;
+    void* Zt;
+};
+
+WsView view_workspace(const Plan& p, void* ws) {
+    unsigned char* w = (unsigned char*)ws;
+    WsView v{};
+    v.st.T = (const int*)(w + p.off_T);
+    v.st.U = (const int*)(w + p.off_U);
+    v.st.tile_off = (const int*)(w + p.off_tile_off);
+    v.st.row_off = (const long long*)(w + p.off_row_off);
+    v.ls.lse = (float*)(w + p.off_lse);
+    v.ls.lpb = (float*)(w + p.off_lpb);
+    v.ls.lpy = (float*)(w + p.off_lpy);
+    v.ls.alpha = (float*)(w + p.off_alpha);
+    v.ls.beta = (float*)(w + p.off_beta);
+    v.ls.lnP = (float*)(w + p.off_lnP);
+    v.ls.shift = (float*)(w + p.off_shift);
+    v.ls.row_base = 0;
+    v.wpack = w + p.off_wpack;
+    v.dH = w + p.off_dh;
+    v.dHt = w + p.off_dht;
+    v.Zt = w + p.off_zt;
+    return v;
+}
+
+rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const void* W_out, const float* b_out,
+                const int32_t* labels, const int32_t* T_len, const int32_t* U_len, float* loss, float* d_enc,
+                float* d_pred, float* dW_out, float* db_out, void* workspace, size_t workspace_bytes,
+                void* hip_stream, bool grads) {
+    rnnt_status stt = check_desc(desc);
+    if (stt != RNNT_OK) return stt;
+    if (!enc || !pred || !W_out || !b_out || !loss || !T_len || !U_len) return RNNT_ERR_NULL;
+    if (desc->U_max > 0 && !labels) return RNNT_ERR_NULL;
+    if (grads && (!d_enc || !d_pred || !dW_out || !db_out)) return RNNT_ERR_NULL;
+    stt = check_lengths(desc, T_len, U_len);
+    if (stt != RNNT_OK) return stt;
+    if (!workspace || ((uintptr_t)workspace % WS_ALIGN) != 0 || workspace_bytes == 0) return RNNT_ERR_WORKSPACE;
+    Plan plan;
+    build_plan(*desc, T_len, U_len, workspace_bytes, plan);
+    if (plan.total_bytes > workspace_bytes) return RNNT_ERR_WORKSPACE;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const WsView wv = view_workspace(plan, workspace);
+    unsigned char* w = (unsigned char*)workspace;
+    const size_t B = (size_t)desc->B;
+    // host tables -> workspace (pageable sources: consumed before these calls return)
+    RNNT_HIP(hipMemcpyAsync(w + plan.off_T, T_len, B * 4, hipMemcpyHostToDevice, stream));
+    RNNT_HIP(hipMemcpyAsync(w + plan.off_U, U_len, B * 4, hipMemcpyHostToDevice, stream));
+    RNNT_HIP(hipMemcpyAsync(w + plan.off_tile_off, plan.tile_off.data(), (B + 1) * 4, hipMemcpyHostToDevice, stream));
+    RNNT_HIP(hipMemcpyAsync(w + plan.off_row_off, plan.row_off.data(), (B + 1) * 8, hipMemcpyHostToDevice, stream));
+
+    Problem pr{desc->B, desc->T_max, desc->U_max, desc->H, desc->V, desc->blank, enc, pred, W_out, b_out, labels};
+    GradOut go{d_enc, d_pred, dW_out, db_out};
+    const bool bf16 = (desc->dtype == RNNT_BF16);
+    if (grads) {
+        RNNT_HIP(launch_fill_zero(d_enc, B * desc->T_max * desc->H, stream));
+        RNNT_HIP(launch_fill_zero(d_pred, B * (desc->U_max + 1) * desc->H, stream));
+        if (!desc->accumulate_params) {
+            RNNT_HIP(launch_fill_zero(dW_out, (size_t)desc->H * desc->V, stream));
+            RNNT_HIP(launch_fill_zero(db_out, (size_t)desc->V, stream));
+        }
+    }
+    if (bf16) RNNT_HIP(launch_pack_w(W_out, wv.wpack, desc->H, desc->V, stream));
+
+    size_t ci = 0;
+    for (size_t gi = 0; gi < plan.groups.size(); ++gi) {
+        const Group& g = plan.groups[gi];
+        LatticeState ls = wv.ls;
+        ls.row_base = plan.row_off[g.s0];
+        // Eq. 4, Eq. 6, f^W_1
+        if (bf16)
+            RNNT_HIP(launch_fwd_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, g.tile0, g.tile1, stream));
+        else
+            RNNT_HIP(launch_fwd_f32(pr, wv.st, ls, g.s0, g.s1, g.rows, stream));
+        // f^W_2, f^W_3
+        RNNT_HIP(launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, loss, stream));
+        // f^W_4 and Algorithm 1 lines 8, 10, 11
+        for (; ci < plan.chunks.size() && plan.chunks[ci].group == (int)gi; ++ci) {
+            if (!grads) continue;
+            const Chunk& c = plan.chunks[ci];
+            if (bf16) {
+                const long long rows = (long long)(c.tile1 - c.tile0) * TILE_ROWS;
+                RNNT_HIP(launch_bwd_scores_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
+                                                wv.dHt, wv.Zt, plan.chunk_rows, stream));
+                RNNT_HIP(launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred, stream));
+                RNNT_HIP(launch_gemm_dw_bf16(desc->H, desc->V, rows, wv.Zt, wv.dHt, plan.chunk_rows, dW_out,
+                                             db_out, stream));
+            } else {
+                RNNT_HIP(launch_bwd_f32(pr, wv.st, ls, go, g.s0, g.s1, g.rows, stream));
+            }
+        }
+    }
+    return RNNT_OK;
+}
+
+}  // namespace
+
+extern "C" rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc, const void* enc, const void* pred,
+                                               const void* W_out, const float* b_out, const int32_t* labels,
+                                               const int32_t* T_len, const int32_t* U_len, float* loss,
+                                               float* d_enc, float* d_pred, float* dW_out, float* db_out,
+                                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW_out, db_out,
+               workspace, workspace_bytes, hip_stream, true);
+}
+
+extern "C" rnnt_status rnnt_joint_loss_fwd(const rnnt_desc* desc, const void* enc, const void* pred,
+                                           const void* W_out, const float* b_out, const int32_t* labels,
+                                           const int32_t* T_len, const int32_t* U_len, float* loss,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, nullptr, nullptr, nullptr, nullptr,
+               workspace, workspace_bytes, hip_stream, false);
+}
+
+extern "C" rnnt_status rnnt_debug_read_lattice(const rnnt_desc* desc, const int32_t* T_len, const int32_t* U_len,
+                                               const void* workspace, size_t workspace_bytes, int32_t b,
+                                               float* alpha_host, float* beta_host) {
+    rnnt_status stt = check_desc(desc);
+    if (stt != RNNT_OK) return stt;
+    stt = check_lengths(desc, T_len, U_len);
+    if (stt != RNNT_OK) return stt;
+    if (!workspace || !alpha_host || !beta_host) return RNNT_ERR_NULL;
+    if (b < 0 || b >= desc->B) return RNNT_ERR_SHAPE;
+    Plan plan;
+    build_plan(*desc, T_len, U_len, workspace_bytes, plan);
+    if (plan.total_bytes > workspace_bytes) return RNNT_ERR_WORKSPACE;
+    if (plan.groups.size() != 1) return RNNT_ERR_UNSUPPORTED;
+    const unsigned char* w = (const unsigned char*)workspace;
+    const int T = T_len[b], U = U_len[b];
+    const size_t n = (size_t)T * (U + 1);
+    const size_t off = (size_t)plan.row_off[b] * 4;
+    float shift = 0.0f;
+    RNNT_HIP(hipDeviceSynchronize());
+    RNNT_HIP(hipMemcpy(alpha_host, w + plan.off_alpha + off, n * 4, hipMemcpyDeviceToHost));
+    RNNT_HIP(hipMemcpy(beta_host, w + plan.off_beta + off, n * 4, hipMemcpyDeviceToHost));
+    RNNT_HIP(hipMemcpy(&shift, w + plan.off_shift + (size_t)b * 4, 4, hipMemcpyDeviceToHost));
+    for (int t = 0; t < T; ++t)
+        for (int u = 0; u <= U; ++u) {
+            const size_t i = (size_t)t * (U + 1) + u;
+            alpha_host[i] -= shift * (float)(t + u);
+            beta_host[i] -= shift * (float)((T - t) + (U - u));
+        }
+    return RNNT_OK;
+}

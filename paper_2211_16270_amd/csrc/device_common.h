@@ -1,0 +1,89 @@
+// Device helpers shared by the HIP kernels of this library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace rnnt {
+
+constexpr float LOG2E_F = 1.4426950408889634f;
+constexpr float LN2_F = 0.6931471805599453f;
+#define RNNT_NEG_INF (-__builtin_huge_valf())
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Largest s in [lo, hi) with off[s] <= x  (off is non-decreasing, off[lo] <= x < off[hi]).
+template <typename T>
+__device__ __forceinline__ int find_segment(const T* __restrict__ off, int lo, int hi, T x) {
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (off[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Position of an 8x8 lattice tile: sample, first frame, first label position.
+struct TilePos {
+    int s, T, U, t0, u0;
+};
+
+__device__ __forceinline__ TilePos locate_tile(const SampleTable& st, int s0, int s1, int tile) {
+    TilePos p;
+    p.s = find_segment<int>(st.tile_off, s0, s1, tile);
+    p.T = st.T[p.s];
+    p.U = st.U[p.s];
+    const int tiles_u = (p.U + 8) >> 3;           // ceil((U+1)/8)
+    const int lt = tile - st.tile_off[p.s];
+    const int tb = lt / tiles_u;
+    p.t0 = tb * 8;
+    p.u0 = (lt - tb * tiles_u) * 8;
+    return p;
+}
+
+// tanh through one exp and one reciprocal; absolute error ~1e-7, saturates cleanly at +-1.
+__device__ __forceinline__ float fast_tanh(float x) {
+    float e = __builtin_amdgcn_exp2f(x * (2.0f * LOG2E_F));
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+// ln(e^a + e^b); either may be -inf.
+__device__ __forceinline__ float log_add_exp(float a, float b) {
+    float m = fmaxf(a, b);
+    if (m == RNNT_NEG_INF) return m;
+    float d = -fabsf(a - b);                      // -inf when exactly one is -inf
+    return m + __logf(1.0f + __expf(d));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// Posterior weights of one lattice node (f^W_4): ln gamma, and the occupation of its blank and
+// label transitions.  alpha/beta/lnP carry the per-sample emission offset `shift`, which cancels.
+struct RowPost {
+    float log_gamma, Bk, Yk;
+};
+__device__ __forceinline__ RowPost row_posteriors(const LatticeState& ls, long long idx, int t, int u,
+                                                   int T, int U, int s) {
+    const float a = ls.alpha[idx], lnP = ls.lnP[s], c = ls.shift[s];
+    RowPost r;
+    r.log_gamma = a + ls.beta[idx] - lnP;
+    const float ab = a + ls.lpb[idx] + c - lnP;
+    if (t < T - 1) r.Bk = __expf(ab + ls.beta[idx + (U + 1)]);
+    else r.Bk = (u == U) ? __expf(ab) : 0.0f;
+    r.Yk = (u < U) ? __expf(a + ls.lpy[idx] + c - lnP + ls.beta[idx + 1]) : 0.0f;
+    return r;
+}
+
+}  // namespace rnnt

@@ -1,0 +1,77 @@
+// Internal launch interface between the C-ABI layer (api.cpp) and the HIP kernels.
+// Every function enqueues on `stream` and returns the launch status; none synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace rnnt {
+
+// Device-resident description of the scheduled samples (one table per call).
+struct SampleTable {
+    const int* T;              // [B] T_len
+    const int* U;              // [B] U_len
+    const int* tile_off;       // [B+1] cumulative 8x8 lattice-tile counts
+    const long long* row_off;  // [B+1] cumulative lattice-node counts
+};
+
+// Per-group lattice state; arrays are indexed by (row_off[s] - row_base) + t*(U_s+1) + u.
+struct LatticeState {
+    float* lse;    // ln of the softmax denominator (f^W_1)
+    float* lpb;    // blank log-probability
+    float* lpy;    // log-probability of label y_u (unused at u = U_s)
+    float* alpha;  // forward variable, offset by shift*(t+u)
+    float* beta;   // backward variable, offset by shift*((T-t)+(U-u))
+    float* lnP;    // [B] ln P(y|x) + shift*(T+U), per sample
+    float* shift;  // [B] per-sample offset added to every emission log-probability
+    long long row_base;
+};
+
+struct Problem {
+    int B, T_max, U_max, H, V, blank;
+    const void* enc;
+    const void* pred;
+    const void* W;         // [H,V] as given by the caller
+    const float* b_out;
+    const int* labels;
+};
+
+struct GradOut {
+    float* d_enc;
+    float* d_pred;
+    float* dW;
+    float* db;
+};
+
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream);
+
+// ---- fp32 path (plain FMA kernels, any H, V) ------------------------------------------------
+hipError_t launch_fwd_f32(const Problem& pr, const SampleTable& st, const LatticeState& ls,
+                          int s0, int s1, long long rows, hipStream_t stream);
+hipError_t launch_bwd_f32(const Problem& pr, const SampleTable& st, const LatticeState& ls,
+                          const GradOut& go, int s0, int s1, long long rows, hipStream_t stream);
+
+// ---- lattice (alpha, beta, loss) ------------------------------------------------------------
+hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0, int s1, int u_max,
+                          float* loss, hipStream_t stream);
+
+// ---- bf16 MFMA path -------------------------------------------------------------------------
+// W [H,V] -> fragment-major copy for the A operand of the score GEMM
+hipError_t launch_pack_w(const void* W, void* Wpack, int H, int V, hipStream_t stream);
+// joint tile in LDS -> scores on MFMA -> online log-softmax -> lse, lpb, lpy   (tiles [tile0,tile1))
+hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
+                           const LatticeState& ls, int s0, int s1, int tile0, int tile1,
+                           hipStream_t stream);
+// joint tile -> scores recomputed -> dh (bf16) into the chunk buffers dH [rows,V], dHt [V,ld], Zt [H,ld]
+hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
+                                  const LatticeState& ls, int s0, int s1, int tile0, int tile1,
+                                  void* dH, void* dHt, void* Zt, long long ld, hipStream_t stream);
+// dz = dH W^T, times the tanh derivative, reduced over the tile's u resp. t, added to d_enc, d_pred
+hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0,
+                               int tile1, const void* dH, float* d_enc, float* d_pred,
+                               hipStream_t stream);
+// dW += Zt dHt^T (split over the rows), db += row sums of dHt
+hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, const void* dHt,
+                               long long ld, float* dW, float* db, hipStream_t stream);
+
+}  // namespace rnnt

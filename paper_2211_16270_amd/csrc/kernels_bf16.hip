@@ -1,0 +1,554 @@
+// bf16 MFMA path (gfx950): joint tile in LDS -> score GEMM -> softmax statistics / score gradients,
+// and the two backward GEMMs.  fp32 accumulation everywhere; tanh, exp, softmax in fp32.
+//
+// Work unit: an 8x8 lattice tile of one sample (8 frames x 8 label positions = 64 rows, row
+// r = 8*tl + ul).  Such a tile needs only 8 + 8 input vectors, and its contribution to d_enc /
+// d_pred can be summed over ul resp. tl before it leaves the registers.
+//
+// MFMA operand layouts used below (v_mfma_f32_32x32x16_bf16, D = A B + C, wave64):
+//   A (32 x 16): lane l holds row l%32, k = 8*(l/32) .. +7        (8 bf16)
+//   B (16 x 32): lane l holds column l%32, k = 8*(l/32) .. +7     (8 bf16)
+//   C/D (32x32): lane l holds column l%32; register 4*j+i is row 8*j + 4*(l/32) + i
+// The score GEMM is run "transposed" (A = W_out^T tile, B = joint tile), so a lane owns one
+// lattice row and its 16 registers are 16 vocabulary entries: the softmax reductions over the
+// vocabulary are then register-local.
+#include "device_common.h"
+
+namespace rnnt {
+
+// ------------------------------------------------------------------------------------------------
+// W [H,V] -> fragment-major copy: Wp[((vt*KK + kk)*64 + lane)*8 + j] = W[kk*16 + 8*(lane/32) + j][vt*32 + lane%32]
+// so that one A fragment of the score GEMM is a contiguous 1 KiB block.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_pack_w(const bf16_t* __restrict__ W, bf16_t* __restrict__ Wp, int H, int V) {
+    const int KK = H >> 4;
+    const long long total = (long long)(V >> 5) * KK * 64;
+    long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= total) return;
+    const int lane = (int)(g & 63);
+    const long long f = g >> 6;
+    const int kk = (int)(f % KK);
+    const int vt = (int)(f / KK);
+    const int v = vt * 32 + (lane & 31);
+    const int k0 = kk * 16 + 8 * (lane >> 5);
+    bf16x8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = W[(size_t)(k0 + j) * V + v];
+    *reinterpret_cast<bf16x8*>(Wp + g * 8) = o;
+}
+
+hipError_t launch_pack_w(const void* W, void* Wpack, int H, int V, hipStream_t stream) {
+    const long long total = (long long)(V / 32) * (H / 16) * 64;
+    k_pack_w<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>((const bf16_t*)W, (bf16_t*)Wpack, H, V);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Joint tile + score GEMM.  MODE 0: softmax statistics (forward).  MODE 1: score gradients (backward).
+// 256 threads = 4 waves; per step of 128 vocabulary entries wave w owns entries [32w, 32w+32) for
+// all 64 rows (two 32x32 accumulator tiles).
+// ------------------------------------------------------------------------------------------------
+constexpr int JT_ROWS = 64;
+constexpr int JT_VSTEP = 128;
+constexpr int STG_PITCH = 40;   // bf16 elements per row of a wave's 32x32 transposition buffer
+
+struct JointArgs {
+    Problem pr;
+    SampleTable st;
+    LatticeState ls;
+    const bf16_t* Wp;
+    int s0, s1, tile0, tile1;
+    // MODE 1 outputs
+    bf16_t* dH;     // [chunk rows, V]
+    bf16_t* dHt;    // [V, ld]
+    bf16_t* Zt;     // [H, ld]
+    long long ld;
+};
+
+__device__ __forceinline__ size_t jt_smem_bytes(int H) { return 0; }
+
+template <int MODE>
+__global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int H = a.pr.H, V = a.pr.V;
+    const int ZP = H + 8;                                   // padded row pitch of the joint tile
+    bf16_t* zs = reinterpret_cast<bf16_t*>(smem);           // [64][ZP]
+    unsigned char* p_after = smem + (size_t)JT_ROWS * ZP * 2;
+    int* row_lat = reinterpret_cast<int*>(p_after);         // [64] lattice index, -1 = outside the sample
+    int* row_lab = row_lat + 64;                            // [64] label, -1 = none
+    float* row_f0 = reinterpret_cast<float*>(row_lab + 64); // MODE 0: cap_b   MODE 1: exponent offset
+    float* row_f1 = row_f0 + 64;                            // MODE 0: cap_y   MODE 1: Bk
+    float* row_f2 = row_f1 + 64;                            // MODE 1: Yk
+    float* red_m = row_f2 + 64;                             // MODE 0: [8][64] partial maxima
+    float* red_s = red_m + 512;                             // MODE 0: [8][64] partial sums
+    bf16_t* stg = reinterpret_cast<bf16_t*>(row_f2 + 64);   // MODE 1: [4][32][STG_PITCH] (aliases red_*)
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
+    const int tile = a.tile0 + blockIdx.x;
+    const TilePos tp = locate_tile(a.st, a.s0, a.s1, tile);
+    const int b = tp.s;
+    const long long chunk_row0 = (long long)blockIdx.x * JT_ROWS;
+
+    // ---- joint tile: z = tanh(enc_t + pred_u), bf16, rows outside the sample are zero (Eq. 4)
+    {
+        const bf16_t* enc = reinterpret_cast<const bf16_t*>(a.pr.enc) + (size_t)b * a.pr.T_max * H;
+        const bf16_t* prd = reinterpret_cast<const bf16_t*>(a.pr.pred) + (size_t)b * (a.pr.U_max + 1) * H;
+        const int items = JT_ROWS * (H >> 3);
+        for (int it = tid; it < items; it += 256) {
+            const int r = it & 63, c = it >> 6;
+            const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
+            bf16x8 z;
+            if (t < tp.T && u <= tp.U) {
+                const bf16x8 e = *reinterpret_cast<const bf16x8*>(enc + (size_t)t * H + c * 8);
+                const bf16x8 q = *reinterpret_cast<const bf16x8*>(prd + (size_t)u * H + c * 8);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) z[j] = (bf16_t)fast_tanh((float)e[j] + (float)q[j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) z[j] = (bf16_t)0.0f;
+            }
+            *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = z;
+            if (MODE == 1) {
+                bf16_t* zt = a.Zt + (size_t)(c * 8) * a.ld + chunk_row0 + r;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) zt[(size_t)j * a.ld] = z[j];
+            }
+        }
+    }
+    if (tid < 64) {
+        const int r = tid;
+        const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
+        const bool valid = (t < tp.T && u <= tp.U);
+        const long long idx = (a.st.row_off[b] - a.ls.row_base) + (long long)t * (tp.U + 1) + u;
+        row_lat[r] = valid ? (int)idx : -1;
+        row_lab[r] = (valid && u < tp.U) ? a.pr.labels[(size_t)b * a.pr.U_max + u] : -1;
+        if (MODE == 0) {
+            row_f0[r] = RNNT_NEG_INF;
+            row_f1[r] = RNNT_NEG_INF;
+        } else {
+            if (valid) {
+                const RowPost rp = row_posteriors(a.ls, idx, t, u, tp.T, tp.U, b);
+                row_f0[r] = (rp.log_gamma - a.ls.lse[idx]) * LOG2E_F;
+                row_f1[r] = rp.Bk;
+                row_f2[r] = rp.Yk;
+            } else {
+                row_f0[r] = RNNT_NEG_INF;
+                row_f1[r] = 0.0f;
+                row_f2[r] = 0.0f;
+            }
+        }
+    }
+    __syncthreads();
+
+    const int KK = H >> 4;
+    int lab[2] = {row_lab[l32], row_lab[32 + l32]};
+    float m_run[2] = {RNNT_NEG_INF, RNNT_NEG_INF}, s_run[2] = {0.0f, 0.0f};
+    float gexp[2], Bk[2], Yk[2];
+    if (MODE == 1) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            gexp[rt] = row_f0[rt * 32 + l32];
+            Bk[rt] = row_f1[rt * 32 + l32];
+            Yk[rt] = row_f2[rt * 32 + l32];
+        }
+    }
+    const bf16_t* zrow0 = zs + l32 * ZP + hb * 8;
+    const bf16_t* zrow1 = zs + (32 + l32) * ZP + hb * 8;
+
+    for (int vs = 0; vs < V / JT_VSTEP; ++vs) {
+        const int vbase = vs * JT_VSTEP + wave * 32;
+        const bf16x8* ap = reinterpret_cast<const bf16x8*>(a.Wp) + (size_t)(vbase >> 5) * KK * 64 + lane;
+        f32x16 acc0 = {0}, acc1 = {0};
+        // K loop, two k16-steps per iteration, A fragments one iteration ahead
+        bf16x8 a0 = ap[0], a1 = ap[64];
+        for (int kk = 0; kk < KK; kk += 2) {
+            bf16x8 n0 = a0, n1 = a1;
+            if (kk + 2 < KK) {
+                n0 = ap[(size_t)(kk + 2) * 64];
+                n1 = ap[(size_t)(kk + 3) * 64];
+            }
+            const bf16x8 b00 = *reinterpret_cast<const bf16x8*>(zrow0 + kk * 16);
+            const bf16x8 b10 = *reinterpret_cast<const bf16x8*>(zrow1 + kk * 16);
+            const bf16x8 b01 = *reinterpret_cast<const bf16x8*>(zrow0 + kk * 16 + 16);
+            const bf16x8 b11 = *reinterpret_cast<const bf16x8*>(zrow1 + kk * 16 + 16);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b00, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b10, acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b01, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b11, acc1, 0, 0, 0);
+            a0 = n0;
+            a1 = n1;
+        }
+        // bias of this lane's 16 vocabulary entries: v = vbase + 8j + 4hb + i
+        float bv[16];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const f32x4 t4 = *reinterpret_cast<const f32x4*>(a.pr.b_out + vbase + 8 * j + 4 * hb);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bv[4 * j + i] = t4[i];
+        }
+        const int relb = a.pr.blank - vbase;
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            const f32x16 acc = rt ? acc1 : acc0;
+            const int rely = lab[rt] - vbase;
+            const bool hit_y = ((unsigned)rely < 32u);
+            const bool slow = __any(hit_y) || ((unsigned)relb < 32u);
+            if (MODE == 0) {
+                // f^W_1: running maximum and sum of exponentials of this lane's share of the row
+                float x[16];
+                float tmax = RNNT_NEG_INF;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    x[i] = acc[i] + bv[i];
+                    tmax = fmaxf(tmax, x[i]);
+                }
+                const float mn = fmaxf(m_run[rt], tmax);
+                const float mn2 = mn * LOG2E_F;
+                float ssum = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) ssum += __builtin_amdgcn_exp2f(fmaf(x[i], LOG2E_F, -mn2));
+                s_run[rt] = s_run[rt] * __builtin_amdgcn_exp2f((m_run[rt] - mn) * LOG2E_F) + ssum;
+                m_run[rt] = mn;
+                if (slow) {
+                    float cb = RNNT_NEG_INF, cy = RNNT_NEG_INF;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int vloc = 8 * (i >> 2) + 4 * hb + (i & 3);
+                        if (vloc == relb) cb = x[i];
+                        if (vloc == rely) cy = x[i];
+                    }
+                    const int row = rt * 32 + l32;
+                    if (cb != RNNT_NEG_INF) row_f0[row] = cb;
+                    if (cy != RNNT_NEG_INF) row_f1[row] = cy;
+                }
+            } else {
+                // f^W_4: dh = gamma * softmax - posteriors, rounded to bf16 for the backward GEMMs
+                float d[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    d[i] = __builtin_amdgcn_exp2f(fmaf(acc[i] + bv[i], LOG2E_F, gexp[rt]));
+                if (slow) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int vloc = 8 * (i >> 2) + 4 * hb + (i & 3);
+                        if (vloc == relb) d[i] -= Bk[rt];
+                        if (vloc == rely) d[i] -= Yk[rt];
+                    }
+                }
+                bf16_t dbf[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dbf[i] = (bf16_t)d[i];
+                // transposed copy dHt[v][row]: consecutive lanes are consecutive rows
+                {
+                    bf16_t* o = a.dHt + (size_t)(vbase + 4 * hb) * a.ld + chunk_row0 + rt * 32 + l32;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[(size_t)(8 * (i >> 2) + (i & 3)) * a.ld] = dbf[i];
+                }
+                // row-major copy dH[row][v] through this wave's 32x32 transposition buffer
+                {
+                    bf16_t* sw = stg + wave * (32 * STG_PITCH);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        bf16x4 q4 = {dbf[4 * j], dbf[4 * j + 1], dbf[4 * j + 2], dbf[4 * j + 3]};
+                        *reinterpret_cast<bf16x4*>(sw + l32 * STG_PITCH + 8 * j + 4 * hb) = q4;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                    for (int it = 0; it < 2; ++it) {
+                        const int row = (lane >> 2) + 16 * it, seg = lane & 3;
+                        const bf16x8 v8 = *reinterpret_cast<const bf16x8*>(sw + row * STG_PITCH + seg * 8);
+                        *reinterpret_cast<bf16x8*>(a.dH + (size_t)(chunk_row0 + rt * 32 + row) * V + vbase + seg * 8) = v8;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+    }
+
+    if (MODE == 0) {
+        // combine the 8 partial (max, sum) pairs of every row, then lse, lpb, lpy
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            red_m[(wave * 2 + hb) * 64 + rt * 32 + l32] = m_run[rt];
+            red_s[(wave * 2 + hb) * 64 + rt * 32 + l32] = s_run[rt];
+        }
+        __syncthreads();
+        if (tid < 64) {
+            const int r = tid;
+            const int idx = row_lat[r];
+            if (idx >= 0) {
+                float M = RNNT_NEG_INF;
+#pragma unroll
+                for (int p = 0; p < 8; ++p) M = fmaxf(M, red_m[p * 64 + r]);
+                float S = 0.0f;
+#pragma unroll
+                for (int p = 0; p < 8; ++p) S += red_s[p * 64 + r] * __expf(red_m[p * 64 + r] - M);
+                const float lse = M + __logf(S);
+                a.ls.lse[idx] = lse;
+                a.ls.lpb[idx] = row_f0[r] - lse;
+                a.ls.lpy[idx] = (row_lab[r] >= 0) ? row_f1[r] - lse : 0.0f;
+            }
+        }
+    }
+}
+
+static size_t joint_smem_bytes(int H, int mode) {
+    size_t z = (size_t)JT_ROWS * (H + 8) * 2;
+    size_t meta = 64 * 4 * 5;
+    size_t tail = mode == 0 ? (size_t)2 * 512 * 4 : (size_t)4 * 32 * STG_PITCH * 2;
+    return z + meta + tail;
+}
+
+template <int MODE>
+static hipError_t launch_joint(const JointArgs& a, hipStream_t stream) {
+    const int n = a.tile1 - a.tile0;
+    if (n <= 0) return hipSuccess;
+    const size_t smem = joint_smem_bytes(a.pr.H, MODE);
+    static size_t configured = 0;
+    if (smem > configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_scores<MODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        configured = smem;
+    }
+    k_joint_scores<MODE><<<dim3((unsigned)n), dim3(256), smem, stream>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st, const LatticeState& ls,
+                           int s0, int s1, int tile0, int tile1, hipStream_t stream) {
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr, nullptr, 0};
+    return launch_joint<0>(a, stream);
+}
+
+hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
+                                  const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
+                                  void* dHt, void* Zt, long long ld, hipStream_t stream) {
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)dH, (bf16_t*)dHt, (bf16_t*)Zt, ld};
+    return launch_joint<1>(a, stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// C = A B^T on bf16 MFMA: A [M,K], B [N,K], both with the contraction index contiguous.
+// 128x128 tile per workgroup, 32-wide K steps through double-buffered LDS, 4 waves in 2x2,
+// each wave 64x64 (2x2 accumulator tiles).
+//   MODE 0 (dz):  A = dH [rows,V], B = W_out [H,V]; epilogue applies the tanh derivative and sums
+//                 over the label positions / frames of each 8x8 lattice tile (Alg. 1 lines 10, 11)
+//   MODE 1 (dW):  A = Zt [H,ld], B = dHt [V,ld], K split over blockIdx.z; epilogue adds into dW_out
+//                 (Alg. 1 line 8)
+// ------------------------------------------------------------------------------------------------
+constexpr int GT = 128;       // tile edge
+constexpr int GK = 32;        // K step
+constexpr int GP = 40;        // LDS row pitch in bf16 elements (80 B: conflict-free 16 B reads)
+
+struct GemmArgs {
+    const bf16_t* A;
+    const bf16_t* B;
+    long long lda, ldb;
+    long long K;             // contraction length (MODE 1: whole row count)
+    long long k_per_split;   // MODE 1
+    // MODE 0
+    Problem pr;
+    SampleTable st;
+    int s0, s1, tile0, tile1;
+    float* d_enc;
+    float* d_pred;
+    // MODE 1
+    float* dW;
+    int V;
+};
+
+template <int MODE>
+__global__ __launch_bounds__(256, 2) void k_gemm_nt(GemmArgs g) {
+    __shared__ __align__(16) bf16_t As[2][GT * GP];
+    __shared__ __align__(16) bf16_t Bs[2][GT * GP];
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+    const long long m0 = (long long)blockIdx.x * GT, n0 = (long long)blockIdx.y * GT;
+    long long ks = 0, ke = g.K;
+    if (MODE == 1) {
+        ks = (long long)blockIdx.z * g.k_per_split;
+        ke = ks + g.k_per_split < g.K ? ks + g.k_per_split : g.K;
+        if (ks >= ke) return;
+    }
+    const int lrow = tid >> 2, lseg = tid & 3;
+    const bf16_t* Ag = g.A + (m0 + lrow) * g.lda + lseg * 8;
+    const bf16_t* Bg = g.B + (n0 + lrow) * g.ldb + lseg * 8;
+    bf16x8 ra0, ra1, rb0, rb1;
+    auto gload = [&](long long k0) {
+        ra0 = *reinterpret_cast<const bf16x8*>(Ag + k0);
+        ra1 = *reinterpret_cast<const bf16x8*>(Ag + 64 * g.lda + k0);
+        rb0 = *reinterpret_cast<const bf16x8*>(Bg + k0);
+        rb1 = *reinterpret_cast<const bf16x8*>(Bg + 64 * g.ldb + k0);
+    };
+    auto sstore = [&](int buf) {
+        *reinterpret_cast<bf16x8*>(&As[buf][lrow * GP + lseg * 8]) = ra0;
+        *reinterpret_cast<bf16x8*>(&As[buf][(lrow + 64) * GP + lseg * 8]) = ra1;
+        *reinterpret_cast<bf16x8*>(&Bs[buf][lrow * GP + lseg * 8]) = rb0;
+        *reinterpret_cast<bf16x8*>(&Bs[buf][(lrow + 64) * GP + lseg * 8]) = rb1;
+    };
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{0};
+
+    gload(ks);
+    sstore(0);
+    __syncthreads();
+    int buf = 0;
+    for (long long k0 = ks; k0 < ke; k0 += GK) {
+        const bool more = (k0 + GK < ke);
+        if (more) gload(k0 + GK);
+        const bf16_t* as = &As[buf][(wm * 64 + l32) * GP + hb * 8];
+        const bf16_t* bs = &Bs[buf][(wn * 64 + l32) * GP + hb * 8];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(as + kk * 16);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(as + 32 * GP + kk * 16);
+            const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(bs + kk * 16);
+            const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(bs + 32 * GP + kk * 16);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        if (more) sstore(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    if (MODE == 1) {
+        // C[m = hidden index][n = vocabulary index]; lanes are consecutive vocabulary entries
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const long long n = n0 + wn * 64 + nt * 32 + l32;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const long long m = m0 + wm * 64 + mt * 32 + 8 * (i >> 2) + 4 * hb + (i & 3);
+                    atomicAdd(&g.dW[m * g.V + n], acc[mt][nt][i]);
+                }
+            }
+    } else {
+        // rows wm*64 .. +63 of this workgroup are one lattice tile: row = 8*tl + ul, and in the
+        // accumulator layout register 4j+i of row-tile mt is tl = 4*mt + j, ul = 4*hb + i.
+        const int tile = g.tile0 + (int)blockIdx.x * 2 + wm;
+        if (tile < g.tile1) {
+            const TilePos tp = locate_tile(g.st, g.s0, g.s1, tile);
+            const int b = tp.s, H = g.pr.H;
+            const bf16_t* enc = reinterpret_cast<const bf16_t*>(g.pr.enc) + (size_t)b * g.pr.T_max * H;
+            const bf16_t* prd = reinterpret_cast<const bf16_t*>(g.pr.pred) + (size_t)b * (g.pr.U_max + 1) * H;
+            float* d_enc = g.d_enc + (size_t)b * g.pr.T_max * H;
+            float* d_prd = g.d_pred + (size_t)b * (g.pr.U_max + 1) * H;
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const int h = (int)n0 + wn * 64 + nt * 32 + l32;
+                float e[8], q[4], pu[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int tl = 0; tl < 8; ++tl)
+                    e[tl] = (tp.t0 + tl < tp.T) ? (float)enc[(size_t)(tp.t0 + tl) * H + h] : 0.0f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    q[i] = (tp.u0 + 4 * hb + i <= tp.U) ? (float)prd[(size_t)(tp.u0 + 4 * hb + i) * H + h] : 0.0f;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int tl = 4 * mt + j;
+                        const bool tv = (tp.t0 + tl < tp.T);
+                        float se = 0.0f;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const bool ok = tv && (tp.u0 + 4 * hb + i <= tp.U);
+                            const float z = fast_tanh(e[tl] + q[i]);
+                            const float dx = ok ? acc[mt][nt][4 * j + i] * (1.0f - z * z) : 0.0f;
+                            se += dx;
+                            pu[i] += dx;
+                        }
+                        se += __shfl_xor(se, 32, 64);
+                        if (tv && hb == (j & 1)) atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (tp.u0 + 4 * hb + i <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + 4 * hb + i) * H + h], pu[i]);
+            }
+        }
+    }
+}
+
+hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0, int tile1,
+                               const void* dH, float* d_enc, float* d_pred, hipStream_t stream) {
+    const int n = tile1 - tile0;
+    if (n <= 0) return hipSuccess;
+    GemmArgs g{};
+    g.A = (const bf16_t*)dH;
+    g.lda = pr.V;
+    g.B = (const bf16_t*)pr.W;
+    g.ldb = pr.V;
+    g.K = pr.V;
+    g.k_per_split = pr.V;
+    g.pr = pr;
+    g.st = st;
+    g.s0 = s0;
+    g.s1 = s1;
+    g.tile0 = tile0;
+    g.tile1 = tile1;
+    g.d_enc = d_enc;
+    g.d_pred = d_pred;
+    k_gemm_nt<0><<<dim3((unsigned)((n + 1) / 2), (unsigned)(pr.H / GT)), dim3(256), 0, stream>>>(g);
+    return hipGetLastError();
+}
+
+// db[v] += sum over rows of dHt[v][.]: one wave per vocabulary entry
+__global__ __launch_bounds__(256) void k_db(const bf16_t* __restrict__ dHt, long long ld, long long rows,
+                                            float* __restrict__ db, int V) {
+    const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= V) return;
+    const int lane = threadIdx.x & 63;
+    const bf16x8* p = reinterpret_cast<const bf16x8*>(dHt + (size_t)v * ld);
+    float acc = 0.0f;
+    for (long long i = lane; i < rows / 8; i += 64) {
+        const bf16x8 x = p[i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc += (float)x[j];
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) atomicAdd(&db[v], acc);
+}
+
+hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, const void* dHt, long long ld,
+                               float* dW, float* db, hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    GemmArgs g{};
+    g.A = (const bf16_t*)Zt;
+    g.lda = ld;
+    g.B = (const bf16_t*)dHt;
+    g.ldb = ld;
+    g.K = rows;
+    g.dW = dW;
+    g.V = V;
+    // enough K splits to give every CU a few workgroups, each at least 512 rows long
+    const long long out_tiles = (long long)(H / GT) * (V / GT);
+    long long splits = (1024 + out_tiles - 1) / out_tiles;
+    long long max_splits = (rows + 511) / 512;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    long long per = (rows + splits - 1) / splits;
+    per = (per + GK - 1) / GK * GK;
+    splits = (rows + per - 1) / per;
+    g.k_per_split = per;
+    k_gemm_nt<1><<<dim3((unsigned)(H / GT), (unsigned)(V / GT), (unsigned)splits), dim3(256), 0, stream>>>(g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_db<<<dim3((unsigned)((V + 3) / 4)), dim3(256), 0, stream>>>((const bf16_t*)dHt, ld, rows, db, V);
+    return hipGetLastError();
+}
+
+}  // namespace rnnt

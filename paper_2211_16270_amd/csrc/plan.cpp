@@ -1,0 +1,191 @@
+// Host scheduler and workspace layout (see plan.h).  No HIP in this file.
+#include "plan.h"
+
+#include <algorithm>
+#include <cmath>
+
+namespace rnnt {
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+rnnt_status check_desc(const rnnt_desc* d) {
+    if (!d) return RNNT_ERR_NULL;
+    if (d->B < 1 || d->T_max < 1 || d->U_max < 0 || d->H < 1 || d->V < 2) return RNNT_ERR_SHAPE;
+    if (d->blank < 0 || d->blank >= d->V) return RNNT_ERR_SHAPE;
+    if (d->accumulate_params != 0 && d->accumulate_params != 1) return RNNT_ERR_SHAPE;
+    if (d->dtype != RNNT_F32 && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
+    if (d->U_max > 1023) return RNNT_ERR_UNSUPPORTED;           // one lattice thread per label position
+    if ((long long)d->T_max * (d->U_max + 1) > (1LL << 30)) return RNNT_ERR_UNSUPPORTED;
+    if (d->dtype == RNNT_BF16) {
+        if (d->H % 128 != 0 || d->H > 1024) return RNNT_ERR_UNSUPPORTED;
+        if (d->V % 128 != 0) return RNNT_ERR_UNSUPPORTED;
+    } else {
+        if (d->H > 4096 || d->V > 16384) return RNNT_ERR_UNSUPPORTED;
+    }
+    return RNNT_OK;
+}
+
+rnnt_status check_lengths(const rnnt_desc* d, const int32_t* T_len, const int32_t* U_len) {
+    if (!T_len || !U_len) return RNNT_ERR_NULL;
+    for (int b = 0; b < d->B; ++b) {
+        if (T_len[b] < 1 || T_len[b] > d->T_max) return RNNT_ERR_LENGTH;
+        if (U_len[b] < 0 || U_len[b] > d->U_max) return RNNT_ERR_LENGTH;
+    }
+    return RNNT_OK;
+}
+
+namespace {
+
+struct Sizes {
+    size_t fixed;          // tables + packed W
+    size_t chunk_row_bytes;
+};
+
+// Fills every offset for the given capacities and returns the total size.
+size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_rows) {
+    const size_t B = (size_t)d.B;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, WS_ALIGN); return at; };
+    p.off_T = take(B * 4);
+    p.off_U = take(B * 4);
+    p.off_tile_off = take((B + 1) * 4);
+    p.off_row_off = take((B + 1) * 8);
+    p.off_lnP = take(B * 4);
+    p.off_shift = take(B * 4);
+    p.off_wpack = take(p.bf16 ? (size_t)d.H * d.V * 2 : 0);
+    size_t lat0 = o;
+    p.off_lse = take((size_t)lat_cap * 4);
+    p.off_lpb = take((size_t)lat_cap * 4);
+    p.off_lpy = take((size_t)lat_cap * 4);
+    p.off_alpha = take((size_t)lat_cap * 4);
+    p.off_beta = take((size_t)lat_cap * 4);
+    p.lattice_bytes = o - lat0;
+    size_t ch0 = o;
+    if (p.bf16) {
+        p.off_dh = take((size_t)chunk_rows * d.V * 2);
+        p.off_dht = take((size_t)chunk_rows * d.V * 2);
+        p.off_zt = take((size_t)chunk_rows * d.H * 2);
+    } else {
+        p.off_dh = p.off_dht = p.off_zt = o;
+    }
+    p.chunk_bytes = o - ch0;
+    p.group_rows_cap = lat_cap;
+    p.chunk_rows = p.bf16 ? chunk_rows : 0;
+    p.total_bytes = o;
+    return o;
+}
+
+}  // namespace
+
+void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
+                size_t workspace_bytes, Plan& p) {
+    const int B = d.B;
+    p.B = B;
+    p.bf16 = (d.dtype == RNNT_BF16);
+    p.tile_off.assign(B + 1, 0);
+    p.row_off.assign(B + 1, 0);
+    long long max_rows = 0;
+    for (int b = 0; b < B; ++b) {
+        long long rows = (long long)T_len[b] * (U_len[b] + 1);
+        long long tiles = (long long)((T_len[b] + TILE_T - 1) / TILE_T) * ((U_len[b] + 1 + TILE_U - 1) / TILE_U);
+        p.row_off[b + 1] = p.row_off[b] + rows;
+        p.tile_off[b + 1] = (int)(p.tile_off[b] + tiles);
+        max_rows = std::max(max_rows, rows);
+    }
+    p.rows_total = p.row_off[B];
+    p.tiles_total = p.tile_off[B];
+    const long long all_tile_rows =
+        (long long)align_up((size_t)p.tiles_total * TILE_ROWS, GEMM_TILE);
+    const size_t crb = p.bf16 ? (size_t)4 * d.V + (size_t)2 * d.H : 0;
+
+    // smallest workable plan: one (largest) sample per group, one GEMM tile of rows per chunk
+    Plan tmp = p;
+    p.min_bytes = lay_out(d, tmp, max_rows, p.bf16 ? GEMM_TILE : 0);
+
+    long long lat_cap, chunk_rows;
+    if (workspace_bytes == 0) {
+        const long long lat_default = (256LL << 20) / 20;
+        lat_cap = std::min(p.rows_total, std::max(max_rows, lat_default));
+        chunk_rows = 0;
+        if (p.bf16) {
+            long long by_bytes = (long long)((768ULL << 20) / crb) / GEMM_TILE * GEMM_TILE;
+            chunk_rows = std::min(all_tile_rows, std::max<long long>(GEMM_TILE, by_bytes));
+        }
+    } else if (workspace_bytes < p.min_bytes) {
+        lat_cap = max_rows;
+        chunk_rows = p.bf16 ? GEMM_TILE : 0;
+    } else {
+        // the fixed part and the alignment slack come off first
+        Plan probe = p;
+        size_t fixed = lay_out(d, probe, 0, 0) + 8 * WS_ALIGN;
+        size_t avail = workspace_bytes > fixed ? workspace_bytes - fixed : 0;
+        if (!p.bf16) {
+            lat_cap = std::min<long long>(p.rows_total, std::max<long long>(max_rows, (long long)(avail / 20)));
+            chunk_rows = 0;
+        } else {
+            long long lat_quarter = (long long)(avail / 4 / 20);
+            lat_cap = std::min(p.rows_total, std::max(max_rows, lat_quarter));
+            size_t lat_bytes = (size_t)lat_cap * 20;
+            size_t rest = avail > lat_bytes ? avail - lat_bytes : 0;
+            chunk_rows = (long long)(rest / crb) / GEMM_TILE * GEMM_TILE;
+            chunk_rows = std::min(all_tile_rows, std::max<long long>(GEMM_TILE, chunk_rows));
+            // what the chunk buffers do not need goes to the lattice
+            size_t chunk_bytes = (size_t)chunk_rows * crb;
+            if (avail > chunk_bytes) {
+                long long more = (long long)((avail - chunk_bytes) / 20);
+                lat_cap = std::min(p.rows_total, std::max(lat_cap, more));
+            }
+        }
+        // never below the minimum, never above the given size
+        Plan t2 = p;
+        while (lay_out(d, t2, lat_cap, chunk_rows) > workspace_bytes) {
+            if (chunk_rows > GEMM_TILE) chunk_rows -= GEMM_TILE;
+            else if (lat_cap > max_rows) lat_cap = std::max(max_rows, lat_cap - 4096);
+            else break;
+        }
+    }
+    lay_out(d, p, lat_cap, chunk_rows);
+    if (workspace_bytes != 0 && workspace_bytes < p.min_bytes) p.total_bytes = p.min_bytes;
+
+    // groups: consecutive samples while the lattice state fits
+    p.groups.clear();
+    p.chunks.clear();
+    int s = 0;
+    while (s < B) {
+        Group g{};
+        g.s0 = s;
+        g.rows = 0;
+        g.u_max = 0;
+        while (s < B) {
+            long long rows = p.row_off[s + 1] - p.row_off[s];
+            if (g.rows > 0 && g.rows + rows > lat_cap) break;
+            g.rows += rows;
+            g.u_max = std::max(g.u_max, (int)U_len[s]);
+            ++s;
+        }
+        g.s1 = s;
+        g.tile0 = p.tile_off[g.s0];
+        g.tile1 = p.tile_off[g.s1];
+        p.groups.push_back(g);
+    }
+    // backward chunks: balanced tile ranges of at most chunk_rows rows, even tile counts
+    if (p.bf16) {
+        const long long cap_tiles = chunk_rows / TILE_ROWS;
+        for (int gi = 0; gi < (int)p.groups.size(); ++gi) {
+            const Group& g = p.groups[gi];
+            long long n = g.tile1 - g.tile0;
+            long long nch = (n + cap_tiles - 1) / cap_tiles;
+            long long per = (n + nch - 1) / nch;
+            per = std::min(cap_tiles, (per + 1) / 2 * 2);
+            for (long long t = g.tile0; t < g.tile1; t += per) {
+                Chunk c{gi, (int)t, (int)std::min<long long>(g.tile1, t + per)};
+                p.chunks.push_back(c);
+            }
+        }
+    } else {
+        for (int gi = 0; gi < (int)p.groups.size(); ++gi)
+            p.chunks.push_back(Chunk{gi, p.groups[gi].tile0, p.groups[gi].tile1});
+    }
+}
+
+}  // namespace rnnt

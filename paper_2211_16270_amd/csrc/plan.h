@@ -1,0 +1,66 @@
+// Host-side scheduler: packs the samples of a call into groups and backward chunks and lays
+// out the workspace.  Pure C++ (no HIP), so it is unit-testable without a GPU.
+//
+// The paper recovers parallelism lost by sample-wise processing by running several loop
+// iterations of Algorithm 1 at once, as many as a memory limit allows (Section 4.1.2, Eq. 11).
+// Here the same idea is a packing problem: samples are cut into 8x8 lattice tiles, the tiles of
+// all samples of a *group* are processed by one launch, and a group holds as many samples as
+// its per-node state (5 floats per lattice node) fits the workspace.  The backward pass walks a
+// group in *chunks* of tiles whose bf16 score-gradient buffers fit the rest of the workspace.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/rnnt_joint_loss.h"
+
+namespace rnnt {
+
+constexpr int TILE_T = 8;     // lattice tile: 8 frames x 8 label positions = 64 rows
+constexpr int TILE_U = 8;
+constexpr int TILE_ROWS = TILE_T * TILE_U;
+constexpr int GEMM_TILE = 128;   // row granularity of the backward GEMMs (two lattice tiles)
+constexpr size_t WS_ALIGN = 256;
+
+struct Group {
+    int s0, s1;          // samples [s0, s1)
+    int tile0, tile1;    // global tile range
+    long long rows;      // lattice nodes of the group
+    int u_max;           // largest U_len in the group
+};
+
+struct Chunk {
+    int group;
+    int tile0, tile1;    // global tile range, inside the group's range
+};
+
+struct Plan {
+    int B = 0;
+    bool bf16 = false;
+    std::vector<int> tile_off;          // [B+1] cumulative tile counts
+    std::vector<long long> row_off;     // [B+1] cumulative lattice nodes
+    std::vector<Group> groups;
+    std::vector<Chunk> chunks;
+    long long rows_total = 0, tiles_total = 0;
+    long long group_rows_cap = 0;       // lattice nodes a group may hold
+    long long chunk_rows = 0;           // rows (multiple of GEMM_TILE) of the chunk buffers
+    // workspace layout (byte offsets)
+    size_t off_T = 0, off_U = 0, off_tile_off = 0, off_row_off = 0, off_lnP = 0, off_shift = 0;
+    size_t off_wpack = 0;
+    size_t off_lse = 0, off_lpb = 0, off_lpy = 0, off_alpha = 0, off_beta = 0;
+    size_t off_dh = 0, off_dht = 0, off_zt = 0;
+    size_t lattice_bytes = 0, chunk_bytes = 0, total_bytes = 0;
+    size_t min_bytes = 0;               // smallest workable workspace
+};
+
+// Argument checks shared by every entry point (no pointers to data arrays here).
+rnnt_status check_desc(const rnnt_desc* d);
+rnnt_status check_lengths(const rnnt_desc* d, const int32_t* T_len, const int32_t* U_len);
+
+// Builds the plan for a workspace of `workspace_bytes` (0 = default trade-off).  If the size
+// is below the smallest workable one, plan.total_bytes = plan.min_bytes > workspace_bytes and
+// the group/chunk lists are those of the smallest plan.
+void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
+                size_t workspace_bytes, Plan& plan);
+
+}  // namespace rnnt

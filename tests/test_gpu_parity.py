@@ -1,0 +1,203 @@
+"""GPU parity: the C-ABI library against the float64 checker, element by element, on the same
+seeded inputs (run with -m gpu on an MI355X)."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import rnnt_oracle as O
+from paper_2211_16270_amd import binding as Bd
+from paper_2211_16270_amd import synth
+from tests.gpu_util import (GRADS, TOL, assert_padding_zero, assert_parity, rel_grad_err, rel_loss_err,
+                            run_gpu, run_oracle)
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ fp32 path
+def test_f32_smallest_workload_full_parity():
+    batch = synth.make_batch("C1")
+    _say("C1 fp32", batch.T_len, batch.U_len)
+    got, ref = run_gpu(batch), run_oracle(batch)
+    e, errs = assert_parity(got, ref, "f32", "C1")
+    _say("C1 errs", e, errs)
+    assert abs(float(got["db_out"].sum())) < 1e-3
+
+
+@pytest.mark.parametrize("T_len,U_len,blank", [
+    ([1, 1], [0, 0], 0),            # single-node lattices: loss = -ln p(blank)
+    ([9, 4], [0, 0], 2),            # no labels
+    ([1, 1], [5, 3], 0),            # single frame
+    ([11, 7], [6, 2], 3),           # ragged, blank in the middle of the vocabulary
+    ([13, 2], [1, 6], 0),
+])
+def test_f32_degenerate_and_ragged_lattices(T_len, U_len, blank):
+    wl = synth.custom_workload("edge", B=2, T_max=13, U_max=6, H=24, V=11, dtype="f32", index=101)
+    batch = synth.with_lengths(synth.make_batch(wl), T_len, U_len)
+    batch.labels[0, :1] = blank if U_len[0] > 0 else batch.labels[0, :1]   # a label equal to the blank
+    _say("edge f32", T_len, U_len, blank)
+    got, ref = run_gpu(batch, blank=blank), run_oracle(batch, blank=blank)
+    assert_parity(got, ref, "f32", f"edge {T_len} {U_len}")
+    assert_padding_zero(got, batch)
+
+
+def test_f32_moderate_shape_and_group_splitting():
+    wl = synth.custom_workload("mid32", B=5, T_max=33, U_max=12, H=48, V=70, dtype="f32", index=102,
+                               t_rule="uniform", t_lo=5, u_rule="uniform", u_lo=0)
+    batch = synth.make_batch(wl)
+    ref = run_oracle(batch)
+    got = run_gpu(batch)
+    assert_parity(got, ref, "f32", "mid32")
+    assert_padding_zero(got, batch)
+    # smallest possible workspace: one sample per group
+    desc = got["desc"]
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(desc, batch.T_len, batch.U_len, 1)
+    st, info, _ = Bd.rnnt_joint_loss_plan(desc, batch.T_len, batch.U_len, nmin)
+    assert st == 0 and info["n_groups"] >= 2
+    got2 = run_gpu(batch, budget_bytes=nmin)
+    assert_parity(got2, ref, "f32", "mid32 min workspace")
+
+
+# ------------------------------------------------------------------ bf16 MFMA path
+def _mid_bf16(index=110, **kw):
+    args = dict(B=4, T_max=37, U_max=19, H=128, V=256, dtype="bf16", index=index,
+                t_rule="uniform", t_lo=3, u_rule="uniform", u_lo=0)
+    args.update(kw)
+    return synth.custom_workload("mid16", **args)
+
+
+def test_bf16_mid_shape_full_parity_and_lattice():
+    batch = synth.make_batch(_mid_bf16())
+    _say("mid bf16", batch.T_len, batch.U_len)
+    got, ref = run_gpu(batch), run_oracle(batch)
+    e, errs = assert_parity(got, ref, "bf16", "mid16")
+    _say("mid16 errs", e, errs)
+    assert_padding_zero(got, batch)
+    # forward/backward variables against the checker (fp32 lattice, bf16 GEMM inputs)
+    b = 1
+    st, al, be = Bd.rnnt_debug_read_lattice(got["desc"], batch.T_len, batch.U_len, got["workspace"].buf, b)
+    assert st == 0
+    T, U = int(batch.T_len[b]), int(batch.U_len[b])
+    r = O.sample_loss_and_grads(batch.enc[b, :T], batch.pred[b, :U + 1], batch.W_out, batch.b_out,
+                                batch.labels[b, :U], 0, want_intermediates=True)
+    assert np.max(np.abs(al - r["alpha"])) < 2e-3 * max(1.0, np.abs(r["alpha"]).max())
+    assert np.max(np.abs(be - r["beta"])) < 2e-3 * max(1.0, np.abs(r["beta"]).max())
+
+
+@pytest.mark.parametrize("T_len,U_len,blank", [
+    ([1, 1, 8, 9], [0, 7, 0, 8], 0),
+    ([37, 16, 17, 1], [19, 15, 16, 19], 5),
+    ([8, 8, 8, 8], [7, 7, 7, 7], 255),
+])
+def test_bf16_edge_lattices(T_len, U_len, blank):
+    batch = synth.with_lengths(synth.make_batch(_mid_bf16(111, t_rule="full", u_rule="full")), T_len, U_len)
+    batch.labels[1, :1] = blank
+    _say("edge bf16", T_len, U_len, blank)
+    got, ref = run_gpu(batch, blank=blank), run_oracle(batch, blank=blank)
+    assert_parity(got, ref, "bf16", f"edge16 {T_len}")
+    assert_padding_zero(got, batch)
+
+
+def test_bf16_grouping_and_chunking_do_not_change_the_result():
+    batch = synth.make_batch(_mid_bf16(112, B=6))
+    ref = run_oracle(batch)
+    full = run_gpu(batch)
+    desc = full["desc"]
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(desc, batch.T_len, batch.U_len, 1)
+    st, info, _ = Bd.rnnt_joint_loss_plan(desc, batch.T_len, batch.U_len, nmin)
+    _say("min plan", info)
+    assert st == 0 and info["n_groups"] >= 2 and info["n_chunks"] > info["n_groups"]
+    small = run_gpu(batch, budget_bytes=nmin)
+    assert_parity(small, ref, "bf16", "min workspace")
+    assert_parity(full, ref, "bf16", "default workspace")
+    assert rel_loss_err(small["loss"], full["loss"]) < 1e-6     # the loss has no atomics in it
+    # permuting the batch permutes the per-sample outputs
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    pb = synth.Batch(batch.wl, batch.sample_ids[perm], batch.enc[perm], batch.pred[perm], batch.W_out,
+                     batch.b_out, batch.labels[perm], batch.T_len[perm], batch.U_len[perm])
+    p = run_gpu(pb)
+    assert rel_loss_err(p["loss"], full["loss"][perm]) < 1e-6
+    assert rel_grad_err(p["d_enc"], full["d_enc"][perm]) < 1e-5
+    assert rel_grad_err(p["dW_out"], full["dW_out"]) < 1e-4
+
+
+def test_bf16_accumulate_params_and_forward_only():
+    import torch
+    batch = synth.make_batch(_mid_bf16(113, B=2))
+    first = run_gpu(batch)
+    dW = torch.full((batch.wl.H, batch.wl.V), 0.5, dtype=torch.float32, device="cuda:0")
+    db = torch.full((batch.wl.V,), -0.25, dtype=torch.float32, device="cuda:0")
+    second = run_gpu(batch, accumulate_into=(dW, db))
+    assert rel_grad_err(second["dW_out"] - 0.5, first["dW_out"]) < 1e-4
+    assert rel_grad_err(second["db_out"] + 0.25, first["db_out"]) < 1e-4
+    dev = first["dev"]
+    loss = torch.zeros(batch.B, dtype=torch.float32, device="cuda:0")
+    st = Bd.rnnt_joint_loss_fwd(first["desc"], dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                dev["T_len"], dev["U_len"], loss, first["workspace"].buf)
+    torch.cuda.synchronize()
+    assert st == 0
+    np.testing.assert_array_equal(loss.cpu().numpy(), first["loss"])
+
+
+def _closed_form(T, U, V):
+    with open(os.path.join(GOLD, "uniform_scores_closed_form.txt")) as f:
+        for line in f:
+            if line.startswith("#"):
+                continue
+            t, u, v, val = line.split()
+            if (int(t), int(u), int(v)) == (T, U, V):
+                return float(val)
+    raise KeyError((T, U, V))
+
+
+def test_uniform_scores_closed_form_at_the_largest_lattice():
+    # W_out = 0: every emission has probability 1/V; checks the lattice kernel at T=1000, U=200
+    wl = synth.custom_workload("uni", B=2, T_max=1000, U_max=200, H=128, V=1024, dtype="bf16", index=114)
+    batch = synth.make_batch(wl, pad="zero")
+    batch.W_out[:] = 0.0
+    batch = synth.with_lengths(batch, [1000, 250], [200, 50], pad="zero")
+    got = run_gpu(batch)
+    ref = np.array([_closed_form(1000, 200, 1024), _closed_form(250, 50, 1024)])
+    _say("uniform", got["loss"], ref)
+    assert rel_loss_err(got["loss"].astype(np.float64), ref) < 2e-6
+    assert np.abs(got["d_enc"]).max() == 0.0          # dz = dh W^T = 0
+    # dh = gamma/V - posteriors sums to zero over V at every node, hence db sums to zero
+    assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-2
+    # db[blank] = sum gamma / V - T: every alignment emits T blanks and gamma sums to T+U
+    for_b = [(1000 + 200) / 1024 - 1000, (250 + 50) / 1024 - 250]
+    assert abs(float(got["db_out"][0]) - sum(for_b)) < 1e-2 * abs(sum(for_b))
+
+
+# ------------------------------------------------------------------ the benchmarked workload
+def test_bf16_bench_workload_subbatch_parity():
+    ids = [0, 17]
+    batch = synth.make_batch("C2", sample_ids=ids)
+    _say("C2 sub-batch", ids, batch.T_len, batch.U_len)
+    got, ref = run_gpu(batch), run_oracle(batch)
+    e, errs = assert_parity(got, ref, "bf16", "C2 sub")
+    _say("C2 sub errs", e, errs)
+    assert_padding_zero(got, batch)
+
+
+def test_bf16_bench_workload_full_batch_sampled_outputs():
+    # the configuration bench.py times: full C2 batch, default workspace; the checker recomputes
+    # two samples one by one (loss, d_enc, d_pred are per-sample outputs)
+    full = synth.make_batch("C2")
+    got = run_gpu(full)
+    assert np.all(np.isfinite(got["loss"]))
+    assert_padding_zero(got, full)
+    tol = TOL["bf16"]
+    for b in (3, 29):
+        T, U = int(full.T_len[b]), int(full.U_len[b])
+        r = O.sample_loss_and_grads(full.enc[b, :T], full.pred[b, :U + 1], full.W_out, full.b_out,
+                                    full.labels[b, :U], 0)
+        assert abs(got["loss"][b] - r["loss"]) <= tol["loss"] * abs(r["loss"])
+        assert rel_grad_err(got["d_enc"][b, :T], r["d_enc"]) <= tol["grad"]
+        assert rel_grad_err(got["d_pred"][b, :U + 1], r["d_pred"]) <= tol["grad"]
+    # softmax shift invariance: the bias gradient sums to zero (up to bf16 rounding of dh)
+    assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-2 * float(np.abs(got["db_out"]).sum())

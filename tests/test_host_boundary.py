@@ -1,0 +1,144 @@
+"""CPU-only tests of the C-ABI library: it loads, exports what the header declares, rejects bad
+arguments before touching a GPU, and its scheduler packs samples as promised."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2211_16270_amd import binding as Bd
+from paper_2211_16270_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "rnnt_joint_loss.h")
+GOLD = os.path.join(ROOT, "tests", "golden")
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(rnnt_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(Bd.EXPORTS), declared ^ set(Bd.EXPORTS)
+    L = Bd.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert L.rnnt_status_string(0) == b"ok"
+    for code in range(1, 8):
+        assert len(L.rnnt_status_string(code)) > 3
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(Bd.RnntDesc) == 32
+    assert ctypes.sizeof(Bd.RnntPlanInfo) == 8 * 3 + 4 * 2 + 8 * 2 + 8 * 3
+
+
+def _lens(name):
+    wl = synth.WORKLOADS[name]
+    T, U, _ = synth.draw_lengths_labels(wl)
+    dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
+    return wl, Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, 0, dt), T, U
+
+
+def test_argument_checks_happen_on_the_host():
+    wl, desc, T, U = _lens("C2")
+    L = Bd.lib()
+    dummy = ctypes.c_void_p(0x1000)
+
+    def call(d, Tl, Ul, ws=dummy, ws_bytes=1 << 30, enc=dummy):
+        Tl = np.ascontiguousarray(Tl, dtype=np.int32)
+        Ul = np.ascontiguousarray(Ul, dtype=np.int32)
+        return L.rnnt_joint_loss_fwd_bwd(ctypes.byref(d), enc, dummy, dummy, dummy, dummy, Bd._ip(Tl), Bd._ip(Ul),
+                                         dummy, dummy, dummy, dummy, dummy, ws, ws_bytes, None)
+
+    assert call(desc, T, U, enc=None) == 1                       # RNNT_ERR_NULL
+    bad = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.V, Bd.RNNT_BF16)
+    assert call(bad, T, U) == 2                                  # blank out of range
+    T2 = T.copy(); T2[3] = wl.T_max + 1
+    assert call(desc, T2, U) == 3
+    T2[3] = 0
+    assert call(desc, T2, U) == 3
+    U2 = U.copy(); U2[0] = -1
+    assert call(desc, T, U2) == 3
+    assert call(desc, T, U, ws=None) == 5
+    assert call(desc, T, U, ws=ctypes.c_void_p(0x1010)) == 5     # misaligned
+    assert call(desc, T, U, ws_bytes=4096) == 5                  # too small
+    odd = Bd.make_desc(wl.B, wl.T_max, wl.U_max, 500, wl.V, 0, Bd.RNNT_BF16)
+    assert call(odd, T, U) == 6                                  # H not supported by the MFMA path
+    assert Bd.rnnt_joint_loss_workspace_bytes(bad, T, U) == 0
+
+
+def test_label_validation():
+    wl, desc, T, U = _lens("C2")
+    _, _, lab = synth.draw_lengths_labels(wl)
+    assert Bd.rnnt_validate_labels_host(desc, lab, U) == 0
+    lab2 = lab.copy(); lab2[5, U[5] - 1] = wl.V
+    assert Bd.rnnt_validate_labels_host(desc, lab2, U) == 4
+    lab2[5, U[5] - 1] = 3; lab2[5, wl.U_max - 1] = -9 if U[5] < wl.U_max else 3   # beyond U_len: ignored
+    assert Bd.rnnt_validate_labels_host(desc, lab2, U) == 0
+
+
+def test_parallel_iterations_rule_matches_the_worked_values():
+    with open(os.path.join(GOLD, "eq11_parallel_iterations.txt")) as f:
+        rows = [l.split() for l in f if l.strip() and not l.startswith("#")]
+    for T, U, V, _, pi in rows:
+        assert Bd.rnnt_parallel_iterations(int(T), int(U), int(V)) == int(pi)
+    assert Bd.rnnt_parallel_iterations(0, 1, 1) == 0
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_default_plan_properties(name):
+    wl, desc, T, U = _lens(name)
+    n = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 0)
+    assert 0 < n <= (1 << 30) + (64 << 20)
+    st, info, groups = Bd.rnnt_joint_loss_plan(desc, T, U, n)
+    assert st == 0
+    rows = T.astype(np.int64) * (U.astype(np.int64) + 1)
+    assert info["rows_total"] == rows.sum()
+    assert info["rows_padded"] == wl.B * wl.T_max * (wl.U_max + 1)
+    tiles = ((T + 7) // 8).astype(np.int64) * ((U + 8) // 8)
+    assert info["tiles_total"] == tiles.sum()
+    assert info["workspace_bytes"] <= n
+    # every sample in exactly one group, groups are consecutive, each fits the lattice capacity
+    assert groups.min() == 0 and groups.max() == info["n_groups"] - 1
+    assert np.all(np.diff(groups) >= 0)
+    for g in range(info["n_groups"]):
+        assert rows[groups == g].sum() <= info["group_rows_cap"]
+    assert info["lattice_bytes"] >= 20 * info["group_rows_cap"]
+    if wl.dtype == "bf16":
+        assert info["chunk_rows"] % 128 == 0 and info["chunk_rows"] >= 128
+        assert info["chunk_bytes"] >= info["chunk_rows"] * (4 * wl.V + 2 * wl.H)
+
+
+def test_workspace_does_not_grow_with_batch_size_once_capped():
+    # memory "almost independent of batch size" (Section 5.2): doubling B leaves the default plan's size
+    wl = synth.WORKLOADS["C4"]
+    T, U, _ = synth.draw_lengths_labels(wl)
+    d1 = Bd.make_desc(512, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16)
+    d2 = Bd.make_desc(1024, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16)
+    n1 = Bd.rnnt_joint_loss_workspace_bytes(d1, T[:512], U[:512], 0)
+    n2 = Bd.rnnt_joint_loss_workspace_bytes(d2, T, U, 0)
+    assert abs(n2 - n1) <= 64 * 1024      # only the per-sample tables grow
+
+
+def test_budgets_shrink_the_plan_and_a_too_small_budget_is_reported():
+    wl, desc, T, U = _lens("C4")
+    big = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 0)
+    small_budget = 96 << 20
+    n = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, small_budget)
+    assert 0 < n <= small_budget < big
+    st, info, groups = Bd.rnnt_joint_loss_plan(desc, T, U, n)
+    st0, info0, _ = Bd.rnnt_joint_loss_plan(desc, T, U, big)
+    assert st == 0 and st0 == 0
+    assert info["n_groups"] > info0["n_groups"] and info["n_chunks"] > info0["n_chunks"]
+    rows = T.astype(np.int64) * (U.astype(np.int64) + 1)
+    for g in range(info["n_groups"]):
+        assert rows[groups == g].sum() <= info["group_rows_cap"]
+    # the largest sample still fits: it is processed alone, the backward walks it in row chunks
+    assert info["group_rows_cap"] >= rows.max()
+    tiny = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 1 << 20)
+    assert tiny > (1 << 20)
+    st, _, _ = Bd.rnnt_joint_loss_plan(desc, T, U, 1 << 20)
+    assert st == 5
+    st, info_min, _ = Bd.rnnt_joint_loss_plan(desc, T, U, tiny)
+    assert st == 0 and info_min["chunk_rows"] == 128 and info_min["group_rows_cap"] == rows.max()
