@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused joint + RNN-T loss + gradient call on one MI355X.
+
+A step is one call of rnnt_joint_loss_fwd_bwd over one synthetic batch (the whole path:
+joint tiles, score GEMM, softmax statistics, lattice, score gradients, backward GEMMs), with
+all inputs already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2|C3|C4|C5|C1] [--no-cpu-baseline]
+
+`value` is samples/s over K timed steps (whole job, one GPU).  `roofline` describes the kernel
+that takes the most time: its algorithmic flops per launch divided by its average launch
+duration, measured with HIP events recorded on the call's stream in a second pass over the
+same K steps (the events are kept out of the pass that yields `value`).  `cpu_baseline` is
+the float64 checker timed on the host cores on a few samples of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_FLOPS = 2.5e15     # MI355X dense bf16 MFMA
+PEAK_F32_FLOPS = 157.3e12    # MI355X fp32 vector
+CPU_SAMPLE = {"C1": 2, "C2": 6, "C3": 1, "C4": 1, "C5": 2}   # samples the checker is timed on
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C2")
+    ap.add_argument("--budget-mib", type=int, default=0, help="workspace budget (0 = library default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
+              "Sharding over GPUs is described in DESIGN.md, not implemented.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2211_16270_amd import binding as Bd
+    from paper_2211_16270_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.config]
+    steps = args.steps if args.steps is not None else {"C1": 100, "C2": 100, "C3": 20, "C4": 10, "C5": 10}[wl.name]
+    t0 = time.time()
+    batch = synth.make_batch(wl, pad="zero")
+    gen_s = time.time() - t0
+    dev = Bd.to_device(batch)
+    dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
+    desc = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, dt)
+    nbytes = Bd.rnnt_joint_loss_workspace_bytes(desc, dev["T_len"], dev["U_len"], args.budget_mib << 20)
+    st, info, _ = Bd.rnnt_joint_loss_plan(desc, dev["T_len"], dev["U_len"], nbytes)
+    assert st == 0, st
+    torch.cuda.reset_peak_memory_stats()
+    ws = Bd.Workspace(nbytes)
+    loss = torch.empty(wl.B, dtype=torch.float32, device="cuda")
+    d_enc = torch.empty(wl.B, wl.T_max, wl.H, dtype=torch.float32, device="cuda")
+    d_pred = torch.empty(wl.B, wl.U_max + 1, wl.H, dtype=torch.float32, device="cuda")
+    dW = torch.empty(wl.H, wl.V, dtype=torch.float32, device="cuda")
+    db = torch.empty(wl.V, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        s = Bd.rnnt_joint_loss_fwd_bwd(desc, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                       dev["T_len"], dev["U_len"], loss, d_enc, d_pred, dW, db, ws.buf, stream)
+        if s != 0:
+            raise Bd.RnntError(s, "rnnt_joint_loss_fwd_bwd")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / steps * 1e3
+    value = wl.B / (elapsed / steps)
+    assert bool(torch.isfinite(loss).all()), "non-finite loss"
+    peak_bytes = torch.cuda.max_memory_allocated()
+
+    # second pass: the same K steps with every launch bracketed by HIP events on the same stream
+    Bd.rnnt_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed_prof = time.perf_counter() - t0
+    prof = Bd.rnnt_profile_read()
+    Bd.rnnt_profile_enable(False)
+
+    R = int(info["rows_total"])
+    HV = wl.H * wl.V
+    # algorithmic flops per launch of each MFMA kernel: 2*H*V per lattice node it covers
+    alg_flops_per_step = {"joint_scores_fwd": 2.0 * R * HV, "joint_scores_bwd": 2.0 * R * HV,
+                          "gemm_dz": 2.0 * R * HV, "gemm_dw": 2.0 * R * HV,
+                          "fwd_f32": 2.0 * R * HV, "bwd_f32": 6.0 * R * HV}
+    kernels = {}
+    for name, (cnt, ms) in prof.items():
+        if cnt:
+            kernels[name] = {"launches_per_step": cnt / steps, "ms_per_step": ms / steps,
+                             "avg_launch_us": ms / cnt * 1e3}
+    gpu_ms = sum(k["ms_per_step"] for k in kernels.values())
+    cands = [n for n in kernels if n in alg_flops_per_step]
+    dom = max(cands, key=lambda n: kernels[n]["ms_per_step"])
+    launches = kernels[dom]["launches_per_step"]
+    avg_s = kernels[dom]["avg_launch_us"] * 1e-6
+    flops_per_launch = alg_flops_per_step[dom] / launches
+    peak = PEAK_BF16_FLOPS if wl.dtype == "bf16" else PEAK_F32_FLOPS
+    achieved = flops_per_launch / avg_s
+    roofline = {"bound": "mfma" if wl.dtype == "bf16" else "alu", "kernel": dom,
+                "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
+                "traffic": None, "alg_flops_per_launch": flops_per_launch,
+                "avg_launch_us": kernels[dom]["avg_launch_us"]}
+    step_s = elapsed / steps
+    util_alg = 6.0 * R * HV / step_s / peak
+    util_exec = 8.0 * R * HV / step_s / peak
+    lat = kernels.get("lattice")
+    lattice_gbs = (24.0 * R / (lat["ms_per_step"] * 1e-3) / 1e9) if lat else None
+
+    out = {
+        "metric": "samples/s fused joint+RNN-T loss+grads",
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B} T_max={wl.T_max} U_max={wl.U_max} H={wl.H} V={wl.V} "
+                               f"{wl.dtype}, ragged lengths, {R} lattice nodes ({100.0 * R / info['rows_padded']:.1f}% of padded)",
+                   "groups": info["n_groups"], "chunks": info["n_chunks"],
+                   "workspace_bytes": int(nbytes)},
+        "mfma_util_alg": util_alg, "mfma_util_exec": util_exec,
+        "peak_hbm_gb": peak_bytes / 1e9,
+        "lattice_gb_per_s": lattice_gbs,
+        "ms_per_step_with_events": elapsed_prof / steps * 1e3,
+        "gpu_kernel_ms_per_step": gpu_ms,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import rnnt_oracle as O
+        n = min(CPU_SAMPLE.get(wl.name, 1), wl.B)
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        f64 = lambda x: np.asarray(x[:n], dtype=np.float64)
+        t0 = time.perf_counter()
+        ref = O.rnnt_joint_loss(f64(batch.enc), f64(batch.pred), batch.W_out.astype(np.float64),
+                                batch.b_out.astype(np.float64), batch.labels[:n], batch.T_len[:n], batch.U_len[:n],
+                                wl.blank)
+        cpu_s = time.perf_counter() - t0
+        rel = float(np.max(np.abs(loss[:n].cpu().numpy() - ref["loss"]) / np.abs(ref["loss"])))
+        out["cpu_baseline"] = {"value": n / cpu_s, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"first {n} of {wl.B} samples of {wl.name}, float64 numpy, {cpu_s:.1f} s",
+                               "gpu_loss_rel_err_on_sample": rel}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -165,6 +165,23 @@ rnnt_status rnnt_debug_read_lattice(const rnnt_desc* desc, const int32_t* T_len_
                                     size_t workspace_bytes, int32_t b,
                                     float* alpha_host, float* beta_host);
 
+/*
+ * Per-kernel timing for the benchmark (not a paper operation; measurement support for the
+ * throughput figures reported against Table 1's cost terms).  While enabled, every launch made
+ * by the two entry points above is bracketed by HIP events recorded on the caller's stream
+ * (process-wide state, not thread-safe; the only state the library keeps).
+ *   rnnt_profile_enable(1/0)    start (and clear) / stop recording
+ *   rnnt_profile_kernel_count() number of kernel classes n
+ *   rnnt_profile_kernel_name(i) name of class i, "" if out of range
+ *   rnnt_profile_read(n, launches, total_ms)  waits for the recorded events, writes per class the
+ *                               number of launches and the summed event time in ms (host arrays of
+ *                               at least n entries), then clears the records
+ */
+rnnt_status rnnt_profile_enable(int32_t enable);
+int32_t rnnt_profile_kernel_count(void);
+const char* rnnt_profile_kernel_name(int32_t cls);
+rnnt_status rnnt_profile_read(int32_t n, int64_t* launches_host, double* total_ms_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,8 @@ STATUS_NAMES = ["RNNT_OK", "RNNT_ERR_NULL", "RNNT_ERR_SHAPE", "RNNT_ERR_LENGTH",
                 "RNNT_ERR_WORKSPACE", "RNNT_ERR_UNSUPPORTED", "RNNT_ERR_HIP"]
 EXPORTS = ["rnnt_status_string", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_loss_plan",
            "rnnt_parallel_iterations", "rnnt_validate_labels_host", "rnnt_joint_loss_fwd_bwd",
-           "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice"]
+           "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice", "rnnt_profile_enable",
+           "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read"]
 
 
 class RnntDesc(ctypes.Structure):
@@ -75,6 +76,14 @@ def lib() -> ctypes.CDLL:
     L.rnnt_joint_loss_fwd.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
     L.rnnt_debug_read_lattice.restype = ctypes.c_int
     L.rnnt_debug_read_lattice.argtypes = [dp, i32p, i32p, vp, ctypes.c_size_t, ctypes.c_int32, vp, vp]
+    L.rnnt_profile_enable.restype = ctypes.c_int
+    L.rnnt_profile_enable.argtypes = [ctypes.c_int32]
+    L.rnnt_profile_kernel_count.restype = ctypes.c_int32
+    L.rnnt_profile_kernel_count.argtypes = []
+    L.rnnt_profile_kernel_name.restype = ctypes.c_char_p
+    L.rnnt_profile_kernel_name.argtypes = [ctypes.c_int32]
+    L.rnnt_profile_read.restype = ctypes.c_int
+    L.rnnt_profile_read.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
     _lib = L
     return L
 
@@ -162,6 +171,29 @@ def rnnt_debug_read_lattice(desc: RnntDesc, T_len, U_len, workspace, b: int):
                                        al.ctypes.data, be.ctypes.data)
     shape = (int(T[b]), int(U[b]) + 1)
     return int(st), al.reshape(shape), be.reshape(shape)
+
+
+def rnnt_profile_enable(enable: bool) -> int:
+    return int(lib().rnnt_profile_enable(1 if enable else 0))
+
+
+def rnnt_profile_kernel_count() -> int:
+    return int(lib().rnnt_profile_kernel_count())
+
+
+def rnnt_profile_kernel_name(cls: int) -> str:
+    return lib().rnnt_profile_kernel_name(int(cls)).decode()
+
+
+def rnnt_profile_read():
+    """{kernel name: (launches, total_ms)} of everything recorded since rnnt_profile_enable(True)."""
+    n = rnnt_profile_kernel_count()
+    cnt = (ctypes.c_int64 * n)()
+    ms = (ctypes.c_double * n)()
+    st = lib().rnnt_profile_read(n, cnt, ms)
+    if st != 0:
+        raise RnntError(st, "rnnt_profile_read")
+    return {rnnt_profile_kernel_name(i): (int(cnt[i]), float(ms[i])) for i in range(n)}
 
 
 # --------------------------------------------------------------------------------------------

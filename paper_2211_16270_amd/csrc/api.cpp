@@ -86,6 +86,44 @@ extern "C" rnnt_status rnnt_validate_labels_host(const rnnt_desc* desc, const in
 
 namespace {
 
+// Optional per-kernel timing with HIP events on the caller's stream (off by default).
+enum KernelClass { KC_FILL = 0, KC_PACK_W, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
+                   KC_DB, KC_FWD_F32, KC_BWD_F32, KC_COUNT };
+const char* const kKernelNames[KC_COUNT] = {"fill_zero", "pack_w", "joint_scores_fwd", "lattice",
+                                            "joint_scores_bwd", "gemm_dz", "gemm_dw", "db_rowsum",
+                                            "fwd_f32", "bwd_f32"};
+struct Profiler {
+    bool enabled = false;
+    struct Rec { int cls; hipEvent_t e0, e1; };
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+    void clear() {
+        for (auto& r : recs) { pool.push_back(r.e0); pool.push_back(r.e1); }
+        recs.clear();
+    }
+};
+Profiler g_prof;
+
+template <typename F>
+hipError_t timed(int cls, hipStream_t stream, F&& launch) {
+    if (!g_prof.enabled) return launch();
+    hipEvent_t e0 = g_prof.get(), e1 = g_prof.get();
+    if (!e0 || !e1) return hipErrorOutOfMemory;
+    hipError_t e = hipEventRecord(e0, stream);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(e1, stream);
+    g_prof.recs.push_back({cls, e0, e1});
+    return e;
+}
+
 #define RNNT_HIP(expr)                           \
     do {                                         \
         if ((expr) != hipSuccess) {              \
@@ -155,14 +193,17 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     GradOut go{d_enc, d_pred, dW_out, db_out};
     const bool bf16 = (desc->dtype == RNNT_BF16);
     if (grads) {
-        RNNT_HIP(launch_fill_zero(d_enc, B * desc->T_max * desc->H, stream));
-        RNNT_HIP(launch_fill_zero(d_pred, B * (desc->U_max + 1) * desc->H, stream));
+        RNNT_HIP(timed(KC_FILL, stream, [&] { return launch_fill_zero(d_enc, B * desc->T_max * desc->H, stream); }));
+        RNNT_HIP(timed(KC_FILL, stream,
+                       [&] { return launch_fill_zero(d_pred, B * (desc->U_max + 1) * desc->H, stream); }));
         if (!desc->accumulate_params) {
-            RNNT_HIP(launch_fill_zero(dW_out, (size_t)desc->H * desc->V, stream));
-            RNNT_HIP(launch_fill_zero(db_out, (size_t)desc->V, stream));
+            RNNT_HIP(timed(KC_FILL, stream,
+                           [&] { return launch_fill_zero(dW_out, (size_t)desc->H * desc->V, stream); }));
+            RNNT_HIP(timed(KC_FILL, stream, [&] { return launch_fill_zero(db_out, (size_t)desc->V, stream); }));
         }
     }
-    if (bf16) RNNT_HIP(launch_pack_w(W_out, wv.wpack, desc->H, desc->V, stream));
+    if (bf16)
+        RNNT_HIP(timed(KC_PACK_W, stream, [&] { return launch_pack_w(W_out, wv.wpack, desc->H, desc->V, stream); }));
 
     size_t ci = 0;
     for (size_t gi = 0; gi < plan.groups.size(); ++gi) {
@@ -171,24 +212,37 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         ls.row_base = plan.row_off[g.s0];
         // Eq. 4, Eq. 6, f^W_1
         if (bf16)
-            RNNT_HIP(launch_fwd_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, g.tile0, g.tile1, stream));
+            RNNT_HIP(timed(KC_FWD_SCORES, stream, [&] {
+                return launch_fwd_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, g.tile0, g.tile1, stream);
+            }));
         else
-            RNNT_HIP(launch_fwd_f32(pr, wv.st, ls, g.s0, g.s1, g.rows, stream));
+            RNNT_HIP(timed(KC_FWD_F32, stream,
+                           [&] { return launch_fwd_f32(pr, wv.st, ls, g.s0, g.s1, g.rows, stream); }));
         // f^W_2, f^W_3
-        RNNT_HIP(launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, loss, stream));
+        RNNT_HIP(timed(KC_LATTICE, stream,
+                       [&] { return launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, loss, stream); }));
         // f^W_4 and Algorithm 1 lines 8, 10, 11
         for (; ci < plan.chunks.size() && plan.chunks[ci].group == (int)gi; ++ci) {
             if (!grads) continue;
             const Chunk& c = plan.chunks[ci];
             if (bf16) {
                 const long long rows = (long long)(c.tile1 - c.tile0) * TILE_ROWS;
-                RNNT_HIP(launch_bwd_scores_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
-                                                wv.dHt, wv.Zt, plan.chunk_rows, stream));
-                RNNT_HIP(launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred, stream));
-                RNNT_HIP(launch_gemm_dw_bf16(desc->H, desc->V, rows, wv.Zt, wv.dHt, plan.chunk_rows, dW_out,
-                                             db_out, stream));
+                RNNT_HIP(timed(KC_BWD_SCORES, stream, [&] {
+                    return launch_bwd_scores_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
+                                                  wv.dHt, wv.Zt, plan.chunk_rows, stream);
+                }));
+                RNNT_HIP(timed(KC_GEMM_DZ, stream, [&] {
+                    return launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred, stream);
+                }));
+                RNNT_HIP(timed(KC_GEMM_DW, stream, [&] {
+                    return launch_gemm_dw_bf16(desc->H, desc->V, rows, wv.Zt, wv.dHt, plan.chunk_rows, dW_out, stream);
+                }));
+                RNNT_HIP(timed(KC_DB, stream, [&] {
+                    return launch_db_bf16(desc->V, rows, wv.dHt, plan.chunk_rows, db_out, stream);
+                }));
             } else {
-                RNNT_HIP(launch_bwd_f32(pr, wv.st, ls, go, g.s0, g.s1, g.rows, stream));
+                RNNT_HIP(timed(KC_BWD_F32, stream,
+                               [&] { return launch_bwd_f32(pr, wv.st, ls, go, g.s0, g.s1, g.rows, stream); }));
             }
         }
     }
@@ -242,5 +296,32 @@ extern "C" rnnt_status rnnt_debug_read_lattice(const rnnt_desc* desc, const int3
             alpha_host[i] -= shift * (float)(t + u);
             beta_host[i] -= shift * (float)((T - t) + (U - u));
         }
+    return RNNT_OK;
+}
+
+extern "C" rnnt_status rnnt_profile_enable(int32_t enable) {
+    g_prof.clear();
+    g_prof.enabled = (enable != 0);
+    return RNNT_OK;
+}
+
+extern "C" int32_t rnnt_profile_kernel_count(void) { return KC_COUNT; }
+
+extern "C" const char* rnnt_profile_kernel_name(int32_t cls) {
+    return (cls >= 0 && cls < KC_COUNT) ? kKernelNames[cls] : "";
+}
+
+extern "C" rnnt_status rnnt_profile_read(int32_t n, int64_t* launches, double* total_ms) {
+    if (!launches || !total_ms) return RNNT_ERR_NULL;
+    if (n < KC_COUNT) return RNNT_ERR_SHAPE;
+    for (int i = 0; i < n; ++i) { launches[i] = 0; total_ms[i] = 0.0; }
+    for (auto& r : g_prof.recs) {
+        RNNT_HIP(hipEventSynchronize(r.e1));
+        float ms = 0.0f;
+        RNNT_HIP(hipEventElapsedTime(&ms, r.e0, r.e1));
+        launches[r.cls] += 1;
+        total_ms[r.cls] += ms;
+    }
+    g_prof.clear();
     return RNNT_OK;
 }

@@ -70,8 +70,11 @@ hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const Sa
 hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0,
                                int tile1, const void* dH, float* d_enc, float* d_pred,
                                hipStream_t stream);
-// dW += Zt dHt^T (split over the rows), db += row sums of dHt
+// dW += Zt dHt^T (split over the rows)
 hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, const void* dHt,
-                               long long ld, float* dW, float* db, hipStream_t stream);
+                               long long ld, float* dW, hipStream_t stream);
+// db += row sums of dHt
+hipError_t launch_db_bf16(int V, long long rows, const void* dHt, long long ld, float* db,
+                          hipStream_t stream);
 
 }  // namespace rnnt

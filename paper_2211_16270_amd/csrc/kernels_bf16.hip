@@ -65,7 +65,6 @@ struct JointArgs {
     long long ld;
 };
 
-__device__ __forceinline__ size_t jt_smem_bytes(int H) { return 0; }
 
 template <int MODE>
 __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
@@ -523,8 +522,14 @@ __global__ __launch_bounds__(256) void k_db(const bf16_t* __restrict__ dHt, long
     if (lane == 0) atomicAdd(&db[v], acc);
 }
 
+hipError_t launch_db_bf16(int V, long long rows, const void* dHt, long long ld, float* db, hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    k_db<<<dim3((unsigned)((V + 3) / 4)), dim3(256), 0, stream>>>((const bf16_t*)dHt, ld, rows, db, V);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, const void* dHt, long long ld,
-                               float* dW, float* db, hipStream_t stream) {
+                               float* dW, hipStream_t stream) {
     if (rows <= 0) return hipSuccess;
     GemmArgs g{};
     g.A = (const bf16_t*)Zt;
@@ -545,9 +550,6 @@ hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, con
     splits = (rows + per - 1) / per;
     g.k_per_split = per;
     k_gemm_nt<1><<<dim3((unsigned)(H / GT), (unsigned)(V / GT), (unsigned)splits), dim3(256), 0, stream>>>(g);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    k_db<<<dim3((unsigned)((V + 3) / 4)), dim3(256), 0, stream>>>((const bf16_t*)dHt, ld, rows, db, V);
     return hipGetLastError();
 }
 

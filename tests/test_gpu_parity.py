@@ -167,7 +167,7 @@ def test_uniform_scores_closed_form_at_the_largest_lattice():
     assert rel_loss_err(got["loss"].astype(np.float64), ref) < 2e-6
     assert np.abs(got["d_enc"]).max() == 0.0          # dz = dh W^T = 0
     # dh = gamma/V - posteriors sums to zero over V at every node, hence db sums to zero
-    assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-2
+    assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-4 * float(np.abs(got["db_out"]).sum())
     # db[blank] = sum gamma / V - T: every alignment emits T blanks and gamma sums to T+U
     for_b = [(1000 + 200) / 1024 - 1000, (250 + 50) / 1024 - 250]
     assert abs(float(got["db_out"][0]) - sum(for_b)) < 1e-2 * abs(sum(for_b))
