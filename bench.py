@@ -38,6 +38,7 @@ def main():
     ap.add_argument("--config", default="C2")
     ap.add_argument("--budget-mib", type=int, default=0, help="workspace budget (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=0, help="use only the first N samples (profiling aid)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
@@ -53,7 +54,13 @@ def main():
     wl = synth.WORKLOADS[args.config]
     steps = args.steps if args.steps is not None else {"C1": 100, "C2": 100, "C3": 20, "C4": 10, "C5": 10}[wl.name]
     t0 = time.time()
-    batch = synth.make_batch(wl, pad="zero")
+    if args.batch:
+        import dataclasses
+        batch = synth.make_batch(wl, sample_ids=list(range(args.batch)), pad="zero")
+        wl = dataclasses.replace(wl, B=args.batch)
+        batch.wl = wl
+    else:
+        batch = synth.make_batch(wl, pad="zero")
     gen_s = time.time() - t0
     dev = Bd.to_device(batch)
     dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
@@ -103,7 +110,7 @@ def main():
     HV = wl.H * wl.V
     # algorithmic flops per launch of each MFMA kernel: 2*H*V per lattice node it covers
     alg_flops_per_step = {"joint_scores_fwd": 2.0 * R * HV, "joint_scores_bwd": 2.0 * R * HV,
-                          "gemm_dz": 2.0 * R * HV, "gemm_dw": 2.0 * R * HV,
+                          "gemm_dz": 2.0 * R * HV, "gemm_dw_db": 2.0 * R * HV,
                           "fwd_f32": 2.0 * R * HV, "bwd_f32": 6.0 * R * HV}
     kernels = {}
     for name, (cnt, ms) in prof.items():

@@ -88,9 +88,9 @@ namespace {
 
 // Optional per-kernel timing with HIP events on the caller's stream (off by default).
 enum KernelClass { KC_FILL = 0, KC_PACK_W, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
-                   KC_DB, KC_FWD_F32, KC_BWD_F32, KC_COUNT };
+                   KC_FWD_F32, KC_BWD_F32, KC_COUNT };
 const char* const kKernelNames[KC_COUNT] = {"fill_zero", "pack_w", "joint_scores_fwd", "lattice",
-                                            "joint_scores_bwd", "gemm_dz", "gemm_dw", "db_rowsum",
+                                            "joint_scores_bwd", "gemm_dz", "gemm_dw_db",
                                             "fwd_f32", "bwd_f32"};
 struct Profiler {
     bool enabled = false;
@@ -148,6 +148,7 @@ WsView view_workspace(const Plan& p, void* ws) {
     v.st.U = (const int*)(w + p.off_U);
     v.st.tile_off = (const int*)(w + p.off_tile_off);
     v.st.row_off = (const long long*)(w + p.off_row_off);
+    v.st.tile_sample = (const int*)(w + p.off_tile_sample);
     v.ls.lse = (float*)(w + p.off_lse);
     v.ls.lpb = (float*)(w + p.off_lpb);
     v.ls.lpy = (float*)(w + p.off_lpy);
@@ -188,6 +189,10 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     RNNT_HIP(hipMemcpyAsync(w + plan.off_U, U_len, B * 4, hipMemcpyHostToDevice, stream));
     RNNT_HIP(hipMemcpyAsync(w + plan.off_tile_off, plan.tile_off.data(), (B + 1) * 4, hipMemcpyHostToDevice, stream));
     RNNT_HIP(hipMemcpyAsync(w + plan.off_row_off, plan.row_off.data(), (B + 1) * 8, hipMemcpyHostToDevice, stream));
+
+    RNNT_HIP(timed(KC_FILL, stream, [&] {
+        return launch_fill_tile_sample(wv.st.tile_off, (int*)(w + plan.off_tile_sample), desc->B, stream);
+    }));
 
     Problem pr{desc->B, desc->T_max, desc->U_max, desc->H, desc->V, desc->blank, enc, pred, W_out, b_out, labels};
     GradOut go{d_enc, d_pred, dW_out, db_out};
@@ -235,10 +240,8 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                     return launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred, stream);
                 }));
                 RNNT_HIP(timed(KC_GEMM_DW, stream, [&] {
-                    return launch_gemm_dw_bf16(desc->H, desc->V, rows, wv.Zt, wv.dHt, plan.chunk_rows, dW_out, stream);
-                }));
-                RNNT_HIP(timed(KC_DB, stream, [&] {
-                    return launch_db_bf16(desc->V, rows, wv.dHt, plan.chunk_rows, db_out, stream);
+                    return launch_gemm_dw_bf16(desc->H, desc->V, rows, wv.Zt, wv.dHt, plan.chunk_rows, dW_out,
+                                               db_out, stream);
                 }));
             } else {
                 RNNT_HIP(timed(KC_BWD_F32, stream,

@@ -33,7 +33,9 @@ struct TilePos {
 
 __device__ __forceinline__ TilePos locate_tile(const SampleTable& st, int s0, int s1, int tile) {
     TilePos p;
-    p.s = find_segment<int>(st.tile_off, s0, s1, tile);
+    (void)s0;
+    (void)s1;
+    p.s = st.tile_sample[tile];
     p.T = st.T[p.s];
     p.U = st.U[p.s];
     const int tiles_u = (p.U + 8) >> 3;           // ceil((U+1)/8)

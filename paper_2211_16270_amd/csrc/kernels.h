@@ -12,6 +12,7 @@ struct SampleTable {
     const int* T;              // [B] T_len
     const int* U;              // [B] U_len
     const int* tile_off;       // [B+1] cumulative 8x8 lattice-tile counts
+    const int* tile_sample;    // [tiles] sample that owns each tile (filled by launch_fill_tile_sample)
     const long long* row_off;  // [B+1] cumulative lattice-node counts
 };
 
@@ -44,6 +45,8 @@ struct GradOut {
 };
 
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream);
+// tile_sample[tile] = s for every tile of every sample (one lookup instead of a search per workgroup)
+hipError_t launch_fill_tile_sample(const int* tile_off, int* tile_sample, int B, hipStream_t stream);
 
 // ---- fp32 path (plain FMA kernels, any H, V) ------------------------------------------------
 hipError_t launch_fwd_f32(const Problem& pr, const SampleTable& st, const LatticeState& ls,
@@ -70,11 +73,8 @@ hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const Sa
 hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0,
                                int tile1, const void* dH, float* d_enc, float* d_pred,
                                hipStream_t stream);
-// dW += Zt dHt^T (split over the rows)
+// dW += Zt dHt^T (split over the rows) and db += row sums of dHt
 hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, const void* dHt,
-                               long long ld, float* dW, hipStream_t stream);
-// db += row sums of dHt
-hipError_t launch_db_bf16(int V, long long rows, const void* dHt, long long ld, float* db,
-                          hipStream_t stream);
+                               long long ld, float* dW, float* db, hipStream_t stream);
 
 }  // namespace rnnt

@@ -45,11 +45,12 @@ hipError_t launch_pack_w(const void* W, void* Wpack, int H, int V, hipStream_t s
 
 // ------------------------------------------------------------------------------------------------
 // Joint tile + score GEMM.  MODE 0: softmax statistics (forward).  MODE 1: score gradients (backward).
-// 256 threads = 4 waves; per step of 128 vocabulary entries wave w owns entries [32w, 32w+32) for
-// all 64 rows (two 32x32 accumulator tiles).
+// 256 threads = 4 waves; per step of 256 vocabulary entries wave w owns entries [64w, 64w+64) for
+// all 64 rows (2 x 2 accumulator tiles of 32x32).
 // ------------------------------------------------------------------------------------------------
 constexpr int JT_ROWS = 64;
-constexpr int JT_VSTEP = 128;
+constexpr int JT_VSTEP = 256;
+constexpr int JT_PF = 4;        // A-fragment prefetch distance in k16-steps (H/16 must be a multiple)
 constexpr int STG_PITCH = 40;   // bf16 elements per row of a wave's 32x32 transposition buffer
 
 struct JointArgs {
@@ -93,25 +94,37 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
     {
         const bf16_t* enc = reinterpret_cast<const bf16_t*>(a.pr.enc) + (size_t)b * a.pr.T_max * H;
         const bf16_t* prd = reinterpret_cast<const bf16_t*>(a.pr.pred) + (size_t)b * (a.pr.U_max + 1) * H;
-        const int items = JT_ROWS * (H >> 3);
-        for (int it = tid; it < items; it += 256) {
-            const int r = it & 63, c = it >> 6;
-            const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
-            bf16x8 z;
-            if (t < tp.T && u <= tp.U) {
-                const bf16x8 e = *reinterpret_cast<const bf16x8*>(enc + (size_t)t * H + c * 8);
-                const bf16x8 q = *reinterpret_cast<const bf16x8*>(prd + (size_t)u * H + c * 8);
+        // thread -> row r = tid % 64 and the 8-element column chunks c = tid/64 + 4*i; the loads of
+        // 8 chunks are issued together so that only H/256 memory latencies are exposed
+        const int r = tid & 63;
+        const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
+        const bool valid = (t < tp.T && u <= tp.U);
+        const bf16_t* er = enc + (size_t)(valid ? t : 0) * H;
+        const bf16_t* qr = prd + (size_t)(valid ? u : 0) * H;
+        const int nch = H >> 5;                              // chunks per thread
+        for (int i0 = 0; i0 < nch; i0 += 8) {
+            bf16x8 e[8], q[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) z[j] = (bf16_t)fast_tanh((float)e[j] + (float)q[j]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) z[j] = (bf16_t)0.0f;
+            for (int i = 0; i < 8; ++i) {
+                const int c = (tid >> 6) + 4 * ((i0 + i < nch) ? i0 + i : 0);
+                e[i] = *reinterpret_cast<const bf16x8*>(er + c * 8);
+                q[i] = *reinterpret_cast<const bf16x8*>(qr + c * 8);
             }
-            *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = z;
-            if (MODE == 1) {
-                bf16_t* zt = a.Zt + (size_t)(c * 8) * a.ld + chunk_row0 + r;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) zt[(size_t)j * a.ld] = z[j];
+            for (int i = 0; i < 8; ++i) {
+                if (i0 + i < nch) {
+                    const int c = (tid >> 6) + 4 * (i0 + i);
+                    bf16x8 z;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        z[j] = valid ? (bf16_t)fast_tanh((float)e[i][j] + (float)q[i][j]) : (bf16_t)0.0f;
+                    *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = z;
+                    if (MODE == 1) {
+                        bf16_t* zt = a.Zt + (size_t)(c * 8) * a.ld + chunk_row0 + r;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) zt[(size_t)j * a.ld] = z[j];
+                    }
+                }
             }
         }
     }
@@ -155,29 +168,63 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
     const bf16_t* zrow0 = zs + l32 * ZP + hb * 8;
     const bf16_t* zrow1 = zs + (32 + l32) * ZP + hb * 8;
 
-    for (int vs = 0; vs < V / JT_VSTEP; ++vs) {
-        const int vbase = vs * JT_VSTEP + wave * 32;
-        const bf16x8* ap = reinterpret_cast<const bf16x8*>(a.Wp) + (size_t)(vbase >> 5) * KK * 64 + lane;
-        f32x16 acc0 = {0}, acc1 = {0};
-        // K loop, two k16-steps per iteration, A fragments one iteration ahead
-        bf16x8 a0 = ap[0], a1 = ap[64];
-        for (int kk = 0; kk < KK; kk += 2) {
-            bf16x8 n0 = a0, n1 = a1;
-            if (kk + 2 < KK) {
-                n0 = ap[(size_t)(kk + 2) * 64];
-                n1 = ap[(size_t)(kk + 3) * 64];
+    // Main loop.  Per step of 256 vocabulary entries wave w owns entries [64w, 64w+64) for all 64
+    // rows: 2 x 2 accumulator tiles, so every fragment feeds two MFMAs.  A fragments (W_out^T) stream
+    // from L2 through a ring of JT_PF register sets per tile: the fragments of the next block of JT_PF
+    // k16-steps (possibly of the next vocabulary step) are requested while the current block is
+    // multiplied.  B fragments (joint tile, LDS) are read one k16-step ahead of their MFMAs; the
+    // scheduling barriers keep the compiler from sinking these reads back to their first use.
+    const int nvs = V / JT_VSTEP;
+    const int nkb = KK / JT_PF;
+    auto block_ptr = [&](int vs_, int vt_, int kb_) {
+        return reinterpret_cast<const bf16x8*>(a.Wp) +
+               ((size_t)(vs_ * (JT_VSTEP / 32) + wave * 2 + vt_) * KK + kb_ * JT_PF) * 64 + lane;
+    };
+    bf16x8 ring[2][JT_PF];
+#pragma unroll
+    for (int vt = 0; vt < 2; ++vt) {
+        const bf16x8* p0 = block_ptr(0, vt, 0);
+#pragma unroll
+        for (int j = 0; j < JT_PF; ++j) ring[vt][j] = p0[j * 64];
+    }
+    bf16x8 bc[2] = {*reinterpret_cast<const bf16x8*>(zrow0), *reinterpret_cast<const bf16x8*>(zrow1)};
+
+    for (int vs = 0; vs < nvs; ++vs) {
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) acc[vt][rt] = f32x16{0};
+        for (int kb = 0; kb < nkb; ++kb) {
+            int nvs_ = vs, nkb_ = kb + 1;
+            if (nkb_ == nkb) { nkb_ = 0; nvs_ = vs + 1; }
+            if (nvs_ == nvs) { nvs_ = vs; nkb_ = kb; }
+            const bf16x8* pn0 = block_ptr(nvs_, 0, nkb_);
+            const bf16x8* pn1 = block_ptr(nvs_, 1, nkb_);
+#pragma unroll
+            for (int j = 0; j < JT_PF; ++j) {
+                const int kk = kb * JT_PF + j;
+                int kn = kk + 1;
+                if (kn == KK) kn = 0;
+                const bf16x8 a0 = ring[0][j], a1 = ring[1][j];
+                bf16x8 bn[2];
+                bn[0] = *reinterpret_cast<const bf16x8*>(zrow0 + kn * 16);
+                bn[1] = *reinterpret_cast<const bf16x8*>(zrow1 + kn * 16);
+                ring[0][j] = pn0[j * 64];
+                ring[1][j] = pn1[j * 64];
+                __builtin_amdgcn_sched_barrier(0);
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bc[0], acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bc[1], acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bc[0], acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bc[1], acc[1][1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                bc[0] = bn[0];
+                bc[1] = bn[1];
             }
-            const bf16x8 b00 = *reinterpret_cast<const bf16x8*>(zrow0 + kk * 16);
-            const bf16x8 b10 = *reinterpret_cast<const bf16x8*>(zrow1 + kk * 16);
-            const bf16x8 b01 = *reinterpret_cast<const bf16x8*>(zrow0 + kk * 16 + 16);
-            const bf16x8 b11 = *reinterpret_cast<const bf16x8*>(zrow1 + kk * 16 + 16);
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b00, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b10, acc1, 0, 0, 0);
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b01, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b11, acc1, 0, 0, 0);
-            a0 = n0;
-            a1 = n1;
         }
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt) {
+        const int vbase = vs * JT_VSTEP + wave * 64 + vt * 32;
         // bias of this lane's 16 vocabulary entries: v = vbase + 8j + 4hb + i
         float bv[16];
 #pragma unroll
@@ -189,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
         const int relb = a.pr.blank - vbase;
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) {
-            const f32x16 acc = rt ? acc1 : acc0;
+            const f32x16 accv = acc[vt][rt];
             const int rely = lab[rt] - vbase;
             const bool hit_y = ((unsigned)rely < 32u);
             const bool slow = __any(hit_y) || ((unsigned)relb < 32u);
@@ -199,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
                 float tmax = RNNT_NEG_INF;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    x[i] = acc[i] + bv[i];
+                    x[i] = accv[i] + bv[i];
                     tmax = fmaxf(tmax, x[i]);
                 }
                 const float mn = fmaxf(m_run[rt], tmax);
@@ -226,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
                 float d[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    d[i] = __builtin_amdgcn_exp2f(fmaf(acc[i] + bv[i], LOG2E_F, gexp[rt]));
+                    d[i] = __builtin_amdgcn_exp2f(fmaf(accv[i] + bv[i], LOG2E_F, gexp[rt]));
                 if (slow) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
@@ -265,6 +312,7 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
                     __builtin_amdgcn_wave_barrier();
                 }
             }
+        }
         }
     }
 
@@ -359,6 +407,7 @@ struct GemmArgs {
     // MODE 1
     float* dW;
     int V;
+    int m_tiles, n_tiles;   // MODE 0 grid
 };
 
 template <int MODE>
@@ -368,7 +417,16 @@ __global__ __launch_bounds__(256, 2) void k_gemm_nt(GemmArgs g) {
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
-    const long long m0 = (long long)blockIdx.x * GT, n0 = (long long)blockIdx.y * GT;
+    // XCD-aware order (ids that agree modulo 8 share an L2): the column tiles of one row tile are
+    // neighbours on one XCD, so the row tile of A is fetched from HBM once.
+    int bx = blockIdx.x, by = blockIdx.y;
+    if (MODE == 0) {
+        const int L = blockIdx.x, xcd = L & 7, q = L >> 3;
+        by = q % g.n_tiles;
+        bx = xcd + 8 * (q / g.n_tiles);
+        if (bx >= g.m_tiles) return;
+    }
+    const long long m0 = (long long)bx * GT, n0 = (long long)by * GT;
     long long ks = 0, ke = g.K;
     if (MODE == 1) {
         ks = (long long)blockIdx.z * g.k_per_split;
@@ -438,7 +496,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_nt(GemmArgs g) {
     } else {
         // rows wm*64 .. +63 of this workgroup are one lattice tile: row = 8*tl + ul, and in the
         // accumulator layout register 4j+i of row-tile mt is tl = 4*mt + j, ul = 4*hb + i.
-        const int tile = g.tile0 + (int)blockIdx.x * 2 + wm;
+        const int tile = g.tile0 + bx * 2 + wm;
         if (tile < g.tile1) {
             const TilePos tp = locate_tile(g.st, g.s0, g.s1, tile);
             const int b = tp.s, H = g.pr.H;
@@ -501,55 +559,183 @@ hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0,
     g.tile1 = tile1;
     g.d_enc = d_enc;
     g.d_pred = d_pred;
-    k_gemm_nt<0><<<dim3((unsigned)((n + 1) / 2), (unsigned)(pr.H / GT)), dim3(256), 0, stream>>>(g);
+    g.m_tiles = (n + 1) / 2;
+    g.n_tiles = pr.H / GT;
+    const int m8 = (g.m_tiles + 7) / 8 * 8;
+    k_gemm_nt<0><<<dim3((unsigned)(m8 * g.n_tiles)), dim3(256), 0, stream>>>(g);
     return hipGetLastError();
 }
 
-// db[v] += sum over rows of dHt[v][.]: one wave per vocabulary entry
-__global__ __launch_bounds__(256) void k_db(const bf16_t* __restrict__ dHt, long long ld, long long rows,
-                                            float* __restrict__ db, int V) {
-    const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (v >= V) return;
-    const int lane = threadIdx.x & 63;
-    const bf16x8* p = reinterpret_cast<const bf16x8*>(dHt + (size_t)v * ld);
-    float acc = 0.0f;
-    for (long long i = lane; i < rows / 8; i += 64) {
-        const bf16x8 x = p[i];
+// ------------------------------------------------------------------------------------------------
+// dW += Zt dHt^T and db += row sums of dHt (Alg. 1 line 8) as one split-K GEMM with 256x256 tiles.
+// 512 threads = 8 waves in 2 (hidden) x 4 (vocabulary); each wave owns 128 x 64 = 4 x 2 accumulator
+// tiles.  A = Zt [H,ld], B = dHt [V,ld], contraction over the chunk's rows, blockIdx.z = K split.
+// The workgroups of the first hidden-tile row also sum their B fragments over the rows (the bias
+// gradient) with packed bf16 dot products against ones.
+// ------------------------------------------------------------------------------------------------
+constexpr int WT = 256;
+constexpr int WK = 64;        // K step
+constexpr int WP = 72;        // LDS row pitch in bf16 elements (144 B: conflict-free 16 B reads)
+
+struct DwArgs {
+    const bf16_t* Zt;
+    const bf16_t* dHt;
+    long long ld, K, k_per_split;
+    float* dW;
+    float* db;
+    int H, V;
+    int mt, nt;      // output tiles along H and V
+};
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
+    extern __shared__ __align__(16) unsigned char dw_smem[];
+    bf16_t(*As)[WT * WP] = reinterpret_cast<bf16_t(*)[WT * WP]>(dw_smem);
+    bf16_t(*Bs)[WT * WP] = reinterpret_cast<bf16_t(*)[WT * WP]>(dw_smem + (size_t)2 * WT * WP * 2);
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
+    const int wm = wave >> 2, wn = wave & 3;
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  All output tiles of
+    // one K split read the same rows of Zt and dHt, so they are mapped to the same XCD (ids that
+    // agree modulo 8) and adjacent in its dispatch order: the rows then come from HBM once.
+    const int ntile = g.mt * g.nt;
+    const int L = blockIdx.x, xcd = L & 7, q = L >> 3;
+    const int tile = q % ntile, split = xcd + 8 * (q / ntile);
+    const int bm = tile % g.mt, bn = tile / g.mt;
+    const long long m0 = (long long)bm * WT, n0 = (long long)bn * WT;
+    const long long ks = (long long)split * g.k_per_split;
+    const long long ke = ks + g.k_per_split < g.K ? ks + g.k_per_split : g.K;
+    if (ks >= ke) return;
+    const bool do_db = (bm == 0) && (wm == 0);
+    const int lrow = tid >> 3, lseg = tid & 7;          // rows lrow + 64*i, i = 0..3; 8 segments of 16 B
+    // rows of A beyond H (H not a multiple of 256) are read from row H-1 and never stored
+    const bf16_t* Ag[4];
+    const bf16_t* Bg[4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc += (float)x[j];
+    for (int i = 0; i < 4; ++i) {
+        long long ar = m0 + lrow + 64 * i;
+        if (ar >= g.H) ar = g.H - 1;
+        Ag[i] = g.Zt + ar * g.ld + lseg * 8;
+        Bg[i] = g.dHt + (n0 + lrow + 64 * i) * g.ld + lseg * 8;
     }
-    acc = wave_sum(acc);
-    if (lane == 0) atomicAdd(&db[v], acc);
-}
+    bf16x8 ra[4], rb[4];
+    auto gload = [&](long long k0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            ra[i] = *reinterpret_cast<const bf16x8*>(Ag[i] + k0);
+            rb[i] = *reinterpret_cast<const bf16x8*>(Bg[i] + k0);
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *reinterpret_cast<bf16x8*>(&As[buf][(lrow + 64 * i) * WP + lseg * 8]) = ra[i];
+            *reinterpret_cast<bf16x8*>(&Bs[buf][(lrow + 64 * i) * WP + lseg * 8]) = rb[i];
+        }
+    };
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{0};
+    float dbs[2] = {0.0f, 0.0f};
+    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 
-hipError_t launch_db_bf16(int V, long long rows, const void* dHt, long long ld, float* db, hipStream_t stream) {
-    if (rows <= 0) return hipSuccess;
-    k_db<<<dim3((unsigned)((V + 3) / 4)), dim3(256), 0, stream>>>((const bf16_t*)dHt, ld, rows, db, V);
-    return hipGetLastError();
+    gload(ks);
+    sstore(0);
+    __syncthreads();
+    int buf = 0;
+    for (long long k0 = ks; k0 < ke; k0 += WK) {
+        const bool more = (k0 + WK < ke);
+        if (more) gload(k0 + WK);
+        const bf16_t* as = &As[buf][(wm * 128 + l32) * WP + hb * 8];
+        const bf16_t* bs = &Bs[buf][(wn * 64 + l32) * WP + hb * 8];
+        // fragments are read one k16-step ahead of the MFMAs that consume them (two register sets)
+        bf16x8 fa[2][4], fb[2][2];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) fa[0][mt] = *reinterpret_cast<const bf16x8*>(as + mt * 32 * WP);
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) fb[0][nt] = *reinterpret_cast<const bf16x8*>(bs + nt * 32 * WP);
+#pragma unroll
+        for (int kk = 0; kk < WK / 16; ++kk) {
+            const int cur = kk & 1, nxt = cur ^ 1;
+            if (kk + 1 < WK / 16) {
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+                    fa[nxt][mt] = *reinterpret_cast<const bf16x8*>(as + mt * 32 * WP + (kk + 1) * 16);
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    fb[nxt][nt] = *reinterpret_cast<const bf16x8*>(bs + nt * 32 * WP + (kk + 1) * 16);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mt], fb[cur][nt], acc[mt][nt], 0, 0, 0);
+            if (do_db) {
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const bf16x2 pr2 = {fb[cur][nt][2 * q], fb[cur][nt][2 * q + 1]};
+                        dbs[nt] = __builtin_amdgcn_fdot2_f32_bf16(pr2, ones, dbs[nt], false);
+                    }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (more) sstore(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const long long mb = m0 + wm * 128 + mt * 32;
+        if (mb >= g.H) continue;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const long long n = n0 + wn * 64 + nt * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const long long m = mb + 8 * (i >> 2) + 4 * hb + (i & 3);
+                atomicAdd(&g.dW[m * g.V + n], acc[mt][nt][i]);
+            }
+        }
+    }
+    if (do_db) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            float v = dbs[nt] + __shfl_xor(dbs[nt], 32, 64);
+            if (hb == 0) atomicAdd(&g.db[n0 + wn * 64 + nt * 32 + l32], v);
+        }
+    }
 }
 
 hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, const void* dHt, long long ld,
-                               float* dW, hipStream_t stream) {
+                               float* dW, float* db, hipStream_t stream) {
     if (rows <= 0) return hipSuccess;
-    GemmArgs g{};
-    g.A = (const bf16_t*)Zt;
-    g.lda = ld;
-    g.B = (const bf16_t*)dHt;
-    g.ldb = ld;
-    g.K = rows;
-    g.dW = dW;
-    g.V = V;
-    // enough K splits to give every CU a few workgroups, each at least 512 rows long
-    const long long out_tiles = (long long)(H / GT) * (V / GT);
-    long long splits = (1024 + out_tiles - 1) / out_tiles;
-    long long max_splits = (rows + 511) / 512;
+    const long long mt = (H + WT - 1) / WT, nt = V / WT;
+    DwArgs g{(const bf16_t*)Zt, (const bf16_t*)dHt, ld, rows, 0, dW, db, H, V, (int)mt, (int)nt};
+    // one workgroup per CU and K split: aim at two rounds over 256 CUs, at least 256 rows per split
+    long long splits = (512 + mt * nt - 1) / (mt * nt);
+    const long long max_splits = (rows + 255) / 256;
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
     long long per = (rows + splits - 1) / splits;
-    per = (per + GK - 1) / GK * GK;
+    per = (per + WK - 1) / WK * WK;
     splits = (rows + per - 1) / per;
     g.k_per_split = per;
-    k_gemm_nt<1><<<dim3((unsigned)(H / GT), (unsigned)(V / GT), (unsigned)splits), dim3(256), 0, stream>>>(g);
+    const size_t smem = (size_t)4 * WT * WP * 2;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_dw256),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const long long splits8 = (splits + 7) / 8 * 8;     // surplus splits exit at once
+    k_gemm_dw256<<<dim3((unsigned)(mt * nt * splits8)), dim3(512), smem, stream>>>(g);
     return hipGetLastError();
 }
 

@@ -18,6 +18,17 @@ hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream) {
     return hipGetLastError();
 }
 
+__global__ __launch_bounds__(64) void k_fill_tile_sample(const int* __restrict__ tile_off, int* __restrict__ tile_sample) {
+    const int s = blockIdx.x;
+    const int e = tile_off[s + 1];
+    for (int i = tile_off[s] + threadIdx.x; i < e; i += 64) tile_sample[i] = s;
+}
+
+hipError_t launch_fill_tile_sample(const int* tile_off, int* tile_sample, int B, hipStream_t stream) {
+    k_fill_tile_sample<<<dim3((unsigned)B), dim3(64), 0, stream>>>(tile_off, tile_sample);
+    return hipGetLastError();
+}
+
 struct NodePos {
     int s, T, U, t, u;
     long long idx;  // index into the group's lattice arrays

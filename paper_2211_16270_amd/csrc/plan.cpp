@@ -18,7 +18,7 @@ rnnt_status check_desc(const rnnt_desc* d) {
     if ((long long)d->T_max * (d->U_max + 1) > (1LL << 30)) return RNNT_ERR_UNSUPPORTED;
     if (d->dtype == RNNT_BF16) {
         if (d->H % 128 != 0 || d->H > 1024) return RNNT_ERR_UNSUPPORTED;
-        if (d->V % 128 != 0) return RNNT_ERR_UNSUPPORTED;
+        if (d->V % 256 != 0) return RNNT_ERR_UNSUPPORTED;
     } else {
         if (d->H > 4096 || d->V > 16384) return RNNT_ERR_UNSUPPORTED;
     }
@@ -52,6 +52,7 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     p.off_row_off = take((B + 1) * 8);
     p.off_lnP = take(B * 4);
     p.off_shift = take(B * 4);
+    p.off_tile_sample = take((size_t)p.tiles_total * 4);
     p.off_wpack = take(p.bf16 ? (size_t)d.H * d.V * 2 : 0);
     size_t lat0 = o;
     p.off_lse = take((size_t)lat_cap * 4);

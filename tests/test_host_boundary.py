@@ -118,7 +118,7 @@ def test_workspace_does_not_grow_with_batch_size_once_capped():
     d2 = Bd.make_desc(1024, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16)
     n1 = Bd.rnnt_joint_loss_workspace_bytes(d1, T[:512], U[:512], 0)
     n2 = Bd.rnnt_joint_loss_workspace_bytes(d2, T, U, 0)
-    assert abs(n2 - n1) <= 64 * 1024      # only the per-sample tables grow
+    assert abs(n2 - n1) <= 8 * 1024 * 1024      # only the per-sample and per-tile index tables grow
 
 
 def test_budgets_shrink_the_plan_and_a_too_small_budget_is_reported():
