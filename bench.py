@@ -110,7 +110,7 @@ def main():
     HV = wl.H * wl.V
     # algorithmic flops per launch of each MFMA kernel: 2*H*V per lattice node it covers
     alg_flops_per_step = {"joint_scores_fwd": 2.0 * R * HV, "joint_scores_bwd": 2.0 * R * HV,
-                          "gemm_dz": 2.0 * R * HV, "gemm_dw_db": 2.0 * R * HV,
+                          "gemm_dz": 2.0 * R * HV, "gemm_dw_db": 2.0 * R * HV, "joint_bwd_fused": 4.0 * R * HV,
                           "fwd_f32": 2.0 * R * HV, "bwd_f32": 6.0 * R * HV}
     kernels = {}
     for name, (cnt, ms) in prof.items():

@@ -88,9 +88,9 @@ namespace {
 
 // Optional per-kernel timing with HIP events on the caller's stream (off by default).
 enum KernelClass { KC_FILL = 0, KC_PACK_W, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
-                   KC_FWD_F32, KC_BWD_F32, KC_COUNT };
+                   KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_COUNT };
 const char* const kKernelNames[KC_COUNT] = {"fill_zero", "pack_w", "joint_scores_fwd", "lattice",
-                                            "joint_scores_bwd", "gemm_dz", "gemm_dw_db",
+                                            "joint_scores_bwd", "gemm_dz", "gemm_dw_db", "joint_bwd_fused",
                                             "fwd_f32", "bwd_f32"};
 struct Profiler {
     bool enabled = false;
@@ -136,6 +136,7 @@ struct WsView {
     SampleTable st;
     LatticeState ls;   // row_base filled per group
     void* wpack;
+    void* wq;
     void* dH;
     void* dHt;
     void* Zt;
@@ -158,6 +159,7 @@ WsView view_workspace(const Plan& p, void* ws) {
     v.ls.shift = (float*)(w + p.off_shift);
     v.ls.row_base = 0;
     v.wpack = w + p.off_wpack;
+    v.wq = w + p.off_wq;
     v.dH = w + p.off_dh;
     v.dHt = w + p.off_dht;
     v.Zt = w + p.off_zt;
@@ -209,6 +211,8 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     }
     if (bf16)
         RNNT_HIP(timed(KC_PACK_W, stream, [&] { return launch_pack_w(W_out, wv.wpack, desc->H, desc->V, stream); }));
+    if (plan.fused && grads)
+        RNNT_HIP(timed(KC_PACK_W, stream, [&] { return launch_pack_wq(W_out, wv.wq, desc->H, desc->V, stream); }));
 
     size_t ci = 0;
     for (size_t gi = 0; gi < plan.groups.size(); ++gi) {
@@ -232,13 +236,21 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
             const Chunk& c = plan.chunks[ci];
             if (bf16) {
                 const long long rows = (long long)(c.tile1 - c.tile0) * TILE_ROWS;
-                RNNT_HIP(timed(KC_BWD_SCORES, stream, [&] {
-                    return launch_bwd_scores_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
-                                                  wv.dHt, wv.Zt, plan.chunk_rows, stream);
-                }));
-                RNNT_HIP(timed(KC_GEMM_DZ, stream, [&] {
-                    return launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred, stream);
-                }));
+                if (plan.fused) {
+                    RNNT_HIP(timed(KC_BWD_FUSED, stream, [&] {
+                        return launch_bwd_fused_bf16(pr, wv.wpack, wv.wq, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1,
+                                                     wv.dHt, wv.Zt, plan.chunk_rows, d_enc, d_pred, stream);
+                    }));
+                } else {
+                    RNNT_HIP(timed(KC_BWD_SCORES, stream, [&] {
+                        return launch_bwd_scores_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
+                                                      wv.dHt, wv.Zt, plan.chunk_rows, stream);
+                    }));
+                    RNNT_HIP(timed(KC_GEMM_DZ, stream, [&] {
+                        return launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred,
+                                                   stream);
+                    }));
+                }
                 RNNT_HIP(timed(KC_GEMM_DW, stream, [&] {
                     return launch_gemm_dw_bf16(desc->H, desc->V, rows, wv.Zt, wv.dHt, plan.chunk_rows, dW_out,
                                                db_out, stream);

@@ -1,0 +1,369 @@
+// Fused backward kernel of the bf16 MFMA path (gfx950): for one 8x8 lattice tile (64 rows)
+//   joint tile z = tanh(enc_t + pred_u) in LDS                                  (Eq. 4)
+//   scores recomputed on MFMA, dh = gamma * softmax - posteriors               (Eq. 6, f^W_4)
+//   dz = dh W_out^T accumulated over the whole vocabulary in registers           (Alg. 1 lines 10, 11)
+//   dx = dz (1 - z^2), summed over the tile's label positions / frames, added to d_enc / d_pred
+// and dh (transposed, bf16) plus z (transposed, bf16) written out for the dW_out GEMM.
+// The score gradient never exists in row-major form in HBM and is not re-read for dz.
+//
+// 512 threads = 8 waves, one workgroup per CU.
+//  Phase 1, per step of 512 vocabulary entries: wave w owns entries [64w, 64w+64) for all 64 rows
+//   (2 x 2 accumulator tiles, A = packed W_out^T fragments from L2, B = joint tile from LDS).
+//  Between the phases the 64 x 512 block of dh (bf16) is laid down in LDS, row-major.
+//  Phase 2: every wave multiplies that block into its own hidden columns (hidden 32-tiles w, w+8,
+//   ...): A = dh from LDS (rows), B = packed W_out fragments from L2 (hidden x vocabulary).
+//  Two workgroup barriers per step.
+// MFMA operand layouts: see kernels_bf16.hip.
+#include "device_common.h"
+
+namespace rnnt {
+
+constexpr int FB_ROWS = 64;
+constexpr int FB_VSTEP = 512;
+constexpr int FB_PF = 2;        // phase-1 A-fragment prefetch distance in k16-steps
+constexpr int FB_DP = FB_VSTEP + 8;   // pitch (bf16 elements) of the dh LDS tile [64 rows][512 entries]
+
+// W [H,V] -> fragment-major copy for the B operand of dz = dh W^T:
+//   Wq[((ht*(V/16) + vk)*64 + lane)*8 + j] = W[ht*32 + lane%32][vk*16 + 8*(lane/32) + j]
+__global__ __launch_bounds__(256) void k_pack_wq(const bf16_t* __restrict__ W, bf16_t* __restrict__ Wq, int H, int V) {
+    const int VK = V >> 4;
+    const long long total = (long long)(H >> 5) * VK * 64;
+    const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= total) return;
+    const int lane = (int)(g & 63);
+    const long long f = g >> 6;
+    const int vk = (int)(f % VK);
+    const int ht = (int)(f / VK);
+    const bf16_t* src = W + (size_t)(ht * 32 + (lane & 31)) * V + vk * 16 + 8 * (lane >> 5);
+    *reinterpret_cast<bf16x8*>(Wq + g * 8) = *reinterpret_cast<const bf16x8*>(src);
+}
+
+hipError_t launch_pack_wq(const void* W, void* Wq, int H, int V, hipStream_t stream) {
+    const long long total = (long long)(H / 32) * (V / 16) * 64;
+    k_pack_wq<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>((const bf16_t*)W, (bf16_t*)Wq, H, V);
+    return hipGetLastError();
+}
+
+struct FusedArgs {
+    Problem pr;
+    SampleTable st;
+    LatticeState ls;
+    const bf16_t* Wp;   // fragment-major W_out^T (phase 1)
+    const bf16_t* Wq;   // fragment-major W_out   (phase 2)
+    int s0, s1, tile0, tile1;
+    bf16_t* dHt;        // [V, ld]
+    bf16_t* Zt;         // [H, ld]
+    long long ld;
+    float* d_enc;
+    float* d_pred;
+};
+
+template <int HT>
+__global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int H = a.pr.H, V = a.pr.V;
+    const int ZP = H + 8;
+    bf16_t* zs = reinterpret_cast<bf16_t*>(smem);                        // [64][ZP]
+    bf16_t* dhs = zs + (size_t)FB_ROWS * ZP;                             // [64][FB_DP]
+    int* row_lab = reinterpret_cast<int*>(dhs + FB_ROWS * FB_DP);        // [64]
+    float* row_g = reinterpret_cast<float*>(row_lab + 64);               // [64] exponent offset (log2 units)
+    float* row_B = row_g + 64;                                           // [64] blank posterior
+    float* row_Y = row_B + 64;                                           // [64] label posterior
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
+    const int tile = a.tile0 + blockIdx.x;
+    const TilePos tp = locate_tile(a.st, a.s0, a.s1, tile);
+    const int b = tp.s;
+    const long long chunk_row0 = (long long)blockIdx.x * FB_ROWS;
+
+    // ---- joint tile (Eq. 4): thread -> row r = tid % 64, column chunks c = tid/64 + 8*i
+    {
+        const bf16_t* enc = reinterpret_cast<const bf16_t*>(a.pr.enc) + (size_t)b * a.pr.T_max * H;
+        const bf16_t* prd = reinterpret_cast<const bf16_t*>(a.pr.pred) + (size_t)b * (a.pr.U_max + 1) * H;
+        const int r = tid & 63;
+        const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
+        const bool valid = (t < tp.T && u <= tp.U);
+        const bf16_t* er = enc + (size_t)(valid ? t : 0) * H;
+        const bf16_t* qr = prd + (size_t)(valid ? u : 0) * H;
+        const int nch = H >> 6;                              // chunks per thread
+        for (int i0 = 0; i0 < nch; i0 += 8) {
+            bf16x8 e[8], q[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = (tid >> 6) + 8 * ((i0 + i < nch) ? i0 + i : 0);
+                e[i] = *reinterpret_cast<const bf16x8*>(er + c * 8);
+                q[i] = *reinterpret_cast<const bf16x8*>(qr + c * 8);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i0 + i < nch) {
+                    const int c = (tid >> 6) + 8 * (i0 + i);
+                    bf16x8 z;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        z[j] = valid ? (bf16_t)fast_tanh((float)e[i][j] + (float)q[i][j]) : (bf16_t)0.0f;
+                    *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = z;
+                    bf16_t* zt = a.Zt + (size_t)(c * 8) * a.ld + chunk_row0 + r;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) zt[(size_t)j * a.ld] = z[j];
+                }
+            }
+        }
+    }
+    if (tid < 64) {
+        const int r = tid;
+        const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
+        const bool valid = (t < tp.T && u <= tp.U);
+        row_lab[r] = (valid && u < tp.U) ? a.pr.labels[(size_t)b * a.pr.U_max + u] : -1;
+        if (valid) {
+            const long long idx = (a.st.row_off[b] - a.ls.row_base) + (long long)t * (tp.U + 1) + u;
+            const RowPost rp = row_posteriors(a.ls, idx, t, u, tp.T, tp.U, b);
+            row_g[r] = (rp.log_gamma - a.ls.lse[idx]) * LOG2E_F;
+            row_B[r] = rp.Bk;
+            row_Y[r] = rp.Yk;
+        } else {
+            row_g[r] = RNNT_NEG_INF;
+            row_B[r] = 0.0f;
+            row_Y[r] = 0.0f;
+        }
+    }
+    __syncthreads();
+
+    const int KK = H >> 4;             // k16-steps of the score GEMM
+    const int VK = V >> 4;             // k16-steps of the dz GEMM (whole vocabulary)
+    const int nht = H >> 5;            // hidden 32-tiles
+    const int nvs = (V + FB_VSTEP - 1) / FB_VSTEP;
+    const int nkb = KK / FB_PF;
+    int lab[2] = {row_lab[l32], row_lab[32 + l32]};
+    float gexp[2] = {row_g[l32], row_g[32 + l32]};
+    float Bk[2] = {row_B[l32], row_B[32 + l32]};
+    float Yk[2] = {row_Y[l32], row_Y[32 + l32]};
+    const bf16_t* zrow0 = zs + l32 * ZP + hb * 8;
+    const bf16_t* zrow1 = zs + (32 + l32) * ZP + hb * 8;
+    const bf16_t* drow0 = dhs + l32 * FB_DP + hb * 8;
+    const bf16_t* drow1 = dhs + (32 + l32) * FB_DP + hb * 8;
+
+    // dz accumulators: hidden tiles wave, wave+8, ... (HT of them at most), two row tiles
+    f32x16 dz[HT][2];
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) dz[i][rt] = f32x16{0};
+
+    // phase-2 B fragments (W_out, hidden x vocabulary): blocks of 4 k16-steps, one block ahead
+    auto wq_ptr = [&](int i, int vk) {
+        int ht = wave + 8 * i;
+        if (ht >= nht) ht = wave;      // unused slot: any valid fragment
+        return reinterpret_cast<const bf16x8*>(a.Wq) + ((size_t)ht * VK + vk) * 64 + lane;
+    };
+    bf16x8 ringB[HT][4];
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) ringB[i][kk] = wq_ptr(i, 0)[kk * 64];
+
+    // phase-1 A fragments (W_out^T, vocabulary x hidden)
+    auto wp_ptr = [&](int vs_, int vt_, int kb_) {
+        return reinterpret_cast<const bf16x8*>(a.Wp) +
+               ((size_t)(vs_ * (FB_VSTEP / 32) + wave * 2 + vt_) * KK + kb_ * FB_PF) * 64 + lane;
+    };
+
+    for (int vs = 0; vs < nvs; ++vs) {
+        const int vleft = V - vs * FB_VSTEP;
+        const int nact = (vleft < FB_VSTEP ? vleft : FB_VSTEP) >> 6;   // waves with vocabulary entries
+        f32x16 acc[2][2];
+        if (wave < nact) {
+            // -------- phase 1: scores of 64 entries x 64 rows; accumulators start from the bias
+#pragma unroll
+            for (int vt = 0; vt < 2; ++vt) {
+                const float* bp = a.pr.b_out + vs * FB_VSTEP + wave * 64 + vt * 32 + 4 * hb;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const f32x4 t4 = *reinterpret_cast<const f32x4*>(bp + 8 * j);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        acc[vt][0][4 * j + i] = t4[i];
+                        acc[vt][1][4 * j + i] = t4[i];
+                    }
+                }
+            }
+            bf16x8 ringA[2][FB_PF];
+#pragma unroll
+            for (int vt = 0; vt < 2; ++vt) {
+                const bf16x8* p0 = wp_ptr(vs, vt, 0);
+#pragma unroll
+                for (int j = 0; j < FB_PF; ++j) ringA[vt][j] = p0[j * 64];
+            }
+            bf16x8 bc[2] = {*reinterpret_cast<const bf16x8*>(zrow0), *reinterpret_cast<const bf16x8*>(zrow1)};
+            for (int kb = 0; kb < nkb; ++kb) {
+                const int nkb_ = (kb + 1 < nkb) ? kb + 1 : kb;
+                const bf16x8* pn0 = wp_ptr(vs, 0, nkb_);
+                const bf16x8* pn1 = wp_ptr(vs, 1, nkb_);
+#pragma unroll
+                for (int j = 0; j < FB_PF; ++j) {
+                    const int kk = kb * FB_PF + j;
+                    int kn = kk + 1;
+                    if (kn == KK) kn = 0;
+                    const bf16x8 a0 = ringA[0][j], a1 = ringA[1][j];
+                    bf16x8 bn[2];
+                    bn[0] = *reinterpret_cast<const bf16x8*>(zrow0 + kn * 16);
+                    bn[1] = *reinterpret_cast<const bf16x8*>(zrow1 + kn * 16);
+                    ringA[0][j] = pn0[j * 64];
+                    ringA[1][j] = pn1[j * 64];
+                    __builtin_amdgcn_sched_barrier(0);
+                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bc[0], acc[0][0], 0, 0, 0);
+                    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bc[1], acc[0][1], 0, 0, 0);
+                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bc[0], acc[1][0], 0, 0, 0);
+                    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bc[1], acc[1][1], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    bc[0] = bn[0];
+                    bc[1] = bn[1];
+                }
+            }
+        }
+        __syncthreads();    // every wave is done reading the dh tile of the previous step
+        if (wave < nact) {
+            // -------- f^W_4: dh = gamma * softmax - posteriors, to bf16; into the LDS tile (row-major)
+            //          for phase 2 and, transposed, to HBM for the dW GEMM
+#pragma unroll
+            for (int vt = 0; vt < 2; ++vt) {
+                const int vbase = vs * FB_VSTEP + wave * 64 + vt * 32;
+                const int relb = a.pr.blank - vbase;
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt) {
+                    const int rely = lab[rt] - vbase;
+                    const bool slow = __any((unsigned)rely < 32u) || ((unsigned)relb < 32u);
+                    float d[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        d[i] = __builtin_amdgcn_exp2f(fmaf(acc[vt][rt][i], LOG2E_F, gexp[rt]));
+                    if (slow) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int vloc = 8 * (i >> 2) + 4 * hb + (i & 3);
+                            if (vloc == relb) d[i] -= Bk[rt];
+                            if (vloc == rely) d[i] -= Yk[rt];
+                        }
+                    }
+                    bf16_t* o = a.dHt + (size_t)(vbase + 4 * hb) * a.ld + chunk_row0 + rt * 32 + l32;
+                    bf16_t* sd = dhs + (rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + 4 * hb;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        bf16x4 q4 = {(bf16_t)d[4 * j], (bf16_t)d[4 * j + 1], (bf16_t)d[4 * j + 2], (bf16_t)d[4 * j + 3]};
+                        *reinterpret_cast<bf16x4*>(sd + 8 * j) = q4;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) o[(size_t)(8 * j + i) * a.ld] = q4[i];
+                    }
+                }
+            }
+        }
+        __syncthreads();    // the dh tile of this step is complete
+        // -------- phase 2: dz += dh W^T over the nact*64 vocabulary entries of this step
+        {
+            const int nb2 = nact;                      // blocks of 4 k16-steps
+            const int vk0 = vs * (FB_VSTEP / 16);
+            bf16x8 ac[2] = {*reinterpret_cast<const bf16x8*>(drow0), *reinterpret_cast<const bf16x8*>(drow1)};
+            for (int kb = 0; kb < nb2; ++kb) {
+                // next block of B fragments: next block of this step, else first block of the next step
+                int vkn = vk0 + (kb + 1) * 4;
+                if (vkn >= VK) vkn = vk0 + kb * 4;
+                const bf16x8* pn[HT];
+#pragma unroll
+                for (int i = 0; i < HT; ++i) pn[i] = wq_ptr(i, vkn);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int kk = kb * 4 + j;
+                    int kn = kk + 1;
+                    if (kn == nb2 * 4) kn = 0;
+                    bf16x8 an[2];
+                    an[0] = *reinterpret_cast<const bf16x8*>(drow0 + kn * 16);
+                    an[1] = *reinterpret_cast<const bf16x8*>(drow1 + kn * 16);
+                    bf16x8 bfr[HT];
+#pragma unroll
+                    for (int i = 0; i < HT; ++i) {
+                        bfr[i] = ringB[i][j];
+                        ringB[i][j] = pn[i][j * 64];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < HT; ++i) {
+                        dz[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[0], bfr[i], dz[i][0], 0, 0, 0);
+                        dz[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[1], bfr[i], dz[i][1], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    ac[0] = an[0];
+                    ac[1] = an[1];
+                }
+            }
+        }
+    }
+
+    // ---- Alg. 1 lines 10, 11: dx = dz (1 - z^2); sum over label positions -> d_enc, over frames -> d_pred.
+    // Accumulator register 4j+i of row tile rt is tile row 32 rt + 8j + 4 hb + i: frame 4 rt + j, label 4 hb + i.
+    {
+        float* d_enc = a.d_enc + (size_t)b * a.pr.T_max * H;
+        float* d_prd = a.d_pred + (size_t)b * (a.pr.U_max + 1) * H;
+#pragma unroll
+        for (int i = 0; i < HT; ++i) {
+            const int ht = wave + 8 * i;
+            if (ht >= nht) continue;
+            const int h = ht * 32 + l32;
+            float pu[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int tl = 4 * rt + j;
+                    float se = 0.0f;
+#pragma unroll
+                    for (int ii = 0; ii < 4; ++ii) {
+                        const int r = rt * 32 + 8 * j + 4 * hb + ii;
+                        const float z = (float)zs[r * ZP + h];
+                        const float dx = dz[i][rt][4 * j + ii] * (1.0f - z * z);
+                        se += dx;
+                        pu[ii] += dx;
+                    }
+                    se += __shfl_xor(se, 32, 64);
+                    if (hb == (j & 1) && tp.t0 + tl < tp.T) atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
+                }
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii)
+                if (tp.u0 + 4 * hb + ii <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + 4 * hb + ii) * H + h], pu[ii]);
+        }
+    }
+}
+
+static size_t fused_smem_bytes(int H) {
+    return (size_t)FB_ROWS * (H + 8) * 2 + (size_t)FB_ROWS * FB_DP * 2 + 64 * 4 * 4;
+}
+
+template <int HT>
+static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t stream) {
+    const int n = a.tile1 - a.tile0;
+    const size_t smem = fused_smem_bytes(a.pr.H);
+    static size_t configured = 0;
+    if (smem > configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_bwd_fused<HT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        configured = smem;
+    }
+    k_joint_bwd_fused<HT><<<dim3((unsigned)n), dim3(512), smem, stream>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const void* Wq, const SampleTable& st,
+                                 const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dHt, void* Zt,
+                                 long long ld, float* d_enc, float* d_pred, hipStream_t stream) {
+    if (tile1 <= tile0) return hipSuccess;
+    FusedArgs a{pr, st, ls, (const bf16_t*)Wpack, (const bf16_t*)Wq, s0, s1, tile0, tile1,
+                (bf16_t*)dHt, (bf16_t*)Zt, ld, d_enc, d_pred};
+    const int ht = (pr.H / 32 + 7) / 8;
+    if (ht <= 1) return launch_fused_t<1>(a, stream);
+    if (ht == 2) return launch_fused_t<2>(a, stream);
+    if (ht == 3) return launch_fused_t<3>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace rnnt

@@ -54,6 +54,7 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     p.off_shift = take(B * 4);
     p.off_tile_sample = take((size_t)p.tiles_total * 4);
     p.off_wpack = take(p.bf16 ? (size_t)d.H * d.V * 2 : 0);
+    p.off_wq = take(p.fused ? (size_t)d.H * d.V * 2 : 0);
     size_t lat0 = o;
     p.off_lse = take((size_t)lat_cap * 4);
     p.off_lpb = take((size_t)lat_cap * 4);
@@ -63,7 +64,7 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     p.lattice_bytes = o - lat0;
     size_t ch0 = o;
     if (p.bf16) {
-        p.off_dh = take((size_t)chunk_rows * d.V * 2);
+        p.off_dh = take(p.fused ? 0 : (size_t)chunk_rows * d.V * 2);
         p.off_dht = take((size_t)chunk_rows * d.V * 2);
         p.off_zt = take((size_t)chunk_rows * d.H * 2);
     } else {
@@ -83,6 +84,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     const int B = d.B;
     p.B = B;
     p.bf16 = (d.dtype == RNNT_BF16);
+    p.fused = p.bf16 && fused_backward_shape(d.H, d.V);
     p.tile_off.assign(B + 1, 0);
     p.row_off.assign(B + 1, 0);
     long long max_rows = 0;
@@ -97,7 +99,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     p.tiles_total = p.tile_off[B];
     const long long all_tile_rows =
         (long long)align_up((size_t)p.tiles_total * TILE_ROWS, GEMM_TILE);
-    const size_t crb = p.bf16 ? (size_t)4 * d.V + (size_t)2 * d.H : 0;
+    const size_t crb = p.bf16 ? (size_t)(p.fused ? 2 : 4) * d.V + (size_t)2 * d.H : 0;
 
     // smallest workable plan: one (largest) sample per group, one GEMM tile of rows per chunk
     Plan tmp = p;

@@ -37,6 +37,7 @@ struct Chunk {
 struct Plan {
     int B = 0;
     bool bf16 = false;
+    bool fused = false;                 // bf16 only: backward runs in the fused kernel (no row-major dh buffer)
     std::vector<int> tile_off;          // [B+1] cumulative tile counts
     std::vector<long long> row_off;     // [B+1] cumulative lattice nodes
     std::vector<Group> groups;
@@ -46,12 +47,15 @@ struct Plan {
     long long chunk_rows = 0;           // rows (multiple of GEMM_TILE) of the chunk buffers
     // workspace layout (byte offsets)
     size_t off_T = 0, off_U = 0, off_tile_off = 0, off_row_off = 0, off_lnP = 0, off_shift = 0, off_tile_sample = 0;
-    size_t off_wpack = 0;
+    size_t off_wpack = 0, off_wq = 0;
     size_t off_lse = 0, off_lpb = 0, off_lpy = 0, off_alpha = 0, off_beta = 0;
     size_t off_dh = 0, off_dht = 0, off_zt = 0;
     size_t lattice_bytes = 0, chunk_bytes = 0, total_bytes = 0;
     size_t min_bytes = 0;               // smallest workable workspace
 };
+
+// Shapes the fused backward kernel covers (its dz accumulators must fit the register file).
+inline bool fused_backward_shape(int H, int V) { return H % 128 == 0 && H <= 512 && V % 256 == 0; }
 
 // Argument checks shared by every entry point (no pointers to data arrays here).
 rnnt_status check_desc(const rnnt_desc* d);
