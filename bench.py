@@ -27,7 +27,8 @@ if ROOT not in sys.path:
 
 PEAK_BF16_FLOPS = 2.5e15     # MI355X dense bf16 MFMA
 PEAK_F32_FLOPS = 157.3e12    # MI355X fp32 vector
-CPU_SAMPLE = {"C1": 2, "C2": 6, "C3": 1, "C4": 1, "C5": 2}   # samples the checker is timed on
+CPU_SAMPLE = {"C1": 2, "C2": 32, "C3": 4, "C4": 4, "C5": 4}  # samples the checker is timed on (10-30 s)
+COPY_BYTES = 256 << 20
 
 
 def main():
@@ -39,6 +40,8 @@ def main():
     ap.add_argument("--budget-mib", type=int, default=0, help="workspace budget (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="use only the first N samples (profiling aid)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the 256 MiB plain copy kernel 5 times (HBM counter calibration under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
@@ -106,6 +109,14 @@ def main():
     prof = Bd.rnnt_profile_read()
     Bd.rnnt_profile_enable(False)
 
+    if args.calibrate_copy:
+        src = torch.ones(COPY_BYTES // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            assert Bd.rnnt_debug_copy_f32(src, dst) == 0
+        torch.cuda.synchronize()
+        del src, dst
+
     R = int(info["rows_total"])
     HV = wl.H * wl.V
     # algorithmic flops per launch of each MFMA kernel: 2*H*V per lattice node it covers
@@ -125,9 +136,12 @@ def main():
     flops_per_launch = alg_flops_per_step[dom] / launches
     peak = PEAK_BF16_FLOPS if wl.dtype == "bf16" else PEAK_F32_FLOPS
     achieved = flops_per_launch / avg_s
+    # HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if any
+    from paper_2211_16270_amd.pmc_summary import read_traffic
+    traffic = read_traffic(os.path.join(ROOT, "profiles", f"hbm_traffic_{wl.name}.txt")) if not args.batch else {}
     roofline = {"bound": "mfma" if wl.dtype == "bf16" else "alu", "kernel": dom,
                 "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
-                "traffic": None, "alg_flops_per_launch": flops_per_launch,
+                "traffic": traffic.get(dom), "alg_flops_per_launch": flops_per_launch,
                 "avg_launch_us": kernels[dom]["avg_launch_us"]}
     step_s = elapsed / steps
     util_alg = 6.0 * R * HV / step_s / peak

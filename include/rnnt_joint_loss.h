@@ -166,6 +166,13 @@ rnnt_status rnnt_debug_read_lattice(const rnnt_desc* desc, const int32_t* T_len_
                                     float* alpha_host, float* beta_host);
 
 /*
+ * Measurement support, not a paper operation: copies n floats (n a multiple of 4, both dev, 16-byte
+ * aligned) with a plain grid-stride kernel.  Its known size calibrates the HBM byte counters that
+ * the per-kernel traffic figures are read from.  Enqueues on hip_stream, does not wait.
+ */
+rnnt_status rnnt_debug_copy_f32(const float* src, float* dst, size_t n, void* hip_stream);
+
+/*
  * Per-kernel timing for the benchmark (not a paper operation; measurement support for the
  * throughput figures reported against Table 1's cost terms).  While enabled, every launch made
  * by the two entry points above is bracketed by HIP events recorded on the caller's stream

@@ -21,7 +21,7 @@ STATUS_NAMES = ["RNNT_OK", "RNNT_ERR_NULL", "RNNT_ERR_SHAPE", "RNNT_ERR_LENGTH",
 EXPORTS = ["rnnt_status_string", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_loss_plan",
            "rnnt_parallel_iterations", "rnnt_validate_labels_host", "rnnt_joint_loss_fwd_bwd",
            "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice", "rnnt_profile_enable",
-           "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read"]
+           "rnnt_debug_copy_f32", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read"]
 
 
 class RnntDesc(ctypes.Structure):
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
     L.rnnt_joint_loss_fwd.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
     L.rnnt_debug_read_lattice.restype = ctypes.c_int
     L.rnnt_debug_read_lattice.argtypes = [dp, i32p, i32p, vp, ctypes.c_size_t, ctypes.c_int32, vp, vp]
+    L.rnnt_debug_copy_f32.restype = ctypes.c_int
+    L.rnnt_debug_copy_f32.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.rnnt_profile_enable.restype = ctypes.c_int
     L.rnnt_profile_enable.argtypes = [ctypes.c_int32]
     L.rnnt_profile_kernel_count.restype = ctypes.c_int32
@@ -171,6 +173,12 @@ def rnnt_debug_read_lattice(desc: RnntDesc, T_len, U_len, workspace, b: int):
                                        al.ctypes.data, be.ctypes.data)
     shape = (int(T[b]), int(U[b]) + 1)
     return int(st), al.reshape(shape), be.reshape(shape)
+
+
+def rnnt_debug_copy_f32(src, dst, stream=None) -> int:
+    """Copies the float32 tensor src into dst (same size, multiple of 4 elements) with the library's
+    plain copy kernel."""
+    return int(lib().rnnt_debug_copy_f32(_ptr(src), _ptr(dst), int(src.numel()), _stream_handle(stream)))
 
 
 def rnnt_profile_enable(enable: bool) -> int:

@@ -314,6 +314,13 @@ extern "C" rnnt_status rnnt_debug_read_lattice(const rnnt_desc* desc, const int3
     return RNNT_OK;
 }
 
+extern "C" rnnt_status rnnt_debug_copy_f32(const float* src, float* dst, size_t n, void* hip_stream) {
+    if (!src || !dst) return RNNT_ERR_NULL;
+    if (n % 4 != 0) return RNNT_ERR_SHAPE;
+    RNNT_HIP(launch_copy_f32(src, dst, n, (hipStream_t)hip_stream));
+    return RNNT_OK;
+}
+
 extern "C" rnnt_status rnnt_profile_enable(int32_t enable) {
     g_prof.clear();
     g_prof.enabled = (enable != 0);

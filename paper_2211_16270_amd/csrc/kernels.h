@@ -45,6 +45,8 @@ struct GradOut {
 };
 
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream);
+// plain copy of n floats (n a multiple of 4): the known-size kernel the HBM counters are calibrated with
+hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t stream);
 // tile_sample[tile] = s for every tile of every sample (one lookup instead of a search per workgroup)
 hipError_t launch_fill_tile_sample(const int* tile_off, int* tile_sample, int B, hipStream_t stream);
 

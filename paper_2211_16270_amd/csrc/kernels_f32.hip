@@ -29,6 +29,18 @@ hipError_t launch_fill_tile_sample(const int* tile_off, int* tile_sample, int B,
     return hipGetLastError();
 }
 
+__global__ void k_copy_f32(const float4* __restrict__ src, float4* __restrict__ dst, size_t n4) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n4; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    k_copy_f32<<<dim3(4096), dim3(256), 0, stream>>>((const float4*)src, (float4*)dst, n / 4);
+    return hipGetLastError();
+}
+
 struct NodePos {
     int s, T, U, t, u;
     long long idx;  // index into the group's lattice arrays
