@@ -257,6 +257,7 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
                 s_run[rt] = s_run[rt] * __builtin_amdgcn_exp2f((m_run[rt] - mn) * LOG2E_F) + ssum;
                 m_run[rt] = mn;
                 if (slow) {
+                    asm volatile("" ::: "memory");   // keep this rare path a real branch (no if-conversion)
                     float cb = RNNT_NEG_INF, cy = RNNT_NEG_INF;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {

@@ -67,8 +67,8 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
     bf16_t* dhs = zs + (size_t)FB_ROWS * ZP;                             // [64][FB_DP]
     int* row_lab = reinterpret_cast<int*>(dhs + FB_ROWS * FB_DP);        // [64]
     float* row_g = reinterpret_cast<float*>(row_lab + 64);               // [64] exponent offset (log2 units)
-    float* row_B = row_g + 64;                                           // [64] blank posterior
-    float* row_Y = row_B + 64;                                           // [64] label posterior
+    float* row_B = row_g + 64;                                           // [64] dh at the blank entry
+    float* row_Y = row_B + 64;                                           // [64] dh at the label entry
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
@@ -104,9 +104,10 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
                     for (int j = 0; j < 8; ++j)
                         z[j] = valid ? (bf16_t)fast_tanh((float)e[i][j] + (float)q[i][j]) : (bf16_t)0.0f;
                     *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = z;
-                    bf16_t* zt = a.Zt + (size_t)(c * 8) * a.ld + chunk_row0 + r;
+                    // wave-uniform row base (scalar registers) + lane offset r
+                    bf16_t* zt = a.Zt + (size_t)(c * 8) * a.ld + chunk_row0;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) zt[(size_t)j * a.ld] = z[j];
+                    for (int j = 0; j < 8; ++j) (zt + (size_t)j * a.ld)[r] = z[j];
                 }
             }
         }
@@ -118,10 +119,15 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         row_lab[r] = (valid && u < tp.U) ? a.pr.labels[(size_t)b * a.pr.U_max + u] : -1;
         if (valid) {
             const long long idx = (a.st.row_off[b] - a.ls.row_base) + (long long)t * (tp.U + 1) + u;
+            // dh = gamma * softmax - posteriors differs from gamma * softmax at two entries of the row
+            // only; their final values follow from the stored log-probabilities, so the per-element
+            // path below needs no indicator logic: the owning lane overwrites those two entries.
             const RowPost rp = row_posteriors(a.ls, idx, t, u, tp.T, tp.U, b);
             row_g[r] = (rp.log_gamma - a.ls.lse[idx]) * LOG2E_F;
-            row_B[r] = rp.Bk;
-            row_Y[r] = rp.Yk;
+            const int y = row_lab[r];
+            const float both = (y == a.pr.blank) ? 1.0f : 0.0f;
+            row_B[r] = __expf(rp.log_gamma + a.ls.lpb[idx]) - rp.Bk - both * rp.Yk;
+            row_Y[r] = (y >= 0) ? __expf(rp.log_gamma + a.ls.lpy[idx]) - rp.Yk - both * rp.Bk : 0.0f;
         } else {
             row_g[r] = RNNT_NEG_INF;
             row_B[r] = 0.0f;
@@ -233,27 +239,34 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
 #pragma unroll
                 for (int rt = 0; rt < 2; ++rt) {
                     const int rely = lab[rt] - vbase;
-                    const bool slow = __any((unsigned)rely < 32u) || ((unsigned)relb < 32u);
                     float d[16];
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
                         d[i] = __builtin_amdgcn_exp2f(fmaf(acc[vt][rt][i], LOG2E_F, gexp[rt]));
-                    if (slow) {
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int vloc = 8 * (i >> 2) + 4 * hb + (i & 3);
-                            if (vloc == relb) d[i] -= Bk[rt];
-                            if (vloc == rely) d[i] -= Yk[rt];
-                        }
-                    }
-                    bf16_t* o = a.dHt + (size_t)(vbase + 4 * hb) * a.ld + chunk_row0 + rt * 32 + l32;
+                    // transposed store dHt[v][row]: wave-uniform base per vocabulary entry + 32-bit lane offset
+                    bf16_t* ob = a.dHt + (size_t)vbase * a.ld + chunk_row0 + rt * 32;
+                    const unsigned lane_off = (unsigned)(4 * hb) * (unsigned)a.ld + (unsigned)l32;
                     bf16_t* sd = dhs + (rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + 4 * hb;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         bf16x4 q4 = {(bf16_t)d[4 * j], (bf16_t)d[4 * j + 1], (bf16_t)d[4 * j + 2], (bf16_t)d[4 * j + 3]};
                         *reinterpret_cast<bf16x4*>(sd + 8 * j) = q4;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) o[(size_t)(8 * j + i) * a.ld] = q4[i];
+                        for (int i = 0; i < 4; ++i) (ob + (size_t)(8 * j + i) * a.ld)[lane_off] = q4[i];
+                    }
+                    // the lane that holds the blank / label entry of its row overwrites it (same lane,
+                    // same addresses, program order): entry rel lives in lane half (rel/4)%2
+                    const bool own_b = ((unsigned)relb < 32u) && (((relb >> 2) & 1) == hb);
+                    const bool own_y = ((unsigned)rely < 32u) && (((rely >> 2) & 1) == hb);
+                    if (own_b) {
+                        const bf16_t v = (bf16_t)Bk[rt];
+                        dhs[(rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + relb] = v;
+                        (a.dHt + (size_t)(vbase + relb) * a.ld + chunk_row0 + rt * 32)[l32] = v;
+                    }
+                    if (own_y) {
+                        const bf16_t v = (bf16_t)Yk[rt];
+                        dhs[(rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + rely] = v;
+                        (a.dHt + (size_t)(vbase + rely) * a.ld + chunk_row0 + rt * 32)[l32] = v;
                     }
                 }
             }
