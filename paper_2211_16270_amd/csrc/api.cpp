@@ -138,8 +138,7 @@ struct WsView {
     void* wpack;
     void* wq;
     void* dH;
-    void* dHt;
-    void* Zt;
+    void* Z;
 };
 
 WsView view_workspace(const Plan& p, void* ws) {
@@ -161,8 +160,7 @@ WsView view_workspace(const Plan& p, void* ws) {
     v.wpack = w + p.off_wpack;
     v.wq = w + p.off_wq;
     v.dH = w + p.off_dh;
-    v.dHt = w + p.off_dht;
-    v.Zt = w + p.off_zt;
+    v.Z = w + p.off_z;
     return v;
 }
 
@@ -239,12 +237,12 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                 if (plan.fused) {
                     RNNT_HIP(timed(KC_BWD_FUSED, stream, [&] {
                         return launch_bwd_fused_bf16(pr, wv.wpack, wv.wq, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1,
-                                                     wv.dHt, wv.Zt, plan.chunk_rows, d_enc, d_pred, stream);
+                                                     wv.dH, wv.Z, d_enc, d_pred, stream);
                     }));
                 } else {
                     RNNT_HIP(timed(KC_BWD_SCORES, stream, [&] {
                         return launch_bwd_scores_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
-                                                      wv.dHt, wv.Zt, plan.chunk_rows, stream);
+                                                      wv.Z, stream);
                     }));
                     RNNT_HIP(timed(KC_GEMM_DZ, stream, [&] {
                         return launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred,
@@ -252,8 +250,7 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                     }));
                 }
                 RNNT_HIP(timed(KC_GEMM_DW, stream, [&] {
-                    return launch_gemm_dw_bf16(desc->H, desc->V, rows, wv.Zt, wv.dHt, plan.chunk_rows, dW_out,
-                                               db_out, stream);
+                    return launch_gemm_dw_bf16(desc->H, desc->V, rows, wv.Z, wv.dH, dW_out, db_out, stream);
                 }));
             } else {
                 RNNT_HIP(timed(KC_BWD_F32, stream,

@@ -67,22 +67,23 @@ hipError_t launch_pack_w(const void* W, void* Wpack, int H, int V, hipStream_t s
 hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                            const LatticeState& ls, int s0, int s1, int tile0, int tile1,
                            hipStream_t stream);
-// joint tile -> scores recomputed -> dh (bf16) into the chunk buffers dH [rows,V], dHt [V,ld], Zt [H,ld]
+// joint tile -> scores recomputed -> dh (bf16) into the chunk buffers dH [rows,V], Z [rows,H]
 hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                                   const LatticeState& ls, int s0, int s1, int tile0, int tile1,
-                                  void* dH, void* dHt, void* Zt, long long ld, hipStream_t stream);
+                                  void* dH, void* Z, hipStream_t stream);
 // dz = dH W^T, times the tanh derivative, reduced over the tile's u resp. t, added to d_enc, d_pred
 hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0,
                                int tile1, const void* dH, float* d_enc, float* d_pred,
                                hipStream_t stream);
 // fused backward: scores recomputed, dh, dz = dh W^T, tanh derivative, reductions into d_enc / d_pred;
-// writes dHt [V,ld] and Zt [H,ld] for the dW GEMM.  Wq is the second fragment-major copy of W_out.
+// writes dH [rows,V] and Z [rows,H] (bf16, row-major) for the dW GEMM.  Wq is the second
+// fragment-major copy of W_out.
 hipError_t launch_pack_wq(const void* W, void* Wq, int H, int V, hipStream_t stream);
 hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const void* Wq, const SampleTable& st,
-                                 const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dHt,
-                                 void* Zt, long long ld, float* d_enc, float* d_pred, hipStream_t stream);
-// dW += Zt dHt^T (split over the rows) and db += row sums of dHt
-hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, const void* dHt,
-                               long long ld, float* dW, float* db, hipStream_t stream);
+                                 const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
+                                 void* Z, float* d_enc, float* d_pred, hipStream_t stream);
+// dW += Z^T dH (split over the rows) and db += column sums of dH
+hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Z, const void* dH,
+                               float* dW, float* db, hipStream_t stream);
 
 }  // namespace rnnt

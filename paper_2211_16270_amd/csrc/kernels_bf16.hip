@@ -61,9 +61,7 @@ struct JointArgs {
     int s0, s1, tile0, tile1;
     // MODE 1 outputs
     bf16_t* dH;     // [chunk rows, V]
-    bf16_t* dHt;    // [V, ld]
-    bf16_t* Zt;     // [H, ld]
-    long long ld;
+    bf16_t* Z;      // [chunk rows, H]
 };
 
 
@@ -119,11 +117,6 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
                     for (int j = 0; j < 8; ++j)
                         z[j] = valid ? (bf16_t)fast_tanh((float)e[i][j] + (float)q[i][j]) : (bf16_t)0.0f;
                     *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = z;
-                    if (MODE == 1) {
-                        bf16_t* zt = a.Zt + (size_t)(c * 8) * a.ld + chunk_row0 + r;
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) zt[(size_t)j * a.ld] = z[j];
-                    }
                 }
             }
         }
@@ -152,6 +145,15 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
         }
     }
     __syncthreads();
+    if (MODE == 1) {
+        // joint tile -> Z chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM
+        const int cpr = H >> 3;
+        for (int idx = tid; idx < JT_ROWS * cpr; idx += 256) {
+            const int row = idx / cpr, ch = idx - row * cpr;
+            *reinterpret_cast<bf16x8*>(a.Z + (size_t)(chunk_row0 + row) * H + ch * 8) =
+                *reinterpret_cast<const bf16x8*>(zs + row * ZP + ch * 8);
+        }
+    }
 
     const int KK = H >> 4;
     int lab[2] = {row_lab[l32], row_lab[32 + l32]};
@@ -286,12 +288,6 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
                 bf16_t dbf[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) dbf[i] = (bf16_t)d[i];
-                // transposed copy dHt[v][row]: consecutive lanes are consecutive rows
-                {
-                    bf16_t* o = a.dHt + (size_t)(vbase + 4 * hb) * a.ld + chunk_row0 + rt * 32 + l32;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o[(size_t)(8 * (i >> 2) + (i & 3)) * a.ld] = dbf[i];
-                }
                 // row-major copy dH[row][v] through this wave's 32x32 transposition buffer
                 {
                     bf16_t* sw = stg + wave * (32 * STG_PITCH);
@@ -369,14 +365,14 @@ static hipError_t launch_joint(const JointArgs& a, hipStream_t stream) {
 
 hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st, const LatticeState& ls,
                            int s0, int s1, int tile0, int tile1, hipStream_t stream) {
-    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr, nullptr, 0};
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr};
     return launch_joint<0>(a, stream);
 }
 
 hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                                   const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
-                                  void* dHt, void* Zt, long long ld, hipStream_t stream) {
-    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)dH, (bf16_t*)dHt, (bf16_t*)Zt, ld};
+                                  void* Z, hipStream_t stream) {
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)dH, (bf16_t*)Z};
     return launch_joint<1>(a, stream);
 }
 
@@ -568,20 +564,23 @@ hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0,
 }
 
 // ------------------------------------------------------------------------------------------------
-// dW += Zt dHt^T and db += row sums of dHt (Alg. 1 line 8) as one split-K GEMM with 256x256 tiles.
+// dW += Z^T dH and db += column sums of dH (Alg. 1 line 8) as one split-K GEMM with 256x256 tiles.
 // 512 threads = 8 waves in 2 (hidden) x 4 (vocabulary); each wave owns 128 x 64 = 4 x 2 accumulator
-// tiles.  A = Zt [H,ld], B = dHt [V,ld], contraction over the chunk's rows, blockIdx.z = K split.
+// tiles.  Both operands are row-major with the contraction index (the chunk's rows) as the slow one:
+// Z [rows,H], dH [rows,V].  A K step of 64 rows is staged in LDS as it lies in memory ([row][column],
+// 16-byte chunks XOR-swizzled by 2*(row%4)); MFMA fragments, which need 8 consecutive rows of one
+// column per lane, come from the transposing LDS read (ds_read_b64_tr_b16): within 16 lanes, lane
+// 4j+c supplies 4 columns of row j and lane i receives rows 0..3 of column i.
 // The workgroups of the first hidden-tile row also sum their B fragments over the rows (the bias
 // gradient) with packed bf16 dot products against ones.
 // ------------------------------------------------------------------------------------------------
-constexpr int WT = 256;
-constexpr int WK = 64;        // K step
-constexpr int WP = 72;        // LDS row pitch in bf16 elements (144 B: conflict-free 16 B reads)
+constexpr int WT = 256;       // tile edge
+constexpr int WK = 64;        // rows per K step
 
 struct DwArgs {
-    const bf16_t* Zt;
-    const bf16_t* dHt;
-    long long ld, K, k_per_split;
+    const bf16_t* Z;
+    const bf16_t* dH;
+    long long K, k_per_split;
     float* dW;
     float* db;
     int H, V;
@@ -589,16 +588,26 @@ struct DwArgs {
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ bf16x8 lds_read_tr_frag(const bf16_t* p) {
+    // rows +0..3 and +4..7 of this lane's column: two transposing reads, 4 rows (= 4*256 elements) apart
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * WT));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
 
 __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
     extern __shared__ __align__(16) unsigned char dw_smem[];
-    bf16_t(*As)[WT * WP] = reinterpret_cast<bf16_t(*)[WT * WP]>(dw_smem);
-    bf16_t(*Bs)[WT * WP] = reinterpret_cast<bf16_t(*)[WT * WP]>(dw_smem + (size_t)2 * WT * WP * 2);
+    bf16_t(*As)[WK * WT] = reinterpret_cast<bf16_t(*)[WK * WT]>(dw_smem);
+    bf16_t(*Bs)[WK * WT] = reinterpret_cast<bf16_t(*)[WK * WT]>(dw_smem + (size_t)2 * WK * WT * 2);
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
     const int wm = wave >> 2, wn = wave & 3;
     // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  All output tiles of
-    // one K split read the same rows of Zt and dHt, so they are mapped to the same XCD (ids that
+    // one K split read the same rows of Z and dH, so they are mapped to the same XCD (ids that
     // agree modulo 8) and adjacent in its dispatch order: the rows then come from HBM once.
     const int ntile = g.mt * g.nt;
     const int L = blockIdx.x, xcd = L & 7, q = L >> 3;
@@ -609,32 +618,49 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
     const long long ke = ks + g.k_per_split < g.K ? ks + g.k_per_split : g.K;
     if (ks >= ke) return;
     const bool do_db = (bm == 0) && (wm == 0);
-    const int lrow = tid >> 3, lseg = tid & 7;          // rows lrow + 64*i, i = 0..3; 8 segments of 16 B
-    // rows of A beyond H (H not a multiple of 256) are read from row H-1 and never stored
-    const bf16_t* Ag[4];
-    const bf16_t* Bg[4];
+
+    // global -> LDS staging: thread = 16-byte chunk (tid%32) of rows tid/32 + 16*i
+    const int lch = tid & 31, lrow = tid >> 5;
+    long long acol = m0 + lch * 8;
+    if (acol > g.H - 8) acol = g.H - 8;          // columns beyond H (H not a multiple of 256): never stored
+    const bf16_t* Ag = g.Z + (ks + lrow) * (long long)g.H + acol;
+    const bf16_t* Bg = g.dH + (ks + lrow) * (long long)g.V + n0 + lch * 8;
+    int soff[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        long long ar = m0 + lrow + 64 * i;
-        if (ar >= g.H) ar = g.H - 1;
-        Ag[i] = g.Zt + ar * g.ld + lseg * 8;
-        Bg[i] = g.dHt + (n0 + lrow + 64 * i) * g.ld + lseg * 8;
+        const int row = lrow + 16 * i;
+        soff[i] = row * WT + ((lch ^ ((row & 3) << 1)) << 3);
     }
     bf16x8 ra[4], rb[4];
     auto gload = [&](long long k0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            ra[i] = *reinterpret_cast<const bf16x8*>(Ag[i] + k0);
-            rb[i] = *reinterpret_cast<const bf16x8*>(Bg[i] + k0);
+            ra[i] = *reinterpret_cast<const bf16x8*>(Ag + (k0 + 16 * i) * g.H);
+            rb[i] = *reinterpret_cast<const bf16x8*>(Bg + (k0 + 16 * i) * g.V);
         }
     };
     auto sstore = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<bf16x8*>(&As[buf][(lrow + 64 * i) * WP + lseg * 8]) = ra[i];
-            *reinterpret_cast<bf16x8*>(&Bs[buf][(lrow + 64 * i) * WP + lseg * 8]) = rb[i];
+            *reinterpret_cast<bf16x8*>(&As[buf][soff[i]]) = ra[i];
+            *reinterpret_cast<bf16x8*>(&Bs[buf][soff[i]]) = rb[i];
         }
     };
+    // fragment addresses: lane = 16 g + 4 j + c supplies row 8*(g/2) + j, columns 16*(g%2) + 4c .. +3
+    const int fg = lane >> 4, fj = (lane >> 2) & 3, fc = lane & 3;
+    const int frow = 8 * (fg >> 1) + fj;
+    int aoff[4], boff[2];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const int col = wm * 128 + mt * 32 + 16 * (fg & 1) + 4 * fc;
+        aoff[mt] = frow * WT + (((col >> 3) ^ (fj << 1)) << 3) + (col & 7);
+    }
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int col = wn * 64 + nt * 32 + 16 * (fg & 1) + 4 * fc;
+        boff[nt] = frow * WT + (((col >> 3) ^ (fj << 1)) << 3) + (col & 7);
+    }
+
     f32x16 acc[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -643,31 +669,30 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
     float dbs[2] = {0.0f, 0.0f};
     const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 
-    gload(ks);
+    gload(0);
     sstore(0);
     __syncthreads();
     int buf = 0;
-    for (long long k0 = ks; k0 < ke; k0 += WK) {
-        const bool more = (k0 + WK < ke);
+    const long long klen = ke - ks;
+    for (long long k0 = 0; k0 < klen; k0 += WK) {
+        const bool more = (k0 + WK < klen);
         if (more) gload(k0 + WK);
-        const bf16_t* as = &As[buf][(wm * 128 + l32) * WP + hb * 8];
-        const bf16_t* bs = &Bs[buf][(wn * 64 + l32) * WP + hb * 8];
+        const bf16_t* as = &As[buf][0];
+        const bf16_t* bs = &Bs[buf][0];
         // fragments are read one k16-step ahead of the MFMAs that consume them (two register sets)
         bf16x8 fa[2][4], fb[2][2];
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) fa[0][mt] = *reinterpret_cast<const bf16x8*>(as + mt * 32 * WP);
+        for (int mt = 0; mt < 4; ++mt) fa[0][mt] = lds_read_tr_frag(as + aoff[mt]);
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) fb[0][nt] = *reinterpret_cast<const bf16x8*>(bs + nt * 32 * WP);
+        for (int nt = 0; nt < 2; ++nt) fb[0][nt] = lds_read_tr_frag(bs + boff[nt]);
 #pragma unroll
         for (int kk = 0; kk < WK / 16; ++kk) {
             const int cur = kk & 1, nxt = cur ^ 1;
             if (kk + 1 < WK / 16) {
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-                    fa[nxt][mt] = *reinterpret_cast<const bf16x8*>(as + mt * 32 * WP + (kk + 1) * 16);
+                for (int mt = 0; mt < 4; ++mt) fa[nxt][mt] = lds_read_tr_frag(as + aoff[mt] + (kk + 1) * 16 * WT);
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    fb[nxt][nt] = *reinterpret_cast<const bf16x8*>(bs + nt * 32 * WP + (kk + 1) * 16);
+                for (int nt = 0; nt < 2; ++nt) fb[nxt][nt] = lds_read_tr_frag(bs + boff[nt] + (kk + 1) * 16 * WT);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -679,8 +704,8 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const bf16x2 pr2 = {fb[cur][nt][2 * q], fb[cur][nt][2 * q + 1]};
+                    for (int q2 = 0; q2 < 4; ++q2) {
+                        const bf16x2 pr2 = {fb[cur][nt][2 * q2], fb[cur][nt][2 * q2 + 1]};
                         dbs[nt] = __builtin_amdgcn_fdot2_f32_bf16(pr2, ones, dbs[nt], false);
                     }
             }
@@ -713,13 +738,13 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
     }
 }
 
-hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, const void* dHt, long long ld,
-                               float* dW, float* db, hipStream_t stream) {
+hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Z, const void* dH, float* dW, float* db,
+                               hipStream_t stream) {
     if (rows <= 0) return hipSuccess;
     const long long mt = (H + WT - 1) / WT, nt = V / WT;
-    DwArgs g{(const bf16_t*)Zt, (const bf16_t*)dHt, ld, rows, 0, dW, db, H, V, (int)mt, (int)nt};
-    // one workgroup per CU and K split: aim at two rounds over 256 CUs, at least 256 rows per split
-    long long splits = (512 + mt * nt - 1) / (mt * nt);
+    DwArgs g{(const bf16_t*)Z, (const bf16_t*)dH, rows, 0, dW, db, H, V, (int)mt, (int)nt};
+    // one workgroup per CU and K split: aim at one round over 256 CUs (fewer splits, fewer atomics), at least 256 rows per split
+    long long splits = (256 + mt * nt - 1) / (mt * nt);
     const long long max_splits = (rows + 255) / 256;
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
@@ -727,7 +752,7 @@ hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Zt, con
     per = (per + WK - 1) / WK * WK;
     splits = (rows + per - 1) / per;
     g.k_per_split = per;
-    const size_t smem = (size_t)4 * WT * WP * 2;
+    const size_t smem = (size_t)4 * WK * WT * 2;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_dw256),

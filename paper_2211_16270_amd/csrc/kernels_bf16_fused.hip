@@ -3,8 +3,8 @@
 //   scores recomputed on MFMA, dh = gamma * softmax - posteriors               (Eq. 6, f^W_4)
 //   dz = dh W_out^T accumulated over the whole vocabulary in registers           (Alg. 1 lines 10, 11)
 //   dx = dz (1 - z^2), summed over the tile's label positions / frames, added to d_enc / d_pred
-// and dh (transposed, bf16) plus z (transposed, bf16) written out for the dW_out GEMM.
-// The score gradient never exists in row-major form in HBM and is not re-read for dz.
+// and dh (bf16) plus z (bf16) written out row-major, straight from their LDS tiles, for the dW_out
+// GEMM.  The score gradient is not re-read for dz.
 //
 // 512 threads = 8 waves, one workgroup per CU.
 //  Phase 1, per step of 512 vocabulary entries: wave w owns entries [64w, 64w+64) for all 64 rows
@@ -51,9 +51,8 @@ struct FusedArgs {
     const bf16_t* Wp;   // fragment-major W_out^T (phase 1)
     const bf16_t* Wq;   // fragment-major W_out   (phase 2)
     int s0, s1, tile0, tile1;
-    bf16_t* dHt;        // [V, ld]
-    bf16_t* Zt;         // [H, ld]
-    long long ld;
+    bf16_t* dH;         // [chunk rows, V]
+    bf16_t* Z;          // [chunk rows, H]
     float* d_enc;
     float* d_pred;
 };
@@ -104,10 +103,6 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
                     for (int j = 0; j < 8; ++j)
                         z[j] = valid ? (bf16_t)fast_tanh((float)e[i][j] + (float)q[i][j]) : (bf16_t)0.0f;
                     *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = z;
-                    // wave-uniform row base (scalar registers) + lane offset r
-                    bf16_t* zt = a.Zt + (size_t)(c * 8) * a.ld + chunk_row0;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) (zt + (size_t)j * a.ld)[r] = z[j];
                 }
             }
         }
@@ -135,6 +130,15 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         }
     }
     __syncthreads();
+    // joint tile -> Z chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM
+    {
+        const int cpr = H >> 3;                              // 16-byte chunks per row
+        for (int idx = tid; idx < FB_ROWS * cpr; idx += 512) {
+            const int row = idx / cpr, ch = idx - row * cpr;
+            *reinterpret_cast<bf16x8*>(a.Z + (size_t)(chunk_row0 + row) * H + ch * 8) =
+                *reinterpret_cast<const bf16x8*>(zs + row * ZP + ch * 8);
+        }
+    }
 
     const int KK = H >> 4;             // k16-steps of the score GEMM
     const int VK = V >> 4;             // k16-steps of the dz GEMM (whole vocabulary)
@@ -243,35 +247,38 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
                         d[i] = __builtin_amdgcn_exp2f(fmaf(acc[vt][rt][i], LOG2E_F, gexp[rt]));
-                    // transposed store dHt[v][row]: wave-uniform base per vocabulary entry + 32-bit lane offset
-                    bf16_t* ob = a.dHt + (size_t)vbase * a.ld + chunk_row0 + rt * 32;
-                    const unsigned lane_off = (unsigned)(4 * hb) * (unsigned)a.ld + (unsigned)l32;
                     bf16_t* sd = dhs + (rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + 4 * hb;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         bf16x4 q4 = {(bf16_t)d[4 * j], (bf16_t)d[4 * j + 1], (bf16_t)d[4 * j + 2], (bf16_t)d[4 * j + 3]};
                         *reinterpret_cast<bf16x4*>(sd + 8 * j) = q4;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) (ob + (size_t)(8 * j + i) * a.ld)[lane_off] = q4[i];
                     }
                     // the lane that holds the blank / label entry of its row overwrites it (same lane,
-                    // same addresses, program order): entry rel lives in lane half (rel/4)%2
+                    // same address, program order): entry rel lives in lane half (rel/4)%2
                     const bool own_b = ((unsigned)relb < 32u) && (((relb >> 2) & 1) == hb);
                     const bool own_y = ((unsigned)rely < 32u) && (((rely >> 2) & 1) == hb);
                     if (own_b) {
                         const bf16_t v = (bf16_t)Bk[rt];
                         dhs[(rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + relb] = v;
-                        (a.dHt + (size_t)(vbase + relb) * a.ld + chunk_row0 + rt * 32)[l32] = v;
                     }
                     if (own_y) {
                         const bf16_t v = (bf16_t)Yk[rt];
                         dhs[(rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + rely] = v;
-                        (a.dHt + (size_t)(vbase + rely) * a.ld + chunk_row0 + rt * 32)[l32] = v;
                     }
                 }
             }
         }
         __syncthreads();    // the dh tile of this step is complete
+        // dh tile -> dH chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM
+        {
+            const int cpr = nact * 8;                        // 16-byte chunks per row in this step
+            bf16_t* o = a.dH + (size_t)chunk_row0 * V + vs * FB_VSTEP;
+            for (int idx = tid; idx < FB_ROWS * cpr; idx += 512) {
+                const int row = idx / cpr, ch = idx - row * cpr;
+                *reinterpret_cast<bf16x8*>(o + (size_t)row * V + ch * 8) =
+                    *reinterpret_cast<const bf16x8*>(dhs + row * FB_DP + ch * 8);
+            }
+        }
         // -------- phase 2: dz += dh W^T over the nact*64 vocabulary entries of this step
         {
             const int nb2 = nact;                      // blocks of 4 k16-steps
@@ -367,11 +374,11 @@ static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const void* Wq, const SampleTable& st,
-                                 const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dHt, void* Zt,
-                                 long long ld, float* d_enc, float* d_pred, hipStream_t stream) {
+                                 const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH, void* Z,
+                                 float* d_enc, float* d_pred, hipStream_t stream) {
     if (tile1 <= tile0) return hipSuccess;
     FusedArgs a{pr, st, ls, (const bf16_t*)Wpack, (const bf16_t*)Wq, s0, s1, tile0, tile1,
-                (bf16_t*)dHt, (bf16_t*)Zt, ld, d_enc, d_pred};
+                (bf16_t*)dH, (bf16_t*)Z, d_enc, d_pred};
     const int ht = (pr.H / 32 + 7) / 8;
     if (ht <= 1) return launch_fused_t<1>(a, stream);
     if (ht == 2) return launch_fused_t<2>(a, stream);
