@@ -567,15 +567,17 @@ hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0,
 // dW += Z^T dH and db += column sums of dH (Alg. 1 line 8) as one split-K GEMM with 256x256 tiles.
 // 512 threads = 8 waves in 2 (hidden) x 4 (vocabulary); each wave owns 128 x 64 = 4 x 2 accumulator
 // tiles.  Both operands are row-major with the contraction index (the chunk's rows) as the slow one:
-// Z [rows,H], dH [rows,V].  A K step of 64 rows is staged in LDS as it lies in memory ([row][column],
-// 16-byte chunks XOR-swizzled by 2*(row%4)); MFMA fragments, which need 8 consecutive rows of one
-// column per lane, come from the transposing LDS read (ds_read_b64_tr_b16): within 16 lanes, lane
-// 4j+c supplies 4 columns of row j and lane i receives rows 0..3 of column i.
+// Z [rows,H], dH [rows,V].  Stages of 32 rows travel global -> LDS asynchronously (global_load_lds, no
+// registers), four stages deep, and lie in LDS as in memory ([row][column], 16-byte chunks
+// XOR-swizzled by 2*(row%4)); MFMA fragments, which need 8 consecutive rows of one column per lane,
+// come from the transposing LDS read (ds_read_b64_tr_b16): within 16 lanes, lane 4j+c supplies 4
+// columns of row j and lane i receives rows 0..3 of column i.
 // The workgroups of the first hidden-tile row also sum their B fragments over the rows (the bias
 // gradient) with packed bf16 dot products against ones.
 // ------------------------------------------------------------------------------------------------
 constexpr int WT = 256;       // tile edge
-constexpr int WK = 64;        // rows per K step
+constexpr int WK = 32;        // rows per pipeline stage
+constexpr int WST = 4;        // pipeline stages (LDS buffers)
 
 struct DwArgs {
     const bf16_t* Z;
@@ -599,10 +601,15 @@ __device__ __forceinline__ bf16x8 lds_read_tr_frag(const bf16_t* p) {
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// Asynchronous global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane l's 16 bytes land
+// at LDS byte address lds_base + 16*l (lds_base wave-uniform, passed in M0).  Completion is tracked by
+// the wave's vmcnt counter; the compiler does not see these loads, so the waits are explicit below.
+__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+
 __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
-    extern __shared__ __align__(16) unsigned char dw_smem[];
-    bf16_t(*As)[WK * WT] = reinterpret_cast<bf16_t(*)[WK * WT]>(dw_smem);
-    bf16_t(*Bs)[WK * WT] = reinterpret_cast<bf16_t(*)[WK * WT]>(dw_smem + (size_t)2 * WK * WT * 2);
+    extern __shared__ __align__(16) unsigned char dw_smem[];   // [WST] x { A [WK][256], B [WK][256] } bf16
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
     const int wm = wave >> 2, wn = wave & 3;
@@ -618,32 +625,32 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
     const long long ke = ks + g.k_per_split < g.K ? ks + g.k_per_split : g.K;
     if (ks >= ke) return;
     const bool do_db = (bm == 0) && (wm == 0);
+    constexpr unsigned STAGE_BYTES = 2u * WK * WT * 2u;
+    constexpr unsigned OPER_BYTES = (unsigned)WK * WT * 2u;
+    const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)dw_smem;
 
-    // global -> LDS staging: thread = 16-byte chunk (tid%32) of rows tid/32 + 16*i
-    const int lch = tid & 31, lrow = tid >> 5;
-    long long acol = m0 + lch * 8;
-    if (acol > g.H - 8) acol = g.H - 8;          // columns beyond H (H not a multiple of 256): never stored
-    const bf16_t* Ag = g.Z + (ks + lrow) * (long long)g.H + acol;
-    const bf16_t* Bg = g.dH + (ks + lrow) * (long long)g.V + n0 + lch * 8;
-    int soff[4];
+    // global -> LDS: one DMA instruction moves two tile rows (2 x 512 B).  Wave w moves row pairs w and
+    // w+8 of both operands.  LDS slot (row, position p) receives global chunk p ^ 2*(row%4) of that row.
+    const bf16_t* Ag[2];
+    const bf16_t* Bg[2];
+    unsigned dst[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = lrow + 16 * i;
-        soff[i] = row * WT + ((lch ^ ((row & 3) << 1)) << 3);
+    for (int i = 0; i < 2; ++i) {
+        const int row = 2 * wave + 16 * i + (lane >> 5);
+        const int ch = (lane & 31) ^ ((row & 3) << 1);
+        long long acol = m0 + ch * 8;
+        if (acol > g.H - 8) acol = g.H - 8;      // columns beyond H (H not a multiple of 256): never stored
+        Ag[i] = g.Z + (ks + row) * (long long)g.H + acol;
+        Bg[i] = g.dH + (ks + row) * (long long)g.V + n0 + ch * 8;
+        dst[i] = (unsigned)(2 * wave + 16 * i) * (WT * 2u);
     }
-    bf16x8 ra[4], rb[4];
-    auto gload = [&](long long k0) {
+    auto issue = [&](long long step) {          // stage = step % WST
+        const unsigned sb = smem_base + (unsigned)(step & (WST - 1)) * STAGE_BYTES;
+        const long long k0 = step * WK;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ra[i] = *reinterpret_cast<const bf16x8*>(Ag + (k0 + 16 * i) * g.H);
-            rb[i] = *reinterpret_cast<const bf16x8*>(Bg + (k0 + 16 * i) * g.V);
-        }
-    };
-    auto sstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<bf16x8*>(&As[buf][soff[i]]) = ra[i];
-            *reinterpret_cast<bf16x8*>(&Bs[buf][soff[i]]) = rb[i];
+        for (int i = 0; i < 2; ++i) {
+            lds_dma16(Ag[i] + k0 * g.H, __builtin_amdgcn_readfirstlane(sb + dst[i]));
+            lds_dma16(Bg[i] + k0 * g.V, __builtin_amdgcn_readfirstlane(sb + OPER_BYTES + dst[i]));
         }
     };
     // fragment addresses: lane = 16 g + 4 j + c supplies row 8*(g/2) + j, columns 16*(g%2) + 4c .. +3
@@ -658,7 +665,7 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         const int col = wn * 64 + nt * 32 + 16 * (fg & 1) + 4 * fc;
-        boff[nt] = frow * WT + (((col >> 3) ^ (fj << 1)) << 3) + (col & 7);
+        boff[nt] = WK * WT + frow * WT + (((col >> 3) ^ (fj << 1)) << 3) + (col & 7);
     }
 
     f32x16 acc[4][2];
@@ -669,30 +676,34 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
     float dbs[2] = {0.0f, 0.0f};
     const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    int buf = 0;
-    const long long klen = ke - ks;
-    for (long long k0 = 0; k0 < klen; k0 += WK) {
-        const bool more = (k0 + WK < klen);
-        if (more) gload(k0 + WK);
-        const bf16_t* as = &As[buf][0];
-        const bf16_t* bs = &Bs[buf][0];
-        // fragments are read one k16-step ahead of the MFMAs that consume them (two register sets)
+    const long long nsteps = (ke - ks) / WK;
+    // three stages in flight before the first one is consumed (4 DMA instructions per wave and stage)
+    issue(0);
+    if (nsteps > 1) issue(1);
+    if (nsteps > 2) issue(2);
+    for (long long it = 0; it < nsteps; ++it) {
+        // wait for this wave's part of stage `it` (later stages may stay in flight), then for everyone's
+        const long long ahead = nsteps - 1 - it;
+        if (ahead >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (ahead == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        // every wave is past stage it-1 now: its buffer takes stage it+3
+        if (it + 3 < nsteps) issue(it + 3);
+        const bf16_t* st = reinterpret_cast<const bf16_t*>(dw_smem + (size_t)(it & (WST - 1)) * STAGE_BYTES);
         bf16x8 fa[2][4], fb[2][2];
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) fa[0][mt] = lds_read_tr_frag(as + aoff[mt]);
+        for (int mt = 0; mt < 4; ++mt) fa[0][mt] = lds_read_tr_frag(st + aoff[mt]);
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) fb[0][nt] = lds_read_tr_frag(bs + boff[nt]);
+        for (int nt = 0; nt < 2; ++nt) fb[0][nt] = lds_read_tr_frag(st + boff[nt]);
 #pragma unroll
         for (int kk = 0; kk < WK / 16; ++kk) {
             const int cur = kk & 1, nxt = cur ^ 1;
             if (kk + 1 < WK / 16) {
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt) fa[nxt][mt] = lds_read_tr_frag(as + aoff[mt] + (kk + 1) * 16 * WT);
+                for (int mt = 0; mt < 4; ++mt) fa[nxt][mt] = lds_read_tr_frag(st + aoff[mt] + (kk + 1) * 16 * WT);
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) fb[nxt][nt] = lds_read_tr_frag(bs + boff[nt] + (kk + 1) * 16 * WT);
+                for (int nt = 0; nt < 2; ++nt) fb[nxt][nt] = lds_read_tr_frag(st + boff[nt] + (kk + 1) * 16 * WT);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -711,9 +722,6 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) sstore(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
     }
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
@@ -752,7 +760,7 @@ hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Z, cons
     per = (per + WK - 1) / WK * WK;
     splits = (rows + per - 1) / per;
     g.k_per_split = per;
-    const size_t smem = (size_t)4 * WK * WT * 2;
+    const size_t smem = (size_t)WST * 2 * WK * WT * 2;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_dw256),
