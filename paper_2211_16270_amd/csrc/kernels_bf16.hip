@@ -45,8 +45,8 @@ hipError_t launch_pack_w(const void* W, void* Wpack, int H, int V, hipStream_t s
 
 // ------------------------------------------------------------------------------------------------
 // Joint tile + score GEMM.  MODE 0: softmax statistics (forward).  MODE 1: score gradients (backward).
-// 256 threads = 4 waves; per step of 256 vocabulary entries wave w owns entries [64w, 64w+64) for
-// all 64 rows (2 x 2 accumulator tiles of 32x32).
+// NW waves; per step of 256 vocabulary entries wave w owns NVT tiles of 32 entries for all 64 rows
+// (NVT x 2 accumulator tiles of 32x32).
 // ------------------------------------------------------------------------------------------------
 constexpr int JT_ROWS = 64;
 constexpr int JT_VSTEP = 256;
@@ -65,8 +65,10 @@ struct JointArgs {
 };
 
 
-template <int MODE>
-__global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
+template <int MODE, int NW, int NVT>
+__global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
+    static_assert(NW * NVT * 32 == JT_VSTEP, "waves x tiles must cover one vocabulary step");
+    constexpr int NT = 64 * NW;
     extern __shared__ __align__(16) unsigned char smem[];
     const int H = a.pr.H, V = a.pr.V;
     const int ZP = H + 8;                                   // padded row pitch of the joint tile
@@ -77,9 +79,9 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
     float* row_f0 = reinterpret_cast<float*>(row_lab + 64); // MODE 0: cap_b   MODE 1: exponent offset
     float* row_f1 = row_f0 + 64;                            // MODE 0: cap_y   MODE 1: Bk
     float* row_f2 = row_f1 + 64;                            // MODE 1: Yk
-    float* red_m = row_f2 + 64;                             // MODE 0: [8][64] partial maxima
-    float* red_s = red_m + 512;                             // MODE 0: [8][64] partial sums
-    bf16_t* stg = reinterpret_cast<bf16_t*>(row_f2 + 64);   // MODE 1: [4][32][STG_PITCH] (aliases red_*)
+    float* red_m = row_f2 + 64;                             // MODE 0: [2 NW][64] partial maxima
+    float* red_s = red_m + 2 * NW * 64;                     // MODE 0: [2 NW][64] partial sums
+    bf16_t* stg = reinterpret_cast<bf16_t*>(row_f2 + 64);   // MODE 1: [NW][32][STG_PITCH] (aliases red_*)
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
@@ -92,26 +94,26 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
     {
         const bf16_t* enc = reinterpret_cast<const bf16_t*>(a.pr.enc) + (size_t)b * a.pr.T_max * H;
         const bf16_t* prd = reinterpret_cast<const bf16_t*>(a.pr.pred) + (size_t)b * (a.pr.U_max + 1) * H;
-        // thread -> row r = tid % 64 and the 8-element column chunks c = tid/64 + 4*i; the loads of
-        // 8 chunks are issued together so that only H/256 memory latencies are exposed
+        // thread -> row r = tid % 64 and the 8-element column chunks c = tid/64 + NW*i; the loads of
+        // 8 chunks are issued together so that few memory latencies are exposed
         const int r = tid & 63;
         const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
         const bool valid = (t < tp.T && u <= tp.U);
         const bf16_t* er = enc + (size_t)(valid ? t : 0) * H;
         const bf16_t* qr = prd + (size_t)(valid ? u : 0) * H;
-        const int nch = H >> 5;                              // chunks per thread
+        const int nch = (H >> 3) / NW;                       // chunks per thread
         for (int i0 = 0; i0 < nch; i0 += 8) {
             bf16x8 e[8], q[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int c = (tid >> 6) + 4 * ((i0 + i < nch) ? i0 + i : 0);
+                const int c = (tid >> 6) + NW * ((i0 + i < nch) ? i0 + i : 0);
                 e[i] = *reinterpret_cast<const bf16x8*>(er + c * 8);
                 q[i] = *reinterpret_cast<const bf16x8*>(qr + c * 8);
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 if (i0 + i < nch) {
-                    const int c = (tid >> 6) + 4 * (i0 + i);
+                    const int c = (tid >> 6) + NW * (i0 + i);
                     bf16x8 z;
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
@@ -148,7 +150,7 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
     if (MODE == 1) {
         // joint tile -> Z chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM
         const int cpr = H >> 3;
-        for (int idx = tid; idx < JT_ROWS * cpr; idx += 256) {
+        for (int idx = tid; idx < JT_ROWS * cpr; idx += NT) {
             const int row = idx / cpr, ch = idx - row * cpr;
             *reinterpret_cast<bf16x8*>(a.Z + (size_t)(chunk_row0 + row) * H + ch * 8) =
                 *reinterpret_cast<const bf16x8*>(zs + row * ZP + ch * 8);
@@ -170,71 +172,92 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
     const bf16_t* zrow0 = zs + l32 * ZP + hb * 8;
     const bf16_t* zrow1 = zs + (32 + l32) * ZP + hb * 8;
 
-    // Main loop.  Per step of 256 vocabulary entries wave w owns entries [64w, 64w+64) for all 64
-    // rows: 2 x 2 accumulator tiles, so every fragment feeds two MFMAs.  A fragments (W_out^T) stream
-    // from L2 through a ring of JT_PF register sets per tile: the fragments of the next block of JT_PF
-    // k16-steps (possibly of the next vocabulary step) are requested while the current block is
-    // multiplied.  B fragments (joint tile, LDS) are read one k16-step ahead of their MFMAs; the
-    // scheduling barriers keep the compiler from sinking these reads back to their first use.
+    // Main loop.  Per step of 256 vocabulary entries wave w owns NVT tiles of 32 entries for all 64
+    // rows (NVT x 2 accumulator tiles).  VALU instructions do not overlap with MFMAs on this
+    // hardware, so the loop is written to contain almost none: A fragments (W_out^T) stream from L2
+    // with scalar base + lane offset + immediate addressing into the register set that is not being
+    // consumed (two sets, blocks of JT_PF k16-steps, one block ahead, possibly into the next
+    // vocabulary step); B fragments (joint tile, LDS) are read one k16-step ahead with immediate
+    // offsets from a per-block pointer.  Scheduling barriers keep the reads ahead of the MFMAs.
     const int nvs = V / JT_VSTEP;
-    const int nkb = KK / JT_PF;
-    auto block_ptr = [&](int vs_, int vt_, int kb_) {
-        return reinterpret_cast<const bf16x8*>(a.Wp) +
-               ((size_t)(vs_ * (JT_VSTEP / 32) + wave * 2 + vt_) * KK + kb_ * JT_PF) * 64 + lane;
+    const int nkb = KK / JT_PF;                       // even: H is a multiple of 128
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const char* wpb = reinterpret_cast<const char*>(a.Wp);
+    const unsigned lane_b = (unsigned)lane * 16u;
+    auto block_off = [&](int vs_, int vt_, int kb_) -> size_t {
+        return ((size_t)(vs_ * (JT_VSTEP / 32) + wv * NVT + vt_) * KK + (size_t)kb_ * JT_PF) * 1024;
     };
-    bf16x8 ring[2][JT_PF];
+    auto load_frag = [&](size_t boff, int j) {
+        return *reinterpret_cast<const bf16x8*>(wpb + boff + j * 1024 + lane_b);
+    };
+    bf16x8 ring[2][NVT][JT_PF];
 #pragma unroll
-    for (int vt = 0; vt < 2; ++vt) {
-        const bf16x8* p0 = block_ptr(0, vt, 0);
+    for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
-        for (int j = 0; j < JT_PF; ++j) ring[vt][j] = p0[j * 64];
-    }
+        for (int j = 0; j < JT_PF; ++j) ring[0][vt][j] = load_frag(block_off(0, vt, 0), j);
     bf16x8 bc[2] = {*reinterpret_cast<const bf16x8*>(zrow0), *reinterpret_cast<const bf16x8*>(zrow1)};
+    const bf16_t* zc0 = zrow0;                        // joint-tile pointers of the current block
+    const bf16_t* zc1 = zrow1;
 
     for (int vs = 0; vs < nvs; ++vs) {
-        f32x16 acc[2][2];
+        // accumulators start from the bias of their 16 vocabulary entries: v = vbase + 8j + 4hb + i
+        f32x16 acc[NVT][2];
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
+        for (int vt = 0; vt < NVT; ++vt) {
+            const float* bp = a.pr.b_out + vs * JT_VSTEP + wave * (32 * NVT) + vt * 32 + 4 * hb;
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt) acc[vt][rt] = f32x16{0};
-        for (int kb = 0; kb < nkb; ++kb) {
-            int nvs_ = vs, nkb_ = kb + 1;
-            if (nkb_ == nkb) { nkb_ = 0; nvs_ = vs + 1; }
-            if (nvs_ == nvs) { nvs_ = vs; nkb_ = kb; }
-            const bf16x8* pn0 = block_ptr(nvs_, 0, nkb_);
-            const bf16x8* pn1 = block_ptr(nvs_, 1, nkb_);
+            for (int j = 0; j < 4; ++j) {
+                const f32x4 t4 = *reinterpret_cast<const f32x4*>(bp + 8 * j);
 #pragma unroll
-            for (int j = 0; j < JT_PF; ++j) {
-                const int kk = kb * JT_PF + j;
-                int kn = kk + 1;
-                if (kn == KK) kn = 0;
-                const bf16x8 a0 = ring[0][j], a1 = ring[1][j];
-                bf16x8 bn[2];
-                bn[0] = *reinterpret_cast<const bf16x8*>(zrow0 + kn * 16);
-                bn[1] = *reinterpret_cast<const bf16x8*>(zrow1 + kn * 16);
-                ring[0][j] = pn0[j * 64];
-                ring[1][j] = pn1[j * 64];
-                __builtin_amdgcn_sched_barrier(0);
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bc[0], acc[0][0], 0, 0, 0);
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bc[1], acc[0][1], 0, 0, 0);
-                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bc[0], acc[1][0], 0, 0, 0);
-                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bc[1], acc[1][1], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                bc[0] = bn[0];
-                bc[1] = bn[1];
+                for (int i = 0; i < 4; ++i) {
+                    acc[vt][0][4 * j + i] = t4[i];
+                    acc[vt][1][4 * j + i] = t4[i];
+                }
+            }
+        }
+        for (int kb2 = 0; kb2 < nkb; kb2 += 2) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int kb = kb2 + half;
+                const int cs = half, ns = half ^ 1;   // register sets: consumed / being filled
+                int nvs_ = vs, nkb_ = kb + 1;
+                if (nkb_ == nkb) { nkb_ = 0; nvs_ = vs + 1; }
+                if (nvs_ == nvs) { nvs_ = vs; nkb_ = kb; }
+                size_t noff[NVT];
+#pragma unroll
+                for (int vt = 0; vt < NVT; ++vt) noff[vt] = block_off(nvs_, vt, nkb_);
+                const int knext = (kb + 1 == nkb) ? 0 : (kb + 1) * JT_PF * 16;
+                const bf16_t* zn0 = zrow0 + knext;
+                const bf16_t* zn1 = zrow1 + knext;
+#pragma unroll
+                for (int j = 0; j < JT_PF; ++j) {
+                    bf16x8 bn[2];
+                    if (j + 1 < JT_PF) {
+                        bn[0] = *reinterpret_cast<const bf16x8*>(zc0 + (j + 1) * 16);
+                        bn[1] = *reinterpret_cast<const bf16x8*>(zc1 + (j + 1) * 16);
+                    } else {
+                        bn[0] = *reinterpret_cast<const bf16x8*>(zn0);
+                        bn[1] = *reinterpret_cast<const bf16x8*>(zn1);
+                    }
+#pragma unroll
+                    for (int vt = 0; vt < NVT; ++vt) ring[ns][vt][j] = load_frag(noff[vt], j);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int vt = 0; vt < NVT; ++vt) {
+                        acc[vt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[cs][vt][j], bc[0], acc[vt][0], 0, 0, 0);
+                        acc[vt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[cs][vt][j], bc[1], acc[vt][1], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    bc[0] = bn[0];
+                    bc[1] = bn[1];
+                }
+                zc0 = zn0;
+                zc1 = zn1;
             }
         }
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt) {
-        const int vbase = vs * JT_VSTEP + wave * 64 + vt * 32;
-        // bias of this lane's 16 vocabulary entries: v = vbase + 8j + 4hb + i
-        float bv[16];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const f32x4 t4 = *reinterpret_cast<const f32x4*>(a.pr.b_out + vbase + 8 * j + 4 * hb);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) bv[4 * j + i] = t4[i];
-        }
+        for (int vt = 0; vt < NVT; ++vt) {
+        const int vbase = vs * JT_VSTEP + wave * (32 * NVT) + vt * 32;
         const int relb = a.pr.blank - vbase;
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) {
@@ -248,7 +271,7 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
                 float tmax = RNNT_NEG_INF;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    x[i] = accv[i] + bv[i];
+                    x[i] = accv[i];
                     tmax = fmaxf(tmax, x[i]);
                 }
                 const float mn = fmaxf(m_run[rt], tmax);
@@ -276,7 +299,7 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
                 float d[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    d[i] = __builtin_amdgcn_exp2f(fmaf(accv[i] + bv[i], LOG2E_F, gexp[rt]));
+                    d[i] = __builtin_amdgcn_exp2f(fmaf(accv[i], LOG2E_F, gexp[rt]));
                 if (slow) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
@@ -314,7 +337,7 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
     }
 
     if (MODE == 0) {
-        // combine the 8 partial (max, sum) pairs of every row, then lse, lpb, lpy
+        // combine the 2 NW partial (max, sum) pairs of every row, then lse, lpb, lpy
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) {
             red_m[(wave * 2 + hb) * 64 + rt * 32 + l32] = m_run[rt];
@@ -327,10 +350,10 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
             if (idx >= 0) {
                 float M = RNNT_NEG_INF;
 #pragma unroll
-                for (int p = 0; p < 8; ++p) M = fmaxf(M, red_m[p * 64 + r]);
+                for (int p = 0; p < 2 * NW; ++p) M = fmaxf(M, red_m[p * 64 + r]);
                 float S = 0.0f;
 #pragma unroll
-                for (int p = 0; p < 8; ++p) S += red_s[p * 64 + r] * __expf(red_m[p * 64 + r] - M);
+                for (int p = 0; p < 2 * NW; ++p) S += red_s[p * 64 + r] * __expf(red_m[p * 64 + r] - M);
                 const float lse = M + __logf(S);
                 a.ls.lse[idx] = lse;
                 a.ls.lpb[idx] = row_f0[r] - lse;
@@ -340,40 +363,41 @@ __global__ __launch_bounds__(256, 2) void k_joint_scores(JointArgs a) {
     }
 }
 
-static size_t joint_smem_bytes(int H, int mode) {
+static size_t joint_smem_bytes(int H, int mode, int nw) {
     size_t z = (size_t)JT_ROWS * (H + 8) * 2;
     size_t meta = 64 * 4 * 5;
-    size_t tail = mode == 0 ? (size_t)2 * 512 * 4 : (size_t)4 * 32 * STG_PITCH * 2;
+    size_t tail = mode == 0 ? (size_t)2 * (2 * nw * 64) * 4 : (size_t)nw * 32 * STG_PITCH * 2;
     return z + meta + tail;
 }
 
-template <int MODE>
+// Forward and unfused backward: 4 waves x two 32-entry tiles each.
+template <int MODE, int NW, int NVT>
 static hipError_t launch_joint(const JointArgs& a, hipStream_t stream) {
     const int n = a.tile1 - a.tile0;
     if (n <= 0) return hipSuccess;
-    const size_t smem = joint_smem_bytes(a.pr.H, MODE);
+    const size_t smem = joint_smem_bytes(a.pr.H, MODE, NW);
     static size_t configured = 0;
     if (smem > configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_scores<MODE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_scores<MODE, NW, NVT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         configured = smem;
     }
-    k_joint_scores<MODE><<<dim3((unsigned)n), dim3(256), smem, stream>>>(a);
+    k_joint_scores<MODE, NW, NVT><<<dim3((unsigned)n), dim3(64 * NW), smem, stream>>>(a);
     return hipGetLastError();
 }
 
 hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st, const LatticeState& ls,
                            int s0, int s1, int tile0, int tile1, hipStream_t stream) {
     JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr};
-    return launch_joint<0>(a, stream);
+    return launch_joint<0, 4, 2>(a, stream);
 }
 
 hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                                   const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
                                   void* Z, hipStream_t stream) {
     JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)dH, (bf16_t*)Z};
-    return launch_joint<1>(a, stream);
+    return launch_joint<1, 4, 2>(a, stream);
 }
 
 // ------------------------------------------------------------------------------------------------
