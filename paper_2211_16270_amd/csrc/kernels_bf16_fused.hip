@@ -161,23 +161,30 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) dz[i][rt] = f32x16{0};
 
-    // phase-2 B fragments (W_out, hidden x vocabulary): blocks of 4 k16-steps, one block ahead
-    auto wq_ptr = [&](int i, int vk) {
-        int ht = wave + 8 * i;
-        if (ht >= nht) ht = wave;      // unused slot: any valid fragment
-        return reinterpret_cast<const bf16x8*>(a.Wq) + ((size_t)ht * VK + vk) * 64 + lane;
+    // Fragment streams from L2.  VALU instructions do not overlap with MFMAs on this hardware, so both
+    // MFMA loops address their fragments as scalar base + lane offset + immediate and load into the
+    // register set that is not being consumed (two sets, one block ahead).
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned lane_b = (unsigned)lane * 16u;
+    const char* wqb = reinterpret_cast<const char*>(a.Wq);
+    const char* wpb = reinterpret_cast<const char*>(a.Wp);
+    // phase 2, B operand (W_out, hidden x vocabulary): fragment (ht, vk) at ((ht*VK + vk)*1024) bytes
+    auto wq_off = [&](int i, int vk) -> size_t {
+        int ht = wv + 8 * i;
+        if (ht >= nht) ht = wv;        // unused slot: any valid fragment
+        return ((size_t)ht * VK + vk) * 1024;
     };
-    bf16x8 ringB[HT][4];
+    auto wq_load = [&](size_t off, int j) { return *reinterpret_cast<const bf16x8*>(wqb + off + j * 1024 + lane_b); };
+    bf16x8 ringB[2][HT][4];
 #pragma unroll
     for (int i = 0; i < HT; ++i)
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) ringB[i][kk] = wq_ptr(i, 0)[kk * 64];
-
-    // phase-1 A fragments (W_out^T, vocabulary x hidden)
-    auto wp_ptr = [&](int vs_, int vt_, int kb_) {
-        return reinterpret_cast<const bf16x8*>(a.Wp) +
-               ((size_t)(vs_ * (FB_VSTEP / 32) + wave * 2 + vt_) * KK + kb_ * FB_PF) * 64 + lane;
+        for (int kk = 0; kk < 4; ++kk) ringB[0][i][kk] = wq_load(wq_off(i, 0), kk);
+    // phase 1, A operand (W_out^T, vocabulary x hidden): fragment (vt, kk) at ((vt*KK + kk)*1024) bytes
+    auto wp_off = [&](int vs_, int vt_, int kb_) -> size_t {
+        return ((size_t)(vs_ * (FB_VSTEP / 32) + wv * 2 + vt_) * KK + (size_t)kb_ * FB_PF) * 1024;
     };
+    auto wp_load = [&](size_t off, int j) { return *reinterpret_cast<const bf16x8*>(wpb + off + j * 1024 + lane_b); };
 
     for (int vs = 0; vs < nvs; ++vs) {
         const int vleft = V - vs * FB_VSTEP;
@@ -198,37 +205,47 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
                     }
                 }
             }
-            bf16x8 ringA[2][FB_PF];
+            bf16x8 ringA[2][2][FB_PF];
 #pragma unroll
-            for (int vt = 0; vt < 2; ++vt) {
-                const bf16x8* p0 = wp_ptr(vs, vt, 0);
+            for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-                for (int j = 0; j < FB_PF; ++j) ringA[vt][j] = p0[j * 64];
-            }
+                for (int j = 0; j < FB_PF; ++j) ringA[0][vt][j] = wp_load(wp_off(vs, vt, 0), j);
             bf16x8 bc[2] = {*reinterpret_cast<const bf16x8*>(zrow0), *reinterpret_cast<const bf16x8*>(zrow1)};
-            for (int kb = 0; kb < nkb; ++kb) {
-                const int nkb_ = (kb + 1 < nkb) ? kb + 1 : kb;
-                const bf16x8* pn0 = wp_ptr(vs, 0, nkb_);
-                const bf16x8* pn1 = wp_ptr(vs, 1, nkb_);
+            const bf16_t* zc0 = zrow0;
+            const bf16_t* zc1 = zrow1;
+            for (int kb2 = 0; kb2 < nkb; kb2 += 2) {
 #pragma unroll
-                for (int j = 0; j < FB_PF; ++j) {
-                    const int kk = kb * FB_PF + j;
-                    int kn = kk + 1;
-                    if (kn == KK) kn = 0;
-                    const bf16x8 a0 = ringA[0][j], a1 = ringA[1][j];
-                    bf16x8 bn[2];
-                    bn[0] = *reinterpret_cast<const bf16x8*>(zrow0 + kn * 16);
-                    bn[1] = *reinterpret_cast<const bf16x8*>(zrow1 + kn * 16);
-                    ringA[0][j] = pn0[j * 64];
-                    ringA[1][j] = pn1[j * 64];
-                    __builtin_amdgcn_sched_barrier(0);
-                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bc[0], acc[0][0], 0, 0, 0);
-                    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bc[1], acc[0][1], 0, 0, 0);
-                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bc[0], acc[1][0], 0, 0, 0);
-                    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bc[1], acc[1][1], 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    bc[0] = bn[0];
-                    bc[1] = bn[1];
+                for (int half = 0; half < 2; ++half) {
+                    const int kb = kb2 + half;
+                    const int cs = half, ns = half ^ 1;
+                    const int nkb_ = (kb + 1 < nkb) ? kb + 1 : kb;
+                    const size_t noff0 = wp_off(vs, 0, nkb_), noff1 = wp_off(vs, 1, nkb_);
+                    const int knext = (kb + 1 == nkb) ? 0 : (kb + 1) * FB_PF * 16;
+                    const bf16_t* zn0 = zrow0 + knext;
+                    const bf16_t* zn1 = zrow1 + knext;
+#pragma unroll
+                    for (int j = 0; j < FB_PF; ++j) {
+                        bf16x8 bn[2];
+                        if (j + 1 < FB_PF) {
+                            bn[0] = *reinterpret_cast<const bf16x8*>(zc0 + (j + 1) * 16);
+                            bn[1] = *reinterpret_cast<const bf16x8*>(zc1 + (j + 1) * 16);
+                        } else {
+                            bn[0] = *reinterpret_cast<const bf16x8*>(zn0);
+                            bn[1] = *reinterpret_cast<const bf16x8*>(zn1);
+                        }
+                        ringA[ns][0][j] = wp_load(noff0, j);
+                        ringA[ns][1][j] = wp_load(noff1, j);
+                        __builtin_amdgcn_sched_barrier(0);
+                        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ringA[cs][0][j], bc[0], acc[0][0], 0, 0, 0);
+                        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ringA[cs][0][j], bc[1], acc[0][1], 0, 0, 0);
+                        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ringA[cs][1][j], bc[0], acc[1][0], 0, 0, 0);
+                        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ringA[cs][1][j], bc[1], acc[1][1], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        bc[0] = bn[0];
+                        bc[1] = bn[1];
+                    }
+                    zc0 = zn0;
+                    zc1 = zn1;
                 }
             }
         }
@@ -281,39 +298,49 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         }
         // -------- phase 2: dz += dh W^T over the nact*64 vocabulary entries of this step
         {
-            const int nb2 = nact;                      // blocks of 4 k16-steps
+            const int nb2 = nact;                      // blocks of 4 k16-steps (4 or 8: even)
             const int vk0 = vs * (FB_VSTEP / 16);
             bf16x8 ac[2] = {*reinterpret_cast<const bf16x8*>(drow0), *reinterpret_cast<const bf16x8*>(drow1)};
-            for (int kb = 0; kb < nb2; ++kb) {
-                // next block of B fragments: next block of this step, else first block of the next step
-                int vkn = vk0 + (kb + 1) * 4;
-                if (vkn >= VK) vkn = vk0 + kb * 4;
-                const bf16x8* pn[HT];
+            const bf16_t* dc0 = drow0;
+            const bf16_t* dc1 = drow1;
+            for (int kb2 = 0; kb2 < nb2; kb2 += 2) {
 #pragma unroll
-                for (int i = 0; i < HT; ++i) pn[i] = wq_ptr(i, vkn);
+                for (int half = 0; half < 2; ++half) {
+                    const int kb = kb2 + half;
+                    const int cs = half, ns = half ^ 1;
+                    // next block of B fragments: next block of this step, else first block of the next step
+                    int vkn = vk0 + (kb + 1) * 4;
+                    if (vkn >= VK) vkn = vk0 + kb * 4;
+                    size_t noff[HT];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int kk = kb * 4 + j;
-                    int kn = kk + 1;
-                    if (kn == nb2 * 4) kn = 0;
-                    bf16x8 an[2];
-                    an[0] = *reinterpret_cast<const bf16x8*>(drow0 + kn * 16);
-                    an[1] = *reinterpret_cast<const bf16x8*>(drow1 + kn * 16);
-                    bf16x8 bfr[HT];
+                    for (int i = 0; i < HT; ++i) noff[i] = wq_off(i, vkn);
+                    const int knext = (kb + 1 == nb2) ? 0 : (kb + 1) * 64;
+                    const bf16_t* dn0 = drow0 + knext;
+                    const bf16_t* dn1 = drow1 + knext;
 #pragma unroll
-                    for (int i = 0; i < HT; ++i) {
-                        bfr[i] = ringB[i][j];
-                        ringB[i][j] = pn[i][j * 64];
+                    for (int j = 0; j < 4; ++j) {
+                        bf16x8 an[2];
+                        if (j + 1 < 4) {
+                            an[0] = *reinterpret_cast<const bf16x8*>(dc0 + (j + 1) * 16);
+                            an[1] = *reinterpret_cast<const bf16x8*>(dc1 + (j + 1) * 16);
+                        } else {
+                            an[0] = *reinterpret_cast<const bf16x8*>(dn0);
+                            an[1] = *reinterpret_cast<const bf16x8*>(dn1);
+                        }
+#pragma unroll
+                        for (int i = 0; i < HT; ++i) ringB[ns][i][j] = wq_load(noff[i], j);
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int i = 0; i < HT; ++i) {
+                            dz[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[0], ringB[cs][i][j], dz[i][0], 0, 0, 0);
+                            dz[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[1], ringB[cs][i][j], dz[i][1], 0, 0, 0);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        ac[0] = an[0];
+                        ac[1] = an[1];
                     }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int i = 0; i < HT; ++i) {
-                        dz[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[0], bfr[i], dz[i][0], 0, 0, 0);
-                        dz[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[1], bfr[i], dz[i][1], 0, 0, 0);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                    ac[0] = an[0];
-                    ac[1] = an[1];
+                    dc0 = dn0;
+                    dc1 = dn1;
                 }
             }
         }
