@@ -103,6 +103,20 @@ def test_bf16_edge_lattices(T_len, U_len, blank):
     assert_padding_zero(got, batch)
 
 
+@pytest.mark.parametrize("H,V", [(640, 256), (1024, 512), (256, 768)])
+def test_bf16_other_hidden_sizes(H, V):
+    # H > 512 takes the unfused backward (separate dz GEMM), H = 640 also the partial 256-wide tile of
+    # the dW GEMM; V = 768 is a vocabulary that is not a multiple of the 512-entry step
+    wl = synth.custom_workload("wide", B=3, T_max=21, U_max=11, H=H, V=V, dtype="bf16", index=115,
+                               t_rule="uniform", t_lo=5, u_rule="uniform", u_lo=1)
+    batch = synth.make_batch(wl)
+    _say("wide bf16", H, V, batch.T_len, batch.U_len)
+    got, ref = run_gpu(batch), run_oracle(batch)
+    e, errs = assert_parity(got, ref, "bf16", f"H={H} V={V}")
+    _say("errs", e, errs)
+    assert_padding_zero(got, batch)
+
+
 def test_bf16_grouping_and_chunking_do_not_change_the_result():
     batch = synth.make_batch(_mid_bf16(112, B=6))
     ref = run_oracle(batch)
