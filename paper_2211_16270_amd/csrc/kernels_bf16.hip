@@ -775,8 +775,10 @@ hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Z, cons
     if (rows <= 0) return hipSuccess;
     const long long mt = (H + WT - 1) / WT, nt = V / WT;
     DwArgs g{(const bf16_t*)Z, (const bf16_t*)dH, rows, 0, dW, db, H, V, (int)mt, (int)nt};
-    // one workgroup per CU and K split: aim at one round over 256 CUs (fewer splits, fewer atomics), at least 256 rows per split
+    // K splits: split s runs on XCD s % 8, so their number is a multiple of 8 (all XCDs busy); beyond
+    // that, about one workgroup per CU (fewer splits mean fewer atomics), at least 256 rows per split
     long long splits = (256 + mt * nt - 1) / (mt * nt);
+    splits = (splits + 7) / 8 * 8;
     const long long max_splits = (rows + 255) / 256;
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
