@@ -215,3 +215,26 @@ def test_bf16_bench_workload_full_batch_sampled_outputs():
         assert rel_grad_err(got["d_pred"][b, :U + 1], r["d_pred"]) <= tol["grad"]
     # softmax shift invariance: the bias gradient sums to zero (up to bf16 rounding of dh)
     assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-2 * float(np.abs(got["db_out"]).sum())
+
+
+def test_bf16_memory_headline_workload_sampled():
+    # 12 samples of the B=1024, T<=1000, U<=200 workload: long lattices (multi-wave lattice kernel),
+    # several backward chunks; the checker recomputes the sample with the fewest lattice nodes
+    ids = list(range(12))
+    batch = synth.make_batch("C4", sample_ids=ids)
+    got = run_gpu(batch)
+    assert np.all(np.isfinite(got["loss"]))
+    assert_padding_zero(got, batch)
+    rows = batch.T_len.astype(np.int64) * (batch.U_len + 1)
+    b = int(np.argmin(rows))
+    T, U = int(batch.T_len[b]), int(batch.U_len[b])
+    _say("C4 sample", b, T, U)
+    r = O.sample_loss_and_grads(batch.enc[b, :T], batch.pred[b, :U + 1], batch.W_out, batch.b_out,
+                                batch.labels[b, :U], 0)
+    tol = TOL["bf16"]
+    el = abs(got["loss"][b] - r["loss"]) / abs(r["loss"])
+    ee = rel_grad_err(got["d_enc"][b, :T], r["d_enc"])
+    ep = rel_grad_err(got["d_pred"][b, :U + 1], r["d_pred"])
+    _say("C4 sample errs", el, ee, ep)
+    assert el <= tol["loss"] and ee <= tol["grad"] and ep <= tol["grad"]
+    assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-2 * float(np.abs(got["db_out"]).sum())
