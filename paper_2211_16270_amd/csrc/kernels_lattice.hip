@@ -176,9 +176,50 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
 }
 
 // Same recursion for lattices with at most 64 label positions (U + 1 <= 64): one wavefront per
-// (sample, direction), no LDS and no barrier; the neighbouring column arrives by a lane shift.
+// (sample, direction), no barrier; the neighbouring column arrives by a lane shift.
+//
+// The emission log-probabilities reach the recursion through LDS: rows are staged in blocks of
+// LW_RB lattice frames by asynchronous global -> LDS copies, one block ahead of the block the
+// sweep is in, so the sequential steps wait for LDS reads only, never for global memory.  The ring keeps LW_NB blocks; a step touches frames k-U-1 .. k (in sweep order), i.e. at
+// most the current block and the two before it.
+constexpr int LW_RB = 32;                 // frames per staged block
+constexpr int LW_NB = 4;                  // blocks in the ring
+constexpr int LW_SLOT = LW_RB * 64;       // floats per block slot (row stride U+1 <= 64)
+
+// Value of lane l-1 (lane 0 keeps its own) / lane l+1 (lane 63 keeps its own): whole-wavefront
+// shifts on the data-parallel-primitive path of v_mov, no LDS round trip.
+__device__ __forceinline__ float lane_from_below(float v) {
+    const int x = __float_as_int(v);
+    return __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x138 /* wave_shr:1 */, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_from_above(float v) {
+    const int x = __float_as_int(v);
+    return __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x130 /* wave_shl:1 */, 0xf, 0xf, false));
+}
+
+// ln(e^a + e^b) on the hardware exp2/log2 units; either may be -inf.  The argument of the logarithm
+// lies in [1, 2], so no range fix-up is needed.
+__device__ __forceinline__ float log_add_exp_fast(float a, float b) {
+    const float m = fmaxf(a, b);
+    const float d = -fabsf(a - b);                          // -inf when exactly one is -inf, NaN when both
+    const float e = __builtin_amdgcn_exp2f(d * 1.44269504088896340736f);
+    const float r = fmaf(__builtin_amdgcn_logf(1.0f + e), 0.69314718055994530942f, m);
+    return (m == RNNT_NEG_INF) ? m : r;
+}
+
+// Asynchronous global -> LDS copy of 4 bytes per lane (global_load_lds_dword): lane l's word lands at LDS
+// byte address lds_base + 4*l (lds_base wave-uniform, passed in M0).  The compiler does not see
+// these loads; the sweep waits for them explicitly (vmcnt) before the first step that reads them.
+__device__ __forceinline__ void lds_dma4(const void* gptr, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+
 __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeState ls, int s0,
                                                      float* __restrict__ loss) {
+    extern __shared__ __align__(16) float lw_smem[];    // ring_b [LW_NB][LW_SLOT], ring_y [LW_NB][LW_SLOT]
+    const float* ring_b = lw_smem;
+    const float* ring_y = lw_smem + LW_NB * LW_SLOT;
+    const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) float*)lw_smem;
     const int s = s0 + blockIdx.x;
     const bool is_beta = (blockIdx.y != 0);
     const int u = threadIdx.x;
@@ -190,42 +231,62 @@ __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeStat
     const float c = -wave_sum(emission_max_partial(lpb, lpy, n, W1, U, u, 64)) / (float)n;
     const bool col = (u <= U);
     const int nsteps = T + U;
+    const int nld = (LW_RB * W1 + 63) >> 6;      // 256-byte copies that cover one block
     float own = RNNT_NEG_INF;
-    float pb[LAT_PF], py[LAT_PF];
+
+    // Block q of the sweep holds frames [first(q), first(q) + LW_RB): alpha walks frames upwards
+    // (first = q*LW_RB), beta downwards (first = T - (q+1)*LW_RB).  Indices outside the sample
+    // are clamped to a valid one; such values are never used by an active lane.
+    auto issue = [&](int q) {
+        const int g0 = (is_beta ? T - (q + 1) * LW_RB : q * LW_RB) * W1 + u;
+        const unsigned dst = smem_base + (unsigned)(q & (LW_NB - 1)) * (LW_SLOT * 4);
+        for (int j = 0; j < nld; ++j) {
+            int idx = g0 + j * 64;
+            idx = idx < 0 ? 0 : (idx > n - 1 ? n - 1 : idx);
+            lds_dma4(lpb + idx, dst + j * 256);
+            lds_dma4(lpy + idx, dst + LW_NB * LW_SLOT * 4 + j * 256);
+        }
+    };
+    // waits for the staged copies; the LDS reads already issued must be complete as well, since the
+    // next copy overwrites the block that the current step's (already fetched) operands came from
+    auto landed = [&]() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); };
+    issue(0);
+    issue(1);
+    landed();
+
+    // Step k computes node (t, u) with t = k - u (alpha) or t = T-1 - (k - (U-u)) (beta).  Its two
+    // emission values are read from LDS during step k-1, so that only the lane shift and the
+    // log-add-exp are on the sequential path.
     if (!is_beta) {
         float* __restrict__ alpha = ls.alpha + base;
-        auto fetch = [&](int k, float& fb, float& fy) {
-            const int t = k - u;
-            fb = 0.0f;
-            fy = 0.0f;
-            if (col && t >= 0 && t < T) {
-                if (t > 0) fb = lpb[(t - 1) * W1 + u];
-                if (u > 0) fy = lpy[t * W1 + u - 1];
-            }
+        const int um = u > 0 ? u - 1 : 0;
+        auto ring_at = [&](int t) {           // float index of (frame max(t,0), column 0)
+            const int tc = t < 0 ? 0 : t;
+            return ((tc / LW_RB) & (LW_NB - 1)) * LW_SLOT + (tc & (LW_RB - 1)) * W1;
         };
-#pragma unroll
-        for (int i = 0; i < LAT_PF; ++i) fetch(i, pb[i], py[i]);
-        for (int k0 = 0; k0 < nsteps; k0 += LAT_PF) {
-#pragma unroll
-            for (int i = 0; i < LAT_PF; ++i) {
-                const int k = k0 + i;
-                if (k < nsteps) {
-                    const int t = k - u;
-                    const bool act = col && t >= 0 && t < T;
-                    const float left = __shfl_up(own, 1, 64);       // column u-1, previous step
-                    if (act) {
-                        float val = 0.0f;
-                        if (k != 0) {
-                            const float a = (t > 0) ? own + (pb[i] + c) : RNNT_NEG_INF;
-                            const float b = (u > 0) ? left + (py[i] + c) : RNNT_NEG_INF;
-                            val = log_add_exp(a, b);
-                        }
-                        alpha[t * W1 + u] = val;
-                        own = val;
-                    }
-                    fetch(k + LAT_PF, pb[i], py[i]);
-                }
+        int r_prev = ring_at(-u - 1), r_cur = ring_at(-u);
+        float eb = ring_b[r_prev + u] + c, ey = ring_y[r_cur + um] + c;
+        for (int k = 0; k < nsteps; ++k) {
+            if (((k + 1) & (LW_RB - 1)) == 0) {     // step k+1 is the first to read block (k+1)/LW_RB
+                landed();
+                issue((k + 1) / LW_RB + 1);
             }
+            const int t = k - u;
+            r_prev = r_cur;
+            r_cur = ring_at(t + 1);
+            const float eb_n = ring_b[r_prev + u], ey_n = ring_y[r_cur + um];
+            const bool act = col && t >= 0 && t < T;
+            const float left = lane_from_below(own);            // column u-1, previous step
+            const float a = (t > 0) ? own + eb : RNNT_NEG_INF;
+            const float b = (u > 0) ? left + ey : RNNT_NEG_INF;
+            float val = log_add_exp_fast(a, b);
+            if (k == 0) val = 0.0f;
+            if (act) {
+                alpha[t * W1 + u] = val;
+                own = val;
+            }
+            eb = eb_n + c;
+            ey = ey_n + c;
         }
         if (u == U) {
             const float lnP_off = own + (lpb[(T - 1) * W1 + U] + c);
@@ -235,38 +296,33 @@ __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeStat
         }
     } else {
         float* __restrict__ beta = ls.beta + base;
-        auto fetch = [&](int k, float& fb, float& fy) {
-            const int t = T - 1 - (k - (U - u));
-            fb = 0.0f;
-            fy = 0.0f;
-            if (col && t >= 0 && t < T) {
-                fb = lpb[t * W1 + u];
-                if (u < U) fy = lpy[t * W1 + u];
-            }
+        auto ring_at = [&](int d) {           // float index of (frame T-1-max(d,0), column u)
+            const int dc = d < 0 ? 0 : d;
+            return ((dc / LW_RB) & (LW_NB - 1)) * LW_SLOT + (LW_RB - 1 - (dc & (LW_RB - 1))) * W1 + u;
         };
-#pragma unroll
-        for (int i = 0; i < LAT_PF; ++i) fetch(i, pb[i], py[i]);
-        for (int k0 = 0; k0 < nsteps; k0 += LAT_PF) {
-#pragma unroll
-            for (int i = 0; i < LAT_PF; ++i) {
-                const int k = k0 + i;
-                if (k < nsteps) {
-                    const int t = T - 1 - (k - (U - u));
-                    const bool act = col && t >= 0 && t < T;
-                    const float right = __shfl_down(own, 1, 64);    // column u+1, previous step
-                    if (act) {
-                        float val = pb[i] + c;                      // k == 0: beta[T-1,U] = final blank
-                        if (k != 0) {
-                            const float a = (t < T - 1) ? own + (pb[i] + c) : RNNT_NEG_INF;
-                            const float b = (u < U) ? right + (py[i] + c) : RNNT_NEG_INF;
-                            val = log_add_exp(a, b);
-                        }
-                        beta[t * W1 + u] = val;
-                        own = val;
-                    }
-                    fetch(k + LAT_PF, pb[i], py[i]);
-                }
+        int r = ring_at(-(U - u));
+        float eb = ring_b[r] + c, ey = ring_y[r] + c;
+        for (int k = 0; k < nsteps; ++k) {
+            if (((k + 1) & (LW_RB - 1)) == 0) {
+                landed();
+                issue((k + 1) / LW_RB + 1);
             }
+            const int d = k - (U - u);                          // frames below the last one
+            const int t = T - 1 - d;
+            r = ring_at(d + 1);
+            const float eb_n = ring_b[r], ey_n = ring_y[r];
+            const bool act = col && t >= 0 && t < T;
+            const float right = lane_from_above(own);           // column u+1, previous step
+            const float a = (t < T - 1) ? own + eb : RNNT_NEG_INF;
+            const float b = (u < U) ? right + ey : RNNT_NEG_INF;
+            float val = log_add_exp_fast(a, b);
+            if (k == 0) val = eb;                               // beta[T-1,U] = final blank
+            if (act) {
+                beta[t * W1 + u] = val;
+                own = val;
+            }
+            eb = eb_n + c;
+            ey = ey_n + c;
         }
     }
 }
@@ -275,7 +331,8 @@ hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0,
                           hipStream_t stream) {
     if (s1 <= s0) return hipSuccess;
     if (u_max + 1 <= 64) {
-        k_lattice_wave<<<dim3((unsigned)(s1 - s0), 2), dim3(64), 0, stream>>>(st, ls, s0, loss);
+        k_lattice_wave<<<dim3((unsigned)(s1 - s0), 2), dim3(64), 2 * LW_NB * LW_SLOT * sizeof(float), stream>>>(
+            st, ls, s0, loss);
         return hipGetLastError();
     }
     int threads = ((u_max + 1) + 63) / 64 * 64;
