@@ -87,9 +87,9 @@ extern "C" rnnt_status rnnt_validate_labels_host(const rnnt_desc* desc, const in
 namespace {
 
 // Optional per-kernel timing with HIP events on the caller's stream (off by default).
-enum KernelClass { KC_FILL = 0, KC_PACK_W, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
+enum KernelClass { KC_PREPARE = 0, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
                    KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_COUNT };
-const char* const kKernelNames[KC_COUNT] = {"fill_zero", "pack_w", "joint_scores_fwd", "lattice",
+const char* const kKernelNames[KC_COUNT] = {"prepare", "joint_scores_fwd", "lattice",
                                             "joint_scores_bwd", "gemm_dz", "gemm_dw_db", "joint_bwd_fused",
                                             "fwd_f32", "bwd_f32"};
 struct Profiler {
@@ -184,33 +184,44 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     const WsView wv = view_workspace(plan, workspace);
     unsigned char* w = (unsigned char*)workspace;
     const size_t B = (size_t)desc->B;
-    // host tables -> workspace (pageable sources: consumed before these calls return)
-    RNNT_HIP(hipMemcpyAsync(w + plan.off_T, T_len, B * 4, hipMemcpyHostToDevice, stream));
-    RNNT_HIP(hipMemcpyAsync(w + plan.off_U, U_len, B * 4, hipMemcpyHostToDevice, stream));
-    RNNT_HIP(hipMemcpyAsync(w + plan.off_tile_off, plan.tile_off.data(), (B + 1) * 4, hipMemcpyHostToDevice, stream));
-    RNNT_HIP(hipMemcpyAsync(w + plan.off_row_off, plan.row_off.data(), (B + 1) * 8, hipMemcpyHostToDevice, stream));
-
-    RNNT_HIP(timed(KC_FILL, stream, [&] {
-        return launch_fill_tile_sample(wv.st.tile_off, (int*)(w + plan.off_tile_sample), desc->B, stream);
-    }));
+    // host tables -> workspace in one copy (pageable source: consumed before the call returns)
+    {
+        const size_t tab_bytes = plan.off_row_off + (B + 1) * 8 - plan.off_T;
+        std::vector<unsigned char> tab(tab_bytes, 0);
+        std::memcpy(tab.data(), T_len, B * 4);
+        std::memcpy(tab.data() + (plan.off_U - plan.off_T), U_len, B * 4);
+        std::memcpy(tab.data() + (plan.off_tile_off - plan.off_T), plan.tile_off.data(), (B + 1) * 4);
+        std::memcpy(tab.data() + (plan.off_row_off - plan.off_T), plan.row_off.data(), (B + 1) * 8);
+        RNNT_HIP(hipMemcpyAsync(w + plan.off_T, tab.data(), tab_bytes, hipMemcpyHostToDevice, stream));
+    }
 
     Problem pr{desc->B, desc->T_max, desc->U_max, desc->H, desc->V, desc->blank, enc, pred, W_out, b_out, labels};
     GradOut go{d_enc, d_pred, dW_out, db_out};
     const bool bf16 = (desc->dtype == RNNT_BF16);
-    if (grads) {
-        RNNT_HIP(timed(KC_FILL, stream, [&] { return launch_fill_zero(d_enc, B * desc->T_max * desc->H, stream); }));
-        RNNT_HIP(timed(KC_FILL, stream,
-                       [&] { return launch_fill_zero(d_pred, B * (desc->U_max + 1) * desc->H, stream); }));
-        if (!desc->accumulate_params) {
-            RNNT_HIP(timed(KC_FILL, stream,
-                           [&] { return launch_fill_zero(dW_out, (size_t)desc->H * desc->V, stream); }));
-            RNNT_HIP(timed(KC_FILL, stream, [&] { return launch_fill_zero(db_out, (size_t)desc->V, stream); }));
+    {
+        PrepArgs pa{};
+        if (grads) {
+            pa.zero_ptr[0] = d_enc;
+            pa.zero_n[0] = B * desc->T_max * desc->H;
+            pa.zero_ptr[1] = d_pred;
+            pa.zero_n[1] = B * (desc->U_max + 1) * desc->H;
+            if (!desc->accumulate_params) {
+                pa.zero_ptr[2] = dW_out;
+                pa.zero_n[2] = (size_t)desc->H * desc->V;
+                pa.zero_ptr[3] = db_out;
+                pa.zero_n[3] = (size_t)desc->V;
+            }
         }
+        pa.tile_off = wv.st.tile_off;
+        pa.tile_sample = (int*)(w + plan.off_tile_sample);
+        pa.B = desc->B;
+        pa.W = W_out;
+        pa.Wp = bf16 ? wv.wpack : nullptr;
+        pa.Wq = (plan.fused && grads) ? wv.wq : nullptr;
+        pa.H = desc->H;
+        pa.V = desc->V;
+        RNNT_HIP(timed(KC_PREPARE, stream, [&] { return launch_prepare(pa, stream); }));
     }
-    if (bf16)
-        RNNT_HIP(timed(KC_PACK_W, stream, [&] { return launch_pack_w(W_out, wv.wpack, desc->H, desc->V, stream); }));
-    if (plan.fused && grads)
-        RNNT_HIP(timed(KC_PACK_W, stream, [&] { return launch_pack_wq(W_out, wv.wq, desc->H, desc->V, stream); }));
 
     size_t ci = 0;
     for (size_t gi = 0; gi < plan.groups.size(); ++gi) {

@@ -12,7 +12,7 @@ struct SampleTable {
     const int* T;              // [B] T_len
     const int* U;              // [B] U_len
     const int* tile_off;       // [B+1] cumulative 8x8 lattice-tile counts
-    const int* tile_sample;    // [tiles] sample that owns each tile (filled by launch_fill_tile_sample)
+    const int* tile_sample;    // [tiles] sample that owns each tile (filled by launch_prepare)
     const long long* row_off;  // [B+1] cumulative lattice-node counts
 };
 
@@ -44,11 +44,24 @@ struct GradOut {
     float* db;
 };
 
-hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream);
+// Set-up of one call in a single launch: clears up to four float regions (null or empty ones are
+// skipped), writes tile_sample[tile] = s for every tile of every sample (one lookup instead of a
+// search per workgroup; skipped if tile_sample is null) and the fragment-major copies of W_out [H,V]
+// (bf16): Wp for the A operand of the score GEMM, Wq for the dz GEMM (each skipped if null).
+struct PrepArgs {
+    float* zero_ptr[4];
+    size_t zero_n[4];
+    const int* tile_off;     // [B+1], device
+    int* tile_sample;        // [tiles], device
+    int B;
+    const void* W;
+    void* Wp;
+    void* Wq;
+    int H, V;
+};
+hipError_t launch_prepare(const PrepArgs& a, hipStream_t stream);
 // plain copy of n floats (n a multiple of 4): the known-size kernel the HBM counters are calibrated with
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t stream);
-// tile_sample[tile] = s for every tile of every sample (one lookup instead of a search per workgroup)
-hipError_t launch_fill_tile_sample(const int* tile_off, int* tile_sample, int B, hipStream_t stream);
 
 // ---- fp32 path (plain FMA kernels, any H, V) ------------------------------------------------
 hipError_t launch_fwd_f32(const Problem& pr, const SampleTable& st, const LatticeState& ls,
@@ -61,8 +74,6 @@ hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0,
                           float* loss, hipStream_t stream);
 
 // ---- bf16 MFMA path -------------------------------------------------------------------------
-// W [H,V] -> fragment-major copy for the A operand of the score GEMM
-hipError_t launch_pack_w(const void* W, void* Wpack, int H, int V, hipStream_t stream);
 // joint tile in LDS -> scores on MFMA -> online log-softmax -> lse, lpb, lpy   (tiles [tile0,tile1))
 hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                            const LatticeState& ls, int s0, int s1, int tile0, int tile1,
@@ -78,7 +89,6 @@ hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0,
 // fused backward: scores recomputed, dh, dz = dh W^T, tanh derivative, reductions into d_enc / d_pred;
 // writes dH [rows,V] and Z [rows,H] (bf16, row-major) for the dW GEMM.  Wq is the second
 // fragment-major copy of W_out.
-hipError_t launch_pack_wq(const void* W, void* Wq, int H, int V, hipStream_t stream);
 hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const void* Wq, const SampleTable& st,
                                  const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
                                  void* Z, float* d_enc, float* d_pred, hipStream_t stream);

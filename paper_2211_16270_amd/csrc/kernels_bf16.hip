@@ -17,33 +17,6 @@
 namespace rnnt {
 
 // ------------------------------------------------------------------------------------------------
-// W [H,V] -> fragment-major copy: Wp[((vt*KK + kk)*64 + lane)*8 + j] = W[kk*16 + 8*(lane/32) + j][vt*32 + lane%32]
-// so that one A fragment of the score GEMM is a contiguous 1 KiB block.
-// ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_pack_w(const bf16_t* __restrict__ W, bf16_t* __restrict__ Wp, int H, int V) {
-    const int KK = H >> 4;
-    const long long total = (long long)(V >> 5) * KK * 64;
-    long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= total) return;
-    const int lane = (int)(g & 63);
-    const long long f = g >> 6;
-    const int kk = (int)(f % KK);
-    const int vt = (int)(f / KK);
-    const int v = vt * 32 + (lane & 31);
-    const int k0 = kk * 16 + 8 * (lane >> 5);
-    bf16x8 o;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = W[(size_t)(k0 + j) * V + v];
-    *reinterpret_cast<bf16x8*>(Wp + g * 8) = o;
-}
-
-hipError_t launch_pack_w(const void* W, void* Wpack, int H, int V, hipStream_t stream) {
-    const long long total = (long long)(V / 32) * (H / 16) * 64;
-    k_pack_w<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>((const bf16_t*)W, (bf16_t*)Wpack, H, V);
-    return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------------
 // Joint tile + score GEMM.  MODE 0: softmax statistics (forward).  MODE 1: score gradients (backward).
 // NW waves; per step of 256 vocabulary entries wave w owns NVT tiles of 32 entries for all 64 rows
 // (NVT x 2 accumulator tiles of 32x32).

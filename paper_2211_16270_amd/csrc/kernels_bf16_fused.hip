@@ -23,27 +23,6 @@ constexpr int FB_VSTEP = 512;
 constexpr int FB_PF = 2;        // phase-1 A-fragment prefetch distance in k16-steps
 constexpr int FB_DP = FB_VSTEP + 8;   // pitch (bf16 elements) of the dh LDS tile [64 rows][512 entries]
 
-// W [H,V] -> fragment-major copy for the B operand of dz = dh W^T:
-//   Wq[((ht*(V/16) + vk)*64 + lane)*8 + j] = W[ht*32 + lane%32][vk*16 + 8*(lane/32) + j]
-__global__ __launch_bounds__(256) void k_pack_wq(const bf16_t* __restrict__ W, bf16_t* __restrict__ Wq, int H, int V) {
-    const int VK = V >> 4;
-    const long long total = (long long)(H >> 5) * VK * 64;
-    const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= total) return;
-    const int lane = (int)(g & 63);
-    const long long f = g >> 6;
-    const int vk = (int)(f % VK);
-    const int ht = (int)(f / VK);
-    const bf16_t* src = W + (size_t)(ht * 32 + (lane & 31)) * V + vk * 16 + 8 * (lane >> 5);
-    *reinterpret_cast<bf16x8*>(Wq + g * 8) = *reinterpret_cast<const bf16x8*>(src);
-}
-
-hipError_t launch_pack_wq(const void* W, void* Wq, int H, int V, hipStream_t stream) {
-    const long long total = (long long)(H / 32) * (V / 16) * 64;
-    k_pack_wq<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>((const bf16_t*)W, (bf16_t*)Wq, H, V);
-    return hipGetLastError();
-}
-
 struct FusedArgs {
     Problem pr;
     SampleTable st;

@@ -4,31 +4,6 @@
 
 namespace rnnt {
 
-__global__ void k_fill_zero(float* __restrict__ p, size_t n) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) p[i] = 0.0f;
-}
-
-hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream) {
-    if (n == 0) return hipSuccess;
-    size_t blocks = (n + 255) / 256;
-    if (blocks > 65536) blocks = 65536;
-    k_fill_zero<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(p, n);
-    return hipGetLastError();
-}
-
-__global__ __launch_bounds__(64) void k_fill_tile_sample(const int* __restrict__ tile_off, int* __restrict__ tile_sample) {
-    const int s = blockIdx.x;
-    const int e = tile_off[s + 1];
-    for (int i = tile_off[s] + threadIdx.x; i < e; i += 64) tile_sample[i] = s;
-}
-
-hipError_t launch_fill_tile_sample(const int* tile_off, int* tile_sample, int B, hipStream_t stream) {
-    k_fill_tile_sample<<<dim3((unsigned)B), dim3(64), 0, stream>>>(tile_off, tile_sample);
-    return hipGetLastError();
-}
-
 __global__ void k_copy_f32(const float4* __restrict__ src, float4* __restrict__ dst, size_t n4) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
