@@ -139,6 +139,7 @@ struct WsView {
     void* wq;
     void* dH;
     void* Z;
+    float* dw_slots;
 };
 
 WsView view_workspace(const Plan& p, void* ws) {
@@ -161,6 +162,7 @@ WsView view_workspace(const Plan& p, void* ws) {
     v.wq = w + p.off_wq;
     v.dH = w + p.off_dh;
     v.Z = w + p.off_z;
+    v.dw_slots = (float*)(w + p.off_dwslots);
     return v;
 }
 
@@ -206,8 +208,10 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
             pa.zero_ptr[1] = d_pred;
             pa.zero_n[1] = B * (desc->U_max + 1) * desc->H;
             if (!desc->accumulate_params) {
-                pa.zero_ptr[2] = dW_out;
-                pa.zero_n[2] = (size_t)desc->H * desc->V;
+                if (!bf16) {          // the bf16 path writes dW from its partial sums at the end
+                    pa.zero_ptr[2] = dW_out;
+                    pa.zero_n[2] = (size_t)desc->H * desc->V;
+                }
                 pa.zero_ptr[3] = db_out;
                 pa.zero_n[3] = (size_t)desc->V;
             }
@@ -224,6 +228,7 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     }
 
     size_t ci = 0;
+    int dw_first = 1;
     for (size_t gi = 0; gi < plan.groups.size(); ++gi) {
         const Group& g = plan.groups[gi];
         LatticeState ls = wv.ls;
@@ -261,14 +266,21 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                     }));
                 }
                 RNNT_HIP(timed(KC_GEMM_DW, stream, [&] {
-                    return launch_gemm_dw_bf16(desc->H, desc->V, rows, wv.Z, wv.dH, dW_out, db_out, stream);
+                    return launch_gemm_dw_bf16(desc->H, desc->V, rows, plan.dw_splits, dw_first, wv.Z, wv.dH,
+                                               wv.dw_slots, db_out, stream);
                 }));
+                dw_first = 0;
             } else {
                 RNNT_HIP(timed(KC_BWD_F32, stream,
                                [&] { return launch_bwd_f32(pr, wv.st, ls, go, g.s0, g.s1, g.rows, stream); }));
             }
         }
     }
+    if (bf16 && grads && !dw_first)
+        RNNT_HIP(timed(KC_GEMM_DW, stream, [&] {
+            return launch_dw_reduce(desc->H, desc->V, plan.dw_splits, wv.dw_slots, dW_out, desc->accumulate_params,
+                                    stream);
+        }));
     return RNNT_OK;
 }
 

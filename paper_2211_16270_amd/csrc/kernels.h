@@ -92,8 +92,13 @@ hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0,
 hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const void* Wq, const SampleTable& st,
                                  const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
                                  void* Z, float* d_enc, float* d_pred, hipStream_t stream);
-// dW += Z^T dH (split over the rows) and db += column sums of dH
-hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Z, const void* dH,
-                               float* dW, float* db, hipStream_t stream);
+// Split-K GEMM Z^T dH over one chunk's rows: every (split, tile) workgroup adds its 256x256 partial
+// product to its own slot (`first` != 0: overwrites it), db += column sums of dH.  `splits` and the
+// slot buffer size follow dw_split_count / dw_slot_bytes (plan.h).
+hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, int splits, int first, const void* Z,
+                               const void* dH, float* slots, float* db, hipStream_t stream);
+// dW = (accumulate ? dW : 0) + sum of the slots over the splits
+hipError_t launch_dw_reduce(int H, int V, int splits, const float* slots, float* dW, int accumulate,
+                            hipStream_t stream);
 
 }  // namespace rnnt

@@ -425,8 +425,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_nt(GemmArgs g) {
     if (MODE == 1) {
         ks = (long long)blockIdx.z * g.k_per_split;
         ke = ks + g.k_per_split < g.K ? ks + g.k_per_split : g.K;
-        if (ks >= ke) return;
-    }
+        }
     const int lrow = tid >> 2, lseg = tid & 3;
     const bf16_t* Ag = g.A + (m0 + lrow) * g.lda + lseg * 8;
     const bf16_t* Bg = g.B + (n0 + lrow) * g.ldb + lseg * 8;
@@ -562,11 +561,13 @@ hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0,
 
 // ------------------------------------------------------------------------------------------------
 // dW += Z^T dH and db += column sums of dH (Alg. 1 line 8) as one split-K GEMM with 256x256 tiles.
-// 512 threads = 8 waves in 2 (hidden) x 4 (vocabulary); each wave owns 128 x 64 = 4 x 2 accumulator
-// tiles.  Both operands are row-major with the contraction index (the chunk's rows) as the slow one:
+// 256 threads = 4 waves in 2 (hidden) x 2 (vocabulary), one per SIMD; each wave owns 128 x 128 = 4 x 4
+// accumulator tiles (256 accumulator registers), so that a k16-step reads 8 fragments from LDS for 16
+// MFMAs: the transposing LDS read delivers about 70 bytes per clock and CU, a quarter of the plain
+// 16-byte read, and sets the ratio of fragments to MFMAs this kernel can afford.  Both operands are row-major with the contraction index (the chunk's rows) as the slow one:
 // Z [rows,H], dH [rows,V].  Stages of 32 rows travel global -> LDS asynchronously (global_load_lds, no
 // registers), four stages deep, and lie in LDS as in memory ([row][column], 16-byte chunks
-// XOR-swizzled by 2*(row%4)); MFMA fragments, which need 8 consecutive rows of one column per lane,
+// XOR-swizzled by 4*(row%4), which spreads the four rows a transposing read touches per 32 lanes over all 64 banks); MFMA fragments, which need 8 consecutive rows of one column per lane,
 // come from the transposing LDS read (ds_read_b64_tr_b16): within 16 lanes, lane 4j+c supplies 4
 // columns of row j and lane i receives rows 0..3 of column i.
 // The workgroups of the first hidden-tile row also sum their B fragments over the rows (the bias
@@ -580,8 +581,9 @@ struct DwArgs {
     const bf16_t* Z;
     const bf16_t* dH;
     long long K, k_per_split;
-    float* dW;
+    float* slots;    // [splits][tiles][4 waves][4][4][4][64 lanes] float4: partial sums, accumulator layout
     float* db;
+    int first;       // overwrite the slot instead of adding to it
     int H, V;
     int mt, nt;      // output tiles along H and V
 };
@@ -605,11 +607,11 @@ __device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
 }
 
-__global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
+__global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
     extern __shared__ __align__(16) unsigned char dw_smem[];   // [WST] x { A [WK][256], B [WK][256] } bf16
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave >> 1, wn = wave & 1;
     // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  All output tiles of
     // one K split read the same rows of Z and dH, so they are mapped to the same XCD (ids that
     // agree modulo 8) and adjacent in its dispatch order: the rows then come from HBM once.
@@ -620,32 +622,31 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
     const long long m0 = (long long)bm * WT, n0 = (long long)bn * WT;
     const long long ks = (long long)split * g.k_per_split;
     const long long ke = ks + g.k_per_split < g.K ? ks + g.k_per_split : g.K;
-    if (ks >= ke) return;
     const bool do_db = (bm == 0) && (wm == 0);
     constexpr unsigned STAGE_BYTES = 2u * WK * WT * 2u;
     constexpr unsigned OPER_BYTES = (unsigned)WK * WT * 2u;
     const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)dw_smem;
 
-    // global -> LDS: one DMA instruction moves two tile rows (2 x 512 B).  Wave w moves row pairs w and
-    // w+8 of both operands.  LDS slot (row, position p) receives global chunk p ^ 2*(row%4) of that row.
-    const bf16_t* Ag[2];
-    const bf16_t* Bg[2];
-    unsigned dst[2];
+    // global -> LDS: one DMA instruction moves two tile rows (2 x 512 B).  Wave w moves row pairs w,
+    // w+4, w+8 and w+12 of both operands.  LDS slot (row, position p) receives global chunk p ^ 4*(row%4) of that row.
+    const bf16_t* Ag[4];
+    const bf16_t* Bg[4];
+    unsigned dst[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = 2 * wave + 16 * i + (lane >> 5);
-        const int ch = (lane & 31) ^ ((row & 3) << 1);
+    for (int i = 0; i < 4; ++i) {
+        const int row = 2 * wave + 8 * i + (lane >> 5);
+        const int ch = (lane & 31) ^ ((row & 3) << 2);
         long long acol = m0 + ch * 8;
         if (acol > g.H - 8) acol = g.H - 8;      // columns beyond H (H not a multiple of 256): never stored
         Ag[i] = g.Z + (ks + row) * (long long)g.H + acol;
         Bg[i] = g.dH + (ks + row) * (long long)g.V + n0 + ch * 8;
-        dst[i] = (unsigned)(2 * wave + 16 * i) * (WT * 2u);
+        dst[i] = (unsigned)(2 * wave + 8 * i) * (WT * 2u);
     }
     auto issue = [&](long long step) {          // stage = step % WST
         const unsigned sb = smem_base + (unsigned)(step & (WST - 1)) * STAGE_BYTES;
         const long long k0 = step * WK;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 4; ++i) {
             lds_dma16(Ag[i] + k0 * g.H, __builtin_amdgcn_readfirstlane(sb + dst[i]));
             lds_dma16(Bg[i] + k0 * g.V, __builtin_amdgcn_readfirstlane(sb + OPER_BYTES + dst[i]));
         }
@@ -653,112 +654,120 @@ __global__ __launch_bounds__(512) void k_gemm_dw256(DwArgs g) {
     // fragment addresses: lane = 16 g + 4 j + c supplies row 8*(g/2) + j, columns 16*(g%2) + 4c .. +3
     const int fg = lane >> 4, fj = (lane >> 2) & 3, fc = lane & 3;
     const int frow = 8 * (fg >> 1) + fj;
-    int aoff[4], boff[2];
+    int aoff[4], boff[4];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         const int col = wm * 128 + mt * 32 + 16 * (fg & 1) + 4 * fc;
-        aoff[mt] = frow * WT + (((col >> 3) ^ (fj << 1)) << 3) + (col & 7);
+        aoff[mt] = frow * WT + (((col >> 3) ^ (fj << 2)) << 3) + (col & 7);
     }
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int col = wn * 64 + nt * 32 + 16 * (fg & 1) + 4 * fc;
-        boff[nt] = WK * WT + frow * WT + (((col >> 3) ^ (fj << 1)) << 3) + (col & 7);
+    for (int nt = 0; nt < 4; ++nt) {
+        const int col = wn * 128 + nt * 32 + 16 * (fg & 1) + 4 * fc;
+        boff[nt] = WK * WT + frow * WT + (((col >> 3) ^ (fj << 2)) << 3) + (col & 7);
     }
 
-    f32x16 acc[4][2];
+    f32x16 acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{0};
-    float dbs[2] = {0.0f, 0.0f};
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x16{0};
+    float dbs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 
-    const long long nsteps = (ke - ks) / WK;
-    // three stages in flight before the first one is consumed (4 DMA instructions per wave and stage)
-    issue(0);
-    if (nsteps > 1) issue(1);
-    if (nsteps > 2) issue(2);
-    for (long long it = 0; it < nsteps; ++it) {
-        // wait for this wave's part of stage `it` (later stages may stay in flight), then for everyone's
-        const long long ahead = nsteps - 1 - it;
-        if (ahead >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if (ahead == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    const long long nsteps = ke > ks ? (ke - ks) / WK : 0;   // a split beyond the chunk still writes its slot
+    static_assert(WK == 32, "the loop below is written for two k16-steps per stage");
+    bf16x8 fa[2][4], fb[2][4];
+    auto read_frags = [&](int set, long long stage, int kk) {
+        const bf16_t* st = reinterpret_cast<const bf16_t*>(dw_smem + (size_t)(stage & (WST - 1)) * STAGE_BYTES) +
+                           kk * 16 * WT;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) fa[set][mt] = lds_read_tr_frag(st + aoff[mt]);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) fb[set][nt] = lds_read_tr_frag(st + boff[nt]);
+    };
+    auto multiply = [&](int set) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][mt], fb[set][nt], acc[mt][nt], 0, 0, 0);
+        if (do_db) {
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int q2 = 0; q2 < 4; ++q2) {
+                    const bf16x2 pr2 = {fb[set][nt][2 * q2], fb[set][nt][2 * q2 + 1]};
+                    dbs[nt] = __builtin_amdgcn_fdot2_f32_bf16(pr2, ones, dbs[nt], false);
+                }
+        }
+    };
+    // Three stages in flight before the first one is consumed (8 DMA instructions per wave and stage).
+    // One wave per SIMD: nothing else hides an LDS read, so the fragments of every k16-step, the first
+    // of a stage included, are read during the MFMAs of the step before.  The hand-over to the next
+    // stage (wait for this wave's copies, then for everyone's) therefore sits in the middle of a stage.
+    if (nsteps > 0) {
+        issue(0);
+        if (nsteps > 1) issue(1);
+        if (nsteps > 2) issue(2);
+        if (nsteps > 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else if (nsteps > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        // every wave is past stage it-1 now: its buffer takes stage it+3
-        if (it + 3 < nsteps) issue(it + 3);
-        const bf16_t* st = reinterpret_cast<const bf16_t*>(dw_smem + (size_t)(it & (WST - 1)) * STAGE_BYTES);
-        bf16x8 fa[2][4], fb[2][2];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) fa[0][mt] = lds_read_tr_frag(st + aoff[mt]);
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) fb[0][nt] = lds_read_tr_frag(st + boff[nt]);
-#pragma unroll
-        for (int kk = 0; kk < WK / 16; ++kk) {
-            const int cur = kk & 1, nxt = cur ^ 1;
-            if (kk + 1 < WK / 16) {
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt) fa[nxt][mt] = lds_read_tr_frag(st + aoff[mt] + (kk + 1) * 16 * WT);
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt) fb[nxt][nt] = lds_read_tr_frag(st + boff[nt] + (kk + 1) * 16 * WT);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mt], fb[cur][nt], acc[mt][nt], 0, 0, 0);
-            if (do_db) {
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                    for (int q2 = 0; q2 < 4; ++q2) {
-                        const bf16x2 pr2 = {fb[cur][nt][2 * q2], fb[cur][nt][2 * q2 + 1]};
-                        dbs[nt] = __builtin_amdgcn_fdot2_f32_bf16(pr2, ones, dbs[nt], false);
-                    }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        read_frags(0, 0, 0);
     }
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        const long long mb = m0 + wm * 128 + mt * 32;
-        if (mb >= g.H) continue;
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const long long n = n0 + wn * 64 + nt * 32 + l32;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const long long m = mb + 8 * (i >> 2) + 4 * hb + (i & 3);
-                atomicAdd(&g.dW[m * g.V + n], acc[mt][nt][i]);
-            }
+    for (long long it = 0; it < nsteps; ++it) {
+        read_frags(1, it, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (it + 1 < nsteps) {
+            // stage it+1 landed (stage it+2 may stay in flight); every wave is past stage it-1, whose
+            // buffer takes stage it+3
+            if (it + 2 < nsteps) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (it + 3 < nsteps) issue(it + 3);
+            read_frags(0, it + 1, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // Partial sums go to this workgroup's own slot, in accumulator order (one 16-byte store per lane
+    // and four accumulator rows): no atomics, and the same workgroup adds the next chunk's product.
+    {
+        f32x4* slot = reinterpret_cast<f32x4*>(g.slots) +
+                      (((size_t)split * ntile + tile) * 4 + wave) * (size_t)(4 * 4 * 4 * 64) + lane;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    f32x4 v = {acc[mt][nt][4 * j], acc[mt][nt][4 * j + 1], acc[mt][nt][4 * j + 2],
+                               acc[mt][nt][4 * j + 3]};
+                    f32x4* q = slot + ((mt * 4 + nt) * 4 + j) * 64;
+                    if (!g.first) v += *q;
+                    *q = v;
+                }
     }
     if (do_db) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < 4; ++nt) {
             float v = dbs[nt] + __shfl_xor(dbs[nt], 32, 64);
-            if (hb == 0) atomicAdd(&g.db[n0 + wn * 64 + nt * 32 + l32], v);
+            if (hb == 0) atomicAdd(&g.db[n0 + wn * 128 + nt * 32 + l32], v);
         }
     }
 }
 
-hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Z, const void* dH, float* dW, float* db,
-                               hipStream_t stream) {
-    if (rows <= 0) return hipSuccess;
+hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, int splits, int first, const void* Z, const void* dH,
+                               float* slots, float* db, hipStream_t stream) {
+    if (rows <= 0 || splits <= 0 || (splits & 7) != 0 || rows % WK != 0) return hipErrorInvalidValue;
     const long long mt = (H + WT - 1) / WT, nt = V / WT;
-    DwArgs g{(const bf16_t*)Z, (const bf16_t*)dH, rows, 0, dW, db, H, V, (int)mt, (int)nt};
-    // K splits: split s runs on XCD s % 8, so their number is a multiple of 8 (all XCDs busy); beyond
-    // that, about one workgroup per CU (fewer splits mean fewer atomics), at least 256 rows per split
-    long long splits = (256 + mt * nt - 1) / (mt * nt);
-    splits = (splits + 7) / 8 * 8;
-    const long long max_splits = (rows + 255) / 256;
-    if (splits > max_splits) splits = max_splits;
-    if (splits < 1) splits = 1;
+    DwArgs g{(const bf16_t*)Z, (const bf16_t*)dH, rows, 0, slots, db, first, H, V, (int)mt, (int)nt};
+    // split s runs on XCD s % 8; a split past the end of a short chunk only touches its slot
     long long per = (rows + splits - 1) / splits;
-    per = (per + WK - 1) / WK * WK;
-    splits = (rows + per - 1) / per;
-    g.k_per_split = per;
+    g.k_per_split = (per + WK - 1) / WK * WK;
     const size_t smem = (size_t)WST * 2 * WK * WT * 2;
     static bool configured = false;
     if (!configured) {
@@ -767,8 +776,36 @@ hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, const void* Z, cons
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const long long splits8 = (splits + 7) / 8 * 8;     // surplus splits exit at once
-    k_gemm_dw256<<<dim3((unsigned)(mt * nt * splits8)), dim3(512), smem, stream>>>(g);
+    k_gemm_dw256<<<dim3((unsigned)(mt * nt * splits)), dim3(256), smem, stream>>>(g);
+    return hipGetLastError();
+}
+
+// dW (+)= sum over the splits of the slots.  One thread per float4 of a tile's slot (four consecutive
+// hidden rows of one vocabulary column), decoded back from the accumulator order of k_gemm_dw256.
+__global__ __launch_bounds__(256) void k_dw_reduce(const f32x4* __restrict__ slots, float* __restrict__ dW, int H, int V,
+                                                   int mt_tiles, int ntile, int splits, int accumulate) {
+    const int tile = blockIdx.y;
+    const int e = blockIdx.x * 256 + threadIdx.x;          // 0 .. 16383
+    f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int s = 0; s < splits; ++s) sum += slots[((size_t)s * ntile + tile) * 16384 + e];
+    const int wave = e >> 12, mt = (e >> 10) & 3, nt = (e >> 8) & 3, j = (e >> 6) & 3, lane = e & 63;
+    const int bm = tile % mt_tiles, bn = tile / mt_tiles;
+    const int m = bm * WT + (wave >> 1) * 128 + mt * 32 + 8 * j + 4 * (lane >> 5);
+    const int n = bn * WT + (wave & 1) * 128 + nt * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (m + i < H) {
+            float* q = dW + (size_t)(m + i) * V + n;
+            *q = accumulate ? *q + sum[i] : sum[i];
+        }
+    }
+}
+
+hipError_t launch_dw_reduce(int H, int V, int splits, const float* slots, float* dW, int accumulate,
+                            hipStream_t stream) {
+    const int mt = (H + WT - 1) / WT, nt = V / WT;
+    k_dw_reduce<<<dim3(64, (unsigned)(mt * nt)), dim3(256), 0, stream>>>((const f32x4*)slots, dW, H, V, mt, mt * nt, splits,
+                                                                      accumulate);
     return hipGetLastError();
 }
 

@@ -50,12 +50,27 @@ struct Plan {
     size_t off_wpack = 0, off_wq = 0;
     size_t off_lse = 0, off_lpb = 0, off_lpy = 0, off_alpha = 0, off_beta = 0;
     size_t off_dh = 0, off_z = 0;
+    size_t off_dwslots = 0;             // bf16: per-workgroup partial sums of the dW GEMM
+    int dw_splits = 0;                  // bf16: K splits of the dW GEMM (a multiple of 8)
     size_t lattice_bytes = 0, chunk_bytes = 0, total_bytes = 0;
     size_t min_bytes = 0;               // smallest workable workspace
 };
 
 // Shapes the fused backward kernel covers (its dz accumulators must fit the register file).
 inline bool fused_backward_shape(int H, int V) { return H % 128 == 0 && H <= 512 && V % 256 == 0; }
+
+// dW GEMM geometry: 256x256 output tiles, and as many K splits (a multiple of 8, one set per XCD) as
+// give about one workgroup per compute unit.  Every (split, tile) workgroup owns a 256 KiB slot of
+// partial sums in the workspace.
+constexpr int DW_TILE = 256;
+inline int dw_tiles(int H, int V) { return ((H + DW_TILE - 1) / DW_TILE) * (V / DW_TILE); }
+inline int dw_split_count(int H, int V) {
+    const int t = dw_tiles(H, V);
+    return ((256 + t - 1) / t + 7) / 8 * 8;
+}
+inline size_t dw_slot_bytes(int H, int V) {
+    return (size_t)dw_tiles(H, V) * dw_split_count(H, V) * DW_TILE * DW_TILE * 4;
+}
 
 // Argument checks shared by every entry point (no pointers to data arrays here).
 rnnt_status check_desc(const rnnt_desc* d);
