@@ -52,6 +52,18 @@ __device__ __forceinline__ float fast_tanh(float x) {
     return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
+// Eight joint activations z = tanh(e + q), rounded to bf16; keep = 0 gives zeros, keep = ~0u the values
+// (branch-free: a branch per element would cost more than the arithmetic).
+__device__ __forceinline__ bf16x8 joint_tanh8(bf16x8 e, bf16x8 q, unsigned keep) {
+    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+    bf16x8 z;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) z[j] = (bf16_t)fast_tanh((float)e[j] + (float)q[j]);
+    u32x4_t w = __builtin_bit_cast(u32x4_t, z);
+    w &= keep;
+    return __builtin_bit_cast(bf16x8, w);
+}
+
 // ln(e^a + e^b); either may be -inf.
 __device__ __forceinline__ float log_add_exp(float a, float b) {
     float m = fmaxf(a, b);

@@ -72,6 +72,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
         const int r = tid & 63;
         const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
         const bool valid = (t < tp.T && u <= tp.U);
+        const unsigned keep = valid ? ~0u : 0u;              // rows outside the sample read row 0 and store zeros
         const bf16_t* er = enc + (size_t)(valid ? t : 0) * H;
         const bf16_t* qr = prd + (size_t)(valid ? u : 0) * H;
         const int nch = (H >> 3) / NW;                       // chunks per thread
@@ -87,11 +88,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
             for (int i = 0; i < 8; ++i) {
                 if (i0 + i < nch) {
                     const int c = (tid >> 6) + NW * (i0 + i);
-                    bf16x8 z;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        z[j] = valid ? (bf16_t)fast_tanh((float)e[i][j] + (float)q[i][j]) : (bf16_t)0.0f;
-                    *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = z;
+                    *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = joint_tanh8(e[i], q[i], keep);
                 }
             }
         }

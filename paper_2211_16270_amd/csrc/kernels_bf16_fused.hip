@@ -62,6 +62,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         const int r = tid & 63;
         const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
         const bool valid = (t < tp.T && u <= tp.U);
+        const unsigned keep = valid ? ~0u : 0u;              // rows outside the sample read row 0 and store zeros
         const bf16_t* er = enc + (size_t)(valid ? t : 0) * H;
         const bf16_t* qr = prd + (size_t)(valid ? u : 0) * H;
         const int nch = H >> 6;                              // chunks per thread
@@ -77,11 +78,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
             for (int i = 0; i < 8; ++i) {
                 if (i0 + i < nch) {
                     const int c = (tid >> 6) + 8 * (i0 + i);
-                    bf16x8 z;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        z[j] = valid ? (bf16_t)fast_tanh((float)e[i][j] + (float)q[i][j]) : (bf16_t)0.0f;
-                    *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = z;
+                    *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = joint_tanh8(e[i], q[i], keep);
                 }
             }
         }
@@ -111,11 +108,17 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
     __syncthreads();
     // joint tile -> Z chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM
     {
+        // thread -> chunks tid, tid + 512, ...; (row, chunk) advance by additions (no division per copy)
         const int cpr = H >> 3;                              // 16-byte chunks per row
-        for (int idx = tid; idx < FB_ROWS * cpr; idx += 512) {
-            const int row = idx / cpr, ch = idx - row * cpr;
-            *reinterpret_cast<bf16x8*>(a.Z + (size_t)(chunk_row0 + row) * H + ch * 8) =
+        const int drow = 512 / cpr, dch = 512 - drow * cpr;
+        int row = tid / cpr, ch = tid - row * cpr;
+        bf16_t* zo = a.Z + (size_t)chunk_row0 * H;
+        while (row < FB_ROWS) {
+            *reinterpret_cast<bf16x8*>(zo + (size_t)row * H + ch * 8) =
                 *reinterpret_cast<const bf16x8*>(zs + row * ZP + ch * 8);
+            row += drow;
+            ch += dch;
+            if (ch >= cpr) { ch -= cpr; ++row; }
         }
     }
 
@@ -267,13 +270,13 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         __syncthreads();    // the dh tile of this step is complete
         // dh tile -> dH chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM
         {
-            const int cpr = nact * 8;                        // 16-byte chunks per row in this step
-            bf16_t* o = a.dH + (size_t)chunk_row0 * V + vs * FB_VSTEP;
-            for (int idx = tid; idx < FB_ROWS * cpr; idx += 512) {
-                const int row = idx / cpr, ch = idx - row * cpr;
-                *reinterpret_cast<bf16x8*>(o + (size_t)row * V + ch * 8) =
-                    *reinterpret_cast<const bf16x8*>(dhs + row * FB_DP + ch * 8);
-            }
+            // nact*8 = 32 or 64 16-byte chunks per row in this step: a thread keeps its chunk and walks rows
+            const int sh = (nact == 8) ? 6 : 5;
+            const int ch = tid & ((1 << sh) - 1), drow = 512 >> sh;
+            bf16_t* o = a.dH + (size_t)chunk_row0 * V + vs * FB_VSTEP + ch * 8;
+            const bf16_t* src = dhs + ch * 8;
+            for (int row = tid >> sh; row < FB_ROWS; row += drow)
+                *reinterpret_cast<bf16x8*>(o + (size_t)row * V) = *reinterpret_cast<const bf16x8*>(src + row * FB_DP);
         }
         // -------- phase 2: dz += dh W^T over the nact*64 vocabulary entries of this step
         {
