@@ -88,10 +88,10 @@ namespace {
 
 // Optional per-kernel timing with HIP events on the caller's stream (off by default).
 enum KernelClass { KC_PREPARE = 0, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
-                   KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_COUNT };
+                   KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_DW_REDUCE, KC_COUNT };
 const char* const kKernelNames[KC_COUNT] = {"prepare", "joint_scores_fwd", "lattice",
                                             "joint_scores_bwd", "gemm_dz", "gemm_dw_db", "joint_bwd_fused",
-                                            "fwd_f32", "bwd_f32"};
+                                            "fwd_f32", "bwd_f32", "dw_reduce"};
 struct Profiler {
     bool enabled = false;
     struct Rec { int cls; hipEvent_t e0, e1; };
@@ -277,7 +277,7 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         }
     }
     if (bf16 && grads && !dw_first)
-        RNNT_HIP(timed(KC_GEMM_DW, stream, [&] {
+        RNNT_HIP(timed(KC_DW_REDUCE, stream, [&] {
             return launch_dw_reduce(desc->H, desc->V, plan.dw_splits, wv.dw_slots, dW_out, desc->accumulate_params,
                                     stream);
         }));
