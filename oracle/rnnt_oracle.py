@@ -35,6 +35,11 @@ steps 3-7.  The total loss is the sum over the batch (Section 2), gradients are
 those of the sum, and Algorithm 1 states that accumulating per sample gives the
 batched result; `rnnt_joint_loss_batched_padded` is that batched form.
 
+`rnnt_joint_proj_loss` puts the two input projections of Eq. (4) (W^A h^A + b^Z, W^L h^L) in
+front and chains the gradients back through them (Algorithm 1 line 9); it is pinned by finite
+differences of the whole chain, by its reduction to `rnnt_joint_loss` for identity projections
+and by sum_t d_enc = sum_u d_pred (both are the gradient of b^Z).
+
 Pins (tests/test_oracle_*.py): exhaustive alignment enumeration, the closed forms
 for T=1, U=0 and uniform scores, sum_v dh = 0, occupation identities of the
 lattice, central finite differences through the whole chain, per-sample ==
@@ -231,6 +236,58 @@ def rnnt_joint_loss_batched_padded(enc, pred, W_out, b_out, labels, T_len, U_len
     db = dh2.sum(axis=0)
     dx = (dh @ W_out.T) * (1.0 - z * z)
     return dict(loss=loss, d_enc=dx.sum(axis=2), d_pred=dx.sum(axis=1), dW_out=dW, db_out=db)
+
+
+def input_projections(hA_b, hL_b, W_A, b_Z, W_L):
+    """The two linear maps inside the tanh of Eq. (4) for one unpadded sample:
+    enc[t,:] = hA[t,:] @ W_A + b_Z,  pred[u,:] = hL[u,:] @ W_L.
+    hA_b [T,H_A], hL_b [U+1,H_L], W_A [H_A,H], b_Z [H], W_L [H_L,H] (the paper writes the
+    matrices as H x H_A and H x H_L; here the joint dimension H is the contiguous one)."""
+    hA_b = np.asarray(hA_b, dtype=np.float64)
+    hL_b = np.asarray(hL_b, dtype=np.float64)
+    W_A = np.asarray(W_A, dtype=np.float64)
+    W_L = np.asarray(W_L, dtype=np.float64)
+    b_Z = np.asarray(b_Z, dtype=np.float64)
+    return hA_b @ W_A + b_Z, hL_b @ W_L
+
+
+def sample_proj_loss_and_grads(hA_b, hL_b, W_A, b_Z, W_L, W_out, b_out, y, blank):
+    """Eq. (4) in full (projections inside the tanh) followed by steps 1-9, and the chain rule
+    back through the projections (Algorithm 1 line 9 for theta^J, lines 10-11 for the encodings)."""
+    enc_b, pred_b = input_projections(hA_b, hL_b, W_A, b_Z, W_L)
+    r = sample_loss_and_grads(enc_b, pred_b, W_out, b_out, y, blank)
+    hA_b = np.asarray(hA_b, dtype=np.float64)
+    hL_b = np.asarray(hL_b, dtype=np.float64)
+    W_A = np.asarray(W_A, dtype=np.float64)
+    W_L = np.asarray(W_L, dtype=np.float64)
+    return dict(loss=r["loss"], dW_out=r["dW_out"], db_out=r["db_out"],
+                d_hA=r["d_enc"] @ W_A.T, d_hL=r["d_pred"] @ W_L.T,
+                dW_A=hA_b.T @ r["d_enc"], dW_L=hL_b.T @ r["d_pred"], db_Z=r["d_enc"].sum(axis=0),
+                d_enc=r["d_enc"], d_pred=r["d_pred"])
+
+
+def rnnt_joint_proj_loss(hA, hL, W_A, b_Z, W_L, W_out, b_out, labels, T_len, U_len, blank):
+    """Algorithm 1, lines 3-12, with the joint network of Eq. (4) complete: loop over samples,
+    slice to the true lengths, accumulate all parameter gradients, assign the encoding gradients.
+    hA [B,T_max,H_A], hL [B,U_max+1,H_L]; returns loss [B], d_hA, d_hL (zeros in the padding),
+    dW_A, db_Z, dW_L, dW_out, db_out (gradients of sum_b loss[b])."""
+    hA = np.asarray(hA)
+    hL = np.asarray(hL)
+    B = hA.shape[0]
+    out = dict(loss=np.zeros(B), d_hA=np.zeros(hA.shape), d_hL=np.zeros(hL.shape),
+               dW_A=np.zeros(np.asarray(W_A).shape), db_Z=np.zeros(np.asarray(b_Z).shape),
+               dW_L=np.zeros(np.asarray(W_L).shape), dW_out=np.zeros(np.asarray(W_out).shape),
+               db_out=np.zeros(np.asarray(b_out).shape))
+    for b in range(B):
+        T, U = int(T_len[b]), int(U_len[b])
+        r = sample_proj_loss_and_grads(hA[b, :T], hL[b, :U + 1], W_A, b_Z, W_L, W_out, b_out,
+                                       np.asarray(labels[b, :U]), blank)
+        out["loss"][b] = r["loss"]
+        out["d_hA"][b, :T] = r["d_hA"]
+        out["d_hL"][b, :U + 1] = r["d_hL"]
+        for k in ("dW_A", "db_Z", "dW_L", "dW_out", "db_out"):
+            out[k] += r[k]
+    return out
 
 
 def parallel_iterations(T: int, U: int, V: int) -> int:

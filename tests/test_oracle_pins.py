@@ -340,3 +340,98 @@ def test_planted_mistakes_are_caught(monkeypatch, mistake):
         h = rng.standard_normal((4, 3, 5)); y = np.array([1, 2])
         P = np.exp(h) / np.exp(h).sum(-1, keepdims=True)
         assert abs(_loss_from_scores(h, y, 0) - brute_force_neg_log_likelihood(P, y, 0)) > 1e-3
+
+
+# ---------------------------------------------------------------- Eq. 4 with its projections
+def _rand_proj_problem(rng, B, T_max, U_max, DA, DL, H, V, blank=0):
+    hA = rng.standard_normal((B, T_max, DA))
+    hL = rng.standard_normal((B, U_max + 1, DL))
+    W_A = rng.standard_normal((DA, H)) / math.sqrt(DA)
+    b_Z = rng.standard_normal(H) * 0.2
+    W_L = rng.standard_normal((DL, H)) / math.sqrt(DL)
+    W = rng.standard_normal((H, V)) / math.sqrt(H)
+    b = rng.standard_normal(V) * 0.3
+    labels = rng.integers(0, V, size=(B, U_max))
+    T_len = rng.integers(1, T_max + 1, size=B)
+    U_len = rng.integers(0, U_max + 1, size=B)
+    return [hA, hL, W_A, b_Z, W_L, W, b, labels, T_len, U_len, blank]
+
+
+def test_projected_chain_matches_finite_differences():
+    rng = np.random.default_rng(71)
+    args = _rand_proj_problem(rng, B=3, T_max=4, U_max=3, DA=3, DL=2, H=4, V=5, blank=2)
+    args[8][:] = [4, 2, 1]
+    args[9][:] = [3, 0, 2]
+    g = O.rnnt_joint_proj_loss(*args)
+    eps = 1e-6
+    for name, pos in (("d_hA", 0), ("d_hL", 1), ("dW_A", 2), ("db_Z", 3), ("dW_L", 4), ("dW_out", 5), ("db_out", 6)):
+        x = args[pos]
+        fd = np.zeros_like(x)
+        for idx in np.ndindex(*x.shape):
+            old = x[idx]
+            x[idx] = old + eps
+            lp_ = O.rnnt_joint_proj_loss(*args)["loss"].sum()
+            x[idx] = old - eps
+            lm_ = O.rnnt_joint_proj_loss(*args)["loss"].sum()
+            x[idx] = old
+            fd[idx] = (lp_ - lm_) / (2 * eps)
+        np.testing.assert_allclose(g[name], fd, atol=1e-7, err_msg=name)
+    # padded rows of the encodings get exactly zero
+    for i in range(3):
+        assert np.all(g["d_hA"][i, args[8][i]:] == 0) and np.all(g["d_hL"][i, args[9][i] + 1:] == 0)
+
+
+def test_identity_projections_reduce_to_the_unprojected_path():
+    rng = np.random.default_rng(72)
+    enc, pred, W, b, labels, T_len, U_len, blank = _rand_problem(rng, 3, 5, 4, 6, 7)
+    eye = np.eye(6)
+    ref = O.rnnt_joint_loss(enc, pred, W, b, labels, T_len, U_len, blank)
+    got = O.rnnt_joint_proj_loss(enc, pred, eye, np.zeros(6), eye, W, b, labels, T_len, U_len, blank)
+    np.testing.assert_allclose(got["loss"], ref["loss"], rtol=1e-14)
+    np.testing.assert_allclose(got["d_hA"], ref["d_enc"], atol=1e-15)
+    np.testing.assert_allclose(got["d_hL"], ref["d_pred"], atol=1e-15)
+    np.testing.assert_allclose(got["dW_out"], ref["dW_out"], atol=1e-14)
+    # with identity maps dW_A = sum_b enc_b^T d_enc_b and the bias gradient is the sum of the rows
+    dWA = sum(enc[i, :T_len[i]].T @ ref["d_enc"][i, :T_len[i]] for i in range(3))
+    np.testing.assert_allclose(got["dW_A"], dWA, atol=1e-13)
+    np.testing.assert_allclose(got["db_Z"], ref["d_enc"].sum(axis=(0, 1)), atol=1e-13)
+
+
+def test_bias_gradient_is_the_same_from_either_encoding():
+    # b^Z enters every lattice node once: its gradient is sum_{t,u} dx = sum_t d_enc[t] = sum_u d_pred[u]
+    rng = np.random.default_rng(73)
+    enc, pred, W, b, labels, T_len, U_len, blank = _rand_problem(rng, 4, 6, 5, 5, 6)
+    r = O.rnnt_joint_loss(enc, pred, W, b, labels, T_len, U_len, blank)
+    np.testing.assert_allclose(r["d_enc"].sum(axis=1), r["d_pred"].sum(axis=1), atol=1e-13)
+
+
+@pytest.mark.parametrize("mistake", ["bias_on_both", "transposed_grad", "dropped_bias"])
+def test_planted_projection_mistakes_are_caught(monkeypatch, mistake):
+    rng = np.random.default_rng(74)
+    args = _rand_proj_problem(rng, B=2, T_max=3, U_max=2, DA=3, DL=3, H=3, V=4)
+    args[8][:] = [3, 2]
+    args[9][:] = [2, 1]
+    good = O.rnnt_joint_proj_loss(*args)
+    orig = O.input_projections
+    if mistake == "bias_on_both":
+        monkeypatch.setattr(O, "input_projections", lambda a, l, WA, bZ, WL: (orig(a, l, WA, bZ, WL)[0], orig(a, l, WA, bZ, WL)[1] + bZ))
+    elif mistake == "dropped_bias":
+        monkeypatch.setattr(O, "input_projections", lambda a, l, WA, bZ, WL: orig(a, l, WA, 0 * np.asarray(bZ), WL))
+    else:
+        monkeypatch.setattr(O, "input_projections", lambda a, l, WA, bZ, WL: orig(a, l, np.asarray(WA).T.copy() if np.asarray(WA).shape[0] == np.asarray(WA).shape[1] else WA, bZ, WL))
+    bad = O.rnnt_joint_proj_loss(*args)
+    # the pins above would fail: the loss moves, or the analytic gradient no longer matches the function
+    eps = 1e-6
+    x = args[3]
+    fd = np.zeros_like(x)
+    for i in range(x.size):
+        old = x[i]
+        x[i] = old + eps
+        lp_ = O.rnnt_joint_proj_loss(*args)["loss"].sum()
+        x[i] = old - eps
+        lm_ = O.rnnt_joint_proj_loss(*args)["loss"].sum()
+        x[i] = old
+        fd[i] = (lp_ - lm_) / (2 * eps)
+    moved = not np.allclose(bad["loss"], good["loss"], rtol=1e-9)
+    broken_grad = not np.allclose(bad["db_Z"], fd, atol=1e-6)
+    assert moved or broken_grad
