@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--budget-mib", type=int, default=0, help="workspace budget (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="use only the first N samples (profiling aid)")
+    ap.add_argument("--projections", type=int, default=0, metavar="D",
+                    help="time the entry point with the joint network's input projections inside "
+                         "(Eq. 4 complete), encoder / prediction width D (0 = the north-star entry point)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the 256 MiB plain copy kernel 5 times (HBM counter calibration under rocprofv3)")
     args = ap.parse_args()
@@ -79,8 +82,26 @@ def main():
     dW = torch.empty(wl.H, wl.V, dtype=torch.float32, device="cuda")
     db = torch.empty(wl.V, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
+    if args.projections:
+        D = args.projections
+        proj = synth.make_proj_inputs(batch, D, D, pad="zero")
+        devp = Bd.proj_to_device(proj, wl.dtype)
+        nbytes = Bd.rnnt_joint_proj_workspace_bytes(desc, D, D, dev["T_len"], dev["U_len"], args.budget_mib << 20)
+        del ws, d_enc, d_pred, dev["enc"], dev["pred"]
+        torch.cuda.reset_peak_memory_stats()
+        ws = Bd.Workspace(nbytes)
+        f32 = dict(dtype=torch.float32, device="cuda")
+        d_hA, d_hL = torch.empty(wl.B, wl.T_max, D, **f32), torch.empty(wl.B, wl.U_max + 1, D, **f32)
+        dWA, dbZ, dWL = torch.empty(D, wl.H, **f32), torch.empty(wl.H, **f32), torch.empty(D, wl.H, **f32)
 
     def step():
+        if args.projections:
+            s = Bd.rnnt_joint_proj_loss_fwd_bwd(desc, D, D, devp["hA"], devp["hL"], devp["W_A"], devp["b_Z"],
+                                                devp["W_L"], dev["W_out"], dev["b_out"], dev["labels"], dev["T_len"],
+                                                dev["U_len"], loss, d_hA, d_hL, dWA, dbZ, dWL, dW, db, ws.buf, stream)
+            if s != 0:
+                raise Bd.RnntError(s, "rnnt_joint_proj_loss_fwd_bwd")
+            return
         s = Bd.rnnt_joint_loss_fwd_bwd(desc, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
                                        dev["T_len"], dev["U_len"], loss, d_enc, d_pred, dW, db, ws.buf, stream)
         if s != 0:
@@ -150,12 +171,14 @@ def main():
     lattice_gbs = (24.0 * R / (lat["ms_per_step"] * 1e-3) / 1e9) if lat else None
 
     out = {
-        "metric": "samples/s fused joint+RNN-T loss+grads",
+        "metric": "samples/s fused joint+RNN-T loss+grads" + (" incl. input projections" if args.projections else ""),
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B} T_max={wl.T_max} U_max={wl.U_max} H={wl.H} V={wl.V} "
                                f"{wl.dtype}, ragged lengths, {R} lattice nodes ({100.0 * R / info['rows_padded']:.1f}% of padded)",
+                   "entry_point": "rnnt_joint_proj_loss_fwd_bwd, H_A = H_L = %d" % args.projections
+                   if args.projections else "rnnt_joint_loss_fwd_bwd",
                    "groups": info["n_groups"], "chunks": info["n_chunks"],
                    "workspace_bytes": int(nbytes)},
         "mfma_util_alg": util_alg, "mfma_util_exec": util_exec,
@@ -177,9 +200,15 @@ def main():
             cores = os.cpu_count()
         f64 = lambda x: np.asarray(x[:n], dtype=np.float64)
         t0 = time.perf_counter()
-        ref = O.rnnt_joint_loss(f64(batch.enc), f64(batch.pred), batch.W_out.astype(np.float64),
-                                batch.b_out.astype(np.float64), batch.labels[:n], batch.T_len[:n], batch.U_len[:n],
-                                wl.blank)
+        if args.projections:
+            ref = O.rnnt_joint_proj_loss(f64(proj.hA), f64(proj.hL), proj.W_A.astype(np.float64),
+                                         proj.b_Z.astype(np.float64), proj.W_L.astype(np.float64),
+                                         batch.W_out.astype(np.float64), batch.b_out.astype(np.float64),
+                                         batch.labels[:n], batch.T_len[:n], batch.U_len[:n], wl.blank)
+        else:
+            ref = O.rnnt_joint_loss(f64(batch.enc), f64(batch.pred), batch.W_out.astype(np.float64),
+                                    batch.b_out.astype(np.float64), batch.labels[:n], batch.T_len[:n],
+                                    batch.U_len[:n], wl.blank)
         cpu_s = time.perf_counter() - t0
         rel = float(np.max(np.abs(loss[:n].cpu().numpy() - ref["loss"]) / np.abs(ref["loss"])))
         out["cpu_baseline"] = {"value": n / cpu_s, "unit": "samples/s", "cores": int(cores), "kind": "oracle",

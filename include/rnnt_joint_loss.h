@@ -133,8 +133,9 @@ rnnt_status rnnt_validate_labels_host(const rnnt_desc* desc, const int32_t* labe
  *          a larger workspace lets more samples share a launch
  * hip_stream  a hipStream_t (NULL = the default stream)
  *
- * Floating-point sums into the gradient arrays use atomic adds, so results can differ in the
- * last bits from run to run.  Calls that share a workspace must be ordered on one stream.
+ * Floating-point sums into d_enc, d_pred and db_out (on the fp32 path also dW_out) use atomic
+ * adds, so those results can differ in the last bits from run to run; the bf16 path's dW_out is
+ * summed in a fixed order.  Calls that share a workspace must be ordered on one stream.
  */
 rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc,
                                     const void* enc, const void* pred, const void* W_out,
@@ -154,6 +155,44 @@ rnnt_status rnnt_joint_loss_fwd(const rnnt_desc* desc,
                                 const int32_t* T_len_host, const int32_t* U_len_host,
                                 float* loss, void* workspace, size_t workspace_bytes,
                                 void* hip_stream);
+
+/*
+ * The same path with the joint network of Eq. (4) complete: the two input projections run inside
+ * the call and the gradients are chained back through them (Algorithm 1 line 9 for theta^J, lines
+ * 10-11 for the encodings).
+ *
+ *   enc[b,t,:]  = hA[b,t,:] W_A + b_Z          pred[b,u,:] = hL[b,u,:] W_L
+ *   z[b,t,u,:]  = tanh(enc[b,t,:] + pred[b,u,:])                                      (Eq. 4)
+ *   then as rnnt_joint_loss_fwd_bwd; in addition
+ *   d_hA = d_enc W_A^T, dW_A = sum_{b,t} hA^T d_enc, db_Z = sum_{b,t} d_enc,
+ *   d_hL = d_pred W_L^T, dW_L = sum_{b,u} hL^T d_pred.
+ *
+ * W_A [H_A, H] and W_L [H_L, H] are the transposes of the paper's W^A, W^L (H contiguous).
+ * bf16: hA, hL, W_A, W_L bf16; the projections accumulate in fp32, add b_Z and are rounded to bf16
+ * (they are the bf16 inputs of the joint kernels); d_enc, d_pred are rounded to bf16 as MFMA
+ * operands of the three backward GEMMs.  H_A and H_L must be multiples of 128 (bf16) and at most 4096.
+ *
+ * hA    dev [B, T_max, H_A]    desc->dtype; rows t >= T_len[b] are never used (may hold NaN)
+ * hL    dev [B, U_max+1, H_L]  desc->dtype; rows u >  U_len[b] are never used
+ * W_A   dev [H_A, H], W_L dev [H_L, H]   desc->dtype;   b_Z dev [H] float
+ * d_hA  dev [B, T_max, H_A] float, d_hL dev [B, U_max+1, H_L] float: out, fully overwritten, zeros in padded rows
+ * dW_A, dW_L, db_Z: float, out; overwritten or accumulated like dW_out (desc->accumulate_params)
+ * Everything else as in rnnt_joint_loss_fwd_bwd.  All device pointers 16-byte aligned.
+ * workspace_bytes >= rnnt_joint_proj_workspace_bytes(...): the projected encodings and their
+ * gradients ([B,T_max,H] and [B,U_max+1,H], desc->dtype resp. float) live there, in front of the
+ * workspace of the inner path; budget_bytes (0 = default) applies to that inner part.
+ */
+size_t rnnt_joint_proj_workspace_bytes(const rnnt_desc* desc, int32_t H_A, int32_t H_L,
+                                       const int32_t* T_len_host, const int32_t* U_len_host,
+                                       size_t budget_bytes);
+rnnt_status rnnt_joint_proj_loss_fwd_bwd(const rnnt_desc* desc, int32_t H_A, int32_t H_L,
+                                         const void* hA, const void* hL, const void* W_A,
+                                         const float* b_Z, const void* W_L,
+                                         const void* W_out, const float* b_out, const int32_t* labels,
+                                         const int32_t* T_len_host, const int32_t* U_len_host,
+                                         float* loss, float* d_hA, float* d_hL, float* dW_A,
+                                         float* db_Z, float* dW_L, float* dW_out, float* db_out,
+                                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Test hook: copies the forward/backward variables of sample b (as left in the workspace by the

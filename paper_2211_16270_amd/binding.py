@@ -21,7 +21,8 @@ STATUS_NAMES = ["RNNT_OK", "RNNT_ERR_NULL", "RNNT_ERR_SHAPE", "RNNT_ERR_LENGTH",
 EXPORTS = ["rnnt_status_string", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_loss_plan",
            "rnnt_parallel_iterations", "rnnt_validate_labels_host", "rnnt_joint_loss_fwd_bwd",
            "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice", "rnnt_profile_enable",
-           "rnnt_debug_copy_f32", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read"]
+           "rnnt_debug_copy_f32", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
+           "rnnt_joint_proj_workspace_bytes", "rnnt_joint_proj_loss_fwd_bwd"]
 
 
 class RnntDesc(ctypes.Structure):
@@ -72,6 +73,11 @@ def lib() -> ctypes.CDLL:
     L.rnnt_joint_loss_fwd_bwd.restype = ctypes.c_int
     L.rnnt_joint_loss_fwd_bwd.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, f32p, f32p, f32p, f32p,
                                           vp, ctypes.c_size_t, vp]
+    L.rnnt_joint_proj_workspace_bytes.restype = ctypes.c_size_t
+    L.rnnt_joint_proj_workspace_bytes.argtypes = [dp, ctypes.c_int32, ctypes.c_int32, i32p, i32p, ctypes.c_size_t]
+    L.rnnt_joint_proj_loss_fwd_bwd.restype = ctypes.c_int
+    L.rnnt_joint_proj_loss_fwd_bwd.argtypes = [dp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, f32p, vp, vp, f32p, vp,
+                                               i32p, i32p] + [f32p] * 8 + [vp, ctypes.c_size_t, vp]
     L.rnnt_joint_loss_fwd.restype = ctypes.c_int
     L.rnnt_joint_loss_fwd.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
     L.rnnt_debug_read_lattice.restype = ctypes.c_int
@@ -158,6 +164,25 @@ def rnnt_joint_loss_fwd(desc: RnntDesc, enc, pred, W_out, b_out, labels, T_len, 
     return int(lib().rnnt_joint_loss_fwd(
         ctypes.byref(desc), _ptr(enc), _ptr(pred), _ptr(W_out), _ptr(b_out), _ptr(labels), _ip(T), _ip(U),
         _ptr(loss), _ptr(workspace),
+        int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
+        _stream_handle(stream)))
+
+
+def rnnt_joint_proj_workspace_bytes(desc: RnntDesc, H_A: int, H_L: int, T_len, U_len, budget_bytes: int = 0) -> int:
+    T, U = _i32(T_len), _i32(U_len)
+    return int(lib().rnnt_joint_proj_workspace_bytes(ctypes.byref(desc), int(H_A), int(H_L), _ip(T), _ip(U),
+                                                     int(budget_bytes)))
+
+
+def rnnt_joint_proj_loss_fwd_bwd(desc: RnntDesc, H_A: int, H_L: int, hA, hL, W_A, b_Z, W_L, W_out, b_out, labels,
+                                 T_len, U_len, loss, d_hA, d_hL, dW_A, db_Z, dW_L, dW_out, db_out, workspace,
+                                 stream=None) -> int:
+    """Raw call of the path with the input projections of Eq. (4) inside (see the header)."""
+    T, U = _i32(T_len), _i32(U_len)
+    return int(lib().rnnt_joint_proj_loss_fwd_bwd(
+        ctypes.byref(desc), int(H_A), int(H_L), _ptr(hA), _ptr(hL), _ptr(W_A), _ptr(b_Z), _ptr(W_L), _ptr(W_out),
+        _ptr(b_out), _ptr(labels), _ip(T), _ip(U), _ptr(loss), _ptr(d_hA), _ptr(d_hL), _ptr(dW_A), _ptr(db_Z),
+        _ptr(dW_L), _ptr(dW_out), _ptr(db_out), _ptr(workspace),
         int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
         _stream_handle(stream)))
 
@@ -258,3 +283,46 @@ def run_fwd_bwd(dev: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optio
     if st != 0:
         raise RnntError(st, "rnnt_joint_loss_fwd_bwd")
     return dict(loss=loss, d_enc=d_enc, d_pred=d_pred, dW_out=dW, db_out=db, workspace=workspace, desc=desc)
+
+
+def proj_to_device(proj, dtype: str, device="cuda:0"):
+    """synth.ProjInputs -> dict of torch tensors in the storage types the library expects."""
+    import torch
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+
+    def cvt(x):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(device=device, dtype=dt)
+
+    return dict(hA=cvt(proj.hA), hL=cvt(proj.hL), W_A=cvt(proj.W_A), W_L=cvt(proj.W_L),
+                b_Z=torch.from_numpy(np.ascontiguousarray(proj.b_Z)).to(device))
+
+
+def run_proj_fwd_bwd(dev: dict, devp: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optional[Workspace] = None,
+                     budget_bytes: int = 0, accumulate_into=None, stream=None):
+    """Allocates outputs (and a workspace unless given), calls rnnt_joint_proj_loss_fwd_bwd, raises on a
+    non-zero status.  `dev` as from to_device (enc/pred unused), `devp` as from proj_to_device."""
+    import torch
+    device = devp["hA"].device
+    H_A, H_L = int(devp["hA"].shape[-1]), int(devp["hL"].shape[-1])
+    desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1)
+    if workspace is None:
+        n = rnnt_joint_proj_workspace_bytes(desc, H_A, H_L, dev["T_len"], dev["U_len"], budget_bytes)
+        if n == 0:
+            raise RnntError(2, "rnnt_joint_proj_workspace_bytes")
+        workspace = Workspace(n, device)
+    f32 = dict(dtype=torch.float32, device=device)
+    out = dict(loss=torch.empty(B, **f32), d_hA=torch.empty(B, T_max, H_A, **f32),
+               d_hL=torch.empty(B, U_max + 1, H_L, **f32))
+    if accumulate_into is None:
+        out.update(dW_A=torch.empty(H_A, H, **f32), db_Z=torch.empty(H, **f32), dW_L=torch.empty(H_L, H, **f32),
+                   dW_out=torch.empty(H, V, **f32), db_out=torch.empty(V, **f32))
+    else:
+        out.update(accumulate_into)
+    st = rnnt_joint_proj_loss_fwd_bwd(desc, H_A, H_L, devp["hA"], devp["hL"], devp["W_A"], devp["b_Z"], devp["W_L"],
+                                      dev["W_out"], dev["b_out"], dev["labels"], dev["T_len"], dev["U_len"],
+                                      out["loss"], out["d_hA"], out["d_hL"], out["dW_A"], out["db_Z"], out["dW_L"],
+                                      out["dW_out"], out["db_out"], workspace.buf, stream)
+    if st != 0:
+        raise RnntError(st, "rnnt_joint_proj_loss_fwd_bwd")
+    out.update(workspace=workspace, desc=desc)
+    return out

@@ -88,10 +88,10 @@ namespace {
 
 // Optional per-kernel timing with HIP events on the caller's stream (off by default).
 enum KernelClass { KC_PREPARE = 0, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
-                   KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_DW_REDUCE, KC_COUNT };
+                   KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_DW_REDUCE, KC_PROJ, KC_COUNT };
 const char* const kKernelNames[KC_COUNT] = {"prepare", "joint_scores_fwd", "lattice",
                                             "joint_scores_bwd", "gemm_dz", "gemm_dw_db", "joint_bwd_fused",
-                                            "fwd_f32", "bwd_f32", "dw_reduce"};
+                                            "fwd_f32", "bwd_f32", "dw_reduce", "projections"};
 struct Profiler {
     bool enabled = false;
     struct Rec { int cls; hipEvent_t e0, e1; };
@@ -293,6 +293,113 @@ extern "C" rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc, const void
                                                void* workspace, size_t workspace_bytes, void* hip_stream) {
     return run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW_out, db_out,
                workspace, workspace_bytes, hip_stream, true);
+}
+
+namespace {
+
+struct ProjLayout {
+    size_t off_enc, off_pred, off_denc, off_dpred, bytes;
+};
+ProjLayout proj_layout(const rnnt_desc& d) {
+    const size_t esz = d.dtype == RNNT_BF16 ? 2 : 4;
+    const size_t ne = (size_t)d.B * d.T_max * d.H, np = (size_t)d.B * (d.U_max + 1) * d.H;
+    ProjLayout l{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = (o + bytes + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; return at; };
+    l.off_enc = take(ne * esz);
+    l.off_pred = take(np * esz);
+    l.off_denc = take(ne * 4);
+    l.off_dpred = take(np * 4);
+    l.bytes = o;
+    return l;
+}
+rnnt_status check_proj_dims(const rnnt_desc* d, int32_t H_A, int32_t H_L) {
+    if (H_A < 1 || H_L < 1) return RNNT_ERR_SHAPE;
+    if (H_A > 4096 || H_L > 4096) return RNNT_ERR_UNSUPPORTED;
+    if (d->dtype == RNNT_BF16 && (H_A % 128 != 0 || H_L % 128 != 0)) return RNNT_ERR_UNSUPPORTED;
+    return RNNT_OK;
+}
+
+}  // namespace
+
+extern "C" size_t rnnt_joint_proj_workspace_bytes(const rnnt_desc* desc, int32_t H_A, int32_t H_L,
+                                                  const int32_t* T_len, const int32_t* U_len, size_t budget_bytes) {
+    if (check_desc(desc) != RNNT_OK || check_lengths(desc, T_len, U_len) != RNNT_OK) return 0;
+    if (check_proj_dims(desc, H_A, H_L) != RNNT_OK) return 0;
+    const ProjLayout l = proj_layout(*desc);
+    Plan p;
+    size_t inner_budget = 0;
+    if (budget_bytes != 0) inner_budget = budget_bytes > l.bytes ? budget_bytes - l.bytes : 1;
+    build_plan(*desc, T_len, U_len, inner_budget, p);
+    return l.bytes + p.total_bytes;
+}
+
+extern "C" rnnt_status rnnt_joint_proj_loss_fwd_bwd(const rnnt_desc* desc, int32_t H_A, int32_t H_L, const void* hA,
+                                                    const void* hL, const void* W_A, const float* b_Z,
+                                                    const void* W_L, const void* W_out, const float* b_out,
+                                                    const int32_t* labels, const int32_t* T_len,
+                                                    const int32_t* U_len, float* loss, float* d_hA, float* d_hL,
+                                                    float* dW_A, float* db_Z, float* dW_L, float* dW_out,
+                                                    float* db_out, void* workspace, size_t workspace_bytes,
+                                                    void* hip_stream) {
+    rnnt_status stt = check_desc(desc);
+    if (stt != RNNT_OK) return stt;
+    stt = check_proj_dims(desc, H_A, H_L);
+    if (stt != RNNT_OK) return stt;
+    if (!hA || !hL || !W_A || !b_Z || !W_L || !d_hA || !d_hL || !dW_A || !db_Z || !dW_L) return RNNT_ERR_NULL;
+    if (!W_out || !b_out || !loss || !dW_out || !db_out || !T_len || !U_len) return RNNT_ERR_NULL;
+    stt = check_lengths(desc, T_len, U_len);
+    if (stt != RNNT_OK) return stt;
+    if (!workspace || ((uintptr_t)workspace % WS_ALIGN) != 0) return RNNT_ERR_WORKSPACE;
+    const ProjLayout l = proj_layout(*desc);
+    if (workspace_bytes <= l.bytes) return RNNT_ERR_WORKSPACE;
+    {
+        Plan p;
+        build_plan(*desc, T_len, U_len, workspace_bytes - l.bytes, p);
+        if (p.total_bytes > workspace_bytes - l.bytes) return RNNT_ERR_WORKSPACE;
+    }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    unsigned char* w = (unsigned char*)workspace;
+    void* enc = w + l.off_enc;
+    void* pred = w + l.off_pred;
+    float* d_enc = (float*)(w + l.off_denc);
+    float* d_pred = (float*)(w + l.off_dpred);
+    const int bf16 = desc->dtype == RNNT_BF16;
+    const long long rows_a = (long long)desc->B * desc->T_max, rows_l = (long long)desc->B * (desc->U_max + 1);
+    const int H = desc->H;
+
+    // Eq. 4, the two linear maps.  The length tables of the inner call are not on the device yet:
+    // the projections run over all rows and the padded ones, whose input may be anything, are
+    // skipped by the inner path (never read), so no mask is needed here.
+    const RowMask none{nullptr, 1, 0};
+    RNNT_HIP(timed(KC_PROJ, stream, [&] { return launch_proj_forward(bf16, hA, rows_a, H_A, none, W_A, b_Z, H, enc, stream); }));
+    RNNT_HIP(timed(KC_PROJ, stream, [&] { return launch_proj_forward(bf16, hL, rows_l, H_L, none, W_L, nullptr, H, pred, stream); }));
+
+    stt = run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW_out, db_out,
+              w + l.bytes, workspace_bytes - l.bytes, hip_stream, true);
+    if (stt != RNNT_OK) return stt;
+
+    // the inner call has put T_len, U_len at the start of its workspace (plan offsets off_T, off_U)
+    Plan p;
+    build_plan(*desc, T_len, U_len, workspace_bytes - l.bytes, p);
+    const RowMask mask_a{(const int*)(w + l.bytes + p.off_T), desc->T_max, 0};
+    const RowMask mask_l{(const int*)(w + l.bytes + p.off_U), desc->U_max + 1, 1};
+    if (!desc->accumulate_params) {
+        PrepArgs pa{};
+        pa.zero_ptr[0] = dW_A;
+        pa.zero_n[0] = (size_t)H_A * H;
+        pa.zero_ptr[1] = dW_L;
+        pa.zero_n[1] = (size_t)H_L * H;
+        pa.zero_ptr[2] = db_Z;
+        pa.zero_n[2] = (size_t)H;
+        RNNT_HIP(timed(KC_PREPARE, stream, [&] { return launch_prepare(pa, stream); }));
+    }
+    RNNT_HIP(timed(KC_PROJ, stream, [&] { return launch_proj_backward_input(bf16, d_enc, rows_a, H, W_A, H_A, d_hA, stream); }));
+    RNNT_HIP(timed(KC_PROJ, stream, [&] { return launch_proj_backward_input(bf16, d_pred, rows_l, H, W_L, H_L, d_hL, stream); }));
+    RNNT_HIP(timed(KC_PROJ, stream, [&] { return launch_proj_backward_weight(bf16, hA, rows_a, H_A, mask_a, d_enc, H, dW_A, stream); }));
+    RNNT_HIP(timed(KC_PROJ, stream, [&] { return launch_proj_backward_weight(bf16, hL, rows_l, H_L, mask_l, d_pred, H, dW_L, stream); }));
+    RNNT_HIP(timed(KC_PROJ, stream, [&] { return launch_col_sum(d_enc, rows_a, H, db_Z, stream); }));
+    return RNNT_OK;
 }
 
 extern "C" rnnt_status rnnt_joint_loss_fwd(const rnnt_desc* desc, const void* enc, const void* pred,

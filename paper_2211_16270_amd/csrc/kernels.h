@@ -101,4 +101,24 @@ hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, int splits, int fir
 hipError_t launch_dw_reduce(int H, int V, int splits, const float* slots, float* dW, int accumulate,
                             hipStream_t stream);
 
+// ---- input projections of the joint network (Eq. 4) and their backward -----------------------
+// Row r of a [B*period, D] array is real data iff there is no mask (len == nullptr) or
+// (r % period) < len[r / period] + extra; other rows are read as zero.
+struct RowMask {
+    const int* len;   // device, [B]
+    int period;       // T_max, or U_max + 1
+    int extra;        // 0 for frames (t < T_len), 1 for label positions (u <= U_len)
+};
+// out[r,:] = h[r,:] W + bias  (out in the input dtype; bias may be null)   h [rows,D], W [D,H]
+hipError_t launch_proj_forward(int bf16, const void* h, long long rows, int D, const RowMask& mask, const void* W,
+                               const float* bias, int H, void* out, hipStream_t stream);
+// d_in[r,:] = d_out[r,:] W^T   (d_out fp32 [rows,H], zero in padded rows; d_in fp32 [rows,D])
+hipError_t launch_proj_backward_input(int bf16, const float* d_out, long long rows, int H, const void* W, int D,
+                                      float* d_in, hipStream_t stream);
+// dW += h^T d_out over the real rows   (dW fp32 [D,H])
+hipError_t launch_proj_backward_weight(int bf16, const void* h, long long rows, int D, const RowMask& mask,
+                                       const float* d_out, int H, float* dW, hipStream_t stream);
+// out[c] += sum_r x[r,c]   (x fp32 [rows,cols])
+hipError_t launch_col_sum(const float* x, long long rows, int cols, float* out, hipStream_t stream);
+
 }  // namespace rnnt

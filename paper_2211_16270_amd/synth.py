@@ -194,3 +194,37 @@ def with_lengths(batch: Batch, T_len, U_len, pad: str = "nan") -> Batch:
         pred[j, U_len[j] + 1:] = fill
         labels[j, U_len[j]:] = -1 if pad == "nan" else 0
     return replace(batch, enc=enc, pred=pred, labels=labels, T_len=T_len, U_len=U_len)
+
+
+@dataclass
+class ProjInputs:
+    """Inputs of the two linear maps inside the tanh of the joint network (float32 arrays holding
+    the values every consumer must use, bf16-representable for bf16 workloads)."""
+    hA: np.ndarray     # [B, T_max, H_A]
+    hL: np.ndarray     # [B, U_max+1, H_L]
+    W_A: np.ndarray    # [H_A, H]
+    b_Z: np.ndarray    # [H] float32
+    W_L: np.ndarray    # [H_L, H]
+
+
+def make_proj_inputs(batch: Batch, H_A: int, H_L: int, pad: str = "nan") -> ProjInputs:
+    """Acoustic / label encodings and projection weights for the samples of `batch`: hA, hL ~ N(0,1),
+    W_A ~ N(0, 1/H_A), W_L ~ N(0, 1/H_L) (so that the projected encodings are ~ N(0,1) like the
+    workloads' enc, pred), b_Z ~ 0.1 N(0,1).  Per-sample streams as in make_batch."""
+    wl = batch.wl
+    fill = np.nan if pad == "nan" else 0.0
+    Bs = batch.B
+    hA = np.full((Bs, wl.T_max, H_A), fill, dtype=np.float32)
+    hL = np.full((Bs, wl.U_max + 1, H_L), fill, dtype=np.float32)
+    for j, b in enumerate(batch.sample_ids):
+        g = _rng(wl.index, 3, int(b), H_A, H_L)
+        Tb, Ub = int(batch.T_len[j]), int(batch.U_len[j])
+        hA[j, :Tb] = g.standard_normal((Tb, H_A), dtype=np.float32)
+        hL[j, :Ub + 1] = g.standard_normal((Ub + 1, H_L), dtype=np.float32)
+    gw = _rng(wl.index, 4, H_A, H_L)
+    W_A = gw.standard_normal((H_A, wl.H), dtype=np.float32) * np.float32(1.0 / np.sqrt(H_A))
+    W_L = gw.standard_normal((H_L, wl.H), dtype=np.float32) * np.float32(1.0 / np.sqrt(H_L))
+    b_Z = (gw.standard_normal(wl.H, dtype=np.float32) * np.float32(0.1)).astype(np.float32)
+    if wl.dtype == "bf16":
+        hA, hL, W_A, W_L = (bf16_bits_to_f32(f32_to_bf16_bits(x)) for x in (hA, hL, W_A, W_L))
+    return ProjInputs(hA, hL, W_A.astype(np.float32), b_Z, W_L.astype(np.float32))
