@@ -143,3 +143,28 @@ def test_budgets_shrink_the_plan_and_a_too_small_budget_is_reported():
     assert st == 5
     st, info_min, _ = Bd.rnnt_joint_loss_plan(desc, T, U, tiny)
     assert st == 0 and info_min["chunk_rows"] == 128 and info_min["group_rows_cap"] == rows.max()
+
+
+def test_projected_entry_point_checks_and_workspace():
+    wl, desc, T, U = _lens("C2")
+    L = Bd.lib()
+    dummy = ctypes.c_void_p(0x1000)
+    Tl, Ul = np.ascontiguousarray(T, dtype=np.int32), np.ascontiguousarray(U, dtype=np.int32)
+
+    def call(H_A, H_L, hA=dummy, ws_bytes=1 << 32, d=desc):
+        return L.rnnt_joint_proj_loss_fwd_bwd(ctypes.byref(d), H_A, H_L, hA, dummy, dummy, dummy, dummy, dummy, dummy,
+                                              dummy, Bd._ip(Tl), Bd._ip(Ul), *([dummy] * 8), dummy, ws_bytes, None)
+
+    assert call(512, 512, hA=None) == 1                # RNNT_ERR_NULL
+    assert call(0, 512) == 2                           # RNNT_ERR_SHAPE
+    assert call(200, 512) == 6                         # bf16 needs multiples of 128
+    assert call(8192, 512) == 6
+    inner = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 0)
+    n = Bd.rnnt_joint_proj_workspace_bytes(desc, 512, 256, T, U, 0)
+    # in front of the inner workspace: enc, pred in the input dtype and d_enc, d_pred in fp32
+    rows_a, rows_l = wl.B * wl.T_max, wl.B * (wl.U_max + 1)
+    extra = (rows_a + rows_l) * wl.H * (2 + 4)
+    assert inner + extra <= n <= inner + extra + 4 * 256
+    assert call(512, 256, ws_bytes=extra) == 5         # RNNT_ERR_WORKSPACE: nothing left for the inner path
+    assert call(512, 256, ws_bytes=extra + 4096) == 5  # less than the smallest inner plan
+    assert Bd.rnnt_joint_proj_workspace_bytes(desc, 100, 256, T, U, 0) == 0
