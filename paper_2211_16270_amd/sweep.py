@@ -1,0 +1,117 @@
+"""Sweeps shaped like the paper's experiments (Section 5.1-5.2): joint size H = 1024, vocabulary V = 4096,
+batch of 16 over a grid of T x U from 50 x 10 to 500 x 100, and batch sizes 1..1024 at 500 x 100, with the
+paper's zero-padding scheme (padding grows linearly over the batch: acoustic 0 -> 9.3 %, labels 0 -> 45.8 %).
+
+    python -m paper_2211_16270_amd.sweep grid     # speed over the T x U grid, three ways of running the batch
+    python -m paper_2211_16270_amd.sweep batch    # speed and peak memory over the batch size
+
+Timing only (inputs are seeded random tensors made on the GPU, as in the paper's benchmark); bf16 inputs.
+Ways of running a batch:
+  packed      one call, true lengths: this library's default (padding removed, samples share launches)
+  padded      one call, every length set to the maximum: what a computation on the padded batch costs
+  one_by_one  B calls of one sample each, true lengths: the sample-wise loop without parallel iterations
+Prints one markdown table.
+"""
+from __future__ import annotations
+
+import sys
+import time
+
+import numpy as np
+
+
+def paper_lengths(B: int, T: int, U: int):
+    """Section 5.1: padding grows linearly over the batch, 0 -> 9.3 % of T and 0 -> 45.8 % of U."""
+    f = np.arange(B, dtype=np.float64) / max(B - 1, 1)
+    T_len = np.maximum(1, np.floor(T * (1.0 - 0.093 * f) + 0.5)).astype(np.int32)
+    U_len = np.maximum(0, np.floor(U * (1.0 - 0.458 * f) + 0.5)).astype(np.int32)
+    return T_len, U_len
+
+
+def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211):
+    import torch
+    from . import binding as Bd
+
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    enc = torch.randn(B, T, H, generator=g, device="cuda").to(torch.bfloat16)
+    pred = torch.randn(B, U + 1, H, generator=g, device="cuda").to(torch.bfloat16)
+    W = (torch.randn(H, V, generator=g, device="cuda") / H ** 0.5).to(torch.bfloat16)
+    b_out = torch.zeros(V, dtype=torch.float32, device="cuda")
+    labels = torch.randint(1, V, (B, max(U, 1)), generator=g, device="cuda", dtype=torch.int32)
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()       # from here on: inputs (resident) + outputs + workspace
+    T_len, U_len = paper_lengths(B, T, U)
+    if mode == "padded":
+        T_len[:] = T
+        U_len[:] = U
+    f32 = dict(dtype=torch.float32, device="cuda")
+    loss = torch.empty(B, **f32)
+    d_enc, d_pred = torch.empty(B, T, H, **f32), torch.empty(B, U + 1, H, **f32)
+    dW, db = torch.empty(H, V, **f32), torch.empty(V, **f32)
+    stream = torch.cuda.current_stream()
+    if mode == "one_by_one":
+        desc1 = Bd.make_desc(1, T, U, H, V, 0, Bd.RNNT_BF16, accumulate_params=1)
+        nb = max(Bd.rnnt_joint_loss_workspace_bytes(desc1, T_len[b:b + 1], U_len[b:b + 1]) for b in range(B))
+        ws = Bd.Workspace(nb)
+
+        def step():
+            dW.zero_()
+            db.zero_()
+            for b in range(B):
+                s = Bd.rnnt_joint_loss_fwd_bwd(desc1, enc[b:b + 1], pred[b:b + 1], W, b_out, labels[b:b + 1],
+                                               T_len[b:b + 1], U_len[b:b + 1], loss[b:b + 1], d_enc[b:b + 1],
+                                               d_pred[b:b + 1], dW, db, ws.buf, stream)
+                assert s == 0, s
+    else:
+        desc = Bd.make_desc(B, T, U, H, V, 0, Bd.RNNT_BF16)
+        nb = Bd.rnnt_joint_loss_workspace_bytes(desc, T_len, U_len)
+        ws = Bd.Workspace(nb)
+
+        def step():
+            s = Bd.rnnt_joint_loss_fwd_bwd(desc, enc, pred, W, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW, db,
+                                           ws.buf, stream)
+            assert s == 0, s
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    assert bool(torch.isfinite(loss).all())
+    rows = int(np.sum(T_len.astype(np.int64) * (U_len + 1)))
+    return dict(ms=dt * 1e3, samples_per_s=B / dt, peak_gb=torch.cuda.max_memory_allocated() / 1e9,
+                workspace_gb=nb / 1e9, rows=rows, pflops_exec=8.0 * rows * H * V / dt / 1e15)
+
+
+def main(argv):
+    which = argv[1] if len(argv) > 1 else "grid"
+    H, V = 1024, 4096
+    if which == "grid":
+        print(f"B = 16, H = {H}, V = {V}, bf16; ms per step (samples/s)\n")
+        print("| T x U | packed | padded | one_by_one | packed vs one_by_one | peak GB (packed) |")
+        print("|---|---|---|---|---|---|")
+        for T, U in [(50, 10), (100, 20), (139, 27), (232, 46), (300, 60), (400, 80), (500, 100)]:
+            r = {m: run_case(16, T, U, H, V, m, steps=5 if T <= 232 else 3) for m in ("packed", "padded", "one_by_one")}
+            print(f"| {T} x {U} | " + " | ".join(f"{r[m]['ms']:.2f} ({r[m]['samples_per_s']:.0f})"
+                                                   for m in ("packed", "padded", "one_by_one"))
+                  + f" | {r['one_by_one']['ms'] / r['packed']['ms']:.2f}x | {r['packed']['peak_gb']:.2f} |", flush=True)
+    elif which == "batch":
+        T, U = 500, 100
+        print(f"T x U = {T} x {U}, H = {H}, V = {V}, bf16, packed\n")
+        print("| B | ms per step | samples/s | executed PFLOP/s | workspace GB | peak GB (inputs + outputs + workspace) |")
+        print("|---|---|---|---|---|---|")
+        for B in (1, 4, 16, 64, 256, 1024):
+            r = run_case(B, T, U, H, V, "packed", steps=3 if B <= 64 else 2)
+            print(f"| {B} | {r['ms']:.1f} | {r['samples_per_s']:.1f} | {r['pflops_exec']:.3f} | {r['workspace_gb']:.2f} | "
+                  f"{r['peak_gb']:.2f} |", flush=True)
+    else:
+        raise SystemExit("usage: python -m paper_2211_16270_amd.sweep grid|batch")
+
+
+if __name__ == "__main__":
+    main(sys.argv)
