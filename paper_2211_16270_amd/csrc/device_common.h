@@ -100,4 +100,12 @@ __device__ __forceinline__ RowPost row_posteriors(const LatticeState& ls, long l
     return r;
 }
 
+// Asynchronous global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane l's 16 bytes land
+// at LDS byte address lds_base + 16*l (lds_base wave-uniform, passed in M0).  Completion is tracked by
+// the wave's vmcnt counter; the compiler does not see these loads, so the waits are explicit below.
+__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+
+
 }  // namespace rnnt

@@ -371,192 +371,6 @@ hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const Sa
 }
 
 // ------------------------------------------------------------------------------------------------
-// C = A B^T on bf16 MFMA: A [M,K], B [N,K], both with the contraction index contiguous.
-// 128x128 tile per workgroup, 32-wide K steps through double-buffered LDS, 4 waves in 2x2,
-// each wave 64x64 (2x2 accumulator tiles).
-//   MODE 0 (dz):  A = dH [rows,V], B = W_out [H,V]; epilogue applies the tanh derivative and sums
-//                 over the label positions / frames of each 8x8 lattice tile (Alg. 1 lines 10, 11)
-//   MODE 1 (dW):  A = Zt [H,ld], B = dHt [V,ld], K split over blockIdx.z; epilogue adds into dW_out
-//                 (Alg. 1 line 8)
-// ------------------------------------------------------------------------------------------------
-constexpr int GT = 128;       // tile edge
-constexpr int GK = 32;        // K step
-constexpr int GP = 40;        // LDS row pitch in bf16 elements (80 B: conflict-free 16 B reads)
-
-struct GemmArgs {
-    const bf16_t* A;
-    const bf16_t* B;
-    long long lda, ldb;
-    long long K;             // contraction length (MODE 1: whole row count)
-    long long k_per_split;   // MODE 1
-    // MODE 0
-    Problem pr;
-    SampleTable st;
-    int s0, s1, tile0, tile1;
-    float* d_enc;
-    float* d_pred;
-    // MODE 1
-    float* dW;
-    int V;
-    int m_tiles, n_tiles;   // MODE 0 grid
-};
-
-template <int MODE>
-__global__ __launch_bounds__(256, 2) void k_gemm_nt(GemmArgs g) {
-    __shared__ __align__(16) bf16_t As[2][GT * GP];
-    __shared__ __align__(16) bf16_t Bs[2][GT * GP];
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
-    const int wm = wave >> 1, wn = wave & 1;
-    // XCD-aware order (ids that agree modulo 8 share an L2): the column tiles of one row tile are
-    // neighbours on one XCD, so the row tile of A is fetched from HBM once.
-    int bx = blockIdx.x, by = blockIdx.y;
-    if (MODE == 0) {
-        const int L = blockIdx.x, xcd = L & 7, q = L >> 3;
-        by = q % g.n_tiles;
-        bx = xcd + 8 * (q / g.n_tiles);
-        if (bx >= g.m_tiles) return;
-    }
-    const long long m0 = (long long)bx * GT, n0 = (long long)by * GT;
-    long long ks = 0, ke = g.K;
-    if (MODE == 1) {
-        ks = (long long)blockIdx.z * g.k_per_split;
-        ke = ks + g.k_per_split < g.K ? ks + g.k_per_split : g.K;
-        }
-    const int lrow = tid >> 2, lseg = tid & 3;
-    const bf16_t* Ag = g.A + (m0 + lrow) * g.lda + lseg * 8;
-    const bf16_t* Bg = g.B + (n0 + lrow) * g.ldb + lseg * 8;
-    bf16x8 ra0, ra1, rb0, rb1;
-    auto gload = [&](long long k0) {
-        ra0 = *reinterpret_cast<const bf16x8*>(Ag + k0);
-        ra1 = *reinterpret_cast<const bf16x8*>(Ag + 64 * g.lda + k0);
-        rb0 = *reinterpret_cast<const bf16x8*>(Bg + k0);
-        rb1 = *reinterpret_cast<const bf16x8*>(Bg + 64 * g.ldb + k0);
-    };
-    auto sstore = [&](int buf) {
-        *reinterpret_cast<bf16x8*>(&As[buf][lrow * GP + lseg * 8]) = ra0;
-        *reinterpret_cast<bf16x8*>(&As[buf][(lrow + 64) * GP + lseg * 8]) = ra1;
-        *reinterpret_cast<bf16x8*>(&Bs[buf][lrow * GP + lseg * 8]) = rb0;
-        *reinterpret_cast<bf16x8*>(&Bs[buf][(lrow + 64) * GP + lseg * 8]) = rb1;
-    };
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{0};
-
-    gload(ks);
-    sstore(0);
-    __syncthreads();
-    int buf = 0;
-    for (long long k0 = ks; k0 < ke; k0 += GK) {
-        const bool more = (k0 + GK < ke);
-        if (more) gload(k0 + GK);
-        const bf16_t* as = &As[buf][(wm * 64 + l32) * GP + hb * 8];
-        const bf16_t* bs = &Bs[buf][(wn * 64 + l32) * GP + hb * 8];
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(as + kk * 16);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(as + 32 * GP + kk * 16);
-            const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(bs + kk * 16);
-            const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(bs + 32 * GP + kk * 16);
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
-        }
-        if (more) sstore(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
-    }
-
-    if (MODE == 1) {
-        // C[m = hidden index][n = vocabulary index]; lanes are consecutive vocabulary entries
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
-                const long long n = n0 + wn * 64 + nt * 32 + l32;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const long long m = m0 + wm * 64 + mt * 32 + 8 * (i >> 2) + 4 * hb + (i & 3);
-                    atomicAdd(&g.dW[m * g.V + n], acc[mt][nt][i]);
-                }
-            }
-    } else {
-        // rows wm*64 .. +63 of this workgroup are one lattice tile: row = 8*tl + ul, and in the
-        // accumulator layout register 4j+i of row-tile mt is tl = 4*mt + j, ul = 4*hb + i.
-        const int tile = g.tile0 + bx * 2 + wm;
-        if (tile < g.tile1) {
-            const TilePos tp = locate_tile(g.st, g.s0, g.s1, tile);
-            const int b = tp.s, H = g.pr.H;
-            const bf16_t* enc = reinterpret_cast<const bf16_t*>(g.pr.enc) + (size_t)b * g.pr.T_max * H;
-            const bf16_t* prd = reinterpret_cast<const bf16_t*>(g.pr.pred) + (size_t)b * (g.pr.U_max + 1) * H;
-            float* d_enc = g.d_enc + (size_t)b * g.pr.T_max * H;
-            float* d_prd = g.d_pred + (size_t)b * (g.pr.U_max + 1) * H;
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
-                const int h = (int)n0 + wn * 64 + nt * 32 + l32;
-                float e[8], q[4], pu[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                for (int tl = 0; tl < 8; ++tl)
-                    e[tl] = (tp.t0 + tl < tp.T) ? (float)enc[(size_t)(tp.t0 + tl) * H + h] : 0.0f;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    q[i] = (tp.u0 + 4 * hb + i <= tp.U) ? (float)prd[(size_t)(tp.u0 + 4 * hb + i) * H + h] : 0.0f;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int tl = 4 * mt + j;
-                        const bool tv = (tp.t0 + tl < tp.T);
-                        float se = 0.0f;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const bool ok = tv && (tp.u0 + 4 * hb + i <= tp.U);
-                            const float z = fast_tanh(e[tl] + q[i]);
-                            const float dx = ok ? acc[mt][nt][4 * j + i] * (1.0f - z * z) : 0.0f;
-                            se += dx;
-                            pu[i] += dx;
-                        }
-                        se += __shfl_xor(se, 32, 64);
-                        if (tv && hb == (j & 1)) atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
-                    }
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (tp.u0 + 4 * hb + i <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + 4 * hb + i) * H + h], pu[i]);
-            }
-        }
-    }
-}
-
-hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0, int tile1,
-                               const void* dH, float* d_enc, float* d_pred, hipStream_t stream) {
-    const int n = tile1 - tile0;
-    if (n <= 0) return hipSuccess;
-    GemmArgs g{};
-    g.A = (const bf16_t*)dH;
-    g.lda = pr.V;
-    g.B = (const bf16_t*)pr.W;
-    g.ldb = pr.V;
-    g.K = pr.V;
-    g.k_per_split = pr.V;
-    g.pr = pr;
-    g.st = st;
-    g.s0 = s0;
-    g.s1 = s1;
-    g.tile0 = tile0;
-    g.tile1 = tile1;
-    g.d_enc = d_enc;
-    g.d_pred = d_pred;
-    g.m_tiles = (n + 1) / 2;
-    g.n_tiles = pr.H / GT;
-    const int m8 = (g.m_tiles + 7) / 8 * 8;
-    k_gemm_nt<0><<<dim3((unsigned)(m8 * g.n_tiles)), dim3(256), 0, stream>>>(g);
-    return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------------
 // dW += Z^T dH and db += column sums of dH (Alg. 1 line 8) as one split-K GEMM with 256x256 tiles.
 // 256 threads = 4 waves in 2 (hidden) x 2 (vocabulary), one per SIMD; each wave owns 128 x 128 = 4 x 4
 // accumulator tiles (256 accumulator registers), so that a k16-step reads 8 fragments from LDS for 16
@@ -595,13 +409,6 @@ __device__ __forceinline__ bf16x8 lds_read_tr_frag(const bf16_t* p) {
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * WT));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
-}
-
-// Asynchronous global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane l's 16 bytes land
-// at LDS byte address lds_base + 16*l (lds_base wave-uniform, passed in M0).  Completion is tracked by
-// the wave's vmcnt counter; the compiler does not see these loads, so the waits are explicit below.
-__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
 }
 
 __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {

@@ -1,0 +1,246 @@
+// Unfused backward, second half (Alg. 1 lines 10, 11) for hidden sizes the fused kernel does not cover:
+//   dz = dH W_out^T   (dH [rows,V] from the chunk buffer, W_out [H,V]: both with the contraction index,
+//                      the vocabulary, contiguous),
+//   dx = dz (1 - z^2),  d_enc[t] += sum_u dx,  d_pred[u] += sum_t dx  per 8x8 lattice tile.
+//
+// 256x256 output tile (4 lattice tiles x 256 hidden) per workgroup; 256 threads = 4 waves in 2 x 2, one per
+// SIMD, each 128 x 128 = 4 x 4 accumulator tiles (256 accumulator registers), so that one k16-step is 8
+// LDS fragment reads for 16 MFMAs.  Stages of 64 vocabulary entries (whole 128-byte lines of the operand
+// rows) travel global -> LDS asynchronously (global_load_lds) into two stage buffers.  A stage holds the
+// operand rows as 128-byte LDS rows; the 16-byte segment s of row r lies at position s ^ ((r/2)%8), which
+// makes the 16-byte fragment reads of 16 consecutive rows hit all 64 banks.  Fragments are read one
+// k16-step ahead of their MFMAs, also across the stage hand-over.  The epilogue recomputes
+// z = tanh(enc + pred) in fp32 from input rows staged in LDS.
+#include "device_common.h"
+
+namespace rnnt {
+
+namespace {
+
+constexpr int ZT = 256;       // tile edge
+constexpr int ZK = 64;        // vocabulary entries per stage: one 128-byte line of every operand row
+constexpr int ZST = 2;        // stages
+constexpr unsigned Z_OPER = (unsigned)ZT * ZK * 2u;     // bytes of one operand of a stage
+constexpr unsigned Z_STAGE = 2u * Z_OPER;
+constexpr int Z_EP = 264;     // pitch (bf16 elements) of the epilogue's enc / pred rows in LDS
+
+struct DzArgs {
+    const bf16_t* dH;
+    const bf16_t* W;
+    Problem pr;
+    SampleTable st;
+    int s0, s1, tile0, tile1;
+    float* d_enc;
+    float* d_pred;
+    int m_tiles, n_tiles;
+    long long rows;           // rows of the dH chunk buffer that were written (a multiple of 64)
+};
+
+__global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
+    extern __shared__ __align__(16) unsigned char dz_smem[];   // [ZST] x { A [256][64], B [256][64] } bf16
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+    // XCD-aware order (ids that agree modulo 8 share an L2): the hidden tiles of one row tile are
+    // neighbours on one XCD, so the rows of dH are fetched from HBM once.
+    const int L = blockIdx.x, xcd = L & 7, q = L >> 3;
+    const int by = q % g.n_tiles, bx = xcd + 8 * (q / g.n_tiles);
+    if (bx >= g.m_tiles) return;
+    const int H = g.pr.H, V = g.pr.V;
+    const long long m0 = (long long)bx * ZT;
+    const int n0 = by * ZT;
+    const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)dz_smem;
+
+    // global -> LDS: one DMA instruction moves 8 operand rows of 128 bytes (whole cache lines: with
+    // 64-byte pieces every line would be fetched into L1 twice, by two stages).  Wave w moves row groups
+    // w, w+4, ..., w+28 of both operands.  Lane l serves row l/8 of the group and LDS segment l%8, which
+    // holds global segment (l%8) ^ ((row/2)%8).  Rows past the end of the operand re-read its last row;
+    // their products are never stored.
+    const bf16_t* Ag[8];
+    const bf16_t* Bg[8];
+    unsigned dst[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int row = 8 * (wave + 4 * i) + (lane >> 3);
+        const int seg = (lane & 7) ^ ((row >> 1) & 7);
+        long long ar = m0 + row;
+        if (ar > g.rows - 1) ar = g.rows - 1;
+        int br = n0 + row;
+        if (br > H - 1) br = H - 1;
+        Ag[i] = g.dH + ar * V + seg * 8;
+        Bg[i] = g.W + (long long)br * V + seg * 8;
+        dst[i] = (unsigned)(8 * (wave + 4 * i)) * 128u;
+    }
+    auto issue = [&](int step) {
+        const unsigned sb = smem_base + (unsigned)(step & (ZST - 1)) * Z_STAGE;
+        const int k0 = step * ZK;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            lds_dma16(Ag[i] + k0, __builtin_amdgcn_readfirstlane(sb + dst[i]));
+            lds_dma16(Bg[i] + k0, __builtin_amdgcn_readfirstlane(sb + Z_OPER + dst[i]));
+        }
+    };
+    // fragment of 32 rows, k16-step kk of a stage: lane holds row l32, segment 2*kk + hb at position
+    // (2*kk + hb) ^ ((row/2)%8): sixteen consecutive rows then cover all 64 banks
+    const int xr = (l32 >> 1) & 7;
+    unsigned frag_off[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) frag_off[kk] = (unsigned)l32 * 128u + (unsigned)(((2 * kk + hb) ^ xr) << 4);
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x16{0};
+
+    const int nsteps = V / ZK;
+    bf16x8 fa[2][4], fb[2][4];
+    auto read_frags = [&](int set, int stage, int kk) {
+        const unsigned char* st = dz_smem + (size_t)(stage & (ZST - 1)) * Z_STAGE + frag_off[kk];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+            fa[set][mt] = *reinterpret_cast<const bf16x8*>(st + (wm * 128 + mt * 32) * 128);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+            fb[set][nt] = *reinterpret_cast<const bf16x8*>(st + Z_OPER + (wn * 128 + nt * 32) * 128);
+    };
+    auto multiply = [&](int set) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][mt], fb[set][nt], acc[mt][nt], 0, 0, 0);
+    };
+    // Two stage buffers.  Fragments are read one k16-step ahead of their MFMAs.  Before the last
+    // k16-step of a stage every wave has issued all its reads of that stage: there the next stage is
+    // waited for (own copies, then everyone's) and the stage after it is sent into the buffer just left.
+    issue(0);
+    if (nsteps > 1) issue(1);
+    if (nsteps > 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    read_frags(0, 0, 0);
+    for (int it = 0; it < nsteps; ++it) {
+        read_frags(1, it, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(0, it, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, it, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (it + 1 < nsteps) {
+            // all reads of stage `it` are issued; they must also be complete before its buffer is refilled
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (it + 2 < nsteps) issue(it + 2);
+            read_frags(0, it + 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- epilogue: dx = dz (1 - z^2) with z = tanh(enc + pred) recomputed in fp32, summed over the label
+    // positions / frames of each lattice tile.  The 8 + 8 input rows of the workgroup's four lattice
+    // tiles (this tile's 256 hidden columns) go through LDS, which the main loop no longer needs.
+    __syncthreads();
+    bf16_t* eq = reinterpret_cast<bf16_t*>(dz_smem);              // [4 tiles][16 rows][Z_EP]
+    {
+        // 4 tiles x 16 rows x 32 chunks of 8 columns = 2048 chunks, 8 per thread
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int e = tid + 256 * i;
+            const int c = e & 31, r = (e >> 5) & 15, t4 = e >> 9;
+            const int tile = g.tile0 + bx * 4 + t4;
+            bf16x8 v;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (bf16_t)0.0f;
+            if (tile < g.tile1 && n0 + c * 8 < H) {
+                const TilePos tp = locate_tile(g.st, g.s0, g.s1, tile);
+                if (r < 8) {
+                    if (tp.t0 + r < tp.T)
+                        v = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(g.pr.enc) +
+                                                             ((size_t)tp.s * g.pr.T_max + tp.t0 + r) * H + n0 + c * 8);
+                } else if (tp.u0 + r - 8 <= tp.U) {
+                    v = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(g.pr.pred) +
+                                                         ((size_t)tp.s * (g.pr.U_max + 1) + tp.u0 + r - 8) * H + n0 + c * 8);
+                }
+            }
+            *reinterpret_cast<bf16x8*>(eq + (t4 * 16 + r) * Z_EP + c * 8) = v;
+        }
+    }
+    __syncthreads();
+    // Rows wm*128 + 64*lt .. +63 are one lattice tile (row = 8*tl + ul); accumulator register 4j+i of
+    // row block mt = 2*lt + m2 is frame tl = 4*m2 + j, label position ul = 4*hb + i, hidden column l32.
+#pragma unroll
+    for (int lt = 0; lt < 2; ++lt) {
+        const int t4 = wm * 2 + lt;
+        const int tile = g.tile0 + bx * 4 + t4;
+        if (tile >= g.tile1) continue;
+        const TilePos tp = locate_tile(g.st, g.s0, g.s1, tile);
+        const int b = tp.s;
+        float* d_enc = g.d_enc + (size_t)b * g.pr.T_max * H;
+        float* d_prd = g.d_pred + (size_t)b * (g.pr.U_max + 1) * H;
+        const bf16_t* er = eq + (t4 * 16) * Z_EP;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            const int hc = wn * 128 + nt * 32 + l32;        // column inside the tile
+            const int h = n0 + hc;
+            if (h >= H) continue;
+            float qv[4], pu[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) qv[i] = (float)er[(8 + 4 * hb + i) * Z_EP + hc];
+#pragma unroll
+            for (int m2 = 0; m2 < 2; ++m2)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int tl = 4 * m2 + j;
+                    const bool tv = (tp.t0 + tl < tp.T);
+                    const float ev = (float)er[tl * Z_EP + hc];
+                    float se = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const bool ok = tv && (tp.u0 + 4 * hb + i <= tp.U);
+                        const float z = fast_tanh(ev + qv[i]);
+                        const float dx = ok ? acc[2 * lt + m2][nt][4 * j + i] * (1.0f - z * z) : 0.0f;
+                        se += dx;
+                        pu[i] += dx;
+                    }
+                    se += __shfl_xor(se, 32, 64);
+                    if (tv && hb == (j & 1)) atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
+                }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (tp.u0 + 4 * hb + i <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + 4 * hb + i) * H + h], pu[i]);
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0, int tile1,
+                               const void* dH, float* d_enc, float* d_pred, hipStream_t stream) {
+    const int n = tile1 - tile0;
+    if (n <= 0) return hipSuccess;
+    if (pr.V % ZK != 0) return hipErrorInvalidValue;
+    DzArgs g{(const bf16_t*)dH, (const bf16_t*)pr.W, pr, st, s0, s1, tile0, tile1, d_enc, d_pred,
+             (n + 3) / 4, (pr.H + ZT - 1) / ZT, (long long)n * 64};
+    const size_t smem = (size_t)ZST * Z_STAGE;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_dz256),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int m8 = (g.m_tiles + 7) / 8 * 8;
+    k_gemm_dz256<<<dim3((unsigned)(m8 * g.n_tiles)), dim3(256), smem, stream>>>(g);
+    return hipGetLastError();
+}
+
+}  // namespace rnnt
