@@ -238,3 +238,37 @@ def test_bf16_memory_headline_workload_sampled():
     _say("C4 sample errs", el, ee, ep)
     assert el <= tol["loss"] and ee <= tol["grad"] and ep <= tol["grad"]
     assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-2 * float(np.abs(got["db_out"]).sum())
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_small_shapes_against_the_checker(seed):
+    # seeded random shapes, lengths and blank positions, both precisions; labels may equal the blank
+    rng = np.random.default_rng(9000 + seed)
+    bf16 = bool(seed % 3)
+    if bf16:
+        H = int(rng.choice([128, 256, 384, 512, 640, 768, 1024]))
+        V = int(rng.choice([256, 512, 768, 1024]))
+    else:
+        H = int(rng.integers(1, 70))
+        V = int(rng.integers(2, 90))
+    B = int(rng.integers(1, 6))
+    T_max = int(rng.integers(1, 41))
+    U_max = int(rng.integers(0, 21))
+    blank = int(rng.integers(0, V))
+    wl = synth.custom_workload(f"rnd{seed}", B=B, T_max=T_max, U_max=U_max, H=H, V=V, dtype="bf16" if bf16 else "f32",
+                               index=300 + seed)
+    batch = synth.make_batch(wl)
+    T_len = rng.integers(1, T_max + 1, size=B)
+    U_len = rng.integers(0, U_max + 1, size=B)
+    batch = synth.with_lengths(batch, T_len, U_len)
+    labels = rng.integers(0, V, size=batch.labels.shape).astype(np.int32)        # blank included on purpose
+    for b in range(B):
+        labels[b, U_len[b]:] = -1
+    import dataclasses
+    batch = dataclasses.replace(batch, labels=labels)
+    _say("random shape", seed, "bf16" if bf16 else "f32", dict(B=B, T_max=T_max, U_max=U_max, H=H, V=V, blank=blank),
+         T_len.tolist(), U_len.tolist())
+    got = run_gpu(batch, blank=blank)
+    ref = run_oracle(batch, blank=blank)
+    assert_parity(got, ref, wl.dtype, f"random shape {seed}")
+    assert_padding_zero(got, batch)
