@@ -143,7 +143,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
     const bf16_t* zrow1 = zs + (32 + l32) * ZP + hb * 8;
 
     // Main loop.  Per step of 256 vocabulary entries wave w owns NVT tiles of 32 entries for all 64
-    // rows (NVT x 2 accumulator tiles).  VALU instructions do not overlap with MFMAs on this
+    // rows (NVT x 2 accumulator tiles).  VALU instructions of a wave do not overlap with its own MFMAs on this
     // hardware, so the loop is written to contain almost none: A fragments (W_out^T) stream from L2
     // with scalar base + lane offset + immediate addressing into the register set that is not being
     // consumed (two sets, blocks of JT_PF k16-steps, one block ahead, possibly into the next

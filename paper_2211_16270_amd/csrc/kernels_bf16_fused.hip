@@ -143,7 +143,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) dz[i][rt] = f32x16{0};
 
-    // Fragment streams from L2.  VALU instructions do not overlap with MFMAs on this hardware, so both
+    // Fragment streams from L2.  VALU instructions of a wave do not overlap with its own MFMAs on this hardware, so both
     // MFMA loops address their fragments as scalar base + lane offset + immediate and load into the
     // register set that is not being consumed (two sets, one block ahead).
     const int wv = __builtin_amdgcn_readfirstlane(wave);
