@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_FLOPS = 2.5e15     # MI355X dense bf16 MFMA
 PEAK_F32_FLOPS = 157.3e12    # MI355X fp32 vector
-CPU_SAMPLE = {"C1": 2, "C2": 32, "C3": 12, "C4": 12, "C5": 32}  # samples the checker is timed on (10-30 s)
+CPU_SAMPLE = {"C1": 2, "C2": 32, "C3": 12, "C4": 12, "C5": 8}  # samples the checker is timed on (10-30 s)
 COPY_BYTES = 256 << 20
 
 
