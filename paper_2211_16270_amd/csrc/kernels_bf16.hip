@@ -23,7 +23,6 @@ namespace rnnt {
 // ------------------------------------------------------------------------------------------------
 constexpr int JT_ROWS = 64;
 constexpr int JT_VSTEP = 256;
-constexpr int JT_PF = 4;        // A-fragment prefetch distance in k16-steps (H/16 must be a multiple)
 constexpr int STG_PITCH = 40;   // bf16 elements per row of a wave's 32x32 transposition buffer
 
 struct JointArgs {
@@ -38,7 +37,8 @@ struct JointArgs {
 };
 
 
-template <int MODE, int NW, int NVT>
+// JT_PF: A-fragment prefetch distance in k16-steps; H/16 must be an even multiple of it.
+template <int MODE, int NW, int NVT, int JT_PF>
 __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
     static_assert(NW * NVT * 32 == JT_VSTEP, "waves x tiles must cover one vocabulary step");
     constexpr int NT = 64 * NW;
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
     // vocabulary step); B fragments (joint tile, LDS) are read one k16-step ahead with immediate
     // offsets from a per-block pointer.  Scheduling barriers keep the reads ahead of the MFMAs.
     const int nvs = V / JT_VSTEP;
-    const int nkb = KK / JT_PF;                       // even: H is a multiple of 128
+    const int nkb = KK / JT_PF;                       // even: H is a multiple of 32*JT_PF
     const int wv = __builtin_amdgcn_readfirstlane(wave);
     const char* wpb = reinterpret_cast<const char*>(a.Wp);
     const unsigned lane_b = (unsigned)lane * 16u;
@@ -341,33 +341,35 @@ static size_t joint_smem_bytes(int H, int mode, int nw) {
 }
 
 // Forward and unfused backward: 4 waves x two 32-entry tiles each.
-template <int MODE, int NW, int NVT>
+template <int MODE, int NW, int NVT, int PF>
 static hipError_t launch_joint(const JointArgs& a, hipStream_t stream) {
     const int n = a.tile1 - a.tile0;
     if (n <= 0) return hipSuccess;
     const size_t smem = joint_smem_bytes(a.pr.H, MODE, NW);
     static size_t configured = 0;
     if (smem > configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_scores<MODE, NW, NVT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_scores<MODE, NW, NVT, PF>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         configured = smem;
     }
-    k_joint_scores<MODE, NW, NVT><<<dim3((unsigned)n), dim3(64 * NW), smem, stream>>>(a);
+    k_joint_scores<MODE, NW, NVT, PF><<<dim3((unsigned)n), dim3(64 * NW), smem, stream>>>(a);
     return hipGetLastError();
 }
 
 hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st, const LatticeState& ls,
                            int s0, int s1, int tile0, int tile1, hipStream_t stream) {
     JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr};
-    return launch_joint<0, 4, 2>(a, stream);
+    // a longer prefetch distance where the hidden size allows it (the forward kernel has the registers)
+    if (pr.H % 256 == 0) return launch_joint<0, 4, 2, 8>(a, stream);
+    return launch_joint<0, 4, 2, 4>(a, stream);
 }
 
 hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                                   const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
                                   void* Z, hipStream_t stream) {
     JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)dH, (bf16_t*)Z};
-    return launch_joint<1, 4, 2>(a, stream);
+    return launch_joint<1, 4, 2, 4>(a, stream);
 }
 
 // ------------------------------------------------------------------------------------------------
