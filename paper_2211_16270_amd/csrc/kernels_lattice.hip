@@ -178,13 +178,14 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
 // Same recursion for lattices with at most 64 label positions (U + 1 <= 64): one wavefront per
 // (sample, direction), no barrier; the neighbouring column arrives by a lane shift.
 //
-// The emission log-probabilities reach the recursion through LDS: rows are staged in blocks of
-// LW_RB lattice frames by asynchronous global -> LDS copies, one block ahead of the block the
-// sweep is in, so the sequential steps wait for LDS reads only, never for global memory.  The ring keeps LW_NB blocks; a step touches frames k-U-1 .. k (in sweep order), i.e. at
-// most the current block and the two before it.
-constexpr int LW_RB = 32;                 // frames per staged block
-constexpr int LW_NB = 4;                  // blocks in the ring
-constexpr int LW_SLOT = LW_RB * 64;       // floats per block slot (row stride U+1 <= 64)
+// The emission log-probabilities reach the recursion through LDS: a ring of LW_ROWS sweep rows (frames in
+// sweep order: upwards for alpha, downwards for beta) of 64 floats each, filled in blocks of LW_RB rows
+// by asynchronous global -> LDS copies one block ahead of the block the sweep is in.  The sequential
+// steps then wait for LDS reads only, issued one step ahead, and every per-step index advances by an
+// addition: with a single wave per SIMD the step time is the issue time of its instructions.
+constexpr int LW_RB = 32;                 // sweep rows per staged block
+constexpr int LW_ROWS = 128;              // rows in the ring (a step touches its row and the 64 before it)
+constexpr int LW_RING = LW_ROWS * 64;     // floats per array
 
 // Value of lane l-1 (lane 0 keeps its own) / lane l+1 (lane 63 keeps its own): whole-wavefront
 // shifts on the data-parallel-primitive path of v_mov, no LDS round trip.
@@ -216,9 +217,9 @@ __device__ __forceinline__ void lds_dma4(const void* gptr, unsigned lds_base) {
 
 __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeState ls, int s0,
                                                      float* __restrict__ loss) {
-    extern __shared__ __align__(16) float lw_smem[];    // ring_b [LW_NB][LW_SLOT], ring_y [LW_NB][LW_SLOT]
+    extern __shared__ __align__(16) float lw_smem[];    // ring_b [LW_ROWS][64], ring_y [LW_ROWS][64]
     const float* ring_b = lw_smem;
-    const float* ring_y = lw_smem + LW_NB * LW_SLOT;
+    const float* ring_y = lw_smem + LW_RING;
     const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) float*)lw_smem;
     const int s = s0 + blockIdx.x;
     const bool is_beta = (blockIdx.y != 0);
@@ -229,64 +230,70 @@ __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeStat
     const float* __restrict__ lpy = ls.lpy + base;
     const int n = T * W1;
     const float c = -wave_sum(emission_max_partial(lpb, lpy, n, W1, U, u, 64)) / (float)n;
-    const bool col = (u <= U);
     const int nsteps = T + U;
-    const int nld = (LW_RB * W1 + 63) >> 6;      // 256-byte copies that cover one block
-    float own = RNNT_NEG_INF;
+    const unsigned T_act = (u <= U) ? (unsigned)T : 0u;     // lanes beyond the last label position never act
 
-    // Block q of the sweep holds frames [first(q), first(q) + LW_RB): alpha walks frames upwards
-    // (first = q*LW_RB), beta downwards (first = T - (q+1)*LW_RB).  Indices outside the sample
-    // are clamped to a valid one; such values are never used by an active lane.
+    // Block q holds sweep rows d = q*LW_RB .. +LW_RB-1, i.e. frame d (alpha) or T-1-d (beta); one copy per
+    // row and array, lane = column.  Indices outside the sample (rows past its end, lanes past the row)
+    // are clamped to a valid one; such values are never used by an acting lane.
     auto issue = [&](int q) {
-        const int g0 = (is_beta ? T - (q + 1) * LW_RB : q * LW_RB) * W1 + u;
-        const unsigned dst = smem_base + (unsigned)(q & (LW_NB - 1)) * (LW_SLOT * 4);
-        for (int j = 0; j < nld; ++j) {
-            int idx = g0 + j * 64;
+        for (int j = 0; j < LW_RB; ++j) {
+            const int d = q * LW_RB + j;
+            const int t = is_beta ? T - 1 - d : d;
+            int idx = t * W1 + u;
             idx = idx < 0 ? 0 : (idx > n - 1 ? n - 1 : idx);
-            lds_dma4(lpb + idx, dst + j * 256);
-            lds_dma4(lpy + idx, dst + LW_NB * LW_SLOT * 4 + j * 256);
+            const unsigned dst = smem_base + (unsigned)(d & (LW_ROWS - 1)) * 256u;
+            lds_dma4(lpb + idx, __builtin_amdgcn_readfirstlane(dst));
+            lds_dma4(lpy + idx, __builtin_amdgcn_readfirstlane(dst + LW_RING * 4u));
         }
     };
     // waits for the staged copies; the LDS reads already issued must be complete as well, since the
-    // next copy overwrites the block that the current step's (already fetched) operands came from
+    // next copy overwrites rows that an already fetched operand may have come from
     auto landed = [&]() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); };
     issue(0);
     issue(1);
     landed();
 
-    // Step k computes node (t, u) with t = k - u (alpha) or t = T-1 - (k - (U-u)) (beta).  Its two
-    // emission values are read from LDS during step k-1, so that only the lane shift and the
-    // log-add-exp are on the sequential path.
+    // Step k computes the node at sweep row d = k - u (alpha, frame t = d) resp. d = k - (U - u) (beta,
+    // frame t = T-1-d).  Step 0 has a single node, handled up front; the emission values of step k+1 are
+    // read from the ring during step k.
     if (!is_beta) {
         float* __restrict__ alpha = ls.alpha + base;
-        const int um = u > 0 ? u - 1 : 0;
-        auto ring_at = [&](int t) {           // float index of (frame max(t,0), column 0)
-            const int tc = t < 0 ? 0 : t;
-            return ((tc / LW_RB) & (LW_NB - 1)) * LW_SLOT + (tc & (LW_RB - 1)) * W1;
-        };
-        int r_prev = ring_at(-u - 1), r_cur = ring_at(-u);
-        float eb = ring_b[r_prev + u] + c, ey = ring_y[r_cur + um] + c;
-        for (int k = 0; k < nsteps; ++k) {
+        float own = RNNT_NEG_INF;
+        if (u == 0) {
+            alpha[0] = 0.0f;
+            own = 0.0f;
+        }
+        const bool has_left = (u > 0);
+        const int du = has_left ? 1 : 0;
+        int d = 1 - u;                                              // sweep row of step 1
+        unsigned so = (unsigned)(d * W1 + u);                       // index of the node written at step 1
+        // blank emission of frame d-1 at column u, label emission of frame d at column u-1
+        unsigned rb = (unsigned)((((d - 1) & (LW_ROWS - 1)) << 6) + u);
+        unsigned ry = (unsigned)(((d & (LW_ROWS - 1)) << 6) + u - du);
+        float eb = ring_b[rb], ey = ring_y[ry];
+        for (int k = 1; k < nsteps; ++k) {
             if (((k + 1) & (LW_RB - 1)) == 0) {     // step k+1 is the first to read block (k+1)/LW_RB
                 landed();
                 issue((k + 1) / LW_RB + 1);
             }
-            const int t = k - u;
-            r_prev = r_cur;
-            r_cur = ring_at(t + 1);
-            const float eb_n = ring_b[r_prev + u], ey_n = ring_y[r_cur + um];
-            const bool act = col && t >= 0 && t < T;
-            const float left = lane_from_below(own);            // column u-1, previous step
-            const float a = (t > 0) ? own + eb : RNNT_NEG_INF;
-            const float b = (u > 0) ? left + ey : RNNT_NEG_INF;
-            float val = log_add_exp_fast(a, b);
-            if (k == 0) val = 0.0f;
+            rb = ry + du;
+            ry = (ry + 64u) & (LW_RING - 1);
+            const float eb_n = ring_b[rb], ey_n = ring_y[ry];
+            const bool act = (unsigned)d < T_act;
+            const float oc = own + c;
+            const float left = lane_from_below(oc);                 // column u-1, previous step
+            const float a = (d > 0) ? oc + eb : RNNT_NEG_INF;
+            const float b = has_left ? left + ey : RNNT_NEG_INF;
+            const float val = log_add_exp_fast(a, b);
             if (act) {
-                alpha[t * W1 + u] = val;
+                alpha[so] = val;
                 own = val;
             }
-            eb = eb_n + c;
-            ey = ey_n + c;
+            so += (unsigned)W1;
+            d += 1;
+            eb = eb_n;
+            ey = ey_n;
         }
         if (u == U) {
             const float lnP_off = own + (lpb[(T - 1) * W1 + U] + c);
@@ -296,33 +303,37 @@ __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeStat
         }
     } else {
         float* __restrict__ beta = ls.beta + base;
-        auto ring_at = [&](int d) {           // float index of (frame T-1-max(d,0), column u)
-            const int dc = d < 0 ? 0 : d;
-            return ((dc / LW_RB) & (LW_NB - 1)) * LW_SLOT + (LW_RB - 1 - (dc & (LW_RB - 1))) * W1 + u;
-        };
-        int r = ring_at(-(U - u));
-        float eb = ring_b[r] + c, ey = ring_y[r] + c;
-        for (int k = 0; k < nsteps; ++k) {
+        float own = RNNT_NEG_INF;
+        if (u == U) {
+            own = ring_b[u] + c;                                    // beta[T-1,U] = final blank
+            beta[(T - 1) * W1 + U] = own;
+        }
+        const bool has_right = (u < U);
+        int d = 1 - (U - u);                                        // sweep row of step 1
+        unsigned so = (unsigned)((T - 1 - d) * W1 + u);
+        unsigned ro = (unsigned)(((d & (LW_ROWS - 1)) << 6) + u);   // both emissions of the node itself
+        float eb = ring_b[ro], ey = ring_y[ro];
+        for (int k = 1; k < nsteps; ++k) {
             if (((k + 1) & (LW_RB - 1)) == 0) {
                 landed();
                 issue((k + 1) / LW_RB + 1);
             }
-            const int d = k - (U - u);                          // frames below the last one
-            const int t = T - 1 - d;
-            r = ring_at(d + 1);
-            const float eb_n = ring_b[r], ey_n = ring_y[r];
-            const bool act = col && t >= 0 && t < T;
-            const float right = lane_from_above(own);           // column u+1, previous step
-            const float a = (t < T - 1) ? own + eb : RNNT_NEG_INF;
-            const float b = (u < U) ? right + ey : RNNT_NEG_INF;
-            float val = log_add_exp_fast(a, b);
-            if (k == 0) val = eb;                               // beta[T-1,U] = final blank
+            ro = (ro + 64u) & (LW_RING - 1);
+            const float eb_n = ring_b[ro], ey_n = ring_y[ro];
+            const bool act = (unsigned)d < T_act;
+            const float oc = own + c;
+            const float right = lane_from_above(oc);                // column u+1, previous step
+            const float a = (d > 0) ? oc + eb : RNNT_NEG_INF;       // d > 0: frame t < T-1
+            const float b = has_right ? right + ey : RNNT_NEG_INF;
+            const float val = log_add_exp_fast(a, b);
             if (act) {
-                beta[t * W1 + u] = val;
+                beta[so] = val;
                 own = val;
             }
-            eb = eb_n + c;
-            ey = ey_n + c;
+            so -= (unsigned)W1;
+            d += 1;
+            eb = eb_n;
+            ey = ey_n;
         }
     }
 }
@@ -331,7 +342,7 @@ hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0,
                           hipStream_t stream) {
     if (s1 <= s0) return hipSuccess;
     if (u_max + 1 <= 64) {
-        k_lattice_wave<<<dim3((unsigned)(s1 - s0), 2), dim3(64), 2 * LW_NB * LW_SLOT * sizeof(float), stream>>>(
+        k_lattice_wave<<<dim3((unsigned)(s1 - s0), 2), dim3(64), 2 * LW_RING * sizeof(float), stream>>>(
             st, ls, s0, loss);
         return hipGetLastError();
     }
