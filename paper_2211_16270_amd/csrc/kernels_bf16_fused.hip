@@ -157,11 +157,12 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         return ((size_t)ht * VK + vk) * 1024;
     };
     auto wq_load = [&](size_t off, int j) { return *reinterpret_cast<const bf16x8*>(wqb + off + j * 1024 + lane_b); };
-    bf16x8 ringB[2][HT][4];
+    constexpr int PB = (HT >= 3) ? 2 : 4;     // k16-steps per phase-2 fragment block (register budget)
+    bf16x8 ringB[2][HT][PB];
 #pragma unroll
     for (int i = 0; i < HT; ++i)
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) ringB[0][i][kk] = wq_load(wq_off(i, 0), kk);
+        for (int kk = 0; kk < PB; ++kk) ringB[0][i][kk] = wq_load(wq_off(i, 0), kk);
     // phase 1, A operand (W_out^T, vocabulary x hidden): fragment (vt, kk) at ((vt*KK + kk)*1024) bytes
     auto wp_off = [&](int vs_, int vt_, int kb_) -> size_t {
         return ((size_t)(vs_ * (FB_VSTEP / 32) + wv * 2 + vt_) * KK + (size_t)kb_ * FB_PF) * 1024;
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         }
         // -------- phase 2: dz += dh W^T over the nact*64 vocabulary entries of this step
         {
-            const int nb2 = nact;                      // blocks of 4 k16-steps (4 or 8: even)
+            const int nb2 = nact * (4 / PB);           // blocks of PB k16-steps (an even number)
             const int vk0 = vs * (FB_VSTEP / 16);
             bf16x8 ac[2] = {*reinterpret_cast<const bf16x8*>(drow0), *reinterpret_cast<const bf16x8*>(drow1)};
             const bf16_t* dc0 = drow0;
@@ -291,18 +292,18 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
                     const int kb = kb2 + half;
                     const int cs = half, ns = half ^ 1;
                     // next block of B fragments: next block of this step, else first block of the next step
-                    int vkn = vk0 + (kb + 1) * 4;
-                    if (vkn >= VK) vkn = vk0 + kb * 4;
+                    int vkn = vk0 + (kb + 1) * PB;
+                    if (vkn >= VK) vkn = vk0 + kb * PB;
                     size_t noff[HT];
 #pragma unroll
                     for (int i = 0; i < HT; ++i) noff[i] = wq_off(i, vkn);
-                    const int knext = (kb + 1 == nb2) ? 0 : (kb + 1) * 64;
+                    const int knext = (kb + 1 == nb2) ? 0 : (kb + 1) * PB * 16;
                     const bf16_t* dn0 = drow0 + knext;
                     const bf16_t* dn1 = drow1 + knext;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
+                    for (int j = 0; j < PB; ++j) {
                         bf16x8 an[2];
-                        if (j + 1 < 4) {
+                        if (j + 1 < PB) {
                             an[0] = *reinterpret_cast<const bf16x8*>(dc0 + (j + 1) * 16);
                             an[1] = *reinterpret_cast<const bf16x8*>(dc1 + (j + 1) * 16);
                         } else {

@@ -57,7 +57,7 @@ struct Plan {
 };
 
 // Shapes the fused backward kernel covers (its dz accumulators must fit the register file).
-inline bool fused_backward_shape(int H, int V) { return H % 128 == 0 && H <= 512 && V % 256 == 0; }
+inline bool fused_backward_shape(int H, int V) { return H % 128 == 0 && H <= 640 && V % 256 == 0; }
 
 // dW GEMM geometry: 256x256 output tiles, and as many K splits (a multiple of 8, one set per XCD) as
 // give about one workgroup per compute unit.  Every (split, tile) workgroup owns a 256 KiB slot of
