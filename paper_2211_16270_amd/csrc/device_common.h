@@ -9,6 +9,9 @@ namespace rnnt {
 constexpr float LOG2E_F = 1.4426950408889634f;
 constexpr float LN2_F = 0.6931471805599453f;
 #define RNNT_NEG_INF (-__builtin_huge_valf())
+// s_waitcnt operand (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14]) that waits for
+// every outstanding LDS / scalar-memory operation of the wave and for nothing else.
+constexpr int WAIT_LGKM0 = 0xC07F;
 
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -106,6 +109,10 @@ __device__ __forceinline__ RowPost row_posteriors(const LatticeState& ls, long l
 __device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
 }
-
+// The same with a wave-uniform 64-bit base (scalar registers) plus a 32-bit byte offset per lane.
+__device__ __forceinline__ void lds_dma16_s(const void* sbase, unsigned voff, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base)
+                 : "memory", "m0");
+}
 
 }  // namespace rnnt

@@ -434,28 +434,29 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
     const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)dw_smem;
 
     // global -> LDS: one DMA instruction moves two tile rows (2 x 512 B).  Wave w moves row pairs w,
-    // w+4, w+8 and w+12 of both operands.  LDS slot (row, position p) receives global chunk p ^ 4*(row%4) of that row.
-    const bf16_t* Ag[4];
-    const bf16_t* Bg[4];
-    unsigned dst[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = 2 * wave + 8 * i + (lane >> 5);
-        const int ch = (lane & 31) ^ ((row & 3) << 2);
+    // w+4, w+8 and w+12 of both operands.  LDS slot (row, position p) receives global chunk p ^ 4*(row%4) of
+    // that row.  A lane's byte offset within a row pair is the same for all four pairs (8 rows apart, so the
+    // swizzle agrees); everything that changes from pair to pair and stage to stage is wave-uniform and
+    // lives in scalar registers, so issuing a DMA costs no vector instruction.
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    unsigned offA, offB;
+    {
+        const int ch = (lane & 31) ^ (((2 * wave + (lane >> 5)) & 3) << 2);
         long long acol = m0 + ch * 8;
         if (acol > g.H - 8) acol = g.H - 8;      // columns beyond H (H not a multiple of 256): never stored
-        Ag[i] = g.Z + (ks + row) * (long long)g.H + acol;
-        Bg[i] = g.dH + (ks + row) * (long long)g.V + n0 + ch * 8;
-        dst[i] = (unsigned)(2 * wave + 8 * i) * (WT * 2u);
+        offA = (unsigned)(((long long)(lane >> 5) * g.H + acol) * 2);
+        offB = (unsigned)(((long long)(lane >> 5) * g.V + n0 + ch * 8) * 2);
     }
-    auto issue = [&](long long step) {          // stage = step % WST
-        const unsigned sb = smem_base + (unsigned)(step & (WST - 1)) * STAGE_BYTES;
-        const long long k0 = step * WK;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            lds_dma16(Ag[i] + k0 * g.H, __builtin_amdgcn_readfirstlane(sb + dst[i]));
-            lds_dma16(Bg[i] + k0 * g.V, __builtin_amdgcn_readfirstlane(sb + OPER_BYTES + dst[i]));
-        }
+    const char* Zs = reinterpret_cast<const char*>(g.Z) + (ks + 2 * wv) * (long long)g.H * 2;
+    const char* Ds = reinterpret_cast<const char*>(g.dH) + (ks + 2 * wv) * (long long)g.V * 2;
+    const unsigned dst0 = smem_base + (unsigned)(2 * wv) * (WT * 2u);
+    // DMA j (0..7) of the stage that takes rows [gstep*WK, +WK) of the split into LDS buffer buf
+    auto issue_one = [&](long long gstep, unsigned buf, int j) {
+        const int i = j >> 1;
+        const unsigned sb = dst0 + buf * STAGE_BYTES + (unsigned)(8 * i) * (WT * 2u);
+        const long long krow = gstep * WK + 8 * i;
+        if (j & 1) lds_dma16_s(Ds + krow * g.V * 2, offB, sb + OPER_BYTES);
+        else lds_dma16_s(Zs + krow * g.H * 2, offA, sb);
     };
     // fragment addresses: lane = 16 g + 4 j + c supplies row 8*(g/2) + j, columns 16*(g%2) + 4c .. +3
     const int fg = lane >> 4, fj = (lane >> 2) & 3, fc = lane & 3;
@@ -491,12 +492,25 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) fb[set][nt] = lds_read_tr_frag(st + boff[nt]);
     };
-    auto multiply = [&](int set) {
+    // The 16 MFMAs of one k16-step (register set `set`); behind each of the first eight, one fragment of the
+    // following k16-step is read into the other set.  An MFMA keeps the matrix pipe busy for 32 clocks but
+    // the issue port only briefly: the reads go out in its shadow, and the last of them is 8 MFMAs old when
+    // the step ends.
+    // Behind each of the last eight goes one DMA of a later stage (dma_g >= 0).
+    auto multiply = [&](int set, long long next_stage, int next_kk, long long dma_g, unsigned dma_buf) {
+        const bf16_t* st = reinterpret_cast<const bf16_t*>(dw_smem + (size_t)(next_stage & (WST - 1)) * STAGE_BYTES) +
+                           next_kk * 16 * WT;
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt)
+            for (int nt = 0; nt < 4; ++nt) {
                 acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][mt], fb[set][nt], acc[mt][nt], 0, 0, 0);
+                const int idx = mt * 4 + nt;
+                if (idx < 4) fa[set ^ 1][idx] = lds_read_tr_frag(st + aoff[idx]);
+                else if (idx < 8) fb[set ^ 1][idx - 4] = lds_read_tr_frag(st + boff[idx - 4]);
+                else if (set == 1) issue_one(dma_g, dma_buf, idx - 8);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         if (do_db) {
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
@@ -508,36 +522,33 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
         }
     };
     // Three stages in flight before the first one is consumed (8 DMA instructions per wave and stage).
-    // One wave per SIMD: nothing else hides an LDS read, so the fragments of every k16-step, the first
-    // of a stage included, are read during the MFMAs of the step before.  The hand-over to the next
-    // stage (wait for this wave's copies, then for everyone's) therefore sits in the middle of a stage.
+    // One wave per SIMD: nothing else hides an LDS read or the issue of a DMA, so both are spread over the
+    // MFMAs (see multiply).  The hand-over to the next stage (wait for this wave's copies, then for
+    // everyone's) sits in the middle of a stage.  Beyond the last stage the pipeline keeps re-loading the
+    // last one into buffers nobody reads any more, which keeps the loop free of branches and the number of
+    // copies in flight constant.
     if (nsteps > 0) {
-        issue(0);
-        if (nsteps > 1) issue(1);
-        if (nsteps > 2) issue(2);
-        if (nsteps > 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-        else if (nsteps > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const long long last = nsteps - 1;
+#pragma unroll
+        for (int st3 = 0; st3 < 3; ++st3)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) issue_one(st3 < last ? st3 : last, (unsigned)st3, j);
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
         __syncthreads();
         read_frags(0, 0, 0);
-    }
-    for (long long it = 0; it < nsteps; ++it) {
-        read_frags(1, it, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (it + 1 < nsteps) {
-            // stage it+1 landed (stage it+2 may stay in flight); every wave is past stage it-1, whose
-            // buffer takes stage it+3
-            if (it + 2 < nsteps) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        for (long long it = 0; it < nsteps; ++it) {
+            __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);     // set 0 landed (read behind the first MFMAs of the step before)
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(0, it, 1, 0, 0);
+            __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);     // set 1 landed
+            // stage it+1 landed (stage it+2 stays in flight); every wave is past stage it-1, whose buffer
+            // takes stage it+3
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
             __syncthreads();
-            if (it + 3 < nsteps) issue(it + 3);
-            read_frags(0, it + 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(1, it + 1, 0, it + 3 < last ? it + 3 : last, (unsigned)((it + 3) & (WST - 1)));
         }
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(1);
-        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // no copy may land after the workgroup has ended
     }
     // Partial sums go to this workgroup's own slot, in accumulator order (one 16-byte store per lane
     // and four accumulator rows): no atomics, and the same workgroup adds the next chunk's product.
