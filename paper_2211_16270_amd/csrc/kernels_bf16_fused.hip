@@ -6,29 +6,32 @@
 // and dh (bf16) plus z (bf16) written out row-major, straight from their LDS tiles, for the dW_out
 // GEMM.  The score gradient is not re-read for dz.
 //
-// 512 threads = 8 waves, one workgroup per CU.
-//  Phase 1, per step of 512 vocabulary entries: wave w owns entries [64w, 64w+64) for all 64 rows
-//   (2 x 2 accumulator tiles, A = packed W_out^T fragments from L2, B = joint tile from LDS).
-//  Between the phases the 64 x 512 block of dh (bf16) is laid down in LDS, row-major.
-//  Phase 2: every wave multiplies that block into its own hidden columns (hidden 32-tiles w, w+8,
-//   ...): A = dh from LDS (rows), B = packed W_out fragments from L2 (hidden x vocabulary).
-//  Two workgroup barriers per step.
+// 512 threads = 8 waves, one workgroup per CU, two waves per SIMD with different jobs:
+//  waves 0..3 ("score waves"): per step of 256 vocabulary entries, wave w owns entries [64w, 64w+64) for
+//   all 64 rows (2 x 2 accumulator tiles, A = packed W_out^T fragments from L2, B = joint tile from LDS),
+//   turns the scores into dh (exp, bf16) and lays its 64 x 64 piece down in one of two LDS buffers
+//   [64][256], then copies that piece to the dH chunk buffer;
+//  waves 4..7 ("dz waves"): one step behind, multiply the finished buffer into their own hidden columns
+//   (hidden 32-tiles w-4, w, w+4, ...: A = dh from LDS (rows), B = packed W_out fragments from L2
+//   (hidden x vocabulary)), and run the epilogue.
+// The vector-ALU work of a wave never overlaps with that wave's own MFMAs, but it does overlap with the
+// MFMAs of the other wave on its SIMD: while a score wave computes exponentials, the dz wave next to it
+// keeps the matrix pipe busy.  One workgroup barrier per step separates writers and readers of a buffer.
 // MFMA operand layouts: see kernels_bf16.hip.
 #include "device_common.h"
 
 namespace rnnt {
 
 constexpr int FB_ROWS = 64;
-constexpr int FB_VSTEP = 512;
-constexpr int FB_PF = 2;        // phase-1 A-fragment prefetch distance in k16-steps
-constexpr int FB_DP = FB_VSTEP + 8;   // pitch (bf16 elements) of the dh LDS tile [64 rows][512 entries]
+constexpr int FB_VSTEP = 256;         // vocabulary entries per step
+constexpr int FB_DP = FB_VSTEP + 8;   // pitch (bf16 elements) of a dh LDS buffer [64 rows][256 entries]
 
 struct FusedArgs {
     Problem pr;
     SampleTable st;
     LatticeState ls;
-    const bf16_t* Wp;   // fragment-major W_out^T (phase 1)
-    const bf16_t* Wq;   // fragment-major W_out   (phase 2)
+    const bf16_t* Wp;   // fragment-major W_out^T (score waves)
+    const bf16_t* Wq;   // fragment-major W_out   (dz waves)
     int s0, s1, tile0, tile1;
     bf16_t* dH;         // [chunk rows, V]
     bf16_t* Z;          // [chunk rows, H]
@@ -36,14 +39,16 @@ struct FusedArgs {
     float* d_pred;
 };
 
-template <int HT>
+// HT = hidden 32-tiles per dz wave = ceil(H / 128); FB_PF = fragment prefetch distance of the score loop in
+// k16-steps (H/16 must be a multiple of 2*FB_PF); PB = the same for the dz loop
+template <int HT, int FB_PF, int PB>
 __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int H = a.pr.H, V = a.pr.V;
     const int ZP = H + 8;
     bf16_t* zs = reinterpret_cast<bf16_t*>(smem);                        // [64][ZP]
-    bf16_t* dhs = zs + (size_t)FB_ROWS * ZP;                             // [64][FB_DP]
-    int* row_lab = reinterpret_cast<int*>(dhs + FB_ROWS * FB_DP);        // [64]
+    bf16_t* dhs = zs + (size_t)FB_ROWS * ZP;                             // [2][64][FB_DP]
+    int* row_lab = reinterpret_cast<int*>(dhs + 2 * FB_ROWS * FB_DP);    // [64]
     float* row_g = reinterpret_cast<float*>(row_lab + 64);               // [64] exponent offset (log2 units)
     float* row_B = row_g + 64;                                           // [64] dh at the blank entry
     float* row_Y = row_B + 64;                                           // [64] dh at the label entry
@@ -106,78 +111,37 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         }
     }
     __syncthreads();
-    // joint tile -> Z chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM
-    {
-        // thread -> chunks tid, tid + 512, ...; (row, chunk) advance by additions (no division per copy)
-        const int cpr = H >> 3;                              // 16-byte chunks per row
-        const int drow = 512 / cpr, dch = 512 - drow * cpr;
-        int row = tid / cpr, ch = tid - row * cpr;
-        bf16_t* zo = a.Z + (size_t)chunk_row0 * H;
-        while (row < FB_ROWS) {
-            *reinterpret_cast<bf16x8*>(zo + (size_t)row * H + ch * 8) =
-                *reinterpret_cast<const bf16x8*>(zs + row * ZP + ch * 8);
-            row += drow;
-            ch += dch;
-            if (ch >= cpr) { ch -= cpr; ++row; }
-        }
-    }
 
     const int KK = H >> 4;             // k16-steps of the score GEMM
     const int VK = V >> 4;             // k16-steps of the dz GEMM (whole vocabulary)
     const int nht = H >> 5;            // hidden 32-tiles
-    const int nvs = (V + FB_VSTEP - 1) / FB_VSTEP;
-    const int nkb = KK / FB_PF;
-    int lab[2] = {row_lab[l32], row_lab[32 + l32]};
-    float gexp[2] = {row_g[l32], row_g[32 + l32]};
-    float Bk[2] = {row_B[l32], row_B[32 + l32]};
-    float Yk[2] = {row_Y[l32], row_Y[32 + l32]};
-    const bf16_t* zrow0 = zs + l32 * ZP + hb * 8;
-    const bf16_t* zrow1 = zs + (32 + l32) * ZP + hb * 8;
-    const bf16_t* drow0 = dhs + l32 * FB_DP + hb * 8;
-    const bf16_t* drow1 = dhs + (32 + l32) * FB_DP + hb * 8;
-
-    // dz accumulators: hidden tiles wave, wave+8, ... (HT of them at most), two row tiles
-    f32x16 dz[HT][2];
-#pragma unroll
-    for (int i = 0; i < HT; ++i)
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt) dz[i][rt] = f32x16{0};
-
-    // Fragment streams from L2.  VALU instructions of a wave do not overlap with its own MFMAs on this hardware, so both
-    // MFMA loops address their fragments as scalar base + lane offset + immediate and load into the
-    // register set that is not being consumed (two sets, one block ahead).
-    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const int nvs = V / FB_VSTEP;
+    const int w4 = __builtin_amdgcn_readfirstlane(wave & 3);
     const unsigned lane_b = (unsigned)lane * 16u;
-    const char* wqb = reinterpret_cast<const char*>(a.Wq);
-    const char* wpb = reinterpret_cast<const char*>(a.Wp);
-    // phase 2, B operand (W_out, hidden x vocabulary): fragment (ht, vk) at ((ht*VK + vk)*1024) bytes
-    auto wq_off = [&](int i, int vk) -> size_t {
-        int ht = wv + 8 * i;
-        if (ht >= nht) ht = wv;        // unused slot: any valid fragment
-        return ((size_t)ht * VK + vk) * 1024;
-    };
-    auto wq_load = [&](size_t off, int j) { return *reinterpret_cast<const bf16x8*>(wqb + off + j * 1024 + lane_b); };
-    constexpr int PB = (HT >= 3) ? 2 : 4;     // k16-steps per phase-2 fragment block (register budget)
-    bf16x8 ringB[2][HT][PB];
-#pragma unroll
-    for (int i = 0; i < HT; ++i)
-#pragma unroll
-        for (int kk = 0; kk < PB; ++kk) ringB[0][i][kk] = wq_load(wq_off(i, 0), kk);
-    // phase 1, A operand (W_out^T, vocabulary x hidden): fragment (vt, kk) at ((vt*KK + kk)*1024) bytes
-    auto wp_off = [&](int vs_, int vt_, int kb_) -> size_t {
-        return ((size_t)(vs_ * (FB_VSTEP / 32) + wv * 2 + vt_) * KK + (size_t)kb_ * FB_PF) * 1024;
-    };
-    auto wp_load = [&](size_t off, int j) { return *reinterpret_cast<const bf16x8*>(wpb + off + j * 1024 + lane_b); };
 
-    for (int vs = 0; vs < nvs; ++vs) {
-        const int vleft = V - vs * FB_VSTEP;
-        const int nact = (vleft < FB_VSTEP ? vleft : FB_VSTEP) >> 6;   // waves with vocabulary entries
-        f32x16 acc[2][2];
-        if (wave < nact) {
-            // -------- phase 1: scores of 64 entries x 64 rows; accumulators start from the bias
+    if (wave < 4) {
+        // =========================== score waves ===========================
+        const int nkb = KK / FB_PF;
+        const int lab[2] = {row_lab[l32], row_lab[32 + l32]};
+        const float gexp[2] = {row_g[l32], row_g[32 + l32]};
+        const float Bk[2] = {row_B[l32], row_B[32 + l32]};
+        const float Yk[2] = {row_Y[l32], row_Y[32 + l32]};
+        const bf16_t* zrow0 = zs + l32 * ZP + hb * 8;
+        const bf16_t* zrow1 = zs + (32 + l32) * ZP + hb * 8;
+        const char* wpb = reinterpret_cast<const char*>(a.Wp);
+        // A operand (W_out^T, vocabulary x hidden): fragment (vt, kk) at ((vt*KK + kk)*1024) bytes
+        auto wp_off = [&](int vs_, int vt_, int kb_) -> size_t {
+            return ((size_t)(vs_ * (FB_VSTEP / 32) + w4 * 2 + vt_) * KK + (size_t)kb_ * FB_PF) * 1024;
+        };
+        auto wp_load = [&](size_t off, int j) { return *reinterpret_cast<const bf16x8*>(wpb + off + j * 1024 + lane_b); };
+
+        for (int vs = 0; vs < nvs; ++vs) {
+            bf16_t* buf = dhs + (vs & 1) * (FB_ROWS * FB_DP);
+            // -------- scores of 64 entries x 64 rows; accumulators start from the bias
+            f32x16 acc[2][2];
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt) {
-                const float* bp = a.pr.b_out + vs * FB_VSTEP + wave * 64 + vt * 32 + 4 * hb;
+                const float* bp = a.pr.b_out + vs * FB_VSTEP + w4 * 64 + vt * 32 + 4 * hb;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const f32x4 t4 = *reinterpret_cast<const f32x4*>(bp + 8 * j);
@@ -196,6 +160,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
             bf16x8 bc[2] = {*reinterpret_cast<const bf16x8*>(zrow0), *reinterpret_cast<const bf16x8*>(zrow1)};
             const bf16_t* zc0 = zrow0;
             const bf16_t* zc1 = zrow1;
+            __builtin_amdgcn_s_setprio(2);
             for (int kb2 = 0; kb2 < nkb; kb2 += 2) {
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
@@ -231,14 +196,12 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
                     zc1 = zn1;
                 }
             }
-        }
-        __syncthreads();    // every wave is done reading the dh tile of the previous step
-        if (wave < nact) {
-            // -------- f^W_4: dh = gamma * softmax - posteriors, to bf16; into the LDS tile (row-major)
-            //          for phase 2 and, transposed, to HBM for the dW GEMM
+            __builtin_amdgcn_s_setprio(0);
+            // -------- f^W_4: dh = gamma * softmax - posteriors, to bf16, into this step's LDS buffer (row-major).
+            //          The dz waves read the other buffer meanwhile; they left this one before the last barrier.
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt) {
-                const int vbase = vs * FB_VSTEP + wave * 64 + vt * 32;
+                const int vbase = vs * FB_VSTEP + w4 * 64 + vt * 32;
                 const int relb = a.pr.blank - vbase;
 #pragma unroll
                 for (int rt = 0; rt < 2; ++rt) {
@@ -247,7 +210,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
                         d[i] = __builtin_amdgcn_exp2f(fmaf(acc[vt][rt][i], LOG2E_F, gexp[rt]));
-                    bf16_t* sd = dhs + (rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + 4 * hb;
+                    bf16_t* sd = buf + (rt * 32 + l32) * FB_DP + w4 * 64 + vt * 32 + 4 * hb;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         bf16x4 q4 = {(bf16_t)d[4 * j], (bf16_t)d[4 * j + 1], (bf16_t)d[4 * j + 2], (bf16_t)d[4 * j + 3]};
@@ -259,74 +222,123 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
                     const bool own_y = ((unsigned)rely < 32u) && (((rely >> 2) & 1) == hb);
                     if (own_b) {
                         const bf16_t v = (bf16_t)Bk[rt];
-                        dhs[(rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + relb] = v;
+                        buf[(rt * 32 + l32) * FB_DP + w4 * 64 + vt * 32 + relb] = v;
                     }
                     if (own_y) {
                         const bf16_t v = (bf16_t)Yk[rt];
-                        dhs[(rt * 32 + l32) * FB_DP + wave * 64 + vt * 32 + rely] = v;
+                        buf[(rt * 32 + l32) * FB_DP + w4 * 64 + vt * 32 + rely] = v;
                     }
                 }
             }
-        }
-        __syncthreads();    // the dh tile of this step is complete
-        // dh tile -> dH chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM
-        {
-            // nact*8 = 32 or 64 16-byte chunks per row in this step: a thread keeps its chunk and walks rows
-            const int sh = (nact == 8) ? 6 : 5;
-            const int ch = tid & ((1 << sh) - 1), drow = 512 >> sh;
-            bf16_t* o = a.dH + (size_t)chunk_row0 * V + vs * FB_VSTEP + ch * 8;
-            const bf16_t* src = dhs + ch * 8;
-            for (int row = tid >> sh; row < FB_ROWS; row += drow)
-                *reinterpret_cast<bf16x8*>(o + (size_t)row * V) = *reinterpret_cast<const bf16x8*>(src + row * FB_DP);
-        }
-        // -------- phase 2: dz += dh W^T over the nact*64 vocabulary entries of this step
-        {
-            const int nb2 = nact * (4 / PB);           // blocks of PB k16-steps (an even number)
-            const int vk0 = vs * (FB_VSTEP / 16);
-            bf16x8 ac[2] = {*reinterpret_cast<const bf16x8*>(drow0), *reinterpret_cast<const bf16x8*>(drow1)};
-            const bf16_t* dc0 = drow0;
-            const bf16_t* dc1 = drow1;
-            for (int kb2 = 0; kb2 < nb2; kb2 += 2) {
+            // this wave's 64 x 64 piece -> dH chunk buffer (row-major; 8 lanes store the 128 bytes of a row).
+            // LDS operations of one wave execute in order, so the piece is complete for its own wave.
+            {
+                const int seg = lane & 7, r0 = lane >> 3;
+                bf16_t* o = a.dH + (size_t)chunk_row0 * V + vs * FB_VSTEP + w4 * 64 + seg * 8;
+                const bf16_t* src = buf + w4 * 64 + seg * 8;
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int kb = kb2 + half;
-                    const int cs = half, ns = half ^ 1;
-                    // next block of B fragments: next block of this step, else first block of the next step
-                    int vkn = vk0 + (kb + 1) * PB;
-                    if (vkn >= VK) vkn = vk0 + kb * PB;
-                    size_t noff[HT];
-#pragma unroll
-                    for (int i = 0; i < HT; ++i) noff[i] = wq_off(i, vkn);
-                    const int knext = (kb + 1 == nb2) ? 0 : (kb + 1) * PB * 16;
-                    const bf16_t* dn0 = drow0 + knext;
-                    const bf16_t* dn1 = drow1 + knext;
-#pragma unroll
-                    for (int j = 0; j < PB; ++j) {
-                        bf16x8 an[2];
-                        if (j + 1 < PB) {
-                            an[0] = *reinterpret_cast<const bf16x8*>(dc0 + (j + 1) * 16);
-                            an[1] = *reinterpret_cast<const bf16x8*>(dc1 + (j + 1) * 16);
-                        } else {
-                            an[0] = *reinterpret_cast<const bf16x8*>(dn0);
-                            an[1] = *reinterpret_cast<const bf16x8*>(dn1);
-                        }
-#pragma unroll
-                        for (int i = 0; i < HT; ++i) ringB[ns][i][j] = wq_load(noff[i], j);
-                        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                        for (int i = 0; i < HT; ++i) {
-                            dz[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[0], ringB[cs][i][j], dz[i][0], 0, 0, 0);
-                            dz[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[1], ringB[cs][i][j], dz[i][1], 0, 0, 0);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        ac[0] = an[0];
-                        ac[1] = an[1];
-                    }
-                    dc0 = dn0;
-                    dc1 = dn1;
+                for (int i = 0; i < 8; ++i) {
+                    const int row = r0 + 8 * i;
+                    __builtin_nontemporal_store(*reinterpret_cast<const bf16x8*>(src + row * FB_DP),
+                                                reinterpret_cast<bf16x8*>(o + (size_t)row * V));
                 }
             }
+            __syncthreads();    // barrier vs: this step's buffer is complete
         }
+        return;
+    }
+
+    // =========================== dz waves ===========================
+    // joint tile -> Z chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM, while the score
+    // waves work on the first step
+    {
+        const int t4 = tid - 256;
+        const int cpr = H >> 3;                              // 16-byte chunks per row
+        const int drow = 256 / cpr, dch = 256 - drow * cpr;
+        int row = t4 / cpr, ch = t4 - row * cpr;
+        bf16_t* zo = a.Z + (size_t)chunk_row0 * H;
+        while (row < FB_ROWS) {
+            __builtin_nontemporal_store(*reinterpret_cast<const bf16x8*>(zs + row * ZP + ch * 8),
+                                        reinterpret_cast<bf16x8*>(zo + (size_t)row * H + ch * 8));
+            row += drow;
+            ch += dch;
+            if (ch >= cpr) { ch -= cpr; ++row; }
+        }
+    }
+    // dz accumulators: hidden tiles w4, w4+4, ... (HT of them at most), two row tiles
+    f32x16 dz[HT][2];
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) dz[i][rt] = f32x16{0};
+    const char* wqb = reinterpret_cast<const char*>(a.Wq);
+    // B operand (W_out, hidden x vocabulary): fragment (ht, vk) at ((ht*VK + vk)*1024) bytes
+    auto wq_off = [&](int i, int vk) -> size_t {
+        int ht = w4 + 4 * i;
+        if (ht >= nht) ht = w4;        // unused slot: any valid fragment
+        return ((size_t)ht * VK + vk) * 1024;
+    };
+    auto wq_load = [&](size_t off, int j) { return *reinterpret_cast<const bf16x8*>(wqb + off + j * 1024 + lane_b); };
+    constexpr int NB2 = (FB_VSTEP / 16) / PB;  // fragment blocks per step (even)
+    bf16x8 ringB[2][HT][PB];
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+        for (int kk = 0; kk < PB; ++kk) ringB[0][i][kk] = wq_load(wq_off(i, 0), kk);
+    __syncthreads();    // barrier 0: the first buffer is complete
+
+    for (int s = 0; s < nvs; ++s) {
+        // -------- dz += dh W^T over the 256 vocabulary entries of step s
+        const bf16_t* buf = dhs + (s & 1) * (FB_ROWS * FB_DP);
+        const bf16_t* drow0 = buf + l32 * FB_DP + hb * 8;
+        const bf16_t* drow1 = buf + (32 + l32) * FB_DP + hb * 8;
+        const int vk0 = s * (FB_VSTEP / 16);
+        bf16x8 ac[2] = {*reinterpret_cast<const bf16x8*>(drow0), *reinterpret_cast<const bf16x8*>(drow1)};
+        const bf16_t* dc0 = drow0;
+        const bf16_t* dc1 = drow1;
+        __builtin_amdgcn_s_setprio(1);
+        for (int kb2 = 0; kb2 < NB2; kb2 += 2) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int kb = kb2 + half;
+                const int cs = half, ns = half ^ 1;
+                // next block of B fragments: next block of this step, else first block of the next step
+                int vkn = vk0 + (kb + 1) * PB;
+                if (vkn >= VK) vkn = vk0 + kb * PB;
+                size_t noff[HT];
+#pragma unroll
+                for (int i = 0; i < HT; ++i) noff[i] = wq_off(i, vkn);
+                const int knext = (kb + 1 == NB2) ? 0 : (kb + 1) * PB * 16;
+                const bf16_t* dn0 = drow0 + knext;
+                const bf16_t* dn1 = drow1 + knext;
+#pragma unroll
+                for (int j = 0; j < PB; ++j) {
+                    bf16x8 an[2];
+                    if (j + 1 < PB) {
+                        an[0] = *reinterpret_cast<const bf16x8*>(dc0 + (j + 1) * 16);
+                        an[1] = *reinterpret_cast<const bf16x8*>(dc1 + (j + 1) * 16);
+                    } else {
+                        an[0] = *reinterpret_cast<const bf16x8*>(dn0);
+                        an[1] = *reinterpret_cast<const bf16x8*>(dn1);
+                    }
+#pragma unroll
+                    for (int i = 0; i < HT; ++i) ringB[ns][i][j] = wq_load(noff[i], j);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < HT; ++i) {
+                        dz[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[0], ringB[cs][i][j], dz[i][0], 0, 0, 0);
+                        dz[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac[1], ringB[cs][i][j], dz[i][1], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    ac[0] = an[0];
+                    ac[1] = an[1];
+                }
+                dc0 = dn0;
+                dc1 = dn1;
+            }
+        }
+        __builtin_amdgcn_s_setprio(0);
+        if (s + 1 < nvs) __syncthreads();   // barrier s+1: the next buffer is complete, this one may be rewritten
     }
 
     // ---- Alg. 1 lines 10, 11: dx = dz (1 - z^2); sum over label positions -> d_enc, over frames -> d_pred.
@@ -336,7 +348,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         float* d_prd = a.d_pred + (size_t)b * (a.pr.U_max + 1) * H;
 #pragma unroll
         for (int i = 0; i < HT; ++i) {
-            const int ht = wave + 8 * i;
+            const int ht = w4 + 4 * i;
             if (ht >= nht) continue;
             const int h = ht * 32 + l32;
             float pu[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -365,21 +377,21 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
 }
 
 static size_t fused_smem_bytes(int H) {
-    return (size_t)FB_ROWS * (H + 8) * 2 + (size_t)FB_ROWS * FB_DP * 2 + 64 * 4 * 4;
+    return (size_t)FB_ROWS * (H + 8) * 2 + (size_t)2 * FB_ROWS * FB_DP * 2 + 64 * 4 * 4;
 }
 
-template <int HT>
+template <int HT, int FB_PF, int PB>
 static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t stream) {
     const int n = a.tile1 - a.tile0;
     const size_t smem = fused_smem_bytes(a.pr.H);
     static size_t configured = 0;
     if (smem > configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_bwd_fused<HT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_bwd_fused<HT, FB_PF, PB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         configured = smem;
     }
-    k_joint_bwd_fused<HT><<<dim3((unsigned)n), dim3(512), smem, stream>>>(a);
+    k_joint_bwd_fused<HT, FB_PF, PB><<<dim3((unsigned)n), dim3(512), smem, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -389,10 +401,13 @@ hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const voi
     if (tile1 <= tile0) return hipSuccess;
     FusedArgs a{pr, st, ls, (const bf16_t*)Wpack, (const bf16_t*)Wq, s0, s1, tile0, tile1,
                 (bf16_t*)dH, (bf16_t*)Z, d_enc, d_pred};
-    const int ht = (pr.H / 32 + 7) / 8;
-    if (ht <= 1) return launch_fused_t<1>(a, stream);
-    if (ht == 2) return launch_fused_t<2>(a, stream);
-    if (ht == 3) return launch_fused_t<3>(a, stream);
+    const int ht = (pr.H / 32 + 3) / 4;
+    // H = 128 ... 640 in steps of 128: H/16 = 8, 16, 24, 32, 40 k16-steps
+    if (ht <= 1) return launch_fused_t<1, 4, 4>(a, stream);
+    if (ht == 2) return launch_fused_t<2, 8, 4>(a, stream);
+    if (ht == 3) return launch_fused_t<3, 4, 2>(a, stream);
+    if (ht == 4) return launch_fused_t<4, 8, 2>(a, stream);
+    if (ht == 5) return launch_fused_t<5, 4, 1>(a, stream);
     return hipErrorInvalidValue;
 }
 
