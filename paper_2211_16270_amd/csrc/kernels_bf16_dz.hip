@@ -54,30 +54,28 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
     // global -> LDS: one DMA instruction moves 8 operand rows of 128 bytes (whole cache lines: with
     // 64-byte pieces every line would be fetched into L1 twice, by two stages).  Wave w moves row groups
     // w, w+4, ..., w+28 of both operands.  Lane l serves row l/8 of the group and LDS segment l%8, which
-    // holds global segment (l%8) ^ ((row/2)%8).  Rows past the end of the operand re-read its last row;
-    // their products are never stored.
-    const bf16_t* Ag[8];
-    const bf16_t* Bg[8];
-    unsigned dst[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int row = 8 * (wave + 4 * i) + (lane >> 3);
-        const int seg = (lane & 7) ^ ((row >> 1) & 7);
-        long long ar = m0 + row;
-        if (ar > g.rows - 1) ar = g.rows - 1;
-        int br = n0 + row;
-        if (br > H - 1) br = H - 1;
-        Ag[i] = g.dH + ar * V + seg * 8;
-        Bg[i] = g.W + (long long)br * V + seg * 8;
-        dst[i] = (unsigned)(8 * (wave + 4 * i)) * 128u;
-    }
-    auto issue = [&](int step) {
-        const unsigned sb = smem_base + (unsigned)(step & (ZST - 1)) * Z_STAGE;
-        const int k0 = step * ZK;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            lds_dma16(Ag[i] + k0, __builtin_amdgcn_readfirstlane(sb + dst[i]));
-            lds_dma16(Bg[i] + k0, __builtin_amdgcn_readfirstlane(sb + Z_OPER + dst[i]));
+    // holds global segment (l%8) ^ ((row/2)%8); row groups are 32 rows apart, so a lane's byte offset
+    // within its group is the same for all of them and for both operands (both have row pitch V), and
+    // everything else is wave-uniform: issuing a DMA costs no vector instruction.  Rows of dH past the
+    // written ones lie inside the chunk buffer (its size is a multiple of the tile edge) and hidden rows
+    // past H (H is a multiple of 128: the upper half of the last tile) re-read the lower half; their
+    // products are never stored.
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned lane_off =
+        (unsigned)(((long long)(lane >> 3) * V + (((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) * 8)) * 2);
+    const char* As = reinterpret_cast<const char*>(g.dH) + (m0 + 8 * wv) * (long long)V * 2;
+    const char* Bs = reinterpret_cast<const char*>(g.W) + (long long)(n0 + 8 * wv) * V * 2;
+    const bool half_tile = (n0 + 128 >= H);
+    const unsigned dst0 = smem_base + (unsigned)(8 * wv) * 128u;
+    // DMA j (0..15) of the stage that takes vocabulary entries [gstep*ZK, +ZK) into LDS buffer buf
+    auto issue_one = [&](int gstep, unsigned buf, int j) {
+        const int i = j >> 1;
+        const unsigned sb = dst0 + buf * Z_STAGE + (unsigned)(32 * i) * 128u;
+        if (j & 1) {
+            const int ib = (half_tile && i >= 4) ? i - 4 : i;
+            lds_dma16_s(Bs + ((long long)(32 * ib) * V + (long long)gstep * ZK) * 2, lane_off, sb + Z_OPER);
+        } else {
+            lds_dma16_s(As + ((long long)(32 * i) * V + (long long)gstep * ZK) * 2, lane_off, sb);
         }
     };
     // fragment of 32 rows, k16-step kk of a stage: lane holds row l32, segment 2*kk + hb at position
@@ -104,46 +102,62 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
         for (int nt = 0; nt < 4; ++nt)
             fb[set][nt] = *reinterpret_cast<const bf16x8*>(st + Z_OPER + (wn * 128 + nt * 32) * 128);
     };
-    auto multiply = [&](int set) {
+    // The 16 MFMAs of one k16-step (register set `set`).  Behind each of the first eight, one fragment of the
+    // following k16-step is read into the other set; behind each of the last eight go two DMAs of a later
+    // stage (DMA = true).  An MFMA keeps the matrix pipe busy for 32 clocks but the issue port only briefly:
+    // with one wave per SIMD nothing else would hide these instructions.
+    auto multiply = [&](int set, int next_stage, int next_kk, bool DMA, int dma_g, unsigned dma_buf) {
+        const unsigned char* st = dz_smem + (size_t)(next_stage & (ZST - 1)) * Z_STAGE + frag_off[next_kk];
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt)
+            for (int nt = 0; nt < 4; ++nt) {
                 acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][mt], fb[set][nt], acc[mt][nt], 0, 0, 0);
+                const int idx = mt * 4 + nt;
+                if (idx < 4) {
+                    fa[set ^ 1][idx] = *reinterpret_cast<const bf16x8*>(st + (wm * 128 + idx * 32) * 128);
+                } else if (idx < 8) {
+                    fb[set ^ 1][idx - 4] = *reinterpret_cast<const bf16x8*>(st + Z_OPER + (wn * 128 + (idx - 4) * 32) * 128);
+                } else if (DMA) {
+                    issue_one(dma_g, dma_buf, 2 * (idx - 8));
+                    issue_one(dma_g, dma_buf, 2 * (idx - 8) + 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
     };
-    // Two stage buffers.  Fragments are read one k16-step ahead of their MFMAs.  Before the last
-    // k16-step of a stage every wave has issued all its reads of that stage: there the next stage is
+    // Two stage buffers.  Fragments are read one k16-step ahead of their MFMAs.  Before the last k16-step of
+    // a stage every wave has issued and completed all its reads of that stage: there the next stage is
     // waited for (own copies, then everyone's) and the stage after it is sent into the buffer just left.
-    issue(0);
-    if (nsteps > 1) issue(1);
-    if (nsteps > 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // Beyond the last stage the pipeline re-loads the last one into a buffer nobody reads any more, which
+    // keeps the loop free of branches.  The waits for LDS reads are placed by hand (as the builtin the
+    // compiler's own counter tracking understands) before the reads of the following step are issued: the
+    // counter completes in order, so a wait placed after them would wait for them too.
+    const int last = nsteps - 1;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) issue_one(0, 0u, j);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) issue_one(last < 1 ? last : 1, 1u, j);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     __syncthreads();
     read_frags(0, 0, 0);
     for (int it = 0; it < nsteps; ++it) {
-        read_frags(1, it, 1);
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(0);
+        multiply(0, it, 1, false, 0, 0u);
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(0, it, 2);
+        multiply(1, it, 2, false, 0, 0u);
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(1);
+        multiply(0, it, 3, false, 0, 0u);
+        // all reads of stage `it` are complete, stage it+1 has landed: its buffer takes stage it+2
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(1, it, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (it + 1 < nsteps) {
-            // all reads of stage `it` are issued; they must also be complete before its buffer is refilled
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (it + 2 < nsteps) issue(it + 2);
-            read_frags(0, it + 1, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(1);
-        __builtin_amdgcn_sched_barrier(0);
+        multiply(1, it + 1, 0, true, it + 2 < last ? it + 2 : last, (unsigned)(it & (ZST - 1)));
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // no copy may land after the workgroup has ended
 
     // ---- epilogue: dx = dz (1 - z^2) with z = tanh(enc + pred) recomputed in fp32, summed over the label
     // positions / frames of each lattice tile.  The 8 + 8 input rows of the workgroup's four lattice

@@ -103,7 +103,7 @@ def test_bf16_edge_lattices(T_len, U_len, blank):
     assert_padding_zero(got, batch)
 
 
-@pytest.mark.parametrize("H,V", [(640, 256), (1024, 512), (256, 768)])
+@pytest.mark.parametrize("H,V", [(640, 256), (1024, 512), (256, 768), (896, 256)])
 def test_bf16_other_hidden_sizes(H, V):
     # H > 512 takes the unfused backward (separate dz GEMM), H = 640 also the partial 256-wide tile of
     # the dW GEMM; V = 768 is a vocabulary that is not a multiple of the 512-entry step
