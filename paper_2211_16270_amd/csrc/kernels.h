@@ -86,6 +86,10 @@ hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const Sa
 hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0,
                                int tile1, const void* dH, float* d_enc, float* d_pred,
                                hipStream_t stream);
+// Row pitch (elements) of the two bf16 chunk buffers Z [rows, H] and dH [rows, V]: one 128-byte line more
+// than the row, so that rows whose length is a power of two do not all start in the same memory channel.
+__host__ __device__ inline int chunk_pitch(int n) { return n + 64; }
+
 // fused backward: scores recomputed, dh, dz = dh W^T, tanh derivative, reductions into d_enc / d_pred;
 // writes dH [rows,V] and Z [rows,H] (bf16, row-major) for the dW GEMM.  Wq is the second
 // fragment-major copy of W_out.

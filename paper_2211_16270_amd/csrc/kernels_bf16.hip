@@ -122,7 +122,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
         const int cpr = H >> 3;
         for (int idx = tid; idx < JT_ROWS * cpr; idx += NT) {
             const int row = idx / cpr, ch = idx - row * cpr;
-            *reinterpret_cast<bf16x8*>(a.Z + (size_t)(chunk_row0 + row) * H + ch * 8) =
+            *reinterpret_cast<bf16x8*>(a.Z + (size_t)(chunk_row0 + row) * chunk_pitch(H) + ch * 8) =
                 *reinterpret_cast<const bf16x8*>(zs + row * ZP + ch * 8);
         }
     }
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
                     for (int it = 0; it < 2; ++it) {
                         const int row = (lane >> 2) + 16 * it, seg = lane & 3;
                         const bf16x8 v8 = *reinterpret_cast<const bf16x8*>(sw + row * STG_PITCH + seg * 8);
-                        *reinterpret_cast<bf16x8*>(a.dH + (size_t)(chunk_row0 + rt * 32 + row) * V + vbase + seg * 8) = v8;
+                        *reinterpret_cast<bf16x8*>(a.dH + (size_t)(chunk_row0 + rt * 32 + row) * chunk_pitch(V) + vbase + seg * 8) = v8;
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
@@ -439,24 +439,25 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
     // swizzle agrees); everything that changes from pair to pair and stage to stage is wave-uniform and
     // lives in scalar registers, so issuing a DMA costs no vector instruction.
     const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const long long ZL = chunk_pitch(g.H), DL = chunk_pitch(g.V);   // row pitches of the chunk buffers
     unsigned offA, offB;
     {
         const int ch = (lane & 31) ^ (((2 * wave + (lane >> 5)) & 3) << 2);
         long long acol = m0 + ch * 8;
         if (acol > g.H - 8) acol = g.H - 8;      // columns beyond H (H not a multiple of 256): never stored
-        offA = (unsigned)(((long long)(lane >> 5) * g.H + acol) * 2);
-        offB = (unsigned)(((long long)(lane >> 5) * g.V + n0 + ch * 8) * 2);
+        offA = (unsigned)(((long long)(lane >> 5) * ZL + acol) * 2);
+        offB = (unsigned)(((long long)(lane >> 5) * DL + n0 + ch * 8) * 2);
     }
-    const char* Zs = reinterpret_cast<const char*>(g.Z) + (ks + 2 * wv) * (long long)g.H * 2;
-    const char* Ds = reinterpret_cast<const char*>(g.dH) + (ks + 2 * wv) * (long long)g.V * 2;
+    const char* Zs = reinterpret_cast<const char*>(g.Z) + (ks + 2 * wv) * ZL * 2;
+    const char* Ds = reinterpret_cast<const char*>(g.dH) + (ks + 2 * wv) * DL * 2;
     const unsigned dst0 = smem_base + (unsigned)(2 * wv) * (WT * 2u);
     // DMA j (0..7) of the stage that takes rows [gstep*WK, +WK) of the split into LDS buffer buf
     auto issue_one = [&](long long gstep, unsigned buf, int j) {
         const int i = j >> 1;
         const unsigned sb = dst0 + buf * STAGE_BYTES + (unsigned)(8 * i) * (WT * 2u);
         const long long krow = gstep * WK + 8 * i;
-        if (j & 1) lds_dma16_s(Ds + krow * g.V * 2, offB, sb + OPER_BYTES);
-        else lds_dma16_s(Zs + krow * g.H * 2, offA, sb);
+        if (j & 1) lds_dma16_s(Ds + krow * DL * 2, offB, sb + OPER_BYTES);
+        else lds_dma16_s(Zs + krow * ZL * 2, offA, sb);
     };
     // fragment addresses: lane = 16 g + 4 j + c supplies row 8*(g/2) + j, columns 16*(g%2) + 4c .. +3
     const int fg = lane >> 4, fj = (lane >> 2) & 3, fc = lane & 3;

@@ -55,15 +55,17 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
     // 64-byte pieces every line would be fetched into L1 twice, by two stages).  Wave w moves row groups
     // w, w+4, ..., w+28 of both operands.  Lane l serves row l/8 of the group and LDS segment l%8, which
     // holds global segment (l%8) ^ ((row/2)%8); row groups are 32 rows apart, so a lane's byte offset
-    // within its group is the same for all of them and for both operands (both have row pitch V), and
+    // within its group is the same for all of them, and
     // everything else is wave-uniform: issuing a DMA costs no vector instruction.  Rows of dH past the
     // written ones lie inside the chunk buffer (its size is a multiple of the tile edge) and hidden rows
     // past H (H is a multiple of 128: the upper half of the last tile) re-read the lower half; their
     // products are never stored.
     const int wv = __builtin_amdgcn_readfirstlane(wave);
-    const unsigned lane_off =
-        (unsigned)(((long long)(lane >> 3) * V + (((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) * 8)) * 2);
-    const char* As = reinterpret_cast<const char*>(g.dH) + (m0 + 8 * wv) * (long long)V * 2;
+    const long long DL = chunk_pitch(V);      // row pitch of the dH chunk buffer
+    const int lseg = ((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) * 8;
+    const unsigned lane_offA = (unsigned)(((long long)(lane >> 3) * DL + lseg) * 2);
+    const unsigned lane_offB = (unsigned)(((long long)(lane >> 3) * V + lseg) * 2);
+    const char* As = reinterpret_cast<const char*>(g.dH) + (m0 + 8 * wv) * DL * 2;
     const char* Bs = reinterpret_cast<const char*>(g.W) + (long long)(n0 + 8 * wv) * V * 2;
     const bool half_tile = (n0 + 128 >= H);
     const unsigned dst0 = smem_base + (unsigned)(8 * wv) * 128u;
@@ -73,9 +75,9 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
         const unsigned sb = dst0 + buf * Z_STAGE + (unsigned)(32 * i) * 128u;
         if (j & 1) {
             const int ib = (half_tile && i >= 4) ? i - 4 : i;
-            lds_dma16_s(Bs + ((long long)(32 * ib) * V + (long long)gstep * ZK) * 2, lane_off, sb + Z_OPER);
+            lds_dma16_s(Bs + ((long long)(32 * ib) * V + (long long)gstep * ZK) * 2, lane_offB, sb + Z_OPER);
         } else {
-            lds_dma16_s(As + ((long long)(32 * i) * V + (long long)gstep * ZK) * 2, lane_off, sb);
+            lds_dma16_s(As + ((long long)(32 * i) * DL + (long long)gstep * ZK) * 2, lane_offA, sb);
         }
     };
     // fragment of 32 rows, k16-step kk of a stage: lane holds row l32, segment 2*kk + hb at position

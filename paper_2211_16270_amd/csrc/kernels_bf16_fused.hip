@@ -234,13 +234,14 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
             // LDS operations of one wave execute in order, so the piece is complete for its own wave.
             {
                 const int seg = lane & 7, r0 = lane >> 3;
-                bf16_t* o = a.dH + (size_t)chunk_row0 * V + vs * FB_VSTEP + w4 * 64 + seg * 8;
+                const size_t DL = chunk_pitch(V);
+                bf16_t* o = a.dH + (size_t)chunk_row0 * DL + vs * FB_VSTEP + w4 * 64 + seg * 8;
                 const bf16_t* src = buf + w4 * 64 + seg * 8;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int row = r0 + 8 * i;
                     __builtin_nontemporal_store(*reinterpret_cast<const bf16x8*>(src + row * FB_DP),
-                                                reinterpret_cast<bf16x8*>(o + (size_t)row * V));
+                                                reinterpret_cast<bf16x8*>(o + (size_t)row * DL));
                 }
             }
             __syncthreads();    // barrier vs: this step's buffer is complete
@@ -256,10 +257,11 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         const int cpr = H >> 3;                              // 16-byte chunks per row
         const int drow = 256 / cpr, dch = 256 - drow * cpr;
         int row = t4 / cpr, ch = t4 - row * cpr;
-        bf16_t* zo = a.Z + (size_t)chunk_row0 * H;
+        const size_t ZL = chunk_pitch(H);
+        bf16_t* zo = a.Z + (size_t)chunk_row0 * ZL;
         while (row < FB_ROWS) {
             __builtin_nontemporal_store(*reinterpret_cast<const bf16x8*>(zs + row * ZP + ch * 8),
-                                        reinterpret_cast<bf16x8*>(zo + (size_t)row * H + ch * 8));
+                                        reinterpret_cast<bf16x8*>(zo + (size_t)row * ZL + ch * 8));
             row += drow;
             ch += dch;
             if (ch >= cpr) { ch -= cpr; ++row; }

@@ -1,6 +1,8 @@
 // Host scheduler and workspace layout (see plan.h).  No HIP in this file.
 #include "plan.h"
 
+#include "kernels.h"
+
 #include <algorithm>
 #include <cmath>
 
@@ -66,8 +68,8 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     p.lattice_bytes = o - lat0;
     size_t ch0 = o;
     if (p.bf16) {
-        p.off_dh = take((size_t)chunk_rows * d.V * 2);
-        p.off_z = take((size_t)chunk_rows * d.H * 2);
+        p.off_dh = take((size_t)chunk_rows * chunk_pitch(d.V) * 2);
+        p.off_z = take((size_t)chunk_rows * chunk_pitch(d.H) * 2);
     } else {
         p.off_dh = p.off_z = o;
     }
@@ -100,7 +102,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     p.tiles_total = p.tile_off[B];
     const long long all_tile_rows =
         (long long)align_up((size_t)p.tiles_total * TILE_ROWS, GEMM_TILE);
-    const size_t crb = p.bf16 ? (size_t)2 * d.V + (size_t)2 * d.H : 0;
+    const size_t crb = p.bf16 ? (size_t)2 * chunk_pitch(d.V) + (size_t)2 * chunk_pitch(d.H) : 0;
 
     // smallest workable plan: one (largest) sample per group, one GEMM tile of rows per chunk
     Plan tmp = p;
