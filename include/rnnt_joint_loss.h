@@ -77,7 +77,7 @@ const char* rnnt_status_string(rnnt_status s);
 
 /*
  * Workspace size for a call (host only, no GPU needed).
- *   budget_bytes = 0: the library's default trade-off (never more than 1 GiB plus, for bf16,
+ *   budget_bytes = 0: the library's default trade-off (never more than 1088 MiB plus, for bf16,
  *   the two packed copies of W_out and the partial sums of the dW GEMM, which depend on H and V
  *   only (partial sums: about 64 MiB while H*V <= 2^21, 32 bytes per element of W_out beyond),
  *   plus what the largest single sample needs).  Otherwise the largest plan not exceeding budget_bytes; if

@@ -108,15 +108,21 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     Plan tmp = p;
     p.min_bytes = lay_out(d, tmp, max_rows, p.bf16 ? GEMM_TILE : 0);
 
+    // the default plan; a caller that passes exactly the size it was told gets exactly this plan back
+    const long long lat_default = std::min(p.rows_total, std::max(max_rows, (256LL << 20) / 20));
+    long long chunk_default = 0;
+    if (p.bf16) {
+        // 832 MiB: 768 MiB of rows at H = 512, V = 1024 plus the padding of their row pitch
+        long long by_bytes = (long long)((832ULL << 20) / crb) / GEMM_TILE * GEMM_TILE;
+        chunk_default = std::min(all_tile_rows, std::max<long long>(GEMM_TILE, by_bytes));
+    }
+    Plan dflt = p;
+    const size_t default_bytes = lay_out(d, dflt, lat_default, chunk_default);
+
     long long lat_cap, chunk_rows;
-    if (workspace_bytes == 0) {
-        const long long lat_default = (256LL << 20) / 20;
-        lat_cap = std::min(p.rows_total, std::max(max_rows, lat_default));
-        chunk_rows = 0;
-        if (p.bf16) {
-            long long by_bytes = (long long)((768ULL << 20) / crb) / GEMM_TILE * GEMM_TILE;
-            chunk_rows = std::min(all_tile_rows, std::max<long long>(GEMM_TILE, by_bytes));
-        }
+    if (workspace_bytes == 0 || workspace_bytes == default_bytes) {
+        lat_cap = lat_default;
+        chunk_rows = chunk_default;
     } else if (workspace_bytes < p.min_bytes) {
         lat_cap = max_rows;
         chunk_rows = p.bf16 ? GEMM_TILE : 0;

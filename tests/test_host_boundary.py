@@ -90,8 +90,8 @@ def test_parallel_iterations_rule_matches_the_worked_values():
 def test_default_plan_properties(name):
     wl, desc, T, U = _lens(name)
     n = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 0)
-    # 256 MiB lattice state + 768 MiB chunk buffers + tables, packed weights and the dW partial sums
-    assert 0 < n <= (1 << 30) + (192 << 20)
+    # 256 MiB lattice state + 832 MiB chunk buffers + tables, packed weights and the dW partial sums
+    assert 0 < n <= (1088 << 20) + (160 << 20)
     st, info, groups = Bd.rnnt_joint_loss_plan(desc, T, U, n)
     assert st == 0
     rows = T.astype(np.int64) * (U.astype(np.int64) + 1)
