@@ -38,7 +38,8 @@ typedef enum {
     RNNT_ERR_LABEL = 4,       /* a label outside [0,V) (only rnnt_validate_labels_host)       */
     RNNT_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned (256 B) or too small              */
     RNNT_ERR_UNSUPPORTED = 6, /* shape not supported by the kernels of the requested dtype    */
-    RNNT_ERR_HIP = 7          /* a HIP call or launch failed                                  */
+    RNNT_ERR_HIP = 7,         /* a HIP call or launch failed                                  */
+    RNNT_ERR_WEIGHT = 8       /* a sample weight is negative, NaN or infinite                 */
 } rnnt_status;
 
 typedef enum {
@@ -144,6 +145,24 @@ rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc,
                                     float* loss, float* d_enc, float* d_pred,
                                     float* dW_out, float* db_out,
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The same with one weight per sample: loss[b] is still -ln P(y_b|x_b), the gradients are those of
+ * sum_b sample_weight[b] * loss[b] (Section 3: the criterion is a sum over the samples, so a
+ * training loop's mean reduction, loss masks or gradient scaling are such weights; Algorithm 1
+ * lines 8-11 with every sample's posterior weights scaled).  sample_weight: HOST [B], every entry
+ * finite and >= 0 (else RNNT_ERR_WEIGHT, before any launch); NULL means all ones, i.e. exactly
+ * rnnt_joint_loss_fwd_bwd.  A weight of 0 leaves that sample out of every gradient.  Everything
+ * else (layouts, workspace, ownership, errors, stream order) as above.
+ */
+rnnt_status rnnt_joint_loss_fwd_bwd_weighted(const rnnt_desc* desc,
+                                             const void* enc, const void* pred, const void* W_out,
+                                             const float* b_out, const int32_t* labels,
+                                             const int32_t* T_len_host, const int32_t* U_len_host,
+                                             const float* sample_weight_host,
+                                             float* loss, float* d_enc, float* d_pred,
+                                             float* dW_out, float* db_out,
+                                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Loss only (Eqs. 4, 6, 7-9): same inputs, no gradient outputs, same workspace rule

@@ -42,8 +42,9 @@ and by sum_t d_enc = sum_u d_pred (both are the gradient of b^Z).
 
 Pins (tests/test_oracle_*.py): exhaustive alignment enumeration, the closed forms
 for T=1, U=0 and uniform scores, sum_v dh = 0, occupation identities of the
-lattice, central finite differences through the whole chain, per-sample ==
-batched-padded, batch permutation, and the worked values of Eq. (11).
+lattice, central finite differences through the whole chain (also of the weighted
+sum of the samples' losses), per-sample == batched-padded, batch permutation, and
+the worked values of Eq. (11).
 """
 from __future__ import annotations
 
@@ -176,7 +177,7 @@ def sample_loss_and_grads(enc_b, pred_b, W_out, b_out, y, blank, want_intermedia
     return out
 
 
-def rnnt_joint_loss(enc, pred, W_out, b_out, labels, T_len, U_len, blank):
+def rnnt_joint_loss(enc, pred, W_out, b_out, labels, T_len, U_len, blank, sample_weight=None):
     """Algorithm 1, lines 3-12, in float64: loop over samples, slice to the true lengths,
     accumulate the output-layer gradients, assign the encoding gradients.
 
@@ -184,6 +185,9 @@ def rnnt_joint_loss(enc, pred, W_out, b_out, labels, T_len, U_len, blank):
     T_len/U_len [B].  Entries outside a sample's lengths are never read.
     Returns loss [B], d_enc [B,T_max,H], d_pred [B,U_max+1,H], dW_out [H,V], db_out [V]
     (gradients of sum_b loss[b]; zeros in the padded rows of d_enc/d_pred).
+    With sample_weight [B] the gradients are those of sum_b sample_weight[b] * loss[b] (the
+    criterion of Section 2 is a sum over the samples, so each sample's gradients are scaled by
+    its weight before they are accumulated or assigned); loss[b] itself stays -ln P(y_b|x_b).
     """
     enc = np.asarray(enc)
     pred = np.asarray(pred)
@@ -198,11 +202,12 @@ def rnnt_joint_loss(enc, pred, W_out, b_out, labels, T_len, U_len, blank):
         T, U = int(T_len[b]), int(U_len[b])
         r = sample_loss_and_grads(enc[b, :T], pred[b, :U + 1], W_out, b_out,
                                   np.asarray(labels[b, :U]), blank)
+        w = 1.0 if sample_weight is None else float(sample_weight[b])
         loss[b] = r["loss"]
-        d_enc[b, :T] = r["d_enc"]
-        d_pred[b, :U + 1] = r["d_pred"]
-        dW += r["dW_out"]
-        db += r["db_out"]
+        d_enc[b, :T] = w * r["d_enc"]
+        d_pred[b, :U + 1] = w * r["d_pred"]
+        dW += w * r["dW_out"]
+        db += w * r["db_out"]
     return dict(loss=loss, d_enc=d_enc, d_pred=d_pred, dW_out=dW, db_out=db)
 
 

@@ -17,12 +17,12 @@ LIB_PATH = os.path.join(_PKG, "lib", "librnnt_joint_loss.so")
 
 RNNT_F32, RNNT_BF16 = 0, 1
 STATUS_NAMES = ["RNNT_OK", "RNNT_ERR_NULL", "RNNT_ERR_SHAPE", "RNNT_ERR_LENGTH", "RNNT_ERR_LABEL",
-                "RNNT_ERR_WORKSPACE", "RNNT_ERR_UNSUPPORTED", "RNNT_ERR_HIP"]
+                "RNNT_ERR_WORKSPACE", "RNNT_ERR_UNSUPPORTED", "RNNT_ERR_HIP", "RNNT_ERR_WEIGHT"]
 EXPORTS = ["rnnt_status_string", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_loss_plan",
            "rnnt_parallel_iterations", "rnnt_validate_labels_host", "rnnt_joint_loss_fwd_bwd",
            "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice", "rnnt_profile_enable",
            "rnnt_debug_copy_f32", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
-           "rnnt_joint_proj_workspace_bytes", "rnnt_joint_proj_loss_fwd_bwd"]
+           "rnnt_joint_proj_workspace_bytes", "rnnt_joint_proj_loss_fwd_bwd", "rnnt_joint_loss_fwd_bwd_weighted"]
 
 
 class RnntDesc(ctypes.Structure):
@@ -73,6 +73,9 @@ def lib() -> ctypes.CDLL:
     L.rnnt_joint_loss_fwd_bwd.restype = ctypes.c_int
     L.rnnt_joint_loss_fwd_bwd.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, f32p, f32p, f32p, f32p,
                                           vp, ctypes.c_size_t, vp]
+    L.rnnt_joint_loss_fwd_bwd_weighted.restype = ctypes.c_int
+    L.rnnt_joint_loss_fwd_bwd_weighted.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, f32p, f32p, f32p, f32p,
+                                                    f32p, vp, ctypes.c_size_t, vp]
     L.rnnt_joint_proj_workspace_bytes.restype = ctypes.c_size_t
     L.rnnt_joint_proj_workspace_bytes.argtypes = [dp, ctypes.c_int32, ctypes.c_int32, i32p, i32p, ctypes.c_size_t]
     L.rnnt_joint_proj_loss_fwd_bwd.restype = ctypes.c_int
@@ -153,6 +156,19 @@ def rnnt_joint_loss_fwd_bwd(desc: RnntDesc, enc, pred, W_out, b_out, labels, T_l
     T, U = _i32(T_len), _i32(U_len)
     return int(lib().rnnt_joint_loss_fwd_bwd(
         ctypes.byref(desc), _ptr(enc), _ptr(pred), _ptr(W_out), _ptr(b_out), _ptr(labels), _ip(T), _ip(U),
+        _ptr(loss), _ptr(d_enc), _ptr(d_pred), _ptr(dW_out), _ptr(db_out), _ptr(workspace),
+        int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
+        _stream_handle(stream)))
+
+
+def rnnt_joint_loss_fwd_bwd_weighted(desc: RnntDesc, enc, pred, W_out, b_out, labels, T_len, U_len, sample_weight,
+                                     loss, d_enc, d_pred, dW_out, db_out, workspace, stream=None) -> int:
+    """Raw call with one weight per sample (host array of B float32, or None for all ones)."""
+    T, U = _i32(T_len), _i32(U_len)
+    w = None if sample_weight is None else np.ascontiguousarray(sample_weight, dtype=np.float32)
+    wp = None if w is None else w.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+    return int(lib().rnnt_joint_loss_fwd_bwd_weighted(
+        ctypes.byref(desc), _ptr(enc), _ptr(pred), _ptr(W_out), _ptr(b_out), _ptr(labels), _ip(T), _ip(U), wp,
         _ptr(loss), _ptr(d_enc), _ptr(d_pred), _ptr(dW_out), _ptr(db_out), _ptr(workspace),
         int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
         _stream_handle(stream)))
@@ -258,9 +274,10 @@ def to_device(batch, device="cuda:0"):
 
 
 def run_fwd_bwd(dev: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optional[Workspace] = None,
-                budget_bytes: int = 0, accumulate_into=None, stream=None):
-    """Allocates outputs (and a workspace unless given), calls rnnt_joint_loss_fwd_bwd, raises on
-    a non-zero status.  Returns dict(loss, d_enc, d_pred, dW_out, db_out, workspace)."""
+                budget_bytes: int = 0, accumulate_into=None, stream=None, sample_weight=None):
+    """Allocates outputs (and a workspace unless given), calls rnnt_joint_loss_fwd_bwd (its weighted form if
+    sample_weight is given), raises on a non-zero status.  Returns dict(loss, d_enc, d_pred, dW_out, db_out,
+    workspace)."""
     import torch
     device = dev["enc"].device
     desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1)
@@ -278,8 +295,13 @@ def run_fwd_bwd(dev: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optio
         db = torch.empty(V, dtype=torch.float32, device=device)
     else:
         dW, db = accumulate_into
-    st = rnnt_joint_loss_fwd_bwd(desc, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
-                                 dev["T_len"], dev["U_len"], loss, d_enc, d_pred, dW, db, workspace.buf, stream)
+    if sample_weight is None:
+        st = rnnt_joint_loss_fwd_bwd(desc, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                     dev["T_len"], dev["U_len"], loss, d_enc, d_pred, dW, db, workspace.buf, stream)
+    else:
+        st = rnnt_joint_loss_fwd_bwd_weighted(desc, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                              dev["T_len"], dev["U_len"], sample_weight, loss, d_enc, d_pred, dW, db,
+                                              workspace.buf, stream)
     if st != 0:
         raise RnntError(st, "rnnt_joint_loss_fwd_bwd")
     return dict(loss=loss, d_enc=d_enc, d_pred=d_pred, dW_out=dW, db_out=db, workspace=workspace, desc=desc)

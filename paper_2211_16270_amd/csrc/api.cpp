@@ -22,6 +22,7 @@ extern "C" const char* rnnt_status_string(rnnt_status s) {
         case RNNT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case RNNT_ERR_UNSUPPORTED: return "shape not supported for this dtype";
         case RNNT_ERR_HIP: return "HIP runtime error";
+        case RNNT_ERR_WEIGHT: return "a sample weight is negative or not finite";
     }
     return "unknown status";
 }
@@ -169,7 +170,7 @@ WsView view_workspace(const Plan& p, void* ws) {
 rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const void* W_out, const float* b_out,
                 const int32_t* labels, const int32_t* T_len, const int32_t* U_len, float* loss, float* d_enc,
                 float* d_pred, float* dW_out, float* db_out, void* workspace, size_t workspace_bytes,
-                void* hip_stream, bool grads) {
+                void* hip_stream, bool grads, const float* sample_weight = nullptr) {
     rnnt_status stt = check_desc(desc);
     if (stt != RNNT_OK) return stt;
     if (!enc || !pred || !W_out || !b_out || !loss || !T_len || !U_len) return RNNT_ERR_NULL;
@@ -177,6 +178,9 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     if (grads && (!d_enc || !d_pred || !dW_out || !db_out)) return RNNT_ERR_NULL;
     stt = check_lengths(desc, T_len, U_len);
     if (stt != RNNT_OK) return stt;
+    if (sample_weight)
+        for (int b = 0; b < desc->B; ++b)
+            if (!(sample_weight[b] >= 0.0f) || !std::isfinite(sample_weight[b])) return RNNT_ERR_WEIGHT;
     if (!workspace || ((uintptr_t)workspace % WS_ALIGN) != 0 || workspace_bytes == 0) return RNNT_ERR_WORKSPACE;
     Plan plan;
     build_plan(*desc, T_len, U_len, workspace_bytes, plan);
@@ -192,6 +196,7 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         std::vector<unsigned char> tab(tab_bytes, 0);
         std::memcpy(tab.data(), T_len, B * 4);
         std::memcpy(tab.data() + (plan.off_U - plan.off_T), U_len, B * 4);
+        if (sample_weight) std::memcpy(tab.data() + (plan.off_weight - plan.off_T), sample_weight, B * 4);
         std::memcpy(tab.data() + (plan.off_tile_off - plan.off_T), plan.tile_off.data(), (B + 1) * 4);
         std::memcpy(tab.data() + (plan.off_row_off - plan.off_T), plan.row_off.data(), (B + 1) * 8);
         RNNT_HIP(hipMemcpyAsync(w + plan.off_T, tab.data(), tab_bytes, hipMemcpyHostToDevice, stream));
@@ -233,6 +238,7 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         const Group& g = plan.groups[gi];
         LatticeState ls = wv.ls;
         ls.row_base = plan.row_off[g.s0];
+        ls.weight = sample_weight ? (const float*)(w + plan.off_weight) : nullptr;
         // Eq. 4, Eq. 6, f^W_1
         if (bf16)
             RNNT_HIP(timed(KC_FWD_SCORES, stream, [&] {
@@ -293,6 +299,17 @@ extern "C" rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc, const void
                                                void* workspace, size_t workspace_bytes, void* hip_stream) {
     return run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW_out, db_out,
                workspace, workspace_bytes, hip_stream, true);
+}
+
+extern "C" rnnt_status rnnt_joint_loss_fwd_bwd_weighted(const rnnt_desc* desc, const void* enc, const void* pred,
+                                                        const void* W_out, const float* b_out,
+                                                        const int32_t* labels, const int32_t* T_len,
+                                                        const int32_t* U_len, const float* sample_weight,
+                                                        float* loss, float* d_enc, float* d_pred, float* dW_out,
+                                                        float* db_out, void* workspace, size_t workspace_bytes,
+                                                        void* hip_stream) {
+    return run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW_out, db_out,
+               workspace, workspace_bytes, hip_stream, true, sample_weight);
 }
 
 namespace {

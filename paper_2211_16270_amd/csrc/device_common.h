@@ -88,6 +88,7 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // Posterior weights of one lattice node (f^W_4): ln gamma, and the occupation of its blank and
 // label transitions.  alpha/beta/lnP carry the per-sample emission offset `shift`, which cancels.
+// With per-sample loss weights all three are those of w_s * loss_s.
 struct RowPost {
     float log_gamma, Bk, Yk;
 };
@@ -100,6 +101,13 @@ __device__ __forceinline__ RowPost row_posteriors(const LatticeState& ls, long l
     if (t < T - 1) r.Bk = __expf(ab + ls.beta[idx + (U + 1)]);
     else r.Bk = (u == U) ? __expf(ab) : 0.0f;
     r.Yk = (u < U) ? __expf(a + ls.lpy[idx] + c - lnP + ls.beta[idx + 1]) : 0.0f;
+    if (ls.weight) {
+        // gradients of sum_b w_b loss_b: every posterior weight of sample s is scaled by w_s >= 0
+        const float w = ls.weight[s];
+        r.log_gamma += __logf(w);          // -inf for w = 0: the sample contributes nothing
+        r.Bk *= w;
+        r.Yk *= w;
+    }
     return r;
 }
 

@@ -25,6 +25,7 @@ struct LatticeState {
     float* beta;   // backward variable, offset by shift*((T-t)+(U-u))
     float* lnP;    // [B] ln P(y|x) + shift*(T+U), per sample
     float* shift;  // [B] per-sample offset added to every emission log-probability
+    const float* weight;  // [B] weight of loss[b] in the differentiated sum, or null (all ones)
     long long row_base;
 };
 

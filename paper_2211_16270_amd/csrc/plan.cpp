@@ -50,6 +50,7 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, WS_ALIGN); return at; };
     p.off_T = take(B * 4);
     p.off_U = take(B * 4);
+    p.off_weight = take(B * 4);
     p.off_tile_off = take((B + 1) * 4);
     p.off_row_off = take((B + 1) * 8);
     p.off_lnP = take(B * 4);

@@ -10,13 +10,14 @@ TOL = {"f32": dict(loss=1e-5, grad=1e-4), "bf16": dict(loss=2e-3, grad=1e-2)}
 GRADS = ("d_enc", "d_pred", "dW_out", "db_out")
 
 
-def run_gpu(batch, budget_bytes=0, blank=None, workspace=None, accumulate_into=None):
+def run_gpu(batch, budget_bytes=0, blank=None, workspace=None, accumulate_into=None, sample_weight=None):
     import torch
     wl = batch.wl
     dev = Bd.to_device(batch)
     dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
     out = Bd.run_fwd_bwd(dev, batch.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank if blank is None else blank, dt,
-                         workspace=workspace, budget_bytes=budget_bytes, accumulate_into=accumulate_into)
+                         workspace=workspace, budget_bytes=budget_bytes, accumulate_into=accumulate_into,
+                         sample_weight=sample_weight)
     torch.cuda.synchronize()
     res = {k: out[k].float().cpu().numpy() for k in ("loss",) + GRADS}
     res["workspace"] = out["workspace"]
@@ -25,11 +26,12 @@ def run_gpu(batch, budget_bytes=0, blank=None, workspace=None, accumulate_into=N
     return res
 
 
-def run_oracle(batch, blank=None):
+def run_oracle(batch, blank=None, sample_weight=None):
     wl = batch.wl
     return O.rnnt_joint_loss(batch.enc.astype(np.float64), batch.pred.astype(np.float64),
                              batch.W_out.astype(np.float64), batch.b_out.astype(np.float64),
-                             batch.labels, batch.T_len, batch.U_len, wl.blank if blank is None else blank)
+                             batch.labels, batch.T_len, batch.U_len, wl.blank if blank is None else blank,
+                             sample_weight=sample_weight)
 
 
 def rel_loss_err(got, ref):

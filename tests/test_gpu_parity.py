@@ -187,6 +187,62 @@ def test_uniform_scores_closed_form_at_the_largest_lattice():
     assert abs(float(got["db_out"][0]) - sum(for_b)) < 1e-2 * abs(sum(for_b))
 
 
+# ------------------------------------------------------------------ weighted sum of the samples' losses
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sample_weights_against_the_checker(dtype):
+    if dtype == "f32":
+        wl = synth.custom_workload("wf32", B=4, T_max=17, U_max=6, H=32, V=24, dtype="f32", index=121,
+                                   t_rule="uniform", t_lo=3, u_rule="uniform", u_lo=0)
+    else:
+        wl = synth.custom_workload("wbf16", B=4, T_max=37, U_max=19, H=128, V=256, dtype="bf16", index=122,
+                                   t_rule="uniform", t_lo=9, u_rule="uniform", u_lo=2)
+    batch = synth.make_batch(wl)
+    w = np.array([0.5, 0.0, 2.0, 1.0 / 3.0], dtype=np.float32)
+    _say("weights", dtype, batch.T_len, batch.U_len, w)
+    got, ref = run_gpu(batch, sample_weight=w), run_oracle(batch, sample_weight=w.astype(np.float64))
+    e, errs = assert_parity(got, ref, dtype, f"weighted {dtype}")
+    _say("weighted errs", e, errs)
+    assert_padding_zero(got, batch)
+    assert np.all(got["d_enc"][1] == 0.0) and np.all(got["d_pred"][1] == 0.0)       # weight 0: left out
+    plain, ones = run_gpu(batch), run_gpu(batch, sample_weight=np.ones(4, dtype=np.float32))
+    np.testing.assert_array_equal(plain["loss"], got["loss"])
+    for k in GRADS:
+        assert rel_grad_err(ones[k], plain[k].astype(np.float64)) < 1e-5, k
+
+
+def test_autograd_front_end_returns_the_library_gradients():
+    import torch
+    from paper_2211_16270_amd.autograd import rnnt_joint_loss
+    wl = synth.custom_workload("ag", B=3, T_max=21, U_max=7, H=128, V=256, dtype="bf16", index=123,
+                               t_rule="uniform", t_lo=5, u_rule="uniform", u_lo=1)
+    batch = synth.make_batch(wl, pad="zero")
+    dev = Bd.to_device(batch)
+    leaves = [dev[k].clone().requires_grad_(True) for k in ("enc", "pred", "W_out", "b_out")]
+
+    def grads_of(reduce, sample_weight=None):
+        for x in leaves:
+            x.grad = None
+        loss = rnnt_joint_loss(*leaves, dev["labels"], batch.T_len, batch.U_len, 0, sample_weight=sample_weight)
+        reduce(loss).backward()
+        torch.cuda.synchronize()
+        return loss.detach().float().cpu().numpy(), [x.grad.float().cpu().numpy() for x in leaves]
+
+    direct = run_gpu(batch)
+    loss, g_sum = grads_of(lambda l: l.sum())
+    np.testing.assert_array_equal(loss, direct["loss"])
+    for got, k in zip(g_sum, GRADS):
+        want = torch.from_numpy(direct[k]).to(torch.bfloat16 if k != "db_out" else torch.float32).float().numpy()
+        assert rel_grad_err(got, want.astype(np.float64)) < 1e-3, k
+    # a mean and a mask: the incoming gradient differs from the weights of the first call, which is repeated
+    w = np.array([1.0 / 3, 0.0, 1.0 / 3], dtype=np.float32)
+    ref = run_oracle(batch, sample_weight=w.astype(np.float64))
+    _, g_w = grads_of(lambda l: (l * torch.tensor(w, device=l.device)).sum())
+    _, g_w2 = grads_of(lambda l: (l * torch.tensor(w, device=l.device)).sum(), sample_weight=w)
+    for a, b2, k in zip(g_w, g_w2, GRADS):
+        assert rel_grad_err(a, ref[k]) <= 2e-2, k           # bf16 gradients (rounded once more to the leaf dtype)
+        assert rel_grad_err(b2, a.astype(np.float64)) < 1e-3, k
+
+
 # ------------------------------------------------------------------ the benchmarked workload
 def test_bf16_bench_workload_subbatch_parity():
     ids = [0, 17]
@@ -215,6 +271,27 @@ def test_bf16_bench_workload_full_batch_sampled_outputs():
         assert rel_grad_err(got["d_pred"][b, :U + 1], r["d_pred"]) <= tol["grad"]
     # softmax shift invariance: the bias gradient sums to zero (up to bf16 rounding of dh)
     assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-2 * float(np.abs(got["db_out"]).sum())
+
+
+def test_bf16_bench_workload_permutation_and_split_invariance():
+    # properties that hold at any size: the order of the samples only permutes the per-sample outputs, and
+    # the parameter gradients of a batch are the sum of those of its parts (different packing into launches)
+    n = 32
+    full = run_gpu(synth.make_batch("C2"))
+    perm = list(reversed(range(n)))
+    rev = run_gpu(synth.make_batch("C2", sample_ids=perm))
+    assert np.max(np.abs(rev["loss"] - full["loss"][perm]) / np.abs(full["loss"][perm])) < 1e-5
+    for k in ("d_enc", "d_pred"):
+        for i, b in enumerate(perm):
+            assert rel_grad_err(rev[k][i], full[k][b].astype(np.float64)) < 1e-3, (k, b)
+    for k in ("dW_out", "db_out"):
+        assert rel_grad_err(rev[k], full[k].astype(np.float64)) < 2e-3, k
+    lo = run_gpu(synth.make_batch("C2", sample_ids=list(range(0, 12))))
+    hi = run_gpu(synth.make_batch("C2", sample_ids=list(range(12, n))))
+    for k in ("dW_out", "db_out"):
+        both = lo[k].astype(np.float64) + hi[k].astype(np.float64)
+        assert rel_grad_err(full[k], both) < 2e-3, k
+    assert np.max(np.abs(np.concatenate([lo["loss"], hi["loss"]]) - full["loss"]) / np.abs(full["loss"])) < 1e-5
 
 
 def test_bf16_memory_headline_workload_sampled():

@@ -68,6 +68,26 @@ def test_argument_checks_happen_on_the_host():
     assert Bd.rnnt_joint_loss_workspace_bytes(bad, T, U) == 0
 
 
+def test_sample_weights_are_checked_on_the_host():
+    wl, desc, T, U = _lens("C2")
+    L = Bd.lib()
+    dummy = ctypes.c_void_p(0x1000)
+
+    def call(w, ws=dummy):
+        w = None if w is None else np.ascontiguousarray(w, dtype=np.float32)
+        wp = None if w is None else w.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+        return L.rnnt_joint_loss_fwd_bwd_weighted(ctypes.byref(desc), dummy, dummy, dummy, dummy, dummy, Bd._ip(T),
+                                                  Bd._ip(U), wp, dummy, dummy, dummy, dummy, dummy, ws, 1 << 30, None)
+
+    w = np.ones(wl.B, dtype=np.float32)
+    for bad in (-0.5, np.nan, np.inf):
+        w2 = w.copy(); w2[7] = bad
+        assert call(w2) == 8                                     # RNNT_ERR_WEIGHT, before the workspace is looked at
+    assert call(w, ws=None) == 5                                 # valid weights: the next check (workspace) fails
+    assert call(None, ws=None) == 5                              # no weights = the unweighted call
+    assert Bd.lib().rnnt_status_string(8).decode().startswith("a sample weight")
+
+
 def test_label_validation():
     wl, desc, T, U = _lens("C2")
     _, _, lab = synth.draw_lengths_labels(wl)

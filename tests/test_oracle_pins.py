@@ -281,6 +281,40 @@ def test_batch_permutation_and_additivity():
     np.testing.assert_allclose(dW, full["dW_out"], atol=1e-12)
 
 
+def test_weighted_gradients_match_finite_differences_of_the_weighted_sum():
+    # gradients of sum_b w_b loss_b (Section 2: the criterion is a sum over the samples); a weight of
+    # zero removes a sample, unit weights give the unweighted call, the losses themselves do not change
+    rng = np.random.default_rng(43)
+    args = list(_rand_problem(rng, B=3, T_max=5, U_max=3, H=4, V=5, blank=1))
+    args[5][:] = [5, 2, 4]
+    args[6][:] = [3, 1, 0]
+    w = np.array([0.25, 0.0, 1.75])
+    g = O.rnnt_joint_loss(*args, sample_weight=w)
+    plain = O.rnnt_joint_loss(*args)
+    np.testing.assert_array_equal(g["loss"], plain["loss"])
+    ones = O.rnnt_joint_loss(*args, sample_weight=np.ones(3))
+    for k in plain:
+        np.testing.assert_array_equal(ones[k], plain[k])
+    assert np.all(g["d_enc"][1] == 0) and np.all(g["d_pred"][1] == 0)
+    eps = 1e-6
+
+    def weighted_total():
+        return float(np.dot(w, O.rnnt_joint_loss(*args)["loss"]))
+
+    for name, pos in (("d_enc", 0), ("d_pred", 1), ("dW_out", 2), ("db_out", 3)):
+        x = args[pos]
+        fd = np.zeros_like(x)
+        for idx in np.ndindex(*x.shape):
+            old = x[idx]
+            x[idx] = old + eps
+            lp_ = weighted_total()
+            x[idx] = old - eps
+            lm_ = weighted_total()
+            x[idx] = old
+            fd[idx] = (lp_ - lm_) / (2 * eps)
+        np.testing.assert_allclose(g[name], fd, atol=5e-8, err_msg=name)
+
+
 # ---------------------------------------------------------------- Eq. (11)
 def test_parallel_iterations_worked_values():
     with open(os.path.join(GOLD, "eq11_parallel_iterations.txt")) as f:
