@@ -48,7 +48,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
-              "Sharding over GPUs is described in DESIGN.md, not implemented.", file=sys.stderr)
+              "Sharding over GPUs is a design note only (samples over GPUs, one all-reduce of dW_out and db_out); it is not implemented.", file=sys.stderr)
         sys.exit(2)
 
     import torch
