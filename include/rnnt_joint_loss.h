@@ -58,6 +58,13 @@ typedef struct {
     int32_t blank;  /* index of the blank symbol, in [0,V)                                   */
     int32_t dtype;  /* rnnt_dtype                                                            */
     int32_t accumulate_params; /* 0: dW_out, db_out are overwritten; 1: added to (Alg. 1, line 3 / 8) */
+    int32_t keep_scores;       /* RNNT_BF16 only.  0: the backward pass computes the scores a second time
+                                  (the paper's trade: time for memory, Section 4).  1: the forward pass keeps
+                                  the joint activations and the scores (fp16, relative to running row maxima)
+                                  of a group of samples in the workspace and the backward pass reads them:
+                                  three GEMMs per row instead of four, for 2 (H + V) more workspace bytes per
+                                  lattice node of a group (the paper's outlook on other memory trade-offs,
+                                  Section 6)                                                           */
 } rnnt_desc;
 
 /* What the host scheduler decided for a call (Section 4.1.2 analogue; see rnnt_joint_loss_plan). */

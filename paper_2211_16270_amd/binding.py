@@ -28,7 +28,8 @@ EXPORTS = ["rnnt_status_string", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_
 class RnntDesc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32), ("U_max", ctypes.c_int32),
                 ("H", ctypes.c_int32), ("V", ctypes.c_int32), ("blank", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("accumulate_params", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("accumulate_params", ctypes.c_int32),
+                ("keep_scores", ctypes.c_int32)]
 
 
 class RnntPlanInfo(ctypes.Structure):
@@ -99,9 +100,9 @@ def lib() -> ctypes.CDLL:
     return L
 
 
-def make_desc(B, T_max, U_max, H, V, blank=0, dtype=RNNT_BF16, accumulate_params=0) -> RnntDesc:
+def make_desc(B, T_max, U_max, H, V, blank=0, dtype=RNNT_BF16, accumulate_params=0, keep_scores=0) -> RnntDesc:
     return RnntDesc(int(B), int(T_max), int(U_max), int(H), int(V), int(blank), int(dtype),
-                    int(accumulate_params))
+                    int(accumulate_params), int(keep_scores))
 
 
 def _i32(a) -> np.ndarray:
@@ -274,13 +275,13 @@ def to_device(batch, device="cuda:0"):
 
 
 def run_fwd_bwd(dev: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optional[Workspace] = None,
-                budget_bytes: int = 0, accumulate_into=None, stream=None, sample_weight=None):
+                budget_bytes: int = 0, accumulate_into=None, stream=None, sample_weight=None, keep_scores=0):
     """Allocates outputs (and a workspace unless given), calls rnnt_joint_loss_fwd_bwd (its weighted form if
-    sample_weight is given), raises on a non-zero status.  Returns dict(loss, d_enc, d_pred, dW_out, db_out,
+    sample_weight is given), raises on a non-zero status.  keep_scores = 1 sets that field of the descriptor.  Returns dict(loss, d_enc, d_pred, dW_out, db_out,
     workspace)."""
     import torch
     device = dev["enc"].device
-    desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1)
+    desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1, keep_scores)
     if workspace is None:
         n = rnnt_joint_loss_workspace_bytes(desc, dev["T_len"], dev["U_len"], budget_bytes)
         if n == 0:

@@ -89,10 +89,12 @@ namespace {
 
 // Optional per-kernel timing with HIP events on the caller's stream (off by default).
 enum KernelClass { KC_PREPARE = 0, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
-                   KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_DW_REDUCE, KC_PROJ, KC_COUNT };
+                   KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_DW_REDUCE, KC_PROJ, KC_FWD_KEEP, KC_KEPT_TO_DH,
+                   KC_COUNT };
 const char* const kKernelNames[KC_COUNT] = {"prepare", "joint_scores_fwd", "lattice",
                                             "joint_scores_bwd", "gemm_dz", "gemm_dw_db", "joint_bwd_fused",
-                                            "fwd_f32", "bwd_f32", "dw_reduce", "projections"};
+                                            "fwd_f32", "bwd_f32", "dw_reduce", "projections",
+                                            "joint_scores_fwd_keep", "kept_scores_to_dh"};
 struct Profiler {
     bool enabled = false;
     struct Rec { int cls; hipEvent_t e0, e1; };
@@ -140,6 +142,7 @@ struct WsView {
     void* wq;
     void* dH;
     void* Z;
+    float* kept_max;
     float* dw_slots;
 };
 
@@ -163,6 +166,7 @@ WsView view_workspace(const Plan& p, void* ws) {
     v.wq = w + p.off_wq;
     v.dH = w + p.off_dh;
     v.Z = w + p.off_z;
+    v.kept_max = (float*)(w + p.off_kept_max);
     v.dw_slots = (float*)(w + p.off_dwslots);
     return v;
 }
@@ -240,7 +244,13 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         ls.row_base = plan.row_off[g.s0];
         ls.weight = sample_weight ? (const float*)(w + plan.off_weight) : nullptr;
         // Eq. 4, Eq. 6, f^W_1
-        if (bf16)
+        const bool keep = plan.keep && grads;
+        if (keep)
+            RNNT_HIP(timed(KC_FWD_KEEP, stream, [&] {
+                return launch_fwd_keep_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, g.tile0, g.tile1, wv.dH, wv.Z,
+                                            wv.kept_max, stream);
+            }));
+        else if (bf16)
             RNNT_HIP(timed(KC_FWD_SCORES, stream, [&] {
                 return launch_fwd_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, g.tile0, g.tile1, stream);
             }));
@@ -256,7 +266,17 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
             const Chunk& c = plan.chunks[ci];
             if (bf16) {
                 const long long rows = (long long)(c.tile1 - c.tile0) * TILE_ROWS;
-                if (plan.fused) {
+                if (keep) {
+                    // the group's scores are in the chunk buffers already: one pass turns them into dh
+                    RNNT_HIP(timed(KC_KEPT_TO_DH, stream, [&] {
+                        return launch_kept_to_dh_bf16(pr, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
+                                                      wv.kept_max, stream);
+                    }));
+                    RNNT_HIP(timed(KC_GEMM_DZ, stream, [&] {
+                        return launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred,
+                                                   stream);
+                    }));
+                } else if (plan.fused) {
                     RNNT_HIP(timed(KC_BWD_FUSED, stream, [&] {
                         return launch_bwd_fused_bf16(pr, wv.wpack, wv.wq, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1,
                                                      wv.dH, wv.Z, d_enc, d_pred, stream);

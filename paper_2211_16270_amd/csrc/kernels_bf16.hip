@@ -18,12 +18,18 @@ namespace rnnt {
 
 // ------------------------------------------------------------------------------------------------
 // Joint tile + score GEMM.  MODE 0: softmax statistics (forward).  MODE 1: score gradients (backward).
+// MODE 2: forward that also keeps what the backward pass would otherwise compute again: the joint tile
+// (Z chunk buffer) and the scores, as fp16 differences t = h - m to a running maximum m (dH chunk buffer).
+// m is the largest score the wave has seen so far in the row (its 64 of every 256 vocabulary entries), one
+// float per row, wave and vocabulary step; t <= 0, so an entry's error exp(t) |t| 2^-11 in the softmax is
+// at most 2^-11 / e whatever the size of the scores.
 // NW waves; per step of 256 vocabulary entries wave w owns NVT tiles of 32 entries for all 64 rows
 // (NVT x 2 accumulator tiles of 32x32).
 // ------------------------------------------------------------------------------------------------
 constexpr int JT_ROWS = 64;
 constexpr int JT_VSTEP = 256;
 constexpr int STG_PITCH = 40;   // bf16 elements per row of a wave's 32x32 transposition buffer
+constexpr int STG2_PITCH = 72;  // the same for the 32x64 buffer of MODE 2 (whole 128-byte lines per row)
 
 struct JointArgs {
     Problem pr;
@@ -31,9 +37,10 @@ struct JointArgs {
     LatticeState ls;
     const bf16_t* Wp;
     int s0, s1, tile0, tile1;
-    // MODE 1 outputs
-    bf16_t* dH;     // [chunk rows, V]
+    // MODE 1, 2 outputs
+    bf16_t* dH;     // [chunk rows, V]   (MODE 2: fp16 score differences)
     bf16_t* Z;      // [chunk rows, H]
+    float* kept_max;  // MODE 2: [chunk tiles][V/64][64 rows] running maxima
 };
 
 
@@ -54,7 +61,8 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
     float* row_f2 = row_f1 + 64;                            // MODE 1: Yk
     float* red_m = row_f2 + 64;                             // MODE 0: [2 NW][64] partial maxima
     float* red_s = red_m + 2 * NW * 64;                     // MODE 0: [2 NW][64] partial sums
-    bf16_t* stg = reinterpret_cast<bf16_t*>(row_f2 + 64);   // MODE 1: [NW][32][STG_PITCH] (aliases red_*)
+    // [NW][32][STG_PITCH] transposition buffers: MODE 1 aliases red_*, MODE 2 lies behind them
+    bf16_t* stg = reinterpret_cast<bf16_t*>(MODE == 2 ? red_s + 2 * NW * 64 : row_f2 + 64);
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
@@ -100,7 +108,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
         const long long idx = (a.st.row_off[b] - a.ls.row_base) + (long long)t * (tp.U + 1) + u;
         row_lat[r] = valid ? (int)idx : -1;
         row_lab[r] = (valid && u < tp.U) ? a.pr.labels[(size_t)b * a.pr.U_max + u] : -1;
-        if (MODE == 0) {
+        if (MODE != 1) {
             row_f0[r] = RNNT_NEG_INF;
             row_f1[r] = RNNT_NEG_INF;
         } else {
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
         }
     }
     __syncthreads();
-    if (MODE == 1) {
+    if (MODE != 0) {
         // joint tile -> Z chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM
         const int cpr = H >> 3;
         for (int idx = tid; idx < JT_ROWS * cpr; idx += NT) {
@@ -235,7 +243,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
             const int rely = lab[rt] - vbase;
             const bool hit_y = ((unsigned)rely < 32u);
             const bool slow = __any(hit_y) || ((unsigned)relb < 32u);
-            if (MODE == 0) {
+            if (MODE != 1) {
                 // f^W_1: running maximum and sum of exponentials of this lane's share of the row
                 float x[16];
                 float tmax = RNNT_NEG_INF;
@@ -304,9 +312,47 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
             }
         }
         }
+        if (MODE == 2) {
+            // keep the scores of this step: t = h - m (fp16), m = the wave's running maximum of the row
+            typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+            static_assert(MODE != 2 || NVT == 2, "a wave keeps 64 vocabulary entries (one 128-byte line) per row");
+            _Float16* sw = reinterpret_cast<_Float16*>(stg) + wave * (32 * STG2_PITCH);
+            _Float16* kept = reinterpret_cast<_Float16*>(a.dH);
+            const int vbase = vs * JT_VSTEP + wave * (32 * NVT);
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) {
+                const float mw = fmaxf(m_run[rt], __shfl_xor(m_run[rt], 32, 64));
+                if (hb == 0)
+                    a.kept_max[((size_t)blockIdx.x * (V / 64) + vs * NW + wave) * 64 + rt * 32 + l32] = mw;
+#pragma unroll
+                for (int vt = 0; vt < NVT; ++vt) {
+                    const f32x16 accv = acc[vt][rt];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        f16x4 q4 = {(_Float16)(accv[4 * j] - mw), (_Float16)(accv[4 * j + 1] - mw),
+                                    (_Float16)(accv[4 * j + 2] - mw), (_Float16)(accv[4 * j + 3] - mw)};
+                        *reinterpret_cast<f16x4*>(sw + l32 * STG2_PITCH + vt * 32 + 8 * j + 4 * hb) = q4;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                // eight lanes store one row's 128 bytes: whole lines only
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int row = (lane >> 3) + 8 * it, seg = lane & 7;
+                    const bf16x8 v8 = *reinterpret_cast<const bf16x8*>(sw + row * STG2_PITCH + seg * 8);
+                    __builtin_nontemporal_store(
+                        v8, reinterpret_cast<bf16x8*>(kept + (size_t)(chunk_row0 + rt * 32 + row) * chunk_pitch(V) +
+                                                      vbase + seg * 8));
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
     }
 
-    if (MODE == 0) {
+    if (MODE != 1) {
         // combine the 2 NW partial (max, sum) pairs of every row, then lse, lpb, lpy
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) {
@@ -336,8 +382,9 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
 static size_t joint_smem_bytes(int H, int mode, int nw) {
     size_t z = (size_t)JT_ROWS * (H + 8) * 2;
     size_t meta = 64 * 4 * 5;
-    size_t tail = mode == 0 ? (size_t)2 * (2 * nw * 64) * 4 : (size_t)nw * 32 * STG_PITCH * 2;
-    return z + meta + tail;
+    const size_t red = (size_t)2 * (2 * nw * 64) * 4, stg = (size_t)nw * 32 * STG_PITCH * 2;
+    const size_t stg2 = (size_t)nw * 32 * STG2_PITCH * 2;
+    return z + meta + (mode == 0 ? red : mode == 1 ? stg : red + stg2);
 }
 
 // Forward and unfused backward: 4 waves x two 32-entry tiles each.
@@ -359,7 +406,7 @@ static hipError_t launch_joint(const JointArgs& a, hipStream_t stream) {
 
 hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st, const LatticeState& ls,
                            int s0, int s1, int tile0, int tile1, hipStream_t stream) {
-    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr};
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr, nullptr};
     // a longer prefetch distance where the hidden size allows it (the forward kernel has the registers)
     if (pr.H % 256 == 0) return launch_joint<0, 4, 2, 8>(a, stream);
     return launch_joint<0, 4, 2, 4>(a, stream);
@@ -368,8 +415,99 @@ hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTab
 hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                                   const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
                                   void* Z, hipStream_t stream) {
-    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)dH, (bf16_t*)Z};
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)dH, (bf16_t*)Z, nullptr};
     return launch_joint<1, 4, 2, 4>(a, stream);
+}
+
+hipError_t launch_fwd_keep_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
+                                const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* kept,
+                                void* Z, float* kept_max, hipStream_t stream) {
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)kept, (bf16_t*)Z, kept_max};
+    if (pr.H % 256 == 0) return launch_joint<2, 4, 2, 8>(a, stream);
+    return launch_joint<2, 4, 2, 4>(a, stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Kept scores -> score gradients, in place (f^W_4 without the second score GEMM):
+//   dh[r,v] = exp(t[r,v] + m[r, v/64] - lse[r] + ln gamma[r]) - [v = blank] B[r] - [v = y_u] Y[r],
+// rounded to bf16 over the fp16 t.  One workgroup per lattice tile (64 rows); wave w takes rows w, w+4, ...
+// and its lanes consecutive 16-byte pieces of the row.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_kept_to_dh(JointArgs a) {
+    __shared__ int row_lab[64];
+    __shared__ float row_g[64], row_b[64], row_y[64];
+    typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+    const int V = a.pr.V;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tile = a.tile0 + blockIdx.x;
+    const TilePos tp = locate_tile(a.st, a.s0, a.s1, tile);
+    const int b = tp.s;
+    if (tid < 64) {
+        const int r = tid;
+        const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
+        const bool valid = (t < tp.T && u <= tp.U);
+        row_lab[r] = (valid && u < tp.U) ? a.pr.labels[(size_t)b * a.pr.U_max + u] : -1;
+        float g = RNNT_NEG_INF, bk = 0.0f, yk = 0.0f;
+        if (valid) {
+            const long long idx = (a.st.row_off[b] - a.ls.row_base) + (long long)t * (tp.U + 1) + u;
+            const RowPost rp = row_posteriors(a.ls, idx, t, u, tp.T, tp.U, b);
+            g = (rp.log_gamma - a.ls.lse[idx]) * LOG2E_F;
+            bk = rp.Bk;
+            yk = rp.Yk;
+        }
+        row_g[r] = g;
+        row_b[r] = bk;
+        row_y[r] = yk;
+    }
+    __syncthreads();
+    const int cpr = V >> 3;                      // 16-byte pieces per row
+    const float* mx = a.kept_max + (size_t)blockIdx.x * (V / 64) * 64;
+    for (int row = wave; row < 64; row += 4) {
+        bf16_t* rowp = a.dH + (size_t)((long long)blockIdx.x * JT_ROWS + row) * chunk_pitch(V);
+        const float g = row_g[row], bk = row_b[row], yk = row_y[row];
+        const int lab = row_lab[row];
+        for (int c0 = lane; c0 < cpr; c0 += 256) {
+            f16x8 t[4];
+            float e[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = c0 + 64 * i < cpr ? c0 + 64 * i : c0;
+                t[i] = __builtin_nontemporal_load(reinterpret_cast<const f16x8*>(rowp + c * 8));
+                e[i] = fmaf(mx[(c >> 3) * 64 + row], LOG2E_F, g);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = c0 + 64 * i;
+                if (c < cpr) {
+                    float d[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) d[k] = __builtin_amdgcn_exp2f(fmaf((float)t[i][k], LOG2E_F, e[i]));
+                    const int relb = a.pr.blank - c * 8, rely = lab - c * 8;
+                    if ((unsigned)relb < 8u || (unsigned)rely < 8u) {
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            if (k == relb) d[k] -= bk;
+                            if (k == rely) d[k] -= yk;
+                        }
+                    }
+                    bf16x8 o;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) o[k] = (bf16_t)d[k];
+                    __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(rowp + c * 8));
+                }
+            }
+        }
+    }
+}
+
+hipError_t launch_kept_to_dh_bf16(const Problem& pr, const SampleTable& st, const LatticeState& ls, int s0,
+                                  int s1, int tile0, int tile1, void* kept, const float* kept_max,
+                                  hipStream_t stream) {
+    const int n = tile1 - tile0;
+    if (n <= 0) return hipSuccess;
+    JointArgs a{pr, st, ls, nullptr, s0, s1, tile0, tile1, (bf16_t*)kept, nullptr, const_cast<float*>(kept_max)};
+    k_kept_to_dh<<<dim3((unsigned)n), dim3(256), 0, stream>>>(a);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -15,6 +15,8 @@ rnnt_status check_desc(const rnnt_desc* d) {
     if (d->B < 1 || d->T_max < 1 || d->U_max < 0 || d->H < 1 || d->V < 2) return RNNT_ERR_SHAPE;
     if (d->blank < 0 || d->blank >= d->V) return RNNT_ERR_SHAPE;
     if (d->accumulate_params != 0 && d->accumulate_params != 1) return RNNT_ERR_SHAPE;
+    if (d->keep_scores != 0 && d->keep_scores != 1) return RNNT_ERR_SHAPE;
+    if (d->keep_scores && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
     if (d->dtype != RNNT_F32 && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
     if (d->U_max > 1023) return RNNT_ERR_UNSUPPORTED;           // one lattice thread per label position
     if ((long long)d->T_max * (d->U_max + 1) > (1LL << 30)) return RNNT_ERR_UNSUPPORTED;
@@ -69,10 +71,12 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     p.lattice_bytes = o - lat0;
     size_t ch0 = o;
     if (p.bf16) {
-        p.off_dh = take((size_t)chunk_rows * chunk_pitch(d.V) * 2);
+        // the dz GEMM reads dH in tiles of 256 rows: the buffer ends on such a boundary
+        p.off_dh = take(align_up((size_t)chunk_rows, 256) * chunk_pitch(d.V) * 2);
         p.off_z = take((size_t)chunk_rows * chunk_pitch(d.H) * 2);
+        p.off_kept_max = take(p.keep ? (size_t)chunk_rows * (d.V / 64) * 4 : 0);
     } else {
-        p.off_dh = p.off_z = o;
+        p.off_dh = p.off_z = p.off_kept_max = o;
     }
     p.chunk_bytes = o - ch0;
     p.group_rows_cap = lat_cap;
@@ -88,34 +92,42 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     const int B = d.B;
     p.B = B;
     p.bf16 = (d.dtype == RNNT_BF16);
-    p.fused = p.bf16 && fused_backward_shape(d.H, d.V);
+    p.keep = p.bf16 && d.keep_scores;
+    p.fused = p.bf16 && !p.keep && fused_backward_shape(d.H, d.V);
     p.tile_off.assign(B + 1, 0);
     p.row_off.assign(B + 1, 0);
-    long long max_rows = 0;
+    long long max_rows = 0, max_tile_rows = 0;
     for (int b = 0; b < B; ++b) {
         long long rows = (long long)T_len[b] * (U_len[b] + 1);
         long long tiles = (long long)((T_len[b] + TILE_T - 1) / TILE_T) * ((U_len[b] + 1 + TILE_U - 1) / TILE_U);
         p.row_off[b + 1] = p.row_off[b] + rows;
         p.tile_off[b + 1] = (int)(p.tile_off[b] + tiles);
         max_rows = std::max(max_rows, rows);
+        max_tile_rows = std::max(max_tile_rows, (long long)align_up((size_t)tiles * TILE_ROWS, GEMM_TILE));
     }
     p.rows_total = p.row_off[B];
     p.tiles_total = p.tile_off[B];
     const long long all_tile_rows =
         (long long)align_up((size_t)p.tiles_total * TILE_ROWS, GEMM_TILE);
-    const size_t crb = p.bf16 ? (size_t)2 * chunk_pitch(d.V) + (size_t)2 * chunk_pitch(d.H) : 0;
+    const size_t crb = !p.bf16 ? 0
+                               : (size_t)2 * chunk_pitch(d.V) + (size_t)2 * chunk_pitch(d.H) +
+                                     (p.keep ? (size_t)(d.V / 64) * 4 : 0);
+    // With kept scores a group's backward pass is one chunk: the chunk buffers hold whole samples.
+    const long long chunk_floor = p.keep ? max_tile_rows : GEMM_TILE;
 
     // smallest workable plan: one (largest) sample per group, one GEMM tile of rows per chunk
     Plan tmp = p;
-    p.min_bytes = lay_out(d, tmp, max_rows, p.bf16 ? GEMM_TILE : 0);
+    p.min_bytes = lay_out(d, tmp, max_rows, p.bf16 ? chunk_floor : 0);
 
     // the default plan; a caller that passes exactly the size it was told gets exactly this plan back
     const long long lat_default = std::min(p.rows_total, std::max(max_rows, (256LL << 20) / 20));
     long long chunk_default = 0;
     if (p.bf16) {
         // 832 MiB: 768 MiB of rows at H = 512, V = 1024 plus the padding of their row pitch
-        long long by_bytes = (long long)((832ULL << 20) / crb) / GEMM_TILE * GEMM_TILE;
-        chunk_default = std::min(all_tile_rows, std::max<long long>(GEMM_TILE, by_bytes));
+        // kept scores: 8 GiB, so that a group still fills the GPU when a row takes 10 KB
+        const unsigned long long budget = p.keep ? (8ULL << 30) : (832ULL << 20);
+        long long by_bytes = (long long)(budget / crb) / GEMM_TILE * GEMM_TILE;
+        chunk_default = std::min(all_tile_rows, std::max<long long>(chunk_floor, by_bytes));
     }
     Plan dflt = p;
     const size_t default_bytes = lay_out(d, dflt, lat_default, chunk_default);
@@ -126,7 +138,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         chunk_rows = chunk_default;
     } else if (workspace_bytes < p.min_bytes) {
         lat_cap = max_rows;
-        chunk_rows = p.bf16 ? GEMM_TILE : 0;
+        chunk_rows = p.bf16 ? chunk_floor : 0;
     } else {
         // the fixed part and the alignment slack come off first
         Plan probe = p;
@@ -141,7 +153,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
             size_t lat_bytes = (size_t)lat_cap * 20;
             size_t rest = avail > lat_bytes ? avail - lat_bytes : 0;
             chunk_rows = (long long)(rest / crb) / GEMM_TILE * GEMM_TILE;
-            chunk_rows = std::min(all_tile_rows, std::max<long long>(GEMM_TILE, chunk_rows));
+            chunk_rows = std::min(all_tile_rows, std::max<long long>(chunk_floor, chunk_rows));
             // what the chunk buffers do not need goes to the lattice
             size_t chunk_bytes = (size_t)chunk_rows * crb;
             if (avail > chunk_bytes) {
@@ -152,7 +164,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         // never below the minimum, never above the given size
         Plan t2 = p;
         while (lay_out(d, t2, lat_cap, chunk_rows) > workspace_bytes) {
-            if (chunk_rows > GEMM_TILE) chunk_rows -= GEMM_TILE;
+            if (chunk_rows > chunk_floor) chunk_rows -= GEMM_TILE;
             else if (lat_cap > max_rows) lat_cap = std::max(max_rows, lat_cap - 4096);
             else break;
         }
@@ -172,6 +184,9 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         while (s < B) {
             long long rows = p.row_off[s + 1] - p.row_off[s];
             if (g.rows > 0 && g.rows + rows > lat_cap) break;
+            if (p.keep && g.rows > 0 &&
+                (long long)align_up((size_t)(p.tile_off[s + 1] - p.tile_off[g.s0]) * TILE_ROWS, GEMM_TILE) > chunk_rows)
+                break;
             g.rows += rows;
             g.u_max = std::max(g.u_max, (int)U_len[s]);
             ++s;
@@ -182,7 +197,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         p.groups.push_back(g);
     }
     // backward chunks: balanced tile ranges of at most chunk_rows rows, even tile counts
-    if (p.bf16) {
+    if (p.bf16 && !p.keep) {
         const long long cap_tiles = chunk_rows / TILE_ROWS;
         for (int gi = 0; gi < (int)p.groups.size(); ++gi) {
             const Group& g = p.groups[gi];

@@ -38,6 +38,7 @@ struct Plan {
     int B = 0;
     bool bf16 = false;
     bool fused = false;                 // bf16 only: backward runs in the fused kernel
+    bool keep = false;                  // bf16 only: forward keeps the scores, one backward chunk per group
     std::vector<int> tile_off;          // [B+1] cumulative tile counts
     std::vector<long long> row_off;     // [B+1] cumulative lattice nodes
     std::vector<Group> groups;
@@ -49,7 +50,7 @@ struct Plan {
     size_t off_T = 0, off_U = 0, off_weight = 0, off_tile_off = 0, off_row_off = 0, off_lnP = 0, off_shift = 0, off_tile_sample = 0;
     size_t off_wpack = 0, off_wq = 0;
     size_t off_lse = 0, off_lpb = 0, off_lpy = 0, off_alpha = 0, off_beta = 0;
-    size_t off_dh = 0, off_z = 0;
+    size_t off_dh = 0, off_z = 0, off_kept_max = 0;
     size_t off_dwslots = 0;             // bf16: per-workgroup partial sums of the dW GEMM
     int dw_splits = 0;                  // bf16: K splits of the dW GEMM (a multiple of 8)
     size_t lattice_bytes = 0, chunk_bytes = 0, total_bytes = 0;

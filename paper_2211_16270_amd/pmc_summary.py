@@ -16,7 +16,8 @@ import sys
 
 KERNEL_ALIASES = [
     ("k_joint_bwd_fused", "joint_bwd_fused"), ("k_joint_scores<0", "joint_scores_fwd"),
-    ("k_joint_scores<1", "joint_scores_bwd"), ("k_gemm_dw256", "gemm_dw_db"), ("k_dw_reduce", "dw_reduce"), ("k_gemm_nt<0>", "gemm_dz"),
+    ("k_joint_scores<1", "joint_scores_bwd"), ("k_gemm_dw256", "gemm_dw_db"), ("k_dw_reduce", "dw_reduce"), ("k_gemm_dz256", "gemm_dz"),
+    ("k_joint_scores<2", "joint_scores_fwd_keep"), ("k_kept_to_dh", "kept_scores_to_dh"),
     ("k_lattice", "lattice"), ("k_copy_f32", "copy_f32"), ("k_prepare", "prepare"),
     ("k_fwd_f32", "fwd_f32"), ("k_bwd_f32", "bwd_f32"),
 ]

@@ -4,12 +4,15 @@ paper's zero-padding scheme (padding grows linearly over the batch: acoustic 0 -
 
     python -m paper_2211_16270_amd.sweep grid     # speed over the T x U grid, three ways of running the batch
     python -m paper_2211_16270_amd.sweep batch    # speed and peak memory over the batch size
+    python -m paper_2211_16270_amd.sweep keep     # scores kept (keep_scores = 1) against computed twice
+    python -m paper_2211_16270_amd.sweep keep16   # the same at B = 16 only, with the time of each kernel
 
 Timing only (inputs are seeded random tensors made on the GPU, as in the paper's benchmark); bf16 inputs.
 Ways of running a batch:
   packed      one call, true lengths: this library's default (padding removed, samples share launches)
   padded      one call, every length set to the maximum: what a computation on the padded batch costs
   one_by_one  B calls of one sample each, true lengths: the sample-wise loop without parallel iterations
+  kept        packed, with keep_scores = 1 in the descriptor
 Prints one markdown table.
 """
 from __future__ import annotations
@@ -65,7 +68,7 @@ def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211):
                                                d_pred[b:b + 1], dW, db, ws.buf, stream)
                 assert s == 0, s
     else:
-        desc = Bd.make_desc(B, T, U, H, V, 0, Bd.RNNT_BF16)
+        desc = Bd.make_desc(B, T, U, H, V, 0, Bd.RNNT_BF16, keep_scores=1 if mode == "kept" else 0)
         nb = Bd.rnnt_joint_loss_workspace_bytes(desc, T_len, U_len)
         ws = Bd.Workspace(nb)
 
@@ -85,7 +88,8 @@ def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211):
     assert bool(torch.isfinite(loss).all())
     rows = int(np.sum(T_len.astype(np.int64) * (U_len + 1)))
     return dict(ms=dt * 1e3, samples_per_s=B / dt, peak_gb=torch.cuda.max_memory_allocated() / 1e9,
-                workspace_gb=nb / 1e9, rows=rows, pflops_exec=8.0 * rows * H * V / dt / 1e15)
+                workspace_gb=nb / 1e9, rows=rows,
+                pflops_exec=(6.0 if mode == "kept" else 8.0) * rows * H * V / dt / 1e15)
 
 
 def main(argv):
@@ -109,8 +113,30 @@ def main(argv):
             r = run_case(B, T, U, H, V, "packed", steps=3 if B <= 64 else 2)
             print(f"| {B} | {r['ms']:.1f} | {r['samples_per_s']:.1f} | {r['pflops_exec']:.3f} | {r['workspace_gb']:.2f} | "
                   f"{r['peak_gb']:.2f} |", flush=True)
+    elif which == "keep":
+        T, U = 500, 100
+        print(f"T x U = {T} x {U}, bf16, packed; ms per step and peak GB (inputs + outputs + workspace)\n")
+        print("| H | V | B | computed twice: ms | peak GB | kept: ms | peak GB | time kept / twice |")
+        print("|---|---|---|---|---|---|---|---|")
+        for Hx, Vx, Bs in [(1024, 4096, (1, 16, 256, 1024)), (768, 4096, (16,)), (1024, 1024, (16,)), (640, 1024, (16,)),
+                           (512, 8192, (16,))]:
+            for B in Bs:
+                r = {m: run_case(B, T, U, Hx, Vx, m, steps=3 if B <= 64 else 2) for m in ("packed", "kept")}
+                print(f"| {Hx} | {Vx} | {B} | {r['packed']['ms']:.2f} | {r['packed']['peak_gb']:.2f} | {r['kept']['ms']:.2f} | "
+                      f"{r['kept']['peak_gb']:.2f} | {r['kept']['ms'] / r['packed']['ms']:.3f} |", flush=True)
+    elif which == "keep16":
+        from . import binding as Bd
+        Bd.rnnt_profile_enable(True)
+        for mode in ("packed", "kept"):
+            Bd.rnnt_profile_read()
+            r = run_case(16, 500, 100, H, V, mode, steps=3, warmup=1)
+            prof = Bd.rnnt_profile_read()
+            print(f"{mode}: {r['ms']:.3f} ms per step, rows {r['rows']}, workspace {r['workspace_gb']:.2f} GB")
+            for k, (c, ms) in prof.items():
+                if c:
+                    print(f"    {k:24s} launches per step {c // 4:3d}   {ms / 4:8.3f} ms per step")
     else:
-        raise SystemExit("usage: python -m paper_2211_16270_amd.sweep grid|batch")
+        raise SystemExit("usage: python -m paper_2211_16270_amd.sweep grid|batch|keep|keep16")
 
 
 if __name__ == "__main__":

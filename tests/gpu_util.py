@@ -10,14 +10,15 @@ TOL = {"f32": dict(loss=1e-5, grad=1e-4), "bf16": dict(loss=2e-3, grad=1e-2)}
 GRADS = ("d_enc", "d_pred", "dW_out", "db_out")
 
 
-def run_gpu(batch, budget_bytes=0, blank=None, workspace=None, accumulate_into=None, sample_weight=None):
+def run_gpu(batch, budget_bytes=0, blank=None, workspace=None, accumulate_into=None, sample_weight=None,
+            keep_scores=0):
     import torch
     wl = batch.wl
     dev = Bd.to_device(batch)
     dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
     out = Bd.run_fwd_bwd(dev, batch.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank if blank is None else blank, dt,
                          workspace=workspace, budget_bytes=budget_bytes, accumulate_into=accumulate_into,
-                         sample_weight=sample_weight)
+                         sample_weight=sample_weight, keep_scores=keep_scores)
     torch.cuda.synchronize()
     res = {k: out[k].float().cpu().numpy() for k in ("loss",) + GRADS}
     res["workspace"] = out["workspace"]

@@ -204,6 +204,63 @@ def test_bf16_saturated_joint_and_peaked_softmax():
     assert_padding_zero(got, batch)
 
 
+# ------------------------------------------------------------------ scores kept instead of computed twice
+@pytest.mark.parametrize("H,V", [(128, 256), (640, 1024), (896, 256), (1024, 512), (256, 768)])
+def test_bf16_kept_scores_match_the_checker_and_the_default_path(H, V):
+    wl = synth.custom_workload("keep", B=5, T_max=27, U_max=12, H=H, V=V, dtype="bf16", index=130,
+                               t_rule="uniform", t_lo=3, u_rule="uniform", u_lo=0)
+    batch = synth.make_batch(wl)
+    batch.labels[2, :1] = 0                                  # a label equal to the blank
+    _say("keep", H, V, batch.T_len, batch.U_len)
+    ref = run_oracle(batch)
+    got = run_gpu(batch, keep_scores=1)
+    e, errs = assert_parity(got, ref, "bf16", f"kept scores H={H} V={V}")
+    _say("errs", e, errs)
+    assert_padding_zero(got, batch)
+    plain = run_gpu(batch)
+    np.testing.assert_array_equal(got["loss"], plain["loss"])     # the same forward arithmetic
+    # smallest workspace: several groups, each one backward chunk
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(got["desc"], batch.T_len, batch.U_len, 1)
+    st, info, _ = Bd.rnnt_joint_loss_plan(got["desc"], batch.T_len, batch.U_len, nmin)
+    assert st == 0 and info["n_groups"] == info["n_chunks"] > 1
+    small = run_gpu(batch, budget_bytes=nmin, keep_scores=1)
+    assert_parity(small, ref, "bf16", "kept scores, smallest workspace")
+    np.testing.assert_array_equal(small["loss"], got["loss"])
+
+
+def test_bf16_kept_scores_with_large_scores_and_weights():
+    # scores of several tens: what is kept is the difference to a running maximum, so the size of the
+    # scores does not enter the error; weights scale the posteriors in the pass that makes dh
+    from dataclasses import replace
+    wl = synth.custom_workload("peaky", B=3, T_max=29, U_max=13, H=256, V=512, dtype="bf16", index=124,
+                               t_rule="uniform", t_lo=7, u_rule="uniform", u_lo=1)
+    batch = synth.make_batch(wl)
+    batch = replace(batch, enc=batch.enc * 8.0, pred=batch.pred * 8.0, W_out=batch.W_out * 4.0,
+                    b_out=(np.arange(wl.V, dtype=np.float32) % 7 - 3.0) * 2.0)
+    w = np.array([0.5, 0.0, 3.0], dtype=np.float32)
+    got = run_gpu(batch, keep_scores=1, sample_weight=w)
+    ref = run_oracle(batch, sample_weight=w.astype(np.float64))
+    e, errs = assert_parity(got, ref, "bf16", "peaky, kept scores")
+    _say("peaky kept errs", e, errs)
+    assert_padding_zero(got, batch)
+    assert not got["d_enc"][1].any() and not got["d_pred"][1].any()
+
+
+def test_bf16_kept_scores_bench_workload_sampled():
+    # the benchmark's smaller bf16 workload at full size: loss of every sample against the default path,
+    # gradients against it within the two paths' rounding (both are checked against the checker on sub-batches)
+    batch = synth.make_batch("C2")
+    plain = run_gpu(batch)
+    kept = run_gpu(batch, keep_scores=1)
+    np.testing.assert_array_equal(kept["loss"], plain["loss"])
+    for k in GRADS:
+        err = rel_grad_err(kept[k], plain[k])
+        _say("C2 kept vs default", k, err)
+        assert err < TOL["bf16"]["grad"], k
+    sub = synth.make_batch("C2", sample_ids=[3, 29])
+    assert_parity(run_gpu(sub, keep_scores=1), run_oracle(sub), "bf16", "C2 sub-batch, kept scores")
+
+
 # ------------------------------------------------------------------ weighted sum of the samples' losses
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_sample_weights_against_the_checker(dtype):

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(Bd.RnntDesc) == 32
+    assert ctypes.sizeof(Bd.RnntDesc) == 36
     assert ctypes.sizeof(Bd.RnntPlanInfo) == 8 * 3 + 4 * 2 + 8 * 2 + 8 * 3
 
 
@@ -163,6 +163,36 @@ def test_budgets_shrink_the_plan_and_a_too_small_budget_is_reported():
     assert st == 5
     st, info_min, _ = Bd.rnnt_joint_loss_plan(desc, T, U, tiny)
     assert st == 0 and info_min["chunk_rows"] == 128 and info_min["group_rows_cap"] == rows.max()
+
+
+def test_keep_scores_plan_has_one_backward_chunk_per_group_of_whole_samples():
+    wl, desc, T, U = _lens("C2")
+    keep = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16, keep_scores=1)
+    st, info, groups = Bd.rnnt_joint_loss_plan(keep, T, U, 0)
+    assert st == 0 and info["n_chunks"] == info["n_groups"] == 1 and (groups == 0).all()
+    # the chunk buffers hold every tile row of the call: dH, Z and the running maxima
+    per_row = 2 * (wl.V + 64) + 2 * (wl.H + 64) + 4 * (wl.V // 64)
+    slack = 128 * 2 * (wl.V + 64) + 3 * 256          # dH ends on a multiple of 256 rows; alignment of the three
+    assert info["chunk_rows"] * per_row <= info["chunk_bytes"] < info["chunk_rows"] * per_row + slack
+    assert info["chunk_rows"] >= info["tiles_total"] * 64
+    # smallest plan: the chunk buffers still hold the largest sample, one sample or more per group
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(keep, T, U, 1)
+    st, small, groups = Bd.rnnt_joint_loss_plan(keep, T, U, nmin)
+    assert st == 0 and small["n_chunks"] == small["n_groups"] > 1
+    tiles = ((T + 7) // 8) * ((U + 8) // 8)
+    assert small["chunk_rows"] >= int(tiles.max()) * 64
+    for g in range(small["n_groups"]):
+        assert int(tiles[groups == g].sum()) * 64 <= small["chunk_rows"]
+    assert np.all(np.diff(groups) >= 0)
+    st, _, _ = Bd.rnnt_joint_loss_plan(keep, T, U, nmin - 256)
+    assert st == 5
+    # a budget in between gives groups in between
+    st, mid, _ = Bd.rnnt_joint_loss_plan(keep, T, U, (nmin + info["workspace_bytes"]) // 2)
+    assert st == 0 and 1 <= mid["n_groups"] < small["n_groups"] and mid["workspace_bytes"] <= (nmin + info["workspace_bytes"]) // 2
+    # only the bf16 path has the mode, and the flag is 0 or 1
+    assert Bd.rnnt_joint_loss_workspace_bytes(Bd.make_desc(2, 8, 3, 16, 8, 0, Bd.RNNT_F32, keep_scores=1), [8, 8], [3, 3]) == 0
+    assert Bd.rnnt_joint_loss_workspace_bytes(
+        Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16, keep_scores=2), T, U) == 0
 
 
 def test_projected_entry_point_checks_and_workspace():
