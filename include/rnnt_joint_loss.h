@@ -88,7 +88,10 @@ const char* rnnt_status_string(rnnt_status s);
  *   budget_bytes = 0: the library's default trade-off (never more than 1088 MiB plus, for bf16,
  *   the two packed copies of W_out and the partial sums of the dW GEMM, which depend on H and V
  *   only (partial sums: about 64 MiB while H*V <= 2^21, 32 bytes per element of W_out beyond),
- *   plus what the largest single sample needs).  Otherwise the largest plan not exceeding budget_bytes; if
+ *   plus what the largest single sample needs; with desc->keep_scores the chunk buffers of that default
+ *   hold up to 8 GiB, never more than the call's tile rows need, and the smallest plan holds the largest
+ *   sample's rows: 2 (V + 64) + 2 (H + 64) + V / 16 bytes per row of its 8x8 lattice tiles).
+ *   Otherwise the largest plan not exceeding budget_bytes; if
  *   even the smallest workable plan (one sample per group, one tile row per chunk) exceeds it,
  *   that smallest size is returned, so a result > budget_bytes means "budget too small".
  * Returns 0 on invalid arguments.  The result does not depend on B beyond the largest sample

@@ -21,7 +21,7 @@ from . import binding as Bd
 
 class _RnntJointLoss(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, enc, pred, W_out, b_out, labels, T_len, U_len, blank, sample_weight, workspace):
+    def forward(ctx, enc, pred, W_out, b_out, labels, T_len, U_len, blank, sample_weight, workspace, keep_scores):
         if not (enc.is_cuda and enc.is_contiguous() and pred.is_contiguous() and W_out.is_contiguous()):
             raise ValueError("enc, pred, W_out must be contiguous CUDA tensors")
         B, T_max, H = enc.shape
@@ -34,8 +34,8 @@ class _RnntJointLoss(torch.autograd.Function):
             np.ascontiguousarray(sample_weight, dtype=np.float32)
         dev = dict(enc=enc, pred=pred, W_out=W_out, b_out=b_out, labels=labels, T_len=T_host, U_len=U_host)
         shape = (B, T_max, U_max, H, V, int(blank), dtype)
-        out = Bd.run_fwd_bwd(dev, *shape, workspace=workspace, sample_weight=w_host)
-        ctx.dev, ctx.shape, ctx.w_host, ctx.out = dev, shape, w_host, out
+        out = Bd.run_fwd_bwd(dev, *shape, workspace=workspace, sample_weight=w_host, keep_scores=int(keep_scores))
+        ctx.dev, ctx.shape, ctx.w_host, ctx.out, ctx.keep = dev, shape, w_host, out, int(keep_scores)
         ctx.mark_non_differentiable(labels)
         return out["loss"]
 
@@ -44,17 +44,20 @@ class _RnntJointLoss(torch.autograd.Function):
         g = grad_loss.detach().float().cpu().numpy()          # B numbers; also orders this after the forward
         out = ctx.out
         if not np.array_equal(g, ctx.w_host):
-            out = Bd.run_fwd_bwd(ctx.dev, *ctx.shape, workspace=ctx.out["workspace"], sample_weight=g)
+            out = Bd.run_fwd_bwd(ctx.dev, *ctx.shape, workspace=ctx.out["workspace"], sample_weight=g,
+                                 keep_scores=ctx.keep)
         enc, W_out, b_out = ctx.dev["enc"], ctx.dev["W_out"], ctx.dev["b_out"]
         return (out["d_enc"].to(enc.dtype), out["d_pred"].to(enc.dtype), out["dW_out"].to(W_out.dtype),
-                out["db_out"].to(b_out.dtype), None, None, None, None, None, None)
+                out["db_out"].to(b_out.dtype), None, None, None, None, None, None, None)
 
 
 def rnnt_joint_loss(enc, pred, W_out, b_out, labels, T_len, U_len, blank: int = 0, sample_weight=None,
-                    workspace=None):
+                    workspace=None, keep_scores: bool = False):
     """Per-sample transducer loss [B] with gradients for enc, pred, W_out, b_out.
 
     enc [B,T_max,H], pred [B,U_max+1,H], W_out [H,V] (float32 or bfloat16, CUDA, contiguous), b_out [V] float32,
     labels [B,U_max] int32 on the device, T_len / U_len host arrays of B int32.  sample_weight: host array of B
-    non-negative floats, the weights the loss vector is going to be summed with (None: ones)."""
-    return _RnntJointLoss.apply(enc, pred, W_out, b_out, labels, T_len, U_len, blank, sample_weight, workspace)
+    non-negative floats, the weights the loss vector is going to be summed with (None: ones).  keep_scores
+    (bfloat16 only): the descriptor field of that name, scores kept in a larger workspace instead of computed twice."""
+    return _RnntJointLoss.apply(enc, pred, W_out, b_out, labels, T_len, U_len, blank, sample_weight, workspace,
+                                keep_scores)

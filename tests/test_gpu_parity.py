@@ -315,6 +315,14 @@ def test_autograd_front_end_returns_the_library_gradients():
     for a, b2, k in zip(g_w, g_w2, GRADS):
         assert rel_grad_err(a, ref[k]) <= 2e-2, k           # bf16 gradients (rounded once more to the leaf dtype)
         assert rel_grad_err(b2, a.astype(np.float64)) < 1e-3, k
+    # the same through the path that keeps the scores
+    for x in leaves:
+        x.grad = None
+    lk = rnnt_joint_loss(*leaves, dev["labels"], batch.T_len, batch.U_len, 0, keep_scores=True)
+    (lk * torch.tensor(w, device=lk.device)).sum().backward()
+    torch.cuda.synchronize()
+    for x, k in zip(leaves, GRADS):
+        assert rel_grad_err(x.grad.float().cpu().numpy(), ref[k]) <= 2e-2, k
 
 
 # ------------------------------------------------------------------ the benchmarked workload
