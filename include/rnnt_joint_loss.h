@@ -243,6 +243,20 @@ rnnt_status rnnt_debug_read_lattice(const rnnt_desc* desc, const int32_t* T_len_
 rnnt_status rnnt_debug_copy_f32(const float* src, float* dst, size_t n, void* hip_stream);
 
 /*
+ * Measurement support (not a paper operation): a loop of nothing but bf16 MFMAs (32x32x16, fp32
+ * accumulation) on operand values the caller chooses, to see what the matrix units sustain on such
+ * values next to the published peak that the MFMA-bound kernels are priced against.
+ *   frags  dev  32 fragments of 64 lanes x 8 bf16 (32 KiB): wave w of a workgroup uses fragments
+ *               8w .. 8w+3 as A operands and 8w+4 .. 8w+7 as B operands
+ *   out    dev  workgroups * 256 floats, overwritten (a checksum that keeps the loop alive)
+ *   workgroups 1..65536 of 256 threads; iters 1..1000000 iterations of 16 MFMAs per wave:
+ *               2 * 32*32*16 * 16 * iters * 4 * workgroups flop per launch
+ * Enqueues on hip_stream, does not wait.  RNNT_ERR_NULL / RNNT_ERR_SHAPE on bad arguments.
+ */
+rnnt_status rnnt_debug_mfma_loop(const void* frags, float* out, int32_t workgroups, int32_t iters,
+                                 void* hip_stream);
+
+/*
  * Per-kernel timing for the benchmark (not a paper operation; measurement support for the
  * throughput figures reported against Table 1's cost terms).  While enabled, every launch made
  * by the two entry points above is bracketed by HIP events recorded on the caller's stream

@@ -21,7 +21,7 @@ STATUS_NAMES = ["RNNT_OK", "RNNT_ERR_NULL", "RNNT_ERR_SHAPE", "RNNT_ERR_LENGTH",
 EXPORTS = ["rnnt_status_string", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_loss_plan",
            "rnnt_parallel_iterations", "rnnt_validate_labels_host", "rnnt_joint_loss_fwd_bwd",
            "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice", "rnnt_profile_enable",
-           "rnnt_debug_copy_f32", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
+           "rnnt_debug_copy_f32", "rnnt_debug_mfma_loop", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
            "rnnt_joint_proj_workspace_bytes", "rnnt_joint_proj_loss_fwd_bwd", "rnnt_joint_loss_fwd_bwd_weighted"]
 
 
@@ -88,6 +88,8 @@ def lib() -> ctypes.CDLL:
     L.rnnt_debug_read_lattice.argtypes = [dp, i32p, i32p, vp, ctypes.c_size_t, ctypes.c_int32, vp, vp]
     L.rnnt_debug_copy_f32.restype = ctypes.c_int
     L.rnnt_debug_copy_f32.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.rnnt_debug_mfma_loop.restype = ctypes.c_int
+    L.rnnt_debug_mfma_loop.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp]
     L.rnnt_profile_enable.restype = ctypes.c_int
     L.rnnt_profile_enable.argtypes = [ctypes.c_int32]
     L.rnnt_profile_kernel_count.restype = ctypes.c_int32
@@ -223,6 +225,11 @@ def rnnt_debug_copy_f32(src, dst, stream=None) -> int:
     return int(lib().rnnt_debug_copy_f32(_ptr(src), _ptr(dst), int(src.numel()), _stream_handle(stream)))
 
 
+def rnnt_debug_mfma_loop(frags, out, workgroups: int, iters: int, stream=None) -> int:
+    """Runs the library's MFMA-only loop on the 32 KiB of bf16 operand fragments in `frags`."""
+    return int(lib().rnnt_debug_mfma_loop(_ptr(frags), _ptr(out), int(workgroups), int(iters), _stream_handle(stream)))
+
+
 def rnnt_profile_enable(enable: bool) -> int:
     return int(lib().rnnt_profile_enable(1 if enable else 0))
 
@@ -321,13 +328,13 @@ def proj_to_device(proj, dtype: str, device="cuda:0"):
 
 
 def run_proj_fwd_bwd(dev: dict, devp: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optional[Workspace] = None,
-                     budget_bytes: int = 0, accumulate_into=None, stream=None):
+                     budget_bytes: int = 0, accumulate_into=None, stream=None, keep_scores=0):
     """Allocates outputs (and a workspace unless given), calls rnnt_joint_proj_loss_fwd_bwd, raises on a
     non-zero status.  `dev` as from to_device (enc/pred unused), `devp` as from proj_to_device."""
     import torch
     device = devp["hA"].device
     H_A, H_L = int(devp["hA"].shape[-1]), int(devp["hL"].shape[-1])
-    desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1)
+    desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1, keep_scores)
     if workspace is None:
         n = rnnt_joint_proj_workspace_bytes(desc, H_A, H_L, dev["T_len"], dev["U_len"], budget_bytes)
         if n == 0:

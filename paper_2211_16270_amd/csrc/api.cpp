@@ -485,6 +485,14 @@ extern "C" rnnt_status rnnt_debug_copy_f32(const float* src, float* dst, size_t 
     return RNNT_OK;
 }
 
+extern "C" rnnt_status rnnt_debug_mfma_loop(const void* frags, float* out, int32_t workgroups, int32_t iters,
+                                            void* hip_stream) {
+    if (!frags || !out) return RNNT_ERR_NULL;
+    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > 1000000) return RNNT_ERR_SHAPE;
+    RNNT_HIP(launch_mfma_loop(frags, out, workgroups, iters, (hipStream_t)hip_stream));
+    return RNNT_OK;
+}
+
 extern "C" rnnt_status rnnt_profile_enable(int32_t enable) {
     g_prof.clear();
     g_prof.enabled = (enable != 0);

@@ -64,6 +64,10 @@ hipError_t launch_prepare(const PrepArgs& a, hipStream_t stream);
 // plain copy of n floats (n a multiple of 4): the known-size kernel the HBM counters are calibrated with
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t stream);
 
+// loop of workgroups x 4 waves x iters x 16 MFMAs (32x32x16 bf16) on the 32 x 1 KiB fragments at `frags`;
+// writes workgroups x 256 floats to `out` (measurement support)
+hipError_t launch_mfma_loop(const void* frags, float* out, int workgroups, int iters, hipStream_t stream);
+
 // ---- fp32 path (plain FMA kernels, any H, V) ------------------------------------------------
 hipError_t launch_fwd_f32(const Problem& pr, const SampleTable& st, const LatticeState& ls,
                           int s0, int s1, long long rows, hipStream_t stream);

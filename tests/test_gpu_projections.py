@@ -17,14 +17,14 @@ def _say(*a):
     print(*a, flush=True)
 
 
-def run_gpu_proj(batch, proj, budget_bytes=0, accumulate_into=None):
+def run_gpu_proj(batch, proj, budget_bytes=0, accumulate_into=None, keep_scores=0):
     import torch
     wl = batch.wl
     dev = Bd.to_device(batch)
     devp = Bd.proj_to_device(proj, wl.dtype)
     dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
     out = Bd.run_proj_fwd_bwd(dev, devp, batch.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, dt,
-                              budget_bytes=budget_bytes, accumulate_into=accumulate_into)
+                              budget_bytes=budget_bytes, accumulate_into=accumulate_into, keep_scores=keep_scores)
     torch.cuda.synchronize()
     return {k: out[k].float().cpu().numpy() for k in ("loss",) + PGRADS}
 
@@ -80,7 +80,9 @@ def test_bf16_projected_path_small(H_A, H_L):
                                t_rule="uniform", t_lo=5, u_rule="uniform", u_lo=0)
     batch = synth.make_batch(wl)
     proj = synth.make_proj_inputs(batch, H_A=H_A, H_L=H_L)
-    check(run_gpu_proj(batch, proj), run_oracle_proj(batch, proj), "bf16", batch, f"bf16 small {H_A},{H_L}")
+    ref = run_oracle_proj(batch, proj)
+    check(run_gpu_proj(batch, proj), ref, "bf16", batch, f"bf16 small {H_A},{H_L}")
+    check(run_gpu_proj(batch, proj, keep_scores=1), ref, "bf16", batch, f"bf16 small {H_A},{H_L}, kept scores")
 
 
 def test_bf16_projected_path_bench_workload_subbatch_and_accumulate():
