@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--budget-mib", type=int, default=0, help="workspace budget (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="use only the first N samples (profiling aid)")
+    ap.add_argument("--bf16-grads", action="store_true",
+                    help="input_grads_bf16 = 1 in the descriptor: d_enc and d_pred are bfloat16 arrays")
     ap.add_argument("--keep-scores", action="store_true",
                     help="keep_scores = 1 in the descriptor: the backward pass reads the scores the forward pass kept")
     ap.add_argument("--projections", type=int, default=0, metavar="D",
@@ -78,15 +80,17 @@ def main():
     gen_s = time.time() - t0
     dev = Bd.to_device(batch)
     dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
-    desc = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, dt, keep_scores=int(args.keep_scores))
+    desc = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, dt, keep_scores=int(args.keep_scores),
+                        input_grads_bf16=int(args.bf16_grads))
     nbytes = Bd.rnnt_joint_loss_workspace_bytes(desc, dev["T_len"], dev["U_len"], args.budget_mib << 20)
     st, info, _ = Bd.rnnt_joint_loss_plan(desc, dev["T_len"], dev["U_len"], nbytes)
     assert st == 0, st
     torch.cuda.reset_peak_memory_stats()
     ws = Bd.Workspace(nbytes)
     loss = torch.empty(wl.B, dtype=torch.float32, device="cuda")
-    d_enc = torch.empty(wl.B, wl.T_max, wl.H, dtype=torch.float32, device="cuda")
-    d_pred = torch.empty(wl.B, wl.U_max + 1, wl.H, dtype=torch.float32, device="cuda")
+    gdt = torch.bfloat16 if args.bf16_grads else torch.float32
+    d_enc = torch.empty(wl.B, wl.T_max, wl.H, dtype=gdt, device="cuda")
+    d_pred = torch.empty(wl.B, wl.U_max + 1, wl.H, dtype=gdt, device="cuda")
     dW = torch.empty(wl.H, wl.V, dtype=torch.float32, device="cuda")
     db = torch.empty(wl.V, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
@@ -188,7 +192,7 @@ def main():
                                f"{wl.dtype}, ragged lengths, {R} lattice nodes ({100.0 * R / info['rows_padded']:.1f}% of padded)",
                    "entry_point": "rnnt_joint_proj_loss_fwd_bwd, H_A = H_L = %d" % args.projections
                    if args.projections else "rnnt_joint_loss_fwd_bwd",
-                   "keep_scores": int(args.keep_scores),
+                   "keep_scores": int(args.keep_scores), "input_grads_bf16": int(args.bf16_grads),
                    "groups": info["n_groups"], "chunks": info["n_chunks"],
                    "workspace_bytes": int(nbytes)},
         "mfma_util_alg": util_alg, "mfma_util_exec": util_exec,

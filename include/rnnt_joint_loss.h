@@ -65,6 +65,10 @@ typedef struct {
                                   three GEMMs per row instead of four, for 2 (H + V) more workspace bytes per
                                   lattice node of a group (the paper's outlook on other memory trade-offs,
                                   Section 6)                                                           */
+    int32_t input_grads_bf16;  /* RNNT_BF16 only.  0: d_enc, d_pred are float.  1: they are bfloat16 arrays of
+                                  the same shape (half the bytes of the two largest outputs): the sums are
+                                  formed in float for one group of samples at a time in the workspace and
+                                  rounded once (nearest even) on their way out (mixed precision, Section 6) */
 } rnnt_desc;
 
 /* What the host scheduler decided for a call (Section 4.1.2 analogue; see rnnt_joint_loss_plan). */
@@ -136,8 +140,9 @@ rnnt_status rnnt_validate_labels_host(const rnnt_desc* desc, const int32_t* labe
  * T_len    HOST [B]                1..T_max
  * U_len    HOST [B]                0..U_max
  * loss     dev  [B]                float, out
- * d_enc    dev  [B, T_max, H]      float, out, fully overwritten (zeros in padded rows)
- * d_pred   dev  [B, U_max+1, H]    float, out, fully overwritten (zeros in padded rows)
+ * d_enc    dev  [B, T_max, H]      float (bfloat16 if desc->input_grads_bf16), out, fully overwritten
+ *                                  (zeros in padded rows)
+ * d_pred   dev  [B, U_max+1, H]    the same type, out, fully overwritten (zeros in padded rows)
  * dW_out   dev  [H, V]             float, out (overwritten or accumulated, see desc)
  * db_out   dev  [V]                float, out (same)
  * workspace dev, 256-byte aligned, workspace_bytes >= rnnt_joint_loss_workspace_bytes(...);
@@ -152,7 +157,7 @@ rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc,
                                     const void* enc, const void* pred, const void* W_out,
                                     const float* b_out, const int32_t* labels,
                                     const int32_t* T_len_host, const int32_t* U_len_host,
-                                    float* loss, float* d_enc, float* d_pred,
+                                    float* loss, void* d_enc, void* d_pred,
                                     float* dW_out, float* db_out,
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -170,7 +175,7 @@ rnnt_status rnnt_joint_loss_fwd_bwd_weighted(const rnnt_desc* desc,
                                              const float* b_out, const int32_t* labels,
                                              const int32_t* T_len_host, const int32_t* U_len_host,
                                              const float* sample_weight_host,
-                                             float* loss, float* d_enc, float* d_pred,
+                                             float* loss, void* d_enc, void* d_pred,
                                              float* dW_out, float* db_out,
                                              void* workspace, size_t workspace_bytes, void* hip_stream);
 

@@ -34,8 +34,10 @@ class _RnntJointLoss(torch.autograd.Function):
             np.ascontiguousarray(sample_weight, dtype=np.float32)
         dev = dict(enc=enc, pred=pred, W_out=W_out, b_out=b_out, labels=labels, T_len=T_host, U_len=U_host)
         shape = (B, T_max, U_max, H, V, int(blank), dtype)
-        out = Bd.run_fwd_bwd(dev, *shape, workspace=workspace, sample_weight=w_host, keep_scores=int(keep_scores))
-        ctx.dev, ctx.shape, ctx.w_host, ctx.out, ctx.keep = dev, shape, w_host, out, int(keep_scores)
+        # bf16 leaves get bf16 gradients: the library rounds them itself instead of a conversion pass here
+        opts = dict(keep_scores=int(keep_scores), input_grads_bf16=int(dtype == Bd.RNNT_BF16))
+        out = Bd.run_fwd_bwd(dev, *shape, workspace=workspace, sample_weight=w_host, **opts)
+        ctx.dev, ctx.shape, ctx.w_host, ctx.out, ctx.opts = dev, shape, w_host, out, opts
         ctx.mark_non_differentiable(labels)
         return out["loss"]
 
@@ -44,8 +46,7 @@ class _RnntJointLoss(torch.autograd.Function):
         g = grad_loss.detach().float().cpu().numpy()          # B numbers; also orders this after the forward
         out = ctx.out
         if not np.array_equal(g, ctx.w_host):
-            out = Bd.run_fwd_bwd(ctx.dev, *ctx.shape, workspace=ctx.out["workspace"], sample_weight=g,
-                                 keep_scores=ctx.keep)
+            out = Bd.run_fwd_bwd(ctx.dev, *ctx.shape, workspace=ctx.out["workspace"], sample_weight=g, **ctx.opts)
         enc, W_out, b_out = ctx.dev["enc"], ctx.dev["W_out"], ctx.dev["b_out"]
         return (out["d_enc"].to(enc.dtype), out["d_pred"].to(enc.dtype), out["dW_out"].to(W_out.dtype),
                 out["db_out"].to(b_out.dtype), None, None, None, None, None, None, None)

@@ -29,7 +29,7 @@ class RnntDesc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32), ("U_max", ctypes.c_int32),
                 ("H", ctypes.c_int32), ("V", ctypes.c_int32), ("blank", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("accumulate_params", ctypes.c_int32),
-                ("keep_scores", ctypes.c_int32)]
+                ("keep_scores", ctypes.c_int32), ("input_grads_bf16", ctypes.c_int32)]
 
 
 class RnntPlanInfo(ctypes.Structure):
@@ -102,9 +102,10 @@ def lib() -> ctypes.CDLL:
     return L
 
 
-def make_desc(B, T_max, U_max, H, V, blank=0, dtype=RNNT_BF16, accumulate_params=0, keep_scores=0) -> RnntDesc:
+def make_desc(B, T_max, U_max, H, V, blank=0, dtype=RNNT_BF16, accumulate_params=0, keep_scores=0,
+              input_grads_bf16=0) -> RnntDesc:
     return RnntDesc(int(B), int(T_max), int(U_max), int(H), int(V), int(blank), int(dtype),
-                    int(accumulate_params), int(keep_scores))
+                    int(accumulate_params), int(keep_scores), int(input_grads_bf16))
 
 
 def _i32(a) -> np.ndarray:
@@ -282,13 +283,16 @@ def to_device(batch, device="cuda:0"):
 
 
 def run_fwd_bwd(dev: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optional[Workspace] = None,
-                budget_bytes: int = 0, accumulate_into=None, stream=None, sample_weight=None, keep_scores=0):
+                budget_bytes: int = 0, accumulate_into=None, stream=None, sample_weight=None, keep_scores=0,
+                input_grads_bf16=0):
     """Allocates outputs (and a workspace unless given), calls rnnt_joint_loss_fwd_bwd (its weighted form if
-    sample_weight is given), raises on a non-zero status.  keep_scores = 1 sets that field of the descriptor.  Returns dict(loss, d_enc, d_pred, dW_out, db_out,
+    sample_weight is given), raises on a non-zero status.  keep_scores, input_grads_bf16: the descriptor's fields of
+    those names (with the latter d_enc and d_pred are bfloat16 tensors).  Returns dict(loss, d_enc, d_pred, dW_out, db_out,
     workspace)."""
     import torch
     device = dev["enc"].device
-    desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1, keep_scores)
+    desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1, keep_scores,
+                     input_grads_bf16)
     if workspace is None:
         n = rnnt_joint_loss_workspace_bytes(desc, dev["T_len"], dev["U_len"], budget_bytes)
         if n == 0:
@@ -296,8 +300,9 @@ def run_fwd_bwd(dev: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optio
                                                        0, ctypes.byref(RnntPlanInfo()), None), "plan")
         workspace = Workspace(n, device)
     loss = torch.empty(B, dtype=torch.float32, device=device)
-    d_enc = torch.empty(B, T_max, H, dtype=torch.float32, device=device)
-    d_pred = torch.empty(B, U_max + 1, H, dtype=torch.float32, device=device)
+    gdt = torch.bfloat16 if input_grads_bf16 else torch.float32
+    d_enc = torch.empty(B, T_max, H, dtype=gdt, device=device)
+    d_pred = torch.empty(B, U_max + 1, H, dtype=gdt, device=device)
     if accumulate_into is None:
         dW = torch.empty(H, V, dtype=torch.float32, device=device)
         db = torch.empty(V, dtype=torch.float32, device=device)

@@ -90,11 +90,11 @@ namespace {
 // Optional per-kernel timing with HIP events on the caller's stream (off by default).
 enum KernelClass { KC_PREPARE = 0, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
                    KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_DW_REDUCE, KC_PROJ, KC_FWD_KEEP, KC_KEPT_TO_DH,
-                   KC_COUNT };
+                   KC_GRADS_TO_BF16, KC_COUNT };
 const char* const kKernelNames[KC_COUNT] = {"prepare", "joint_scores_fwd", "lattice",
                                             "joint_scores_bwd", "gemm_dz", "gemm_dw_db", "joint_bwd_fused",
                                             "fwd_f32", "bwd_f32", "dw_reduce", "projections",
-                                            "joint_scores_fwd_keep", "kept_scores_to_dh"};
+                                            "joint_scores_fwd_keep", "kept_scores_to_dh", "input_grads_to_bf16"};
 struct Profiler {
     bool enabled = false;
     struct Rec { int cls; hipEvent_t e0, e1; };
@@ -143,6 +143,8 @@ struct WsView {
     void* dH;
     void* Z;
     float* kept_max;
+    float* stage_enc;
+    float* stage_pred;
     float* dw_slots;
 };
 
@@ -167,19 +169,21 @@ WsView view_workspace(const Plan& p, void* ws) {
     v.dH = w + p.off_dh;
     v.Z = w + p.off_z;
     v.kept_max = (float*)(w + p.off_kept_max);
+    v.stage_enc = (float*)(w + p.off_stage_enc);
+    v.stage_pred = (float*)(w + p.off_stage_pred);
     v.dw_slots = (float*)(w + p.off_dwslots);
     return v;
 }
 
 rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const void* W_out, const float* b_out,
-                const int32_t* labels, const int32_t* T_len, const int32_t* U_len, float* loss, float* d_enc,
-                float* d_pred, float* dW_out, float* db_out, void* workspace, size_t workspace_bytes,
+                const int32_t* labels, const int32_t* T_len, const int32_t* U_len, float* loss, void* d_enc_out,
+                void* d_pred_out, float* dW_out, float* db_out, void* workspace, size_t workspace_bytes,
                 void* hip_stream, bool grads, const float* sample_weight = nullptr) {
     rnnt_status stt = check_desc(desc);
     if (stt != RNNT_OK) return stt;
     if (!enc || !pred || !W_out || !b_out || !loss || !T_len || !U_len) return RNNT_ERR_NULL;
     if (desc->U_max > 0 && !labels) return RNNT_ERR_NULL;
-    if (grads && (!d_enc || !d_pred || !dW_out || !db_out)) return RNNT_ERR_NULL;
+    if (grads && (!d_enc_out || !d_pred_out || !dW_out || !db_out)) return RNNT_ERR_NULL;
     stt = check_lengths(desc, T_len, U_len);
     if (stt != RNNT_OK) return stt;
     if (sample_weight)
@@ -207,15 +211,20 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     }
 
     Problem pr{desc->B, desc->T_max, desc->U_max, desc->H, desc->V, desc->blank, enc, pred, W_out, b_out, labels};
-    GradOut go{d_enc, d_pred, dW_out, db_out};
     const bool bf16 = (desc->dtype == RNNT_BF16);
+    // bf16 d_enc / d_pred: the kernels add into fp32 arrays of one group's samples in the workspace
+    const bool stage = plan.stage && grads;
+    float* d_enc = stage ? nullptr : (float*)d_enc_out;
+    float* d_pred = stage ? nullptr : (float*)d_pred_out;
+    const size_t enc_per_sample = (size_t)desc->T_max * desc->H, pred_per_sample = (size_t)(desc->U_max + 1) * desc->H;
+    GradOut go{d_enc, d_pred, dW_out, db_out};
     {
         PrepArgs pa{};
         if (grads) {
-            pa.zero_ptr[0] = d_enc;
-            pa.zero_n[0] = B * desc->T_max * desc->H;
+            pa.zero_ptr[0] = d_enc;                   // null with bf16 outputs: cleared per group below
+            pa.zero_n[0] = B * enc_per_sample;
             pa.zero_ptr[1] = d_pred;
-            pa.zero_n[1] = B * (desc->U_max + 1) * desc->H;
+            pa.zero_n[1] = B * pred_per_sample;
             if (!desc->accumulate_params) {
                 if (!bf16) {          // the bf16 path writes dW from its partial sums at the end
                     pa.zero_ptr[2] = dW_out;
@@ -243,6 +252,18 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         LatticeState ls = wv.ls;
         ls.row_base = plan.row_off[g.s0];
         ls.weight = sample_weight ? (const float*)(w + plan.off_weight) : nullptr;
+        if (stage) {
+            // the kernels index d_enc, d_pred by the sample's number in the call: base pointers such that
+            // sample g.s0 is the first one of the (cleared) workspace arrays
+            PrepArgs pz{};
+            pz.zero_ptr[0] = wv.stage_enc;
+            pz.zero_n[0] = (size_t)(g.s1 - g.s0) * enc_per_sample;
+            pz.zero_ptr[1] = wv.stage_pred;
+            pz.zero_n[1] = (size_t)(g.s1 - g.s0) * pred_per_sample;
+            RNNT_HIP(timed(KC_PREPARE, stream, [&] { return launch_prepare(pz, stream); }));
+            d_enc = (float*)((uintptr_t)wv.stage_enc - (uintptr_t)g.s0 * enc_per_sample * 4);
+            d_pred = (float*)((uintptr_t)wv.stage_pred - (uintptr_t)g.s0 * pred_per_sample * 4);
+        }
         // Eq. 4, Eq. 6, f^W_1
         const bool keep = plan.keep && grads;
         if (keep)
@@ -301,6 +322,17 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                                [&] { return launch_bwd_f32(pr, wv.st, ls, go, g.s0, g.s1, g.rows, stream); }));
             }
         }
+        if (stage) {
+            // the group's sums, padded rows included (zeros), rounded into the caller's bf16 arrays
+            RNNT_HIP(timed(KC_GRADS_TO_BF16, stream, [&] {
+                return launch_f32_to_bf16(wv.stage_enc, (unsigned char*)d_enc_out + (size_t)g.s0 * enc_per_sample * 2,
+                                          (size_t)(g.s1 - g.s0) * enc_per_sample, stream);
+            }));
+            RNNT_HIP(timed(KC_GRADS_TO_BF16, stream, [&] {
+                return launch_f32_to_bf16(wv.stage_pred, (unsigned char*)d_pred_out + (size_t)g.s0 * pred_per_sample * 2,
+                                          (size_t)(g.s1 - g.s0) * pred_per_sample, stream);
+            }));
+        }
     }
     if (bf16 && grads && !dw_first)
         RNNT_HIP(timed(KC_DW_REDUCE, stream, [&] {
@@ -315,7 +347,7 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
 extern "C" rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc, const void* enc, const void* pred,
                                                const void* W_out, const float* b_out, const int32_t* labels,
                                                const int32_t* T_len, const int32_t* U_len, float* loss,
-                                               float* d_enc, float* d_pred, float* dW_out, float* db_out,
+                                               void* d_enc, void* d_pred, float* dW_out, float* db_out,
                                                void* workspace, size_t workspace_bytes, void* hip_stream) {
     return run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW_out, db_out,
                workspace, workspace_bytes, hip_stream, true);
@@ -325,7 +357,7 @@ extern "C" rnnt_status rnnt_joint_loss_fwd_bwd_weighted(const rnnt_desc* desc, c
                                                         const void* W_out, const float* b_out,
                                                         const int32_t* labels, const int32_t* T_len,
                                                         const int32_t* U_len, const float* sample_weight,
-                                                        float* loss, float* d_enc, float* d_pred, float* dW_out,
+                                                        float* loss, void* d_enc, void* d_pred, float* dW_out,
                                                         float* db_out, void* workspace, size_t workspace_bytes,
                                                         void* hip_stream) {
     return run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW_out, db_out,
@@ -352,6 +384,7 @@ ProjLayout proj_layout(const rnnt_desc& d) {
 }
 rnnt_status check_proj_dims(const rnnt_desc* d, int32_t H_A, int32_t H_L) {
     if (H_A < 1 || H_L < 1) return RNNT_ERR_SHAPE;
+    if (d->input_grads_bf16) return RNNT_ERR_UNSUPPORTED;     // d_enc, d_pred are internal here and stay fp32
     if (H_A > 4096 || H_L > 4096) return RNNT_ERR_UNSUPPORTED;
     if (d->dtype == RNNT_BF16 && (H_A % 128 != 0 || H_L % 128 != 0)) return RNNT_ERR_UNSUPPORTED;
     return RNNT_OK;

@@ -61,6 +61,8 @@ struct PrepArgs {
     int H, V;
 };
 hipError_t launch_prepare(const PrepArgs& a, hipStream_t stream);
+// dst[i] = bf16(src[i]), n a multiple of 8 (the gradients of a group, accumulated in fp32, on their way out)
+hipError_t launch_f32_to_bf16(const float* src, void* dst, size_t n, hipStream_t stream);
 // plain copy of n floats (n a multiple of 4): the known-size kernel the HBM counters are calibrated with
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t stream);
 

@@ -61,6 +61,31 @@ __global__ __launch_bounds__(256) void k_prepare(PrepKernelArgs k) {
     }
 }
 
+// dst[i] = bf16(src[i]) (round to nearest even), n a multiple of 8
+__global__ __launch_bounds__(256) void k_f32_to_bf16(const float* __restrict__ src, bf16_t* __restrict__ dst, size_t n8) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(src + i * 8);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(src + i * 8 + 4);
+        bf16x8 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            o[j] = (bf16_t)lo[j];
+            o[4 + j] = (bf16_t)hi[j];
+        }
+        *reinterpret_cast<bf16x8*>(dst + i * 8) = o;
+    }
+}
+
+hipError_t launch_f32_to_bf16(const float* src, void* dst, size_t n, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    if (n % 8 != 0) return hipErrorInvalidValue;
+    const size_t n8 = n / 8;
+    const size_t blocks = (n8 + 255) / 256;
+    k_f32_to_bf16<<<dim3((unsigned)(blocks > 16384 ? 16384 : blocks)), dim3(256), 0, stream>>>(src, (bf16_t*)dst, n8);
+    return hipGetLastError();
+}
+
 hipError_t launch_prepare(const PrepArgs& a, hipStream_t stream) {
     PrepKernelArgs k{};
     k.a = a;

@@ -17,6 +17,8 @@ rnnt_status check_desc(const rnnt_desc* d) {
     if (d->accumulate_params != 0 && d->accumulate_params != 1) return RNNT_ERR_SHAPE;
     if (d->keep_scores != 0 && d->keep_scores != 1) return RNNT_ERR_SHAPE;
     if (d->keep_scores && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
+    if (d->input_grads_bf16 != 0 && d->input_grads_bf16 != 1) return RNNT_ERR_SHAPE;
+    if (d->input_grads_bf16 && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
     if (d->dtype != RNNT_F32 && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
     if (d->U_max > 1023) return RNNT_ERR_UNSUPPORTED;           // one lattice thread per label position
     if ((long long)d->T_max * (d->U_max + 1) > (1LL << 30)) return RNNT_ERR_UNSUPPORTED;
@@ -46,7 +48,7 @@ struct Sizes {
 };
 
 // Fills every offset for the given capacities and returns the total size.
-size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_rows) {
+size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_rows, long long stage_samples) {
     const size_t B = (size_t)d.B;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, WS_ALIGN); return at; };
@@ -79,6 +81,9 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
         p.off_dh = p.off_z = p.off_kept_max = o;
     }
     p.chunk_bytes = o - ch0;
+    p.off_stage_enc = take((size_t)stage_samples * d.T_max * d.H * 4);
+    p.off_stage_pred = take((size_t)stage_samples * (d.U_max + 1) * d.H * 4);
+    p.stage_samples = stage_samples;
     p.group_rows_cap = lat_cap;
     p.chunk_rows = p.bf16 ? chunk_rows : 0;
     p.total_bytes = o;
@@ -94,6 +99,8 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     p.bf16 = (d.dtype == RNNT_BF16);
     p.keep = p.bf16 && d.keep_scores;
     p.fused = p.bf16 && !p.keep && fused_backward_shape(d.H, d.V);
+    p.stage = p.bf16 && d.input_grads_bf16;
+    const size_t stage_per_sample = ((size_t)d.T_max + d.U_max + 1) * d.H * 4;
     p.tile_off.assign(B + 1, 0);
     p.row_off.assign(B + 1, 0);
     long long max_rows = 0, max_tile_rows = 0;
@@ -117,7 +124,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
 
     // smallest workable plan: one (largest) sample per group, one GEMM tile of rows per chunk
     Plan tmp = p;
-    p.min_bytes = lay_out(d, tmp, max_rows, p.bf16 ? chunk_floor : 0);
+    p.min_bytes = lay_out(d, tmp, max_rows, p.bf16 ? chunk_floor : 0, p.stage ? 1 : 0);
 
     // the default plan; a caller that passes exactly the size it was told gets exactly this plan back
     const long long lat_default = std::min(p.rows_total, std::max(max_rows, (256LL << 20) / 20));
@@ -129,21 +136,32 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         long long by_bytes = (long long)(budget / crb) / GEMM_TILE * GEMM_TILE;
         chunk_default = std::min(all_tile_rows, std::max<long long>(chunk_floor, by_bytes));
     }
+    // fp32 sums of d_enc, d_pred for the samples of a group: 256 MiB by default
+    const long long stage_default =
+        !p.stage ? 0 : std::min<long long>(B, std::max<long long>(1, (long long)((256ULL << 20) / stage_per_sample)));
     Plan dflt = p;
-    const size_t default_bytes = lay_out(d, dflt, lat_default, chunk_default);
+    const size_t default_bytes = lay_out(d, dflt, lat_default, chunk_default, stage_default);
 
-    long long lat_cap, chunk_rows;
+    long long lat_cap, chunk_rows, stage_samples;
     if (workspace_bytes == 0 || workspace_bytes == default_bytes) {
         lat_cap = lat_default;
         chunk_rows = chunk_default;
+        stage_samples = stage_default;
     } else if (workspace_bytes < p.min_bytes) {
         lat_cap = max_rows;
         chunk_rows = p.bf16 ? chunk_floor : 0;
+        stage_samples = p.stage ? 1 : 0;
     } else {
         // the fixed part and the alignment slack come off first
         Plan probe = p;
-        size_t fixed = lay_out(d, probe, 0, 0) + 8 * WS_ALIGN;
+        size_t fixed = lay_out(d, probe, 0, 0, 0) + 10 * WS_ALIGN;
         size_t avail = workspace_bytes > fixed ? workspace_bytes - fixed : 0;
+        // an eighth of the rest (at most the default) for the fp32 sums of a group
+        stage_samples = !p.stage ? 0
+                                 : std::min<long long>(stage_default,
+                                                       std::max<long long>(1, (long long)(avail / 8 / stage_per_sample)));
+        const size_t stage_bytes = (size_t)stage_samples * stage_per_sample;
+        avail = avail > stage_bytes ? avail - stage_bytes : 0;
         if (!p.bf16) {
             lat_cap = std::min<long long>(p.rows_total, std::max<long long>(max_rows, (long long)(avail / 20)));
             chunk_rows = 0;
@@ -163,13 +181,14 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         }
         // never below the minimum, never above the given size
         Plan t2 = p;
-        while (lay_out(d, t2, lat_cap, chunk_rows) > workspace_bytes) {
+        while (lay_out(d, t2, lat_cap, chunk_rows, stage_samples) > workspace_bytes) {
             if (chunk_rows > chunk_floor) chunk_rows -= GEMM_TILE;
             else if (lat_cap > max_rows) lat_cap = std::max(max_rows, lat_cap - 4096);
+            else if (stage_samples > 1) --stage_samples;
             else break;
         }
     }
-    lay_out(d, p, lat_cap, chunk_rows);
+    lay_out(d, p, lat_cap, chunk_rows, stage_samples);
     if (workspace_bytes != 0 && workspace_bytes < p.min_bytes) p.total_bytes = p.min_bytes;
 
     // groups: consecutive samples while the lattice state fits
@@ -184,6 +203,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         while (s < B) {
             long long rows = p.row_off[s + 1] - p.row_off[s];
             if (g.rows > 0 && g.rows + rows > lat_cap) break;
+            if (p.stage && s - g.s0 >= stage_samples) break;
             if (p.keep && g.rows > 0 &&
                 (long long)align_up((size_t)(p.tile_off[s + 1] - p.tile_off[g.s0]) * TILE_ROWS, GEMM_TILE) > chunk_rows)
                 break;

@@ -39,6 +39,8 @@ struct Plan {
     bool bf16 = false;
     bool fused = false;                 // bf16 only: backward runs in the fused kernel
     bool keep = false;                  // bf16 only: forward keeps the scores, one backward chunk per group
+    bool stage = false;                 // bf16 only: d_enc, d_pred leave as bf16; fp32 sums of one group in the workspace
+    long long stage_samples = 0;        // samples a group may hold then
     std::vector<int> tile_off;          // [B+1] cumulative tile counts
     std::vector<long long> row_off;     // [B+1] cumulative lattice nodes
     std::vector<Group> groups;
@@ -51,6 +53,7 @@ struct Plan {
     size_t off_wpack = 0, off_wq = 0;
     size_t off_lse = 0, off_lpb = 0, off_lpy = 0, off_alpha = 0, off_beta = 0;
     size_t off_dh = 0, off_z = 0, off_kept_max = 0;
+    size_t off_stage_enc = 0, off_stage_pred = 0;   // fp32 [stage_samples, T_max, H], [stage_samples, U_max+1, H]
     size_t off_dwslots = 0;             // bf16: per-workgroup partial sums of the dW GEMM
     int dw_splits = 0;                  // bf16: K splits of the dW GEMM (a multiple of 8)
     size_t lattice_bytes = 0, chunk_bytes = 0, total_bytes = 0;

@@ -261,6 +261,32 @@ def test_bf16_kept_scores_bench_workload_sampled():
     assert_parity(run_gpu(sub, keep_scores=1), run_oracle(sub), "bf16", "C2 sub-batch, kept scores")
 
 
+# ------------------------------------------------------------------ d_enc, d_pred as bfloat16
+@pytest.mark.parametrize("H,V,keep", [(128, 256, 0), (896, 256, 0), (512, 1024, 0), (256, 512, 1)])
+def test_bf16_input_gradient_outputs(H, V, keep):
+    wl = synth.custom_workload("g16", B=6, T_max=29, U_max=12, H=H, V=V, dtype="bf16", index=140,
+                               t_rule="uniform", t_lo=3, u_rule="uniform", u_lo=0)
+    batch = synth.make_batch(wl)
+    _say("bf16 grads", H, V, keep, batch.T_len, batch.U_len)
+    ref = run_oracle(batch)
+    got = run_gpu(batch, input_grads_bf16=1, keep_scores=keep)
+    e, errs = assert_parity(got, ref, "bf16", f"bf16 d_enc/d_pred H={H} V={V}")
+    _say("errs", e, errs)
+    assert_padding_zero(got, batch)
+    # the float outputs of the default call, rounded, are the same numbers up to the order of the float sums
+    plain = run_gpu(batch, keep_scores=keep)
+    np.testing.assert_array_equal(got["loss"], plain["loss"])
+    for k in ("d_enc", "d_pred"):
+        assert rel_grad_err(got[k], plain[k]) < 5e-3, k
+    # smallest workspace: one sample per group, every group converted on its own
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(got["desc"], batch.T_len, batch.U_len, 1)
+    st, info, _ = Bd.rnnt_joint_loss_plan(got["desc"], batch.T_len, batch.U_len, nmin)
+    assert st == 0 and info["n_groups"] == batch.B
+    small = run_gpu(batch, budget_bytes=nmin, input_grads_bf16=1, keep_scores=keep)
+    assert_parity(small, ref, "bf16", "bf16 d_enc/d_pred, smallest workspace")
+    assert_padding_zero(small, batch)
+
+
 # ------------------------------------------------------------------ weighted sum of the samples' losses
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_sample_weights_against_the_checker(dtype):

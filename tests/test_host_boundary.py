@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(Bd.RnntDesc) == 36
+    assert ctypes.sizeof(Bd.RnntDesc) == 40
     assert ctypes.sizeof(Bd.RnntPlanInfo) == 8 * 3 + 4 * 2 + 8 * 2 + 8 * 3
 
 
@@ -193,6 +193,29 @@ def test_keep_scores_plan_has_one_backward_chunk_per_group_of_whole_samples():
     assert Bd.rnnt_joint_loss_workspace_bytes(Bd.make_desc(2, 8, 3, 16, 8, 0, Bd.RNNT_F32, keep_scores=1), [8, 8], [3, 3]) == 0
     assert Bd.rnnt_joint_loss_workspace_bytes(
         Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16, keep_scores=2), T, U) == 0
+
+
+def test_bf16_input_gradients_add_a_bounded_staging_area_and_cap_the_group_size():
+    wl, desc, T, U = _lens("C4")
+    half = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16, input_grads_bf16=1)
+    n0 = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 0)
+    n1 = Bd.rnnt_joint_loss_workspace_bytes(half, T, U, 0)
+    per_sample = (wl.T_max + wl.U_max + 1) * wl.H * 4
+    cap = (256 << 20) // per_sample
+    assert 0 < n1 - n0 <= (256 << 20) + 512 and n1 - n0 >= cap * per_sample
+    st, info, groups = Bd.rnnt_joint_loss_plan(half, T, U, n1)
+    assert st == 0 and np.bincount(groups).max() <= cap
+    # the outputs shrink by more than the workspace grows
+    assert (n1 - n0) < wl.B * per_sample // 2
+    # smallest plan: one sample per group
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(half, T[:8], U[:8], 1)
+    h8 = Bd.make_desc(8, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16, input_grads_bf16=1)
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(h8, T[:8], U[:8], 1)
+    st, info, groups = Bd.rnnt_joint_loss_plan(h8, T[:8], U[:8], nmin)
+    assert st == 0 and info["n_groups"] == 8
+    # bf16 only; not for the projected entry point, whose d_enc / d_pred are internal
+    assert Bd.rnnt_joint_loss_workspace_bytes(Bd.make_desc(2, 8, 3, 16, 8, 0, Bd.RNNT_F32, input_grads_bf16=1), [8, 8], [3, 3]) == 0
+    assert Bd.rnnt_joint_proj_workspace_bytes(half, 512, 512, T, U, 0) == 0
 
 
 def test_projected_entry_point_checks_and_workspace():
