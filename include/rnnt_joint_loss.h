@@ -86,6 +86,9 @@ typedef struct {
 } rnnt_plan_info;
 
 const char* rnnt_status_string(rnnt_status s);
+/* After a call returned RNNT_ERR_HIP: name and text of the HIP error and the library source line of the
+ * call that reported it ("" if none so far).  Process-wide, overwritten by the next such failure. */
+const char* rnnt_last_hip_error(void);
 
 /*
  * Workspace size for a call (host only, no GPU needed).

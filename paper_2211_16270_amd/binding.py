@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "lib", "librnnt_joint_loss.so")
 RNNT_F32, RNNT_BF16 = 0, 1
 STATUS_NAMES = ["RNNT_OK", "RNNT_ERR_NULL", "RNNT_ERR_SHAPE", "RNNT_ERR_LENGTH", "RNNT_ERR_LABEL",
                 "RNNT_ERR_WORKSPACE", "RNNT_ERR_UNSUPPORTED", "RNNT_ERR_HIP", "RNNT_ERR_WEIGHT"]
-EXPORTS = ["rnnt_status_string", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_loss_plan",
+EXPORTS = ["rnnt_status_string", "rnnt_last_hip_error", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_loss_plan",
            "rnnt_parallel_iterations", "rnnt_validate_labels_host", "rnnt_joint_loss_fwd_bwd",
            "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice", "rnnt_profile_enable",
            "rnnt_debug_copy_f32", "rnnt_debug_mfma_loop", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
@@ -44,7 +44,10 @@ class RnntError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else str(status)
-        super().__init__(f"{where}: {name} ({lib().rnnt_status_string(status).decode()})")
+        text = lib().rnnt_status_string(status).decode()
+        if name == "RNNT_ERR_HIP":
+            text += ": " + lib().rnnt_last_hip_error().decode()
+        super().__init__(f"{where}: {name} ({text})")
 
 
 _lib = None
@@ -58,11 +61,20 @@ def lib() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                            "(hipcc, gfx950) first; this package has no fallback path")
+    # PyTorch ships a HIP runtime of its own.  A process must use one runtime only: if this library were
+    # loaded first it would bring in the system's, and the GPU calls made after torch has initialised its own
+    # would find no device.  Importing torch first makes its runtime the one both sides resolve to.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(LIB_PATH)
     vp, i32p, f32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p
     dp = ctypes.POINTER(RnntDesc)
     L.rnnt_status_string.restype = ctypes.c_char_p
     L.rnnt_status_string.argtypes = [ctypes.c_int]
+    L.rnnt_last_hip_error.restype = ctypes.c_char_p
+    L.rnnt_last_hip_error.argtypes = []
     L.rnnt_joint_loss_workspace_bytes.restype = ctypes.c_size_t
     L.rnnt_joint_loss_workspace_bytes.argtypes = [dp, i32p, i32p, ctypes.c_size_t]
     L.rnnt_joint_loss_plan.restype = ctypes.c_int

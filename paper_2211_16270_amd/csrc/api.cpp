@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <vector>
 
@@ -127,9 +128,16 @@ hipError_t timed(int cls, hipStream_t stream, F&& launch) {
     return e;
 }
 
+// What the last failed HIP call was (process-wide, for rnnt_last_hip_error).
+hipError_t g_last_hip_error = hipSuccess;
+int g_last_hip_line = 0;
+
 #define RNNT_HIP(expr)                           \
     do {                                         \
-        if ((expr) != hipSuccess) {              \
+        const hipError_t rnnt_e_ = (expr);       \
+        if (rnnt_e_ != hipSuccess) {             \
+            g_last_hip_error = rnnt_e_;          \
+            g_last_hip_line = __LINE__;          \
             (void)hipGetLastError();             \
             return RNNT_ERR_HIP;                 \
         }                                        \
@@ -524,6 +532,14 @@ extern "C" rnnt_status rnnt_debug_mfma_loop(const void* frags, float* out, int32
     if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > 1000000) return RNNT_ERR_SHAPE;
     RNNT_HIP(launch_mfma_loop(frags, out, workgroups, iters, (hipStream_t)hip_stream));
     return RNNT_OK;
+}
+
+extern "C" const char* rnnt_last_hip_error(void) {
+    static char text[160];
+    if (g_last_hip_error == hipSuccess) return "";
+    snprintf(text, sizeof text, "%s (%s) at api.cpp:%d", hipGetErrorName(g_last_hip_error),
+             hipGetErrorString(g_last_hip_error), g_last_hip_line);
+    return text;
 }
 
 extern "C" rnnt_status rnnt_profile_enable(int32_t enable) {

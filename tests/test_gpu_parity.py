@@ -451,9 +451,16 @@ def test_random_small_shapes_against_the_checker(seed):
         labels[b, U_len[b]:] = -1
     import dataclasses
     batch = dataclasses.replace(batch, labels=labels)
+    # the descriptor's options (bf16 path) and the smallest workspace, drawn last so that the shapes stay what they were
+    opts = dict(keep_scores=int(rng.integers(0, 2)), input_grads_bf16=int(rng.integers(0, 2))) if bf16 else {}
+    smallest = bool(rng.integers(0, 2))
     _say("random shape", seed, "bf16" if bf16 else "f32", dict(B=B, T_max=T_max, U_max=U_max, H=H, V=V, blank=blank),
-         T_len.tolist(), U_len.tolist())
-    got = run_gpu(batch, blank=blank)
+         T_len.tolist(), U_len.tolist(), opts, "smallest workspace" if smallest else "")
+    budget = 0
+    if smallest:
+        dt = Bd.RNNT_BF16 if bf16 else Bd.RNNT_F32
+        budget = Bd.rnnt_joint_loss_workspace_bytes(Bd.make_desc(B, T_max, U_max, H, V, blank, dt, 0, **opts), T_len, U_len, 1)
+    got = run_gpu(batch, blank=blank, budget_bytes=budget, **opts)
     ref = run_oracle(batch, blank=blank)
     assert_parity(got, ref, wl.dtype, f"random shape {seed}")
     assert_padding_zero(got, batch)
