@@ -205,7 +205,7 @@ def test_bf16_saturated_joint_and_peaked_softmax():
 
 
 # ------------------------------------------------------------------ scores kept instead of computed twice
-@pytest.mark.parametrize("H,V", [(128, 256), (640, 1024), (896, 256), (1024, 512), (256, 768)])
+@pytest.mark.parametrize("H,V", [(128, 256), (640, 1024), (896, 256), (1024, 512), (256, 768), (1024, 4096)])
 def test_bf16_kept_scores_match_the_checker_and_the_default_path(H, V):
     wl = synth.custom_workload("keep", B=5, T_max=27, U_max=12, H=H, V=V, dtype="bf16", index=130,
                                t_rule="uniform", t_lo=3, u_rule="uniform", u_lo=0)
