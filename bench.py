@@ -122,12 +122,16 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]   # one event record between steps
     t0 = time.perf_counter()
-    for _ in range(steps):
+    marks[0].record()
+    for i in range(steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / steps * 1e3
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
     value = wl.B / (elapsed / steps)
     assert bool(torch.isfinite(loss).all()), "non-finite loss"
     peak_bytes = torch.cuda.max_memory_allocated()
@@ -186,7 +190,8 @@ def main():
     out = {
         "metric": "samples/s fused joint+RNN-T loss+grads" + (" incl. input projections" if args.projections else ""),
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B} T_max={wl.T_max} U_max={wl.U_max} H={wl.H} V={wl.V} "
                                f"{wl.dtype}, ragged lengths, {R} lattice nodes ({100.0 * R / info['rows_padded']:.1f}% of padded)",
