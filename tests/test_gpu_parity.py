@@ -425,6 +425,36 @@ def test_bf16_memory_headline_workload_sampled():
     assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-2 * float(np.abs(got["db_out"]).sum())
 
 
+def test_bf16_paper_shaped_workload_sampled_default_and_kept_scores():
+    # the paper's benchmark shape (Section 5.1: 500 x 100, joint size 1024, 4096 word pieces), four samples:
+    # unfused backward (H > 640), and the same with the scores kept and bfloat16 input gradients; the checker
+    # recomputes the sample with the fewest lattice nodes
+    wl = synth.custom_workload("P4", B=4, T_max=500, U_max=100, H=1024, V=4096, dtype="bf16", index=5,
+                               t_rule="uniform", t_lo=454, u_rule="uniform", u_lo=54)
+    batch = synth.make_batch(wl)
+    rows = batch.T_len.astype(np.int64) * (batch.U_len + 1)
+    b = int(np.argmin(rows))
+    T, U = int(batch.T_len[b]), int(batch.U_len[b])
+    _say("paper-shaped sample", b, T, U)
+    r = O.sample_loss_and_grads(batch.enc[b, :T], batch.pred[b, :U + 1], batch.W_out, batch.b_out,
+                                batch.labels[b, :U], 0)
+    tol = TOL["bf16"]
+    plain = run_gpu(batch)
+    kept = run_gpu(batch, keep_scores=1, input_grads_bf16=1)
+    for name, got in (("default", plain), ("kept scores, bf16 input gradients", kept)):
+        assert np.all(np.isfinite(got["loss"])), name
+        assert_padding_zero(got, batch)
+        el = abs(got["loss"][b] - r["loss"]) / abs(r["loss"])
+        ee = rel_grad_err(got["d_enc"][b, :T], r["d_enc"])
+        ep = rel_grad_err(got["d_pred"][b, :U + 1], r["d_pred"])
+        _say(name, "errs", el, ee, ep)
+        assert el <= tol["loss"] and ee <= tol["grad"] and ep <= tol["grad"], name
+        assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-2 * float(np.abs(got["db_out"]).sum())
+    np.testing.assert_array_equal(kept["loss"], plain["loss"])
+    for k in ("dW_out", "db_out"):
+        assert rel_grad_err(kept[k], plain[k]) <= tol["grad"], k
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_small_shapes_against_the_checker(seed):
     # seeded random shapes, lengths and blank positions, both precisions; labels may equal the blank
