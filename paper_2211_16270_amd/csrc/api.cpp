@@ -172,6 +172,7 @@ WsView view_workspace(const Plan& p, void* ws) {
     v.ls.lnP = (float*)(w + p.off_lnP);
     v.ls.shift = (float*)(w + p.off_shift);
     v.ls.row_base = 0;
+    v.ls.tile_esum = p.bf16 ? (float*)(w + p.off_tile_esum) : nullptr;
     v.wpack = w + p.off_wpack;
     v.wq = w + p.off_wq;
     v.dH = w + p.off_dh;

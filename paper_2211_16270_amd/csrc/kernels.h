@@ -26,6 +26,8 @@ struct LatticeState {
     float* lnP;    // [B] ln P(y|x) + shift*(T+U), per sample
     float* shift;  // [B] per-sample offset added to every emission log-probability
     const float* weight;  // [B] weight of loss[b] in the differentiated sum, or null (all ones)
+    float* tile_esum;     // [tiles of the call] sum over a tile's nodes of max(lpb, lpy) (lpb where there is no
+                          // label), written by the bf16 forward kernels for the lattice kernels' offset; or null
     long long row_base;
 };
 

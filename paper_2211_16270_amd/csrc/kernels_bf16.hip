@@ -363,6 +363,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
         if (tid < 64) {
             const int r = tid;
             const int idx = row_lat[r];
+            float esum = 0.0f;
             if (idx >= 0) {
                 float M = RNNT_NEG_INF;
 #pragma unroll
@@ -374,7 +375,12 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
                 a.ls.lse[idx] = lse;
                 a.ls.lpb[idx] = row_f0[r] - lse;
                 a.ls.lpy[idx] = (row_lab[r] >= 0) ? row_f1[r] - lse : 0.0f;
+                // this node's share of the sum the lattice kernels take their per-sample offset from
+                const bool has_label = tp.u0 + (r & 7) < tp.U;
+                esum = has_label ? fmaxf(row_f0[r], row_f1[r]) - lse : row_f0[r] - lse;
             }
+            esum = wave_sum(esum);
+            if (r == 0) a.ls.tile_esum[tile] = esum;
         }
     }
 }

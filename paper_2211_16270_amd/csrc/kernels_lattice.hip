@@ -17,27 +17,40 @@ namespace rnnt {
 
 constexpr int LAT_PF = 8;       // prefetch distance in steps
 
-// Sum over this thread's share (i = first, first + stride, ...) of max(lpb, lpy) over the lattice,
-// eight independent loads in flight.
+// Sum over this thread's share (i = first, first + stride, ...) of max(lpb, lpy) over the lattice.  The
+// sweep cannot start before this sum is known, and a workgroup has few threads for the size of a lattice:
+// 2 x LAT_SUM_DEPTH independent loads are in flight per thread, so that few memory latencies are exposed.
+constexpr int LAT_SUM_DEPTH = 24;
 __device__ __forceinline__ float emission_max_partial(const float* __restrict__ lpb, const float* __restrict__ lpy,
                                                       int n, int W1, int U, int first, int stride) {
     float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-    for (int i0 = first; i0 < n; i0 += 8 * stride) {
-        float b[8], y[8];
+    for (int i0 = first; i0 < n; i0 += LAT_SUM_DEPTH * stride) {
+        float b[LAT_SUM_DEPTH], y[LAT_SUM_DEPTH];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < LAT_SUM_DEPTH; ++j) {
             const int i = i0 + j * stride;
             const int ic = (i < n) ? i : first;
             b[j] = lpb[ic];
             y[j] = lpy[ic];
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < LAT_SUM_DEPTH; ++j) {
             const int i = i0 + j * stride;
-            if (i < n) acc[j] += (i % W1 < U) ? fmaxf(b[j], y[j]) : b[j];
+            const float v = (i % W1 < U) ? fmaxf(b[j], y[j]) : b[j];
+            acc[j & 7] += (i < n) ? v : 0.0f;
         }
     }
     return ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+}
+// The same sum from the per-tile sums the bf16 forward kernels leave behind (a few hundred numbers instead of
+// the whole lattice), if there are any.  Both workgroups of a sample add in the same order.
+__device__ __forceinline__ float emission_sum_partial(const SampleTable& st, const LatticeState& ls, int s,
+                                                      const float* __restrict__ lpb, const float* __restrict__ lpy,
+                                                      int n, int W1, int U, int first, int stride) {
+    if (ls.tile_esum == nullptr) return emission_max_partial(lpb, lpy, n, W1, U, first, stride);
+    float acc = 0.0f;
+    for (int i = st.tile_off[s] + first, e = st.tile_off[s + 1]; i < e; i += stride) acc += ls.tile_esum[i];
+    return acc;
 }
 constexpr int LAT_MAX_T = 1024; // threads per workgroup (label positions 0..U <= 1023)
 
@@ -58,6 +71,9 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
 
     // ---- per-sample offset c (identical in both workgroups of a sample: same code, same order)
     {
+        // (read from the emissions themselves although the forward kernels' per-tile sums would do: this pass
+        // also brings the sample's emissions into the L2 the sweep then reads them from, and without it the
+        // kernel as a whole was 7 % slower on lattices of 1000 x 200)
         float acc = emission_max_partial(lpb, lpy, n, W1, U, tid, (int)blockDim.x);
         acc = wave_sum(acc);
         if ((tid & 63) == 0) red[tid >> 6] = acc;
@@ -187,25 +203,30 @@ constexpr int LW_RB = 32;                 // sweep rows per staged block
 constexpr int LW_ROWS = 128;              // rows in the ring (a step touches its row and the 64 before it)
 constexpr int LW_RING = LW_ROWS * 64;     // floats per array
 
-// Value of lane l-1 (lane 0 keeps its own) / lane l+1 (lane 63 keeps its own): whole-wavefront
-// shifts on the data-parallel-primitive path of v_mov, no LDS round trip.
+// Value of lane l-1 (lane 0 gets 0) / lane l+1 (lane 63 gets 0): whole-wavefront shifts on the
+// data-parallel-primitive path, no LDS round trip.  With nothing to preserve in the lanes that have no
+// source the shift can ride on the addition that consumes it instead of taking a move of its own.
 __device__ __forceinline__ float lane_from_below(float v) {
-    const int x = __float_as_int(v);
-    return __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x138 /* wave_shr:1 */, 0xf, 0xf, false));
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x138 /* wave_shr:1 */, 0xf, 0xf, true));
 }
 __device__ __forceinline__ float lane_from_above(float v) {
-    const int x = __float_as_int(v);
-    return __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x130 /* wave_shl:1 */, 0xf, 0xf, false));
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130 /* wave_shl:1 */, 0xf, 0xf, true));
+}
+// Makes the compiler finish a value where this stands instead of sinking its arithmetic to the first use
+// (for the emission values: into the dependent chain of the next step).
+__device__ __forceinline__ void pin(float& a, float& b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" : "+v"(a), "+v"(b));
+#endif
 }
 
-// ln(e^a + e^b) on the hardware exp2/log2 units; either may be -inf.  The argument of the logarithm
-// lies in [1, 2], so no range fix-up is needed.
+// ln(e^a + e^b) on the hardware exp2/log2 units; one of the two may be -inf (both: NaN, which only lanes
+// outside the lattice ever see and never keep).  The argument of the logarithm lies in [1, 2], so no range
+// fix-up is needed.  Six dependent instructions: the sweep's step time is the latency of this chain.
 __device__ __forceinline__ float log_add_exp_fast(float a, float b) {
     const float m = fmaxf(a, b);
-    const float d = -fabsf(a - b);                          // -inf when exactly one is -inf, NaN when both
-    const float e = __builtin_amdgcn_exp2f(d * 1.44269504088896340736f);
-    const float r = fmaf(__builtin_amdgcn_logf(1.0f + e), 0.69314718055994530942f, m);
-    return (m == RNNT_NEG_INF) ? m : r;
+    const float e = __builtin_amdgcn_exp2f(fabsf(a - b) * -1.44269504088896340736f);   // 0 when one is -inf
+    return fmaf(__builtin_amdgcn_logf(1.0f + e), 0.69314718055994530942f, m);
 }
 
 // Asynchronous global -> LDS copy of 4 bytes per lane (global_load_lds_dword): lane l's word lands at LDS
@@ -214,6 +235,29 @@ __device__ __forceinline__ float log_add_exp_fast(float a, float b) {
 __device__ __forceinline__ void lds_dma4(const void* gptr, unsigned lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
 }
+
+// Steps 1 .. nsteps-1 of a sweep.  Step k with (k+1) % LW_RB == 0 is the last one before the sweep enters the
+// next staged block: it first waits for that block and sends for the one after it.  Whole blocks of LW_RB
+// steps are unrolled (a taken branch costs about as much as the arithmetic of a step); the steps before the
+// first whole block and after the last one run in plain loops.
+#define SWEEP(step)                                                          \
+    {                                                                        \
+        int k = 1;                                                           \
+        for (; k < nsteps && k < LW_RB; ++k) {                               \
+            if (k == LW_RB - 1) {                                            \
+                landed();                                                    \
+                issue(2);                                                    \
+            }                                                                \
+            step();                                                          \
+        }                                                                    \
+        for (; k + LW_RB <= nsteps; k += LW_RB) {                            \
+            _Pragma("unroll") for (int j = 0; j < LW_RB - 1; ++j) step();    \
+            landed();                                                        \
+            issue(k / LW_RB + 2);                                            \
+            step();                                                          \
+        }                                                                    \
+        for (; k < nsteps; ++k) step();                                      \
+    }
 
 __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeState ls, int s0,
                                                      float* __restrict__ loss) {
@@ -229,7 +273,7 @@ __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeStat
     const float* __restrict__ lpb = ls.lpb + base;
     const float* __restrict__ lpy = ls.lpy + base;
     const int n = T * W1;
-    const float c = -wave_sum(emission_max_partial(lpb, lpy, n, W1, U, u, 64)) / (float)n;
+    const float c = -wave_sum(emission_sum_partial(st, ls, s, lpb, lpy, n, W1, U, u, 64)) / (float)n;
     const int nsteps = T + U;
     const unsigned T_act = (u <= U) ? (unsigned)T : 0u;     // lanes beyond the last label position never act
 
@@ -271,30 +315,26 @@ __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeStat
         // blank emission of frame d-1 at column u, label emission of frame d at column u-1
         unsigned rb = (unsigned)((((d - 1) & (LW_ROWS - 1)) << 6) + u);
         unsigned ry = (unsigned)(((d & (LW_ROWS - 1)) << 6) + u - du);
-        float eb = ring_b[rb], ey = ring_y[ry];
-        for (int k = 1; k < nsteps; ++k) {
-            if (((k + 1) & (LW_RB - 1)) == 0) {     // step k+1 is the first to read block (k+1)/LW_RB
-                landed();
-                issue((k + 1) / LW_RB + 1);
-            }
+        // The offset c and the two boundary conditions (no frame below row 0, no column left of 0) go into
+        // the emission values as soon as they arrive, off the dependent chain own -> val -> own.
+        float eb = (d > 0) ? ring_b[rb] + c : RNNT_NEG_INF;
+        float ey = has_left ? ring_y[ry] + c : RNNT_NEG_INF;
+        auto step = [&]() {
             rb = ry + du;
             ry = (ry + 64u) & (LW_RING - 1);
-            const float eb_n = ring_b[rb], ey_n = ring_y[ry];
+            const float eb_r = ring_b[rb], ey_r = ring_y[ry];
             const bool act = (unsigned)d < T_act;
-            const float oc = own + c;
-            const float left = lane_from_below(oc);                 // column u-1, previous step
-            const float a = (d > 0) ? oc + eb : RNNT_NEG_INF;
-            const float b = has_left ? left + ey : RNNT_NEG_INF;
-            const float val = log_add_exp_fast(a, b);
-            if (act) {
-                alpha[so] = val;
-                own = val;
-            }
+            const float left = lane_from_below(own);                // column u-1, previous step
+            const float val = log_add_exp_fast(own + eb, left + ey);
+            own = act ? val : own;
+            if (act) alpha[so] = val;
             so += (unsigned)W1;
             d += 1;
-            eb = eb_n;
-            ey = ey_n;
-        }
+            eb = (d > 0) ? eb_r + c : RNNT_NEG_INF;
+            ey = has_left ? ey_r + c : RNNT_NEG_INF;
+            pin(eb, ey);
+        };
+        SWEEP(step)
         if (u == U) {
             const float lnP_off = own + (lpb[(T - 1) * W1 + U] + c);
             ls.lnP[s] = lnP_off;
@@ -312,29 +352,23 @@ __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeStat
         int d = 1 - (U - u);                                        // sweep row of step 1
         unsigned so = (unsigned)((T - 1 - d) * W1 + u);
         unsigned ro = (unsigned)(((d & (LW_ROWS - 1)) << 6) + u);   // both emissions of the node itself
-        float eb = ring_b[ro], ey = ring_y[ro];
-        for (int k = 1; k < nsteps; ++k) {
-            if (((k + 1) & (LW_RB - 1)) == 0) {
-                landed();
-                issue((k + 1) / LW_RB + 1);
-            }
+        float eb = (d > 0) ? ring_b[ro] + c : RNNT_NEG_INF;        // d > 0: frame t < T-1
+        float ey = has_right ? ring_y[ro] + c : RNNT_NEG_INF;
+        auto step = [&]() {
             ro = (ro + 64u) & (LW_RING - 1);
-            const float eb_n = ring_b[ro], ey_n = ring_y[ro];
+            const float eb_r = ring_b[ro], ey_r = ring_y[ro];
             const bool act = (unsigned)d < T_act;
-            const float oc = own + c;
-            const float right = lane_from_above(oc);                // column u+1, previous step
-            const float a = (d > 0) ? oc + eb : RNNT_NEG_INF;       // d > 0: frame t < T-1
-            const float b = has_right ? right + ey : RNNT_NEG_INF;
-            const float val = log_add_exp_fast(a, b);
-            if (act) {
-                beta[so] = val;
-                own = val;
-            }
+            const float right = lane_from_above(own);               // column u+1, previous step
+            const float val = log_add_exp_fast(own + eb, right + ey);
+            own = act ? val : own;
+            if (act) beta[so] = val;
             so -= (unsigned)W1;
             d += 1;
-            eb = eb_n;
-            ey = ey_n;
-        }
+            eb = (d > 0) ? eb_r + c : RNNT_NEG_INF;
+            ey = has_right ? ey_r + c : RNNT_NEG_INF;
+            pin(eb, ey);
+        };
+        SWEEP(step)
     }
 }
 

@@ -60,6 +60,7 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     p.off_lnP = take(B * 4);
     p.off_shift = take(B * 4);
     p.off_tile_sample = take((size_t)p.tiles_total * 4);
+    p.off_tile_esum = take(p.bf16 ? (size_t)p.tiles_total * 4 : 0);
     p.off_wpack = take(p.bf16 ? (size_t)d.H * d.V * 2 : 0);
     p.off_wq = take(p.fused ? (size_t)d.H * d.V * 2 : 0);
     p.dw_splits = p.bf16 ? dw_split_count(d.H, d.V) : 0;

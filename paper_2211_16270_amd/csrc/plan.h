@@ -50,6 +50,7 @@ struct Plan {
     long long chunk_rows = 0;           // rows (multiple of GEMM_TILE) of the chunk buffers
     // workspace layout (byte offsets)
     size_t off_T = 0, off_U = 0, off_weight = 0, off_tile_off = 0, off_row_off = 0, off_lnP = 0, off_shift = 0, off_tile_sample = 0;
+    size_t off_tile_esum = 0;          // bf16: per-tile emission sums (float per tile)
     size_t off_wpack = 0, off_wq = 0;
     size_t off_lse = 0, off_lpb = 0, off_lpy = 0, off_alpha = 0, off_beta = 0;
     size_t off_dh = 0, off_z = 0, off_kept_max = 0;
