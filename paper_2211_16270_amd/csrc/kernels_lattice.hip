@@ -52,6 +52,15 @@ __device__ __forceinline__ float emission_sum_partial(const SampleTable& st, con
     for (int i = st.tile_off[s] + first, e = st.tile_off[s + 1]; i < e; i += stride) acc += ls.tile_esum[i];
     return acc;
 }
+// ln(e^a + e^b) on the hardware exp2/log2 units; one of the two may be -inf (both: NaN, which only lanes
+// outside the lattice ever see and never keep).  The argument of the logarithm lies in [1, 2], so no range
+// fix-up is needed.  Six dependent instructions: the sweep's step time is the latency of this chain.
+__device__ __forceinline__ float log_add_exp_fast(float a, float b) {
+    const float m = fmaxf(a, b);
+    const float e = __builtin_amdgcn_exp2f(fabsf(a - b) * -1.44269504088896340736f);   // 0 when one is -inf
+    return fmaf(__builtin_amdgcn_logf(1.0f + e), 0.69314718055994530942f, m);
+}
+
 constexpr int LAT_MAX_T = 1024; // threads per workgroup (label positions 0..U <= 1023)
 
 __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeState ls, int s0,
@@ -126,9 +135,11 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
                         if (k == 0) {
                             val = 0.0f;
                         } else {
-                            const float a = (t > 0) ? own + (pb[i] + c) : RNNT_NEG_INF;
-                            const float b = (u > 0) ? left + (py[i] + c) : RNNT_NEG_INF;
-                            val = log_add_exp(a, b);
+                            // the offset and the boundary conditions go into the emission values, which do not
+                            // depend on the step before: the dependent chain is own -> add -> log-add-exp
+                            const float eb = (t > 0) ? pb[i] + c : RNNT_NEG_INF;
+                            const float ey = (u > 0) ? py[i] + c : RNNT_NEG_INF;
+                            val = log_add_exp_fast(own + eb, left + ey);
                         }
                         alpha[t * W1 + u] = val;
                         own = val;
@@ -174,9 +185,9 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
                         if (k == 0) {
                             val = pb[i] + c;                 // beta[T-1,U] = final blank
                         } else {
-                            const float a = (t < T - 1) ? own + (pb[i] + c) : RNNT_NEG_INF;
-                            const float b = (u < U) ? right + (py[i] + c) : RNNT_NEG_INF;
-                            val = log_add_exp(a, b);
+                            const float eb = (t < T - 1) ? pb[i] + c : RNNT_NEG_INF;
+                            const float ey = (u < U) ? py[i] + c : RNNT_NEG_INF;
+                            val = log_add_exp_fast(own + eb, right + ey);
                         }
                         beta[t * W1 + u] = val;
                         own = val;
@@ -218,15 +229,6 @@ __device__ __forceinline__ void pin(float& a, float& b) {
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("" : "+v"(a), "+v"(b));
 #endif
-}
-
-// ln(e^a + e^b) on the hardware exp2/log2 units; one of the two may be -inf (both: NaN, which only lanes
-// outside the lattice ever see and never keep).  The argument of the logarithm lies in [1, 2], so no range
-// fix-up is needed.  Six dependent instructions: the sweep's step time is the latency of this chain.
-__device__ __forceinline__ float log_add_exp_fast(float a, float b) {
-    const float m = fmaxf(a, b);
-    const float e = __builtin_amdgcn_exp2f(fabsf(a - b) * -1.44269504088896340736f);   // 0 when one is -inf
-    return fmaf(__builtin_amdgcn_logf(1.0f + e), 0.69314718055994530942f, m);
 }
 
 // Asynchronous global -> LDS copy of 4 bytes per lane (global_load_lds_dword): lane l's word lands at LDS
