@@ -218,6 +218,49 @@ def test_bf16_input_gradients_add_a_bounded_staging_area_and_cap_the_group_size(
     assert Bd.rnnt_joint_proj_workspace_bytes(half, 512, 512, T, U, 0) == 0
 
 
+def test_random_plans_keep_their_promises():
+    # seeded random shapes, lengths, options and budgets: every sample is in exactly one group, groups are runs of
+    # consecutive samples, a plan never exceeds the workspace it was made for, the size the library asks for is
+    # accepted, and the options' extra limits hold (kept scores: a group's tile rows fit the chunk buffers;
+    # bfloat16 input gradients: groups no larger than the staging area was sized for)
+    rng = np.random.default_rng(20240)
+    for case in range(150):
+        bf16 = bool(rng.integers(0, 4))
+        B = int(rng.integers(1, 40))
+        T_max, U_max = int(rng.integers(1, 300)), int(rng.integers(0, 120))
+        if bf16:
+            H, V = int(rng.choice([128, 256, 512, 640, 768, 1024])), int(rng.choice([256, 512, 1024, 4096]))
+            opts = dict(keep_scores=int(rng.integers(0, 2)), input_grads_bf16=int(rng.integers(0, 2)))
+        else:
+            H, V, opts = int(rng.integers(1, 200)), int(rng.integers(2, 300)), {}
+        T = rng.integers(1, T_max + 1, size=B).astype(np.int32)
+        U = rng.integers(0, U_max + 1, size=B).astype(np.int32)
+        desc = Bd.make_desc(B, T_max, U_max, H, V, 0, Bd.RNNT_BF16 if bf16 else Bd.RNNT_F32, **opts)
+        n_default = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 0)
+        n_min = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 1)
+        assert 0 < n_min <= n_default, (case, n_min, n_default)
+        tiles = ((T + 7) // 8).astype(np.int64) * ((U + 8) // 8)
+        rows = T.astype(np.int64) * (U + 1)
+        for budget in (n_default, n_min, int(rng.integers(n_min, n_default + 1)), n_default + int(rng.integers(1, 1 << 24))):
+            st, info, groups = Bd.rnnt_joint_loss_plan(desc, T, U, budget)
+            what = (case, opts, budget, info)
+            assert st == 0, what
+            assert info["workspace_bytes"] <= budget, what
+            assert groups.min() == 0 and np.all(np.diff(groups) >= 0) and np.all(np.diff(groups) <= 1), what
+            assert groups.max() + 1 == info["n_groups"] and info["n_chunks"] >= info["n_groups"], what
+            assert info["rows_total"] == rows.sum() and info["tiles_total"] == tiles.sum(), what
+            for g in range(info["n_groups"]):
+                m = groups == g
+                assert rows[m].sum() <= info["group_rows_cap"] or m.sum() == 1, what
+                if opts.get("keep_scores"):
+                    assert tiles[m].sum() * 64 <= info["chunk_rows"], what
+            if opts.get("keep_scores"):
+                assert info["n_chunks"] == info["n_groups"], what
+            if bf16:
+                assert info["chunk_rows"] % 128 == 0 and info["chunk_rows"] >= 128, what
+        assert Bd.rnnt_joint_loss_plan(desc, T, U, n_min - 256)[0] == 5, case
+
+
 def test_projected_entry_point_checks_and_workspace():
     wl, desc, T, U = _lens("C2")
     L = Bd.lib()
