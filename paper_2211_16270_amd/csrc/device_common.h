@@ -67,6 +67,76 @@ __device__ __forceinline__ bf16x8 joint_tanh8(bf16x8 e, bf16x8 q, unsigned keep)
     return __builtin_bit_cast(bf16x8, w);
 }
 
+// The joint tile of a lattice tile (Eq. 4): zs[8 tl + ul][h] = tanh(enc[t0 + tl][h] + pred[u0 + ul][h]), bf16, row
+// pitch ZP, rows outside the sample zero (they read row 0 of their input).  enc / prd point at the sample's rows.
+// tanh(x) = 1 - 2 / (e^{2x} + 1) and e^{2(e+q)} = e^{2e} e^{2q}: a thread takes one 8-column piece of TG frames
+// and 4 label positions, forms the TG + 4 exponentials per column once and pays one reciprocal per element, half
+// the transcendental instructions of a tanh per element (at 1024 vocabulary entries building this tile costs a
+// third of the cycles of the tile's score MFMAs).  The product can neither overflow nor lose the small factor
+// while both exponents stay inside +-115 (|input| <= 40); a thread that sees a larger input computes its
+// elements from the sums instead.
+template <int NT, int TG>
+__device__ __forceinline__ void build_joint_tile(bf16_t* __restrict__ zs, int ZP, const bf16_t* __restrict__ enc,
+                                                 const bf16_t* __restrict__ prd, int H, const TilePos& tp, int tid) {
+    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+    constexpr int UG = 4, NUG = 8 / UG, NG = (8 / TG) * NUG;
+    constexpr float K2 = 2.0f * LOG2E_F;
+    const int cpr = H >> 3;
+    for (int item = tid; item < cpr * NG; item += NT) {
+        const int g = item / cpr, c = item - g * cpr;
+        const int tl0 = (g / NUG) * TG, ul0 = (g % NUG) * UG;
+        bf16x8 e[TG], q[UG];
+#pragma unroll
+        for (int i = 0; i < TG; ++i) {
+            const int t = tp.t0 + tl0 + i;
+            e[i] = *reinterpret_cast<const bf16x8*>(enc + (size_t)(t < tp.T ? t : 0) * H + c * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < UG; ++j) {
+            const int u = tp.u0 + ul0 + j;
+            q[j] = *reinterpret_cast<const bf16x8*>(prd + (size_t)(u <= tp.U ? u : 0) * H + c * 8);
+        }
+        float E[TG][8], Q[UG][8], big = 0.0f;
+#pragma unroll
+        for (int i = 0; i < TG; ++i)
+#pragma unroll
+            for (int k = 0; k < 8; k += 2) {
+                const float a0 = (float)e[i][k] * K2, a1 = (float)e[i][k + 1] * K2;
+                big = fmaxf(big, fmaxf(fabsf(a0), fabsf(a1)));
+                E[i][k] = __builtin_amdgcn_exp2f(a0);
+                E[i][k + 1] = __builtin_amdgcn_exp2f(a1);
+            }
+#pragma unroll
+        for (int j = 0; j < UG; ++j)
+#pragma unroll
+            for (int k = 0; k < 8; k += 2) {
+                const float a0 = (float)q[j][k] * K2, a1 = (float)q[j][k + 1] * K2;
+                big = fmaxf(big, fmaxf(fabsf(a0), fabsf(a1)));
+                Q[j][k] = __builtin_amdgcn_exp2f(a0);
+                Q[j][k + 1] = __builtin_amdgcn_exp2f(a1);
+            }
+        const bool by_product = (big <= 115.0f);
+#pragma unroll
+        for (int i = 0; i < TG; ++i)
+#pragma unroll
+            for (int j = 0; j < UG; ++j) {
+                const bool valid = (tp.t0 + tl0 + i < tp.T) && (tp.u0 + ul0 + j <= tp.U);
+                bf16x8 z;
+                if (by_product) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k)
+                        z[k] = (bf16_t)(1.0f - 2.0f * __builtin_amdgcn_rcpf(fmaf(E[i][k], Q[j][k], 1.0f)));
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) z[k] = (bf16_t)fast_tanh((float)e[i][k] + (float)q[j][k]);
+                }
+                u32x4_t w = __builtin_bit_cast(u32x4_t, z);
+                w &= valid ? ~0u : 0u;
+                *reinterpret_cast<u32x4_t*>(zs + (8 * (tl0 + i) + ul0 + j) * ZP + c * 8) = w;
+            }
+    }
+}
+
 // ln(e^a + e^b); either may be -inf.
 __device__ __forceinline__ float log_add_exp(float a, float b) {
     float m = fmaxf(a, b);

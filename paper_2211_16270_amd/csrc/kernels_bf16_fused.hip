@@ -60,34 +60,9 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
     const int b = tp.s;
     const long long chunk_row0 = (long long)blockIdx.x * FB_ROWS;
 
-    // ---- joint tile (Eq. 4): thread -> row r = tid % 64, column chunks c = tid/64 + 8*i
-    {
-        const bf16_t* enc = reinterpret_cast<const bf16_t*>(a.pr.enc) + (size_t)b * a.pr.T_max * H;
-        const bf16_t* prd = reinterpret_cast<const bf16_t*>(a.pr.pred) + (size_t)b * (a.pr.U_max + 1) * H;
-        const int r = tid & 63;
-        const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
-        const bool valid = (t < tp.T && u <= tp.U);
-        const unsigned keep = valid ? ~0u : 0u;              // rows outside the sample read row 0 and store zeros
-        const bf16_t* er = enc + (size_t)(valid ? t : 0) * H;
-        const bf16_t* qr = prd + (size_t)(valid ? u : 0) * H;
-        const int nch = H >> 6;                              // chunks per thread
-        for (int i0 = 0; i0 < nch; i0 += 8) {
-            bf16x8 e[8], q[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int c = (tid >> 6) + 8 * ((i0 + i < nch) ? i0 + i : 0);
-                e[i] = *reinterpret_cast<const bf16x8*>(er + c * 8);
-                q[i] = *reinterpret_cast<const bf16x8*>(qr + c * 8);
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (i0 + i < nch) {
-                    const int c = (tid >> 6) + 8 * (i0 + i);
-                    *reinterpret_cast<bf16x8*>(zs + r * ZP + c * 8) = joint_tanh8(e[i], q[i], keep);
-                }
-            }
-        }
-    }
+    // ---- joint tile (Eq. 4)
+    build_joint_tile<512, 2>(zs, ZP, reinterpret_cast<const bf16_t*>(a.pr.enc) + (size_t)b * a.pr.T_max * H,
+                             reinterpret_cast<const bf16_t*>(a.pr.pred) + (size_t)b * (a.pr.U_max + 1) * H, H, tp, tid);
     if (tid < 64) {
         const int r = tid;
         const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
