@@ -187,16 +187,23 @@ def test_uniform_scores_closed_form_at_the_largest_lattice():
     assert abs(float(got["db_out"][0]) - sum(for_b)) < 1e-2 * abs(sum(for_b))
 
 
-def test_bf16_saturated_joint_and_peaked_softmax():
+@pytest.mark.parametrize("scale", [8.0, 16.0])
+def test_bf16_saturated_joint_and_peaked_softmax(scale):
     # inputs 8x and weights 4x the benchmark's scale (powers of two keep them bf16 values): tanh is
     # saturated for most elements, the scores reach several tens, the softmax is close to one-hot and
-    # the per-sample loss is in the hundreds; nothing may overflow and the result must still match
+    # the per-sample loss is in the hundreds; nothing may overflow and the result must still match.
+    # At 16x some inputs lie beyond +-40, where the joint tile is built from the sums instead of from
+    # products of exponentials (and inputs of opposite sign and that size still cancel exactly).
     from dataclasses import replace
     wl = synth.custom_workload("peaky", B=3, T_max=29, U_max=13, H=256, V=512, dtype="bf16", index=124,
                                t_rule="uniform", t_lo=7, u_rule="uniform", u_lo=1)
     batch = synth.make_batch(wl)
-    batch = replace(batch, enc=batch.enc * 8.0, pred=batch.pred * 8.0, W_out=batch.W_out * 4.0,
+    batch = replace(batch, enc=batch.enc * scale, pred=batch.pred * scale, W_out=batch.W_out * 4.0,
                     b_out=(np.arange(wl.V, dtype=np.float32) % 7 - 3.0) * 2.0)
+    if scale > 8.0:
+        # a frame and a label position whose inputs are large and cancel: z = tanh(0) there, not 0 * inf
+        batch.enc[0, 2, :] = 64.0
+        batch.pred[0, 1, :] = -64.0
     got, ref = run_gpu(batch), run_oracle(batch)
     _say("peaky loss", ref["loss"])
     e, errs = assert_parity(got, ref, "bf16", "peaky")
