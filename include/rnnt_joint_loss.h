@@ -155,6 +155,9 @@ rnnt_status rnnt_validate_labels_host(const rnnt_desc* desc, const int32_t* labe
  * Floating-point sums into d_enc, d_pred and db_out (on the fp32 path also dW_out) use atomic
  * adds, so those results can differ in the last bits from run to run; the bf16 path's dW_out is
  * summed in a fixed order.  Calls that share a workspace must be ordered on one stream.
+ * The call enqueues its launches and returns without waiting; it must not be recorded into a HIP graph:
+ * its first operation copies the length tables from host memory the call owns only until it returns, and
+ * the schedule (number and size of the launches) is a function of those lengths.
  */
 rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc,
                                     const void* enc, const void* pred, const void* W_out,
