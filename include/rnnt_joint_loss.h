@@ -97,12 +97,14 @@ const char* rnnt_last_hip_error(void);
  *   only (partial sums: about 64 MiB while H*V <= 2^21, 32 bytes per element of W_out beyond),
  *   plus what the largest single sample needs; with desc->keep_scores the chunk buffers of that default
  *   hold up to 8 GiB, never more than the call's tile rows need, and the smallest plan holds the largest
- *   sample's rows: 2 (V + 64) + 2 (H + 64) + V / 16 bytes per row of its 8x8 lattice tiles).
+ *   sample's rows: 2 (V + 64) + 2 (H + 64) + V / 16 bytes per row of its 8x8 lattice tiles; with
+ *   desc->input_grads_bf16 up to 256 MiB more, for the float sums of d_enc and d_pred of one group).
  *   Otherwise the largest plan not exceeding budget_bytes; if
  *   even the smallest workable plan (one sample per group, one tile row per chunk) exceeds it,
  *   that smallest size is returned, so a result > budget_bytes means "budget too small".
- * Returns 0 on invalid arguments.  The result does not depend on B beyond the largest sample
- * once the default cap is reached (Section 5.2: memory almost independent of batch size).
+ * Returns 0 on invalid arguments.  Once the default cap is reached the result grows with B only by the
+ * tables (28 bytes per sample, 8 bytes per 8x8 lattice tile; Section 5.2: memory almost independent of
+ * batch size).
  */
 size_t rnnt_joint_loss_workspace_bytes(const rnnt_desc* desc, const int32_t* T_len_host,
                                        const int32_t* U_len_host, size_t budget_bytes);
