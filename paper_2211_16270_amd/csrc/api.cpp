@@ -296,8 +296,15 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
             const Chunk& c = plan.chunks[ci];
             if (bf16) {
                 const long long rows = (long long)(c.tile1 - c.tile0) * TILE_ROWS;
-                if (keep) {
-                    // the group's scores are in the chunk buffers already: one pass turns them into dh
+                if (keep && plan.fused) {
+                    // the group's scores are in the chunk buffers already: the fused kernel turns them into dh
+                    // on their way into the dz GEMM and writes dh back for the dW GEMM
+                    RNNT_HIP(timed(KC_BWD_FUSED, stream, [&] {
+                        return launch_bwd_fused_kept_bf16(pr, wv.wq, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
+                                                          wv.kept_max, d_enc, d_pred, stream);
+                    }));
+                } else if (keep) {
+                    // ... or, for joint sizes the fused kernel does not cover, one pass turns them into dh
                     RNNT_HIP(timed(KC_KEPT_TO_DH, stream, [&] {
                         return launch_kept_to_dh_bf16(pr, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
                                                       wv.kept_max, stream);

@@ -114,6 +114,11 @@ __host__ __device__ inline int chunk_pitch(int n) { return n + 64; }
 hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const void* Wq, const SampleTable& st,
                                  const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
                                  void* Z, float* d_enc, float* d_pred, hipStream_t stream);
+// The same for scores the forward pass has kept (launch_fwd_keep_bf16): `kept` holds them and leaves as dH; Z is
+// not touched.
+hipError_t launch_bwd_fused_kept_bf16(const Problem& pr, const void* Wq, const SampleTable& st, const LatticeState& ls,
+                                      int s0, int s1, int tile0, int tile1, void* kept, const float* kept_max,
+                                      float* d_enc, float* d_pred, hipStream_t stream);
 // Split-K GEMM Z^T dH over one chunk's rows: every (split, tile) workgroup adds its 256x256 partial
 // product to its own slot (`first` != 0: overwrites it), db += column sums of dH.  `splits` and the
 // slot buffer size follow dw_split_count / dw_slot_bytes (plan.h).

@@ -37,11 +37,16 @@ struct FusedArgs {
     bf16_t* Z;          // [chunk rows, H]
     float* d_enc;
     float* d_pred;
+    const float* kept_max;   // KEPT: running maxima of the kept scores, [chunk tiles][V/64][64 rows]
 };
 
 // HT = hidden 32-tiles per dz wave = ceil(H / 128); FB_PF = fragment prefetch distance of the score loop in
-// k16-steps (H/16 must be a multiple of 2*FB_PF); PB = the same for the dz loop
-template <int HT, int FB_PF, int PB>
+// k16-steps (H/16 must be a multiple of 2*FB_PF); PB = the same for the dz loop.
+// KEPT: the forward pass has kept the scores (dH holds them as fp16 differences t to the running maxima
+// kept_max, Z the joint tile): the score waves then only read their 64 x 64 piece of t, turn it into dh
+// (one exponential per element), lay it into the LDS buffer and write it back over t for the dW_out GEMM;
+// no score MFMAs, no copy-out of Z.
+template <int HT, int FB_PF, int PB, bool KEPT>
 __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int H = a.pr.H, V = a.pr.V;
@@ -94,7 +99,72 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
     const int w4 = __builtin_amdgcn_readfirstlane(wave & 3);
     const unsigned lane_b = (unsigned)lane * 16u;
 
-    if (wave < 4) {
+    if (KEPT && wave < 4) {
+        // =========================== score waves, scores kept ===========================
+        typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+        const int seg = lane & 7, r0 = lane >> 3;          // rows r0 + 8 i, eight entries at 64 w4 + 8 seg
+        const size_t DL = chunk_pitch(V);
+        bf16_t* piece = a.dH + (size_t)chunk_row0 * DL + w4 * 64 + seg * 8;
+        const float* mx = a.kept_max + ((size_t)blockIdx.x * (V / 64) + w4) * 64;
+        float g[8], vB[8], vY[8];
+        int lb[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = r0 + 8 * i;
+            g[i] = row_g[row];
+            vB[i] = row_B[row];
+            vY[i] = row_Y[row];
+            lb[i] = row_lab[row];
+        }
+        f16x8 tn[8];
+        float mn[8];
+        auto fetch = [&](int step) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = r0 + 8 * i;
+                tn[i] = __builtin_nontemporal_load(reinterpret_cast<const f16x8*>(piece + (size_t)row * DL + step * FB_VSTEP));
+                mn[i] = mx[(size_t)step * 4 * 64 + row];
+            }
+        };
+        fetch(0);
+        for (int vs = 0; vs < nvs; ++vs) {
+            bf16_t* buf = dhs + (vs & 1) * (FB_ROWS * FB_DP);
+            f16x8 t[8];
+            float e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                t[i] = tn[i];
+                e[i] = fmaf(mn[i], LOG2E_F, g[i]);
+            }
+            fetch(vs + 1 < nvs ? vs + 1 : vs);             // one step ahead (the last step reads its own again)
+            const int cbase = vs * FB_VSTEP + w4 * 64 + seg * 8;
+            const int relb = a.pr.blank - cbase;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = r0 + 8 * i;
+                float d[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) d[k] = __builtin_amdgcn_exp2f(fmaf((float)t[i][k], LOG2E_F, e[i]));
+                // the blank / label entry of the row takes its final value from the stored log-probabilities
+                const int rely = lb[i] - cbase;
+                if ((unsigned)relb < 8u || (unsigned)rely < 8u) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        if (k == relb) d[k] = vB[i];
+                        if (k == rely) d[k] = vY[i];
+                    }
+                }
+                bf16x8 o;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) o[k] = (bf16_t)d[k];
+                *reinterpret_cast<bf16x8*>(buf + row * FB_DP + w4 * 64 + seg * 8) = o;
+                __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(piece + (size_t)row * DL + vs * FB_VSTEP));
+            }
+            __syncthreads();    // barrier vs: this step's buffer is complete
+        }
+        return;
+    }
+    if (!KEPT && wave < 4) {
         // =========================== score waves ===========================
         const int nkb = KK / FB_PF;
         const int lab[2] = {row_lab[l32], row_lab[32 + l32]};
@@ -227,7 +297,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
     // =========================== dz waves ===========================
     // joint tile -> Z chunk buffer (row-major, coalesced 16-byte stores) for the dW GEMM, while the score
     // waves work on the first step
-    {
+    if (!KEPT) {
         const int t4 = tid - 256;
         const int cpr = H >> 3;                              // 16-byte chunks per row
         const int drow = 256 / cpr, dch = 256 - drow * cpr;
@@ -357,18 +427,18 @@ static size_t fused_smem_bytes(int H) {
     return (size_t)FB_ROWS * (H + 8) * 2 + (size_t)2 * FB_ROWS * FB_DP * 2 + 64 * 4 * 4;
 }
 
-template <int HT, int FB_PF, int PB>
+template <int HT, int FB_PF, int PB, bool KEPT>
 static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t stream) {
     const int n = a.tile1 - a.tile0;
     const size_t smem = fused_smem_bytes(a.pr.H);
     static size_t configured = 0;
     if (smem > configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_bwd_fused<HT, FB_PF, PB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_joint_bwd_fused<HT, FB_PF, PB, KEPT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         configured = smem;
     }
-    k_joint_bwd_fused<HT, FB_PF, PB><<<dim3((unsigned)n), dim3(512), smem, stream>>>(a);
+    k_joint_bwd_fused<HT, FB_PF, PB, KEPT><<<dim3((unsigned)n), dim3(512), smem, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -377,14 +447,29 @@ hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const voi
                                  float* d_enc, float* d_pred, hipStream_t stream) {
     if (tile1 <= tile0) return hipSuccess;
     FusedArgs a{pr, st, ls, (const bf16_t*)Wpack, (const bf16_t*)Wq, s0, s1, tile0, tile1,
-                (bf16_t*)dH, (bf16_t*)Z, d_enc, d_pred};
+                (bf16_t*)dH, (bf16_t*)Z, d_enc, d_pred, nullptr};
     const int ht = (pr.H / 32 + 3) / 4;
     // H = 128 ... 640 in steps of 128: H/16 = 8, 16, 24, 32, 40 k16-steps
-    if (ht <= 1) return launch_fused_t<1, 4, 4>(a, stream);
-    if (ht == 2) return launch_fused_t<2, 8, 4>(a, stream);
-    if (ht == 3) return launch_fused_t<3, 4, 2>(a, stream);
-    if (ht == 4) return launch_fused_t<4, 8, 2>(a, stream);
-    if (ht == 5) return launch_fused_t<5, 4, 1>(a, stream);
+    if (ht <= 1) return launch_fused_t<1, 4, 4, false>(a, stream);
+    if (ht == 2) return launch_fused_t<2, 8, 4, false>(a, stream);
+    if (ht == 3) return launch_fused_t<3, 4, 2, false>(a, stream);
+    if (ht == 4) return launch_fused_t<4, 8, 2, false>(a, stream);
+    if (ht == 5) return launch_fused_t<5, 4, 1, false>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_bwd_fused_kept_bf16(const Problem& pr, const void* Wq, const SampleTable& st, const LatticeState& ls,
+                                      int s0, int s1, int tile0, int tile1, void* kept, const float* kept_max,
+                                      float* d_enc, float* d_pred, hipStream_t stream) {
+    if (tile1 <= tile0) return hipSuccess;
+    FusedArgs a{pr, st, ls, nullptr, (const bf16_t*)Wq, s0, s1, tile0, tile1,
+                (bf16_t*)kept, nullptr, d_enc, d_pred, kept_max};
+    const int ht = (pr.H / 32 + 3) / 4;
+    if (ht <= 1) return launch_fused_t<1, 4, 4, true>(a, stream);
+    if (ht == 2) return launch_fused_t<2, 8, 4, true>(a, stream);
+    if (ht == 3) return launch_fused_t<3, 4, 2, true>(a, stream);
+    if (ht == 4) return launch_fused_t<4, 8, 2, true>(a, stream);
+    if (ht == 5) return launch_fused_t<5, 4, 1, true>(a, stream);
     return hipErrorInvalidValue;
 }
 

@@ -99,7 +99,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     p.B = B;
     p.bf16 = (d.dtype == RNNT_BF16);
     p.keep = p.bf16 && d.keep_scores;
-    p.fused = p.bf16 && !p.keep && fused_backward_shape(d.H, d.V);
+    p.fused = p.bf16 && fused_backward_shape(d.H, d.V);
     p.stage = p.bf16 && d.input_grads_bf16;
     const size_t stage_per_sample = ((size_t)d.T_max + d.U_max + 1) * d.H * 4;
     p.tile_off.assign(B + 1, 0);
