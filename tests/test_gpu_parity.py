@@ -211,6 +211,17 @@ def test_bf16_saturated_joint_and_peaked_softmax(scale):
     assert_padding_zero(got, batch)
 
 
+def test_mfma_loop_of_the_measurement_entry_point_multiplies():
+    # ones times ones: every MFMA adds 16 to each accumulator element; the checksum of a lane is the sum of two
+    # elements of each of its 16 accumulator tiles
+    import torch
+    frags = torch.ones(32 * 64 * 8, dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros(3 * 256, dtype=torch.float32, device="cuda")
+    assert Bd.rnnt_debug_mfma_loop(frags, out, 3, 5) == 0
+    torch.cuda.synchronize()
+    assert bool((out == 16 * 2 * 16.0 * 5).all())
+
+
 # ------------------------------------------------------------------ scores kept instead of computed twice
 @pytest.mark.parametrize("H,V", [(128, 256), (640, 1024), (896, 256), (1024, 512), (256, 768), (1024, 4096)])
 def test_bf16_kept_scores_match_the_checker_and_the_default_path(H, V):

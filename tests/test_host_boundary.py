@@ -28,6 +28,13 @@ def test_library_exports_every_declared_symbol():
         assert len(L.rnnt_status_string(code)) > 3
 
 
+def test_no_hip_error_is_reported_before_one_happened():
+    assert Bd.lib().rnnt_last_hip_error() == b""
+    assert Bd.lib().rnnt_debug_mfma_loop(None, None, 1, 1, None) == 1   # null pointers are refused on the host
+    assert Bd.lib().rnnt_debug_mfma_loop(ctypes.c_void_p(256), ctypes.c_void_p(256), 0, 1, None) == 2
+    assert Bd.lib().rnnt_debug_mfma_loop(ctypes.c_void_p(256), ctypes.c_void_p(256), 1, 2000000, None) == 2
+
+
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(Bd.RnntDesc) == 40
     assert ctypes.sizeof(Bd.RnntPlanInfo) == 8 * 3 + 4 * 2 + 8 * 2 + 8 * 3
