@@ -453,7 +453,7 @@ hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const voi
     if (ht <= 1) return launch_fused_t<1, 4, 4, false>(a, stream);
     if (ht == 2) return launch_fused_t<2, 8, 4, false>(a, stream);
     if (ht == 3) return launch_fused_t<3, 4, 2, false>(a, stream);
-    if (ht == 4) return launch_fused_t<4, 8, 2, false>(a, stream);
+    if (ht == 4) return launch_fused_t<4, 4, 2, false>(a, stream);    // (4, 4, 2) measured 1 % ahead of (4, 8, 2)
     if (ht == 5) return launch_fused_t<5, 4, 1, false>(a, stream);
     return hipErrorInvalidValue;
 }
