@@ -169,13 +169,14 @@ def _closed_form(T, U, V):
     raise KeyError((T, U, V))
 
 
-def test_uniform_scores_closed_form_at_the_largest_lattice():
+@pytest.mark.parametrize("opts", [{}, dict(keep_scores=1, input_grads_bf16=1)])
+def test_uniform_scores_closed_form_at_the_largest_lattice(opts):
     # W_out = 0: every emission has probability 1/V; checks the lattice kernel at T=1000, U=200
     wl = synth.custom_workload("uni", B=2, T_max=1000, U_max=200, H=128, V=1024, dtype="bf16", index=114)
     batch = synth.make_batch(wl, pad="zero")
     batch.W_out[:] = 0.0
     batch = synth.with_lengths(batch, [1000, 250], [200, 50], pad="zero")
-    got = run_gpu(batch)
+    got = run_gpu(batch, **opts)
     ref = np.array([_closed_form(1000, 200, 1024), _closed_form(250, 50, 1024)])
     _say("uniform", got["loss"], ref)
     assert rel_loss_err(got["loss"].astype(np.float64), ref) < 2e-6
