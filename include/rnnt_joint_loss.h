@@ -75,7 +75,7 @@ typedef struct {
 typedef struct {
     int64_t rows_total;       /* sum_b T_len[b] * (U_len[b] + 1): lattice nodes without padding */
     int64_t rows_padded;      /* B * T_max * (U_max + 1)                                       */
-    int64_t tiles_total;      /* 8x8 lattice tiles over all samples                            */
+    int64_t tiles_total;      /* 64-node lattice tiles (8 x 8 or 16 x 4 per sample) over all samples */
     int32_t n_groups;         /* launches of the forward/lattice stage; samples of a group run together */
     int32_t n_chunks;         /* launches of the backward stage (row ranges of <= chunk_rows)  */
     int64_t group_rows_cap;   /* lattice rows that fit one group                               */
@@ -97,13 +97,13 @@ const char* rnnt_last_hip_error(void);
  *   only (partial sums: about 64 MiB while H*V <= 2^21, 32 bytes per element of W_out beyond),
  *   plus what the largest single sample needs; with desc->keep_scores the chunk buffers of that default
  *   hold up to 8 GiB, never more than the call's tile rows need, and the smallest plan holds the largest
- *   sample's rows: 2 (V + 64) + 2 (H + 64) + V / 16 bytes per row of its 8x8 lattice tiles; with
+ *   sample's rows: 2 (V + 64) + 2 (H + 64) + V / 16 bytes per row of its 64-node lattice tiles; with
  *   desc->input_grads_bf16 up to 256 MiB more, for the float sums of d_enc and d_pred of one group).
  *   Otherwise the largest plan not exceeding budget_bytes; if
  *   even the smallest workable plan (one sample per group, one tile row per chunk) exceeds it,
  *   that smallest size is returned, so a result > budget_bytes means "budget too small".
  * Returns 0 on invalid arguments.  Once the default cap is reached the result grows with B only by the
- * tables (28 bytes per sample, 8 bytes per 8x8 lattice tile; Section 5.2: memory almost independent of
+ * tables (28 bytes per sample, 8 bytes per 64-node lattice tile; Section 5.2: memory almost independent of
  * batch size).
  */
 size_t rnnt_joint_loss_workspace_bytes(const rnnt_desc* desc, const int32_t* T_len_host,

@@ -29,9 +29,10 @@ __device__ __forceinline__ int find_segment(const T* __restrict__ off, int lo, i
     return lo;
 }
 
-// Position of an 8x8 lattice tile: sample, first frame, first label position.
+// Position of a lattice tile: sample, first frame, first label position, and the sample's tile shape
+// (uw = 8 or 4 label positions, us = log2 uw; row r of the tile is frame t0 + (r >> us), label u0 + (r & (uw-1))).
 struct TilePos {
-    int s, T, U, t0, u0;
+    int s, T, U, t0, u0, uw, us;
 };
 
 __device__ __forceinline__ TilePos locate_tile(const SampleTable& st, int s0, int s1, int tile) {
@@ -41,11 +42,13 @@ __device__ __forceinline__ TilePos locate_tile(const SampleTable& st, int s0, in
     p.s = st.tile_sample[tile];
     p.T = st.T[p.s];
     p.U = st.U[p.s];
-    const int tiles_u = (p.U + 8) >> 3;           // ceil((U+1)/8)
+    p.uw = tile_label_width(p.T, p.U);
+    p.us = p.uw == 8 ? 3 : 2;
+    const int tiles_u = (p.U + p.uw) >> p.us;     // ceil((U+1)/uw)
     const int lt = tile - st.tile_off[p.s];
     const int tb = lt / tiles_u;
-    p.t0 = tb * 8;
-    p.u0 = (lt - tb * tiles_u) * 8;
+    p.t0 = tb * (64 >> p.us);
+    p.u0 = (lt - tb * tiles_u) << p.us;
     return p;
 }
 
@@ -67,7 +70,7 @@ __device__ __forceinline__ bf16x8 joint_tanh8(bf16x8 e, bf16x8 q, unsigned keep)
     return __builtin_bit_cast(bf16x8, w);
 }
 
-// The joint tile of a lattice tile (Eq. 4): zs[8 tl + ul][h] = tanh(enc[t0 + tl][h] + pred[u0 + ul][h]), bf16, row
+// The joint tile of a lattice tile (Eq. 4): zs[uw tl + ul][h] = tanh(enc[t0 + tl][h] + pred[u0 + ul][h]), bf16, row
 // pitch ZP, rows outside the sample zero (they read row 0 of their input).  enc / prd point at the sample's rows.
 // tanh(x) = 1 - 2 / (e^{2x} + 1) and e^{2(e+q)} = e^{2e} e^{2q}: a thread takes one 8-column piece of TG frames
 // and 4 label positions, forms the TG + 4 exponentials per column once and pays one reciprocal per element, half
@@ -79,12 +82,13 @@ template <int NT, int TG>
 __device__ __forceinline__ void build_joint_tile(bf16_t* __restrict__ zs, int ZP, const bf16_t* __restrict__ enc,
                                                  const bf16_t* __restrict__ prd, int H, const TilePos& tp, int tid) {
     typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-    constexpr int UG = 4, NUG = 8 / UG, NG = (8 / TG) * NUG;
+    constexpr int UG = 4, NG = 16 / TG;          // 16 / TG groups of TG frames x 4 label positions for either shape
     constexpr float K2 = 2.0f * LOG2E_F;
     const int cpr = H >> 3;
+    const int nug = tp.uw >> 2;                  // groups side by side along the labels: 2 or 1
     for (int item = tid; item < cpr * NG; item += NT) {
         const int g = item / cpr, c = item - g * cpr;
-        const int tl0 = (g / NUG) * TG, ul0 = (g % NUG) * UG;
+        const int tl0 = (nug == 2 ? g >> 1 : g) * TG, ul0 = (nug == 2 ? g & 1 : 0) * UG;
         bf16x8 e[TG], q[UG];
 #pragma unroll
         for (int i = 0; i < TG; ++i) {
@@ -132,7 +136,7 @@ __device__ __forceinline__ void build_joint_tile(bf16_t* __restrict__ zs, int ZP
                 }
                 u32x4_t w = __builtin_bit_cast(u32x4_t, z);
                 w &= valid ? ~0u : 0u;
-                *reinterpret_cast<u32x4_t*>(zs + (8 * (tl0 + i) + ul0 + j) * ZP + c * 8) = w;
+                *reinterpret_cast<u32x4_t*>(zs + (((tl0 + i) << tp.us) + ul0 + j) * ZP + c * 8) = w;
             }
     }
 }

@@ -11,7 +11,7 @@ namespace rnnt {
 struct SampleTable {
     const int* T;              // [B] T_len
     const int* U;              // [B] U_len
-    const int* tile_off;       // [B+1] cumulative 8x8 lattice-tile counts
+    const int* tile_off;       // [B+1] cumulative lattice-tile counts (64 nodes per tile)
     const int* tile_sample;    // [tiles] sample that owns each tile (filled by launch_prepare)
     const long long* row_off;  // [B+1] cumulative lattice-node counts
 };
@@ -104,6 +104,19 @@ hipError_t launch_kept_to_dh_bf16(const Problem& pr, const SampleTable& st, cons
 hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0,
                                int tile1, const void* dH, float* d_enc, float* d_pred,
                                hipStream_t stream);
+// Shape of a sample's lattice tiles (64 rows each): 8 frames x 8 label positions, or 16 x 4 where that covers the
+// sample's T x (U + 1) lattice with at least 3 % fewer tiles (the padding rows of partly filled tiles cost as
+// much as real ones; a 16 x 4 tile adds to 20 rows of d_enc / d_pred instead of 16, which costs about 2 %).
+// Returns the label positions per tile, 8 or 4; a tile then has 64 / that many frames, and row r of a tile is
+// frame r / uw, label position r % uw.
+__host__ __device__ inline int tile_label_width(int T, int U) {
+    const long long a = (long long)((T + 7) / 8) * ((U + 8) / 8), b = (long long)((T + 15) / 16) * ((U + 4) / 4);
+    return b * 33 < a * 32 ? 4 : 8;
+}
+__host__ __device__ inline long long sample_tiles(int T, int U) {
+    const int uw = tile_label_width(T, U), th = 64 / uw;
+    return (long long)((T + th - 1) / th) * ((U + uw) / uw);
+}
 // Row pitch (elements) of the two bf16 chunk buffers Z [rows, H] and dH [rows, V]: one 128-byte line more
 // than the row, so that rows whose length is a power of two do not all start in the same memory channel.
 __host__ __device__ inline int chunk_pitch(int n) { return n + 64; }

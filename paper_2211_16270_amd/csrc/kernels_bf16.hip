@@ -1,9 +1,10 @@
 // bf16 MFMA path (gfx950): joint tile in LDS -> score GEMM -> softmax statistics / score gradients,
 // and the two backward GEMMs.  fp32 accumulation everywhere; tanh, exp, softmax in fp32.
 //
-// Work unit: an 8x8 lattice tile of one sample (8 frames x 8 label positions = 64 rows, row
-// r = 8*tl + ul).  Such a tile needs only 8 + 8 input vectors, and its contribution to d_enc /
-// d_pred can be summed over ul resp. tl before it leaves the registers.
+// Work unit: a lattice tile of one sample: 8 frames x 8 label positions = 64 rows, row r = 8*tl + ul, or
+// 16 x 4 (r = 4*tl + ul) where that covers the sample with fewer tiles.  Such a tile needs only 8 + 8
+// (16 + 4) input vectors, and its contribution to d_enc / d_pred can be summed over ul resp. tl before
+// it leaves the registers.
 //
 // MFMA operand layouts used below (v_mfma_f32_32x32x16_bf16, D = A B + C, wave64):
 //   A (32 x 16): lane l holds row l%32, k = 8*(l/32) .. +7        (8 bf16)
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
                                             H, tp, tid);
     if (tid < 64) {
         const int r = tid;
-        const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
+        const int t = tp.t0 + (r >> tp.us), u = tp.u0 + (r & (tp.uw - 1));
         const bool valid = (t < tp.T && u <= tp.U);
         const long long idx = (a.st.row_off[b] - a.ls.row_base) + (long long)t * (tp.U + 1) + u;
         row_lat[r] = valid ? (int)idx : -1;
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
                 a.ls.lpb[idx] = row_f0[r] - lse;
                 a.ls.lpy[idx] = (row_lab[r] >= 0) ? row_f1[r] - lse : 0.0f;
                 // this node's share of the sum the lattice kernels take their per-sample offset from
-                const bool has_label = tp.u0 + (r & 7) < tp.U;
+                const bool has_label = tp.u0 + (r & (tp.uw - 1)) < tp.U;
                 esum = has_label ? fmaxf(row_f0[r], row_f1[r]) - lse : row_f0[r] - lse;
             }
             esum = wave_sum(esum);
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(256) void k_kept_to_dh(JointArgs a) {
     const int b = tp.s;
     if (tid < 64) {
         const int r = tid;
-        const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
+        const int t = tp.t0 + (r >> tp.us), u = tp.u0 + (r & (tp.uw - 1));
         const bool valid = (t < tp.T && u <= tp.U);
         row_lab[r] = (valid && u < tp.U) ? a.pr.labels[(size_t)b * a.pr.U_max + u] : -1;
         float g = RNNT_NEG_INF, bk = 0.0f, yk = 0.0f;

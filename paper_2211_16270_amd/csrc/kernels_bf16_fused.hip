@@ -1,4 +1,4 @@
-// Fused backward kernel of the bf16 MFMA path (gfx950): for one 8x8 lattice tile (64 rows)
+// Fused backward kernel of the bf16 MFMA path (gfx950): for one lattice tile (64 rows: 8 frames x 8 label positions, or 16 x 4)
 //   joint tile z = tanh(enc_t + pred_u) in LDS                                  (Eq. 4)
 //   scores recomputed on MFMA, dh = gamma * softmax - posteriors               (Eq. 6, f^W_4)
 //   dz = dh W_out^T accumulated over the whole vocabulary in registers           (Alg. 1 lines 10, 11)
@@ -18,6 +18,8 @@
 // MFMAs of the other wave on its SIMD: while a score wave computes exponentials, the dz wave next to it
 // keeps the matrix pipe busy.  One workgroup barrier per step separates writers and readers of a buffer.
 // MFMA operand layouts: see kernels_bf16.hip.
+#include <type_traits>
+
 #include "device_common.h"
 
 namespace rnnt {
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
                              reinterpret_cast<const bf16_t*>(a.pr.pred) + (size_t)b * (a.pr.U_max + 1) * H, H, tp, tid);
     if (tid < 64) {
         const int r = tid;
-        const int t = tp.t0 + (r >> 3), u = tp.u0 + (r & 7);
+        const int t = tp.t0 + (r >> tp.us), u = tp.u0 + (r & (tp.uw - 1));
         const bool valid = (t < tp.T && u <= tp.U);
         row_lab[r] = (valid && u < tp.U) ? a.pr.labels[(size_t)b * a.pr.U_max + u] : -1;
         if (valid) {
@@ -389,37 +391,56 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
     }
 
     // ---- Alg. 1 lines 10, 11: dx = dz (1 - z^2); sum over label positions -> d_enc, over frames -> d_pred.
-    // Accumulator register 4j+i of row tile rt is tile row 32 rt + 8j + 4 hb + i: frame 4 rt + j, label 4 hb + i.
+    // Accumulator register 4j+i of row tile rt is tile row r = 32 rt + 8j + 4 hb + i: in an 8 x 8 tile frame
+    // 4 rt + j, label 4 hb + i (a frame's eight labels are spread over the two lane halves); in a 16 x 4 tile frame
+    // 8 rt + 2j + hb, label i (a label's sixteen frames are).
     {
         float* d_enc = a.d_enc + (size_t)b * a.pr.T_max * H;
         float* d_prd = a.d_pred + (size_t)b * (a.pr.U_max + 1) * H;
+        // one copy of the loop nest per tile shape (the shape is the same for the whole workgroup)
+        auto reduce = [&](auto wide_tag) {
+            constexpr bool WIDE = decltype(wide_tag)::value;
 #pragma unroll
-        for (int i = 0; i < HT; ++i) {
-            const int ht = w4 + 4 * i;
-            if (ht >= nht) continue;
-            const int h = ht * 32 + l32;
-            float pu[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int i = 0; i < HT; ++i) {
+                const int ht = w4 + 4 * i;
+                if (ht >= nht) continue;
+                const int h = ht * 32 + l32;
+                float pu[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
+                for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int tl = 4 * rt + j;
-                    float se = 0.0f;
+                    for (int j = 0; j < 4; ++j) {
+                        float se = 0.0f;
 #pragma unroll
-                    for (int ii = 0; ii < 4; ++ii) {
-                        const int r = rt * 32 + 8 * j + 4 * hb + ii;
-                        const float z = (float)zs[r * ZP + h];
-                        const float dx = dz[i][rt][4 * j + ii] * (1.0f - z * z);
-                        se += dx;
-                        pu[ii] += dx;
+                        for (int ii = 0; ii < 4; ++ii) {
+                            const int r = rt * 32 + 8 * j + 4 * hb + ii;
+                            const float z = (float)zs[r * ZP + h];
+                            const float dx = dz[i][rt][4 * j + ii] * (1.0f - z * z);
+                            se += dx;
+                            pu[ii] += dx;
+                        }
+                        if (WIDE) {
+                            const int tl = 4 * rt + j;
+                            se += __shfl_xor(se, 32, 64);
+                            if (hb == (j & 1) && tp.t0 + tl < tp.T) atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
+                        } else {
+                            const int t16 = tp.t0 + 8 * rt + 2 * j + hb;
+                            if (t16 < tp.T) atomicAdd(&d_enc[(size_t)t16 * H + h], se);
+                        }
                     }
-                    se += __shfl_xor(se, 32, 64);
-                    if (hb == (j & 1) && tp.t0 + tl < tp.T) atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
-                }
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii)
-                if (tp.u0 + 4 * hb + ii <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + 4 * hb + ii) * H + h], pu[ii]);
-        }
+                for (int ii = 0; ii < 4; ++ii) {
+                    if (WIDE) {
+                        if (tp.u0 + 4 * hb + ii <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + 4 * hb + ii) * H + h], pu[ii]);
+                    } else {
+                        const float both = pu[ii] + __shfl_xor(pu[ii], 32, 64);
+                        if (hb == (ii & 1) && tp.u0 + ii <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + ii) * H + h], both);
+                    }
+                }
+            }
+        };
+        if (tp.uw == 8) reduce(std::true_type{});
+        else reduce(std::false_type{});
     }
 }
 

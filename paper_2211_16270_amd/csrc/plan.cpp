@@ -107,7 +107,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     long long max_rows = 0, max_tile_rows = 0;
     for (int b = 0; b < B; ++b) {
         long long rows = (long long)T_len[b] * (U_len[b] + 1);
-        long long tiles = (long long)((T_len[b] + TILE_T - 1) / TILE_T) * ((U_len[b] + 1 + TILE_U - 1) / TILE_U);
+        long long tiles = sample_tiles(T_len[b], U_len[b]);
         p.row_off[b + 1] = p.row_off[b] + rows;
         p.tile_off[b + 1] = (int)(p.tile_off[b] + tiles);
         max_rows = std::max(max_rows, rows);

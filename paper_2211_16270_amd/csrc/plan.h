@@ -3,7 +3,7 @@
 //
 // The paper recovers parallelism lost by sample-wise processing by running several loop
 // iterations of Algorithm 1 at once, as many as a memory limit allows (Section 4.1.2, Eq. 11).
-// Here the same idea is a packing problem: samples are cut into 8x8 lattice tiles, the tiles of
+// Here the same idea is a packing problem: samples are cut into lattice tiles of 64 nodes (8 frames x 8 label positions, or 16 x 4), the tiles of
 // all samples of a *group* are processed by one launch, and a group holds as many samples as
 // its per-node state (5 floats per lattice node) fits the workspace.  The backward pass walks a
 // group in *chunks* of tiles whose bf16 score-gradient buffers fit the rest of the workspace.
@@ -16,9 +16,7 @@
 
 namespace rnnt {
 
-constexpr int TILE_T = 8;     // lattice tile: 8 frames x 8 label positions = 64 rows
-constexpr int TILE_U = 8;
-constexpr int TILE_ROWS = TILE_T * TILE_U;
+constexpr int TILE_ROWS = 64;    // lattice tile: 8 frames x 8 label positions or 16 x 4 (kernels.h: tile_label_width)
 constexpr int GEMM_TILE = 128;   // row granularity of the backward GEMMs (two lattice tiles)
 constexpr size_t WS_ALIGN = 256;
 

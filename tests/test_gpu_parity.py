@@ -93,6 +93,7 @@ def test_bf16_mid_shape_full_parity_and_lattice():
     ([1, 1, 8, 9], [0, 7, 0, 8], 0),
     ([37, 16, 17, 1], [19, 15, 16, 19], 5),
     ([8, 8, 8, 8], [7, 7, 7, 7], 255),
+    ([16, 8, 32, 5], [3, 7, 11, 2], 0),          # one 16 x 4 tile; one 8 x 8 tile; 16 x 4 tiles, three wide; one partly filled
 ])
 def test_bf16_edge_lattices(T_len, U_len, blank):
     batch = synth.with_lengths(synth.make_batch(_mid_bf16(111, t_rule="full", u_rule="full")), T_len, U_len)

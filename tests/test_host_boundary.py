@@ -40,6 +40,13 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(Bd.RnntPlanInfo) == 8 * 3 + 4 * 2 + 8 * 2 + 8 * 3
 
 
+def _tiles(T, U):
+    """64-row lattice tiles per sample: 8 frames x 8 label positions, or 16 x 4 where that needs 3 % fewer."""
+    T, U = np.asarray(T, dtype=np.int64), np.asarray(U, dtype=np.int64)
+    a, b = ((T + 7) // 8) * ((U + 8) // 8), ((T + 15) // 16) * ((U + 4) // 4)
+    return np.where(b * 33 < a * 32, b, a)
+
+
 def _lens(name):
     wl = synth.WORKLOADS[name]
     T, U, _ = synth.draw_lengths_labels(wl)
@@ -124,7 +131,7 @@ def test_default_plan_properties(name):
     rows = T.astype(np.int64) * (U.astype(np.int64) + 1)
     assert info["rows_total"] == rows.sum()
     assert info["rows_padded"] == wl.B * wl.T_max * (wl.U_max + 1)
-    tiles = ((T + 7) // 8).astype(np.int64) * ((U + 8) // 8)
+    tiles = _tiles(T, U)
     assert info["tiles_total"] == tiles.sum()
     assert info["workspace_bytes"] <= n
     # every sample in exactly one group, groups are consecutive, each fits the lattice capacity
@@ -186,7 +193,7 @@ def test_keep_scores_plan_has_one_backward_chunk_per_group_of_whole_samples():
     nmin = Bd.rnnt_joint_loss_workspace_bytes(keep, T, U, 1)
     st, small, groups = Bd.rnnt_joint_loss_plan(keep, T, U, nmin)
     assert st == 0 and small["n_chunks"] == small["n_groups"] > 1
-    tiles = ((T + 7) // 8) * ((U + 8) // 8)
+    tiles = _tiles(T, U)
     assert small["chunk_rows"] >= int(tiles.max()) * 64
     for g in range(small["n_groups"]):
         assert int(tiles[groups == g].sum()) * 64 <= small["chunk_rows"]
@@ -246,7 +253,7 @@ def test_random_plans_keep_their_promises():
         n_default = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 0)
         n_min = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 1)
         assert 0 < n_min <= n_default, (case, n_min, n_default)
-        tiles = ((T + 7) // 8).astype(np.int64) * ((U + 8) // 8)
+        tiles = _tiles(T, U)
         rows = T.astype(np.int64) * (U + 1)
         for budget in (n_default, n_min, int(rng.integers(n_min, n_default + 1)), n_default + int(rng.integers(1, 1 << 24))):
             st, info, groups = Bd.rnnt_joint_loss_plan(desc, T, U, budget)
@@ -266,6 +273,18 @@ def test_random_plans_keep_their_promises():
             if bf16:
                 assert info["chunk_rows"] % 128 == 0 and info["chunk_rows"] >= 128, what
         assert Bd.rnnt_joint_loss_plan(desc, T, U, n_min - 256)[0] == 5, case
+
+
+def test_tile_shape_per_sample():
+    # 8 x 8 tiles, or 16 x 4 where that covers the lattice with at least 3 % fewer tiles
+    desc = Bd.make_desc(5, 40, 20, 128, 256, 0, Bd.RNNT_BF16)
+    T = np.array([16, 8, 32, 40, 33], dtype=np.int32)
+    U = np.array([3, 7, 11, 20, 8], dtype=np.int32)
+    st, info, _ = Bd.rnnt_joint_loss_plan(desc, T, U, 0)
+    # 16 x 4: 1 (against 2); 8 x 8: 1; 16 x 4: 2 * 3 = 6 (against 4 * 2 = 8); 8 x 8: 5 * 3 = 15 (16 x 4: 3 * 6 = 18);
+    # 33 x 9: 8 x 8 gives 5 * 2 = 10, 16 x 4 gives 3 * 3 = 9
+    assert st == 0 and info["tiles_total"] == 1 + 1 + 6 + 15 + 9
+    assert info["tiles_total"] == int(_tiles(T, U).sum())
 
 
 def test_projected_entry_point_checks_and_workspace():
