@@ -11,6 +11,8 @@
 // makes the 16-byte fragment reads of 16 consecutive rows hit all 64 banks.  Fragments are read one
 // k16-step ahead of their MFMAs, also across the stage hand-over.  The epilogue recomputes
 // z = tanh(enc + pred) in fp32 from input rows staged in LDS.
+#include <type_traits>
+
 #include "device_common.h"
 
 namespace rnnt {
@@ -164,91 +166,106 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
     // ---- epilogue: dx = dz (1 - z^2) with z = tanh(enc + pred) recomputed in fp32, summed over the label
     // positions / frames of each lattice tile.  The input rows of the workgroup's four lattice tiles (8 + 8 or
     // 16 + 4 of them; this tile's 256 hidden columns) go through LDS, which the main loop no longer needs:
-    // per tile 24 row slots, frames in slots 0..15, label positions in slots 16..23.
+    // per tile 20 row slots, the tile's frames first, its label positions behind them.
+    __shared__ TilePos tpos[4];      // where the workgroup's four lattice tiles lie (s < 0: past the last tile)
+    if (tid < 4) {
+        const int tile = g.tile0 + bx * 4 + tid;
+        TilePos t{};
+        t.s = -1;
+        if (tile < g.tile1) t = locate_tile(g.st, g.s0, g.s1, tile);
+        tpos[tid] = t;
+    }
     __syncthreads();
-    bf16_t* eq = reinterpret_cast<bf16_t*>(dz_smem);              // [4 tiles][24 rows][Z_EP]
+    bf16_t* eq = reinterpret_cast<bf16_t*>(dz_smem);              // [4 tiles][20 rows][Z_EP]
     {
-        // 4 tiles x 24 rows x 32 chunks of 8 columns = 3072 chunks, 12 per thread
+        // 4 tiles x 20 rows x 32 chunks of 8 columns = 2560 chunks, 10 per thread
 #pragma unroll
-        for (int i = 0; i < 12; ++i) {
+        for (int i = 0; i < 10; ++i) {
             const int e = tid + 256 * i;
-            const int c = e & 31, r = (e >> 5) % 24, t4 = e / (32 * 24);
-            const int tile = g.tile0 + bx * 4 + t4;
+            const int c = e & 31, r = (e >> 5) % 20, t4 = e / (32 * 20);
+            const TilePos tp = tpos[t4];
             bf16x8 v;
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[j] = (bf16_t)0.0f;
-            if (tile < g.tile1 && n0 + c * 8 < H) {
-                const TilePos tp = locate_tile(g.st, g.s0, g.s1, tile);
-                if (r < 16) {
-                    if (r < (64 >> tp.us) && tp.t0 + r < tp.T)
+            if (tp.s >= 0 && n0 + c * 8 < H) {
+                const int th = 64 >> tp.us;
+                if (r < th) {
+                    if (tp.t0 + r < tp.T)
                         v = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(g.pr.enc) +
                                                              ((size_t)tp.s * g.pr.T_max + tp.t0 + r) * H + n0 + c * 8);
-                } else if (r - 16 < tp.uw && tp.u0 + r - 16 <= tp.U) {
+                } else if (r - th < tp.uw && tp.u0 + r - th <= tp.U) {
                     v = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(g.pr.pred) +
-                                                         ((size_t)tp.s * (g.pr.U_max + 1) + tp.u0 + r - 16) * H + n0 + c * 8);
+                                                         ((size_t)tp.s * (g.pr.U_max + 1) + tp.u0 + r - th) * H + n0 + c * 8);
                 }
             }
-            *reinterpret_cast<bf16x8*>(eq + (t4 * 24 + r) * Z_EP + c * 8) = v;
+            *reinterpret_cast<bf16x8*>(eq + (t4 * 20 + r) * Z_EP + c * 8) = v;
         }
     }
     __syncthreads();
     // Rows wm*128 + 64*lt .. +63 are one lattice tile; accumulator register 4j+i of row block mt = 2*lt + m2 is
     // tile row r = 32 m2 + 8j + 4 hb + i, hidden column l32: in an 8 x 8 tile frame 4 m2 + j, label 4 hb + i; in a
-    // 16 x 4 tile frame 8 m2 + 2j + hb, label i.
-#pragma unroll
-    for (int lt = 0; lt < 2; ++lt) {
+    // 16 x 4 tile frame 8 m2 + 2j + hb, label i.  One copy of the loop nest per shape.
+    // (the two lattice tiles of a wave as two instantiations: every accumulator index is a constant)
+    auto tile_epilogue = [&](auto lt_tag) {
+        constexpr int lt = decltype(lt_tag)::value;
         const int t4 = wm * 2 + lt;
-        const int tile = g.tile0 + bx * 4 + t4;
-        if (tile >= g.tile1) continue;
-        const TilePos tp = locate_tile(g.st, g.s0, g.s1, tile);
+        const TilePos tp = tpos[t4];
+        if (tp.s < 0) return;
         const int b = tp.s;
         float* d_enc = g.d_enc + (size_t)b * g.pr.T_max * H;
         float* d_prd = g.d_pred + (size_t)b * (g.pr.U_max + 1) * H;
-        const bf16_t* er = eq + (t4 * 24) * Z_EP;
-        const bool wide = (tp.uw == 8);
-        const int ulb = wide ? 4 * hb : 0;              // first of this lane's four label positions
+        const bf16_t* er = eq + (t4 * 20) * Z_EP;
+        auto reduce = [&](auto wide_tag) {
+            constexpr bool WIDE = decltype(wide_tag)::value;
+            constexpr int TH = WIDE ? 8 : 16;
+            const int ulb = WIDE ? 4 * hb : 0;              // first of this lane's four label positions
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            const int hc = wn * 128 + nt * 32 + l32;        // column inside the tile
-            const int h = n0 + hc;
-            if (h >= H) continue;
-            float qv[4], pu[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int nt = 0; nt < 4; ++nt) {
+                const int hc = wn * 128 + nt * 32 + l32;        // column inside the tile
+                const int h = n0 + hc;
+                if (h >= H) continue;
+                float qv[4], pu[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) qv[i] = (float)er[(16 + ulb + i) * Z_EP + hc];
+                for (int i = 0; i < 4; ++i) qv[i] = (float)er[(TH + ulb + i) * Z_EP + hc];
 #pragma unroll
-            for (int m2 = 0; m2 < 2; ++m2)
+                for (int m2 = 0; m2 < 2; ++m2)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int tl = wide ? 4 * m2 + j : 8 * m2 + 2 * j + hb;
-                    const bool tv = (tp.t0 + tl < tp.T);
-                    const float ev = (float)er[tl * Z_EP + hc];
-                    float se = 0.0f;
+                    for (int j = 0; j < 4; ++j) {
+                        const int tl = WIDE ? 4 * m2 + j : 8 * m2 + 2 * j + hb;
+                        const bool tv = (tp.t0 + tl < tp.T);
+                        const float ev = (float)er[tl * Z_EP + hc];
+                        float se = 0.0f;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const bool ok = tv && (tp.u0 + ulb + i <= tp.U);
-                        const float z = fast_tanh(ev + qv[i]);
-                        const float dx = ok ? acc[2 * lt + m2][nt][4 * j + i] * (1.0f - z * z) : 0.0f;
-                        se += dx;
-                        pu[i] += dx;
+                        for (int i = 0; i < 4; ++i) {
+                            const bool ok = tv && (tp.u0 + ulb + i <= tp.U);
+                            const float z = fast_tanh(ev + qv[i]);
+                            const float dx = ok ? acc[2 * lt + m2][nt][4 * j + i] * (1.0f - z * z) : 0.0f;
+                            se += dx;
+                            pu[i] += dx;
+                        }
+                        if (WIDE) {
+                            se += __shfl_xor(se, 32, 64);       // a frame's eight labels lie in both lane halves
+                            if (tv && hb == (j & 1)) atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
+                        } else if (tv) {
+                            atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
+                        }
                     }
-                    if (wide) {
-                        se += __shfl_xor(se, 32, 64);       // a frame's eight labels lie in both lane halves
-                        if (tv && hb == (j & 1)) atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
-                    } else if (tv) {
-                        atomicAdd(&d_enc[(size_t)(tp.t0 + tl) * H + h], se);
-                    }
-                }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (wide) {
-                    if (tp.u0 + 4 * hb + i <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + 4 * hb + i) * H + h], pu[i]);
-                } else {
-                    const float both = pu[i] + __shfl_xor(pu[i], 32, 64);   // a label's sixteen frames do
-                    if (hb == (i & 1) && tp.u0 + i <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + i) * H + h], both);
+                for (int i = 0; i < 4; ++i) {
+                    if (WIDE) {
+                        if (tp.u0 + 4 * hb + i <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + 4 * hb + i) * H + h], pu[i]);
+                    } else {
+                        const float both = pu[i] + __shfl_xor(pu[i], 32, 64);   // a label's sixteen frames do
+                        if (hb == (i & 1) && tp.u0 + i <= tp.U) atomicAdd(&d_prd[(size_t)(tp.u0 + i) * H + h], both);
+                    }
                 }
             }
-        }
-    }
+        };
+        if (tp.uw == 8) reduce(std::true_type{});
+        else reduce(std::false_type{});
+    };
+    tile_epilogue(std::integral_constant<int, 0>{});
+    tile_epilogue(std::integral_constant<int, 1>{});
 }
 
 }  // namespace
