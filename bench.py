@@ -176,7 +176,8 @@ def main():
     achieved = flops_per_launch / avg_s
     # HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if any
     from paper_2211_16270_amd.pmc_summary import read_traffic
-    traffic = read_traffic(os.path.join(ROOT, "profiles", f"hbm_traffic_{wl.name}.txt")) if not args.batch else {}
+    tname = f"hbm_traffic_{wl.name}" + ("_keep_scores" if args.keep_scores else "") + ".txt"
+    traffic = read_traffic(os.path.join(ROOT, "profiles", tname)) if not args.batch else {}
     roofline = {"bound": "mfma" if wl.dtype == "bf16" else "alu", "kernel": dom,
                 "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
                 "traffic": traffic.get(dom), "alg_flops_per_launch": flops_per_launch,
