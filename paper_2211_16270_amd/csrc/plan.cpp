@@ -226,9 +226,10 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
             long long nch = (n + cap_tiles - 1) / cap_tiles;
             long long per = (n + nch - 1) / nch;
             per = std::min(cap_tiles, (per + 1) / 2 * 2);
-            // the fused backward kernel runs one workgroup (one tile) per compute unit of the 256: chunks of whole
-            // rounds of tiles leave no partly filled last round (C3: 5 rounds instead of 5.3, that kernel -5 %)
-            if (p.fused && cap_tiles >= 1024 && n > cap_tiles) per = cap_tiles / 256 * 256;
+            // the backward kernels run one workgroup per tile (fused kernel, dz GEMM: one per compute unit of the 256;
+            // score kernel: one or two): chunks of whole rounds of 256 tiles leave no partly filled last round
+            // (B=64, T<=500, U<=100, H=1024, V=4096: 5 rounds instead of 5.3 per chunk, both kernels -12 %)
+            if (cap_tiles >= 1024 && n > cap_tiles) per = cap_tiles / 256 * 256;
             for (long long t = g.tile0; t < g.tile1; t += per) {
                 Chunk c{gi, (int)t, (int)std::min<long long>(g.tile1, t + per)};
                 p.chunks.push_back(c);

@@ -145,6 +145,23 @@ def test_default_plan_properties(name):
         assert info["chunk_bytes"] >= info["chunk_rows"] * (2 * wl.V + 2 * wl.H)
 
 
+def test_backward_chunks_are_whole_rounds_of_256_tiles_when_a_group_needs_several():
+    # one workgroup per tile and 256 compute units: a chunk of a multiple of 256 tiles has no partly filled last round
+    for name in ("C3", "C4"):
+        wl, desc, T, U = _lens(name)
+        st, info, groups = Bd.rnnt_joint_loss_plan(desc, T, U, 0)
+        assert st == 0
+        cap = info["chunk_rows"] // 64
+        assert cap >= 1024
+        per = cap // 256 * 256
+        tiles = _tiles(T, U)
+        want = 0
+        for g in range(info["n_groups"]):
+            n = int(tiles[groups == g].sum())
+            want += -(-n // per) if n > cap else 1
+        assert info["n_chunks"] == want, name
+
+
 def test_workspace_does_not_grow_with_batch_size_once_capped():
     # memory "almost independent of batch size" (Section 5.2): doubling B leaves the default plan's size
     wl = synth.WORKLOADS["C4"]
