@@ -2,6 +2,7 @@
 // launch sequence.  Compiled with hipcc as host code; the kernels live in the .hip files.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -150,6 +151,7 @@ struct WsView {
     void* wq;
     void* dH;
     void* Z;
+    float* dZ32;
     float* kept_max;
     float* stage_enc;
     float* stage_pred;
@@ -177,6 +179,7 @@ WsView view_workspace(const Plan& p, void* ws) {
     v.wq = w + p.off_wq;
     v.dH = w + p.off_dh;
     v.Z = w + p.off_z;
+    v.dZ32 = (float*)(w + p.off_dz32);
     v.kept_max = (float*)(w + p.off_kept_max);
     v.stage_enc = (float*)(w + p.off_stage_enc);
     v.stage_pred = (float*)(w + p.off_stage_pred);
@@ -284,6 +287,12 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
             RNNT_HIP(timed(KC_FWD_SCORES, stream, [&] {
                 return launch_fwd_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, g.tile0, g.tile1, stream);
             }));
+        else if (plan.f32_gemm)
+            for (long long r0 = 0; r0 < g.rows; r0 += plan.chunk_rows)
+                RNNT_HIP(timed(KC_FWD_F32, stream, [&] {
+                    return launch_fwd_f32_gemm(pr, wv.st, ls, g.s0, g.s1, r0, std::min(plan.chunk_rows, g.rows - r0),
+                                               (float*)wv.dH, (float*)wv.Z, stream);
+                }));
         else
             RNNT_HIP(timed(KC_FWD_F32, stream,
                            [&] { return launch_fwd_f32(pr, wv.st, ls, g.s0, g.s1, g.rows, stream); }));
@@ -333,6 +342,13 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                                                wv.dw_slots, db_out, stream);
                 }));
                 dw_first = 0;
+            } else if (plan.f32_gemm) {
+                for (long long r0 = 0; r0 < g.rows; r0 += plan.chunk_rows)
+                    RNNT_HIP(timed(KC_BWD_F32, stream, [&] {
+                        return launch_bwd_f32_gemm(pr, wv.st, ls, go, g.s0, g.s1, r0,
+                                                   std::min(plan.chunk_rows, g.rows - r0), (float*)wv.dH, (float*)wv.Z,
+                                                   wv.dZ32, stream);
+                    }));
             } else {
                 RNNT_HIP(timed(KC_BWD_F32, stream,
                                [&] { return launch_bwd_f32(pr, wv.st, ls, go, g.s0, g.s1, g.rows, stream); }));

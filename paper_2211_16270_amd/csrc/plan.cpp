@@ -78,6 +78,11 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
         p.off_dh = take(align_up((size_t)chunk_rows, 256) * chunk_pitch(d.V) * 2);
         p.off_z = take((size_t)chunk_rows * chunk_pitch(d.H) * 2);
         p.off_kept_max = take(p.keep ? (size_t)chunk_rows * (d.V / 64) * 4 : 0);
+    } else if (p.f32_gemm) {
+        p.off_dh = take((size_t)chunk_rows * d.V * 4);
+        p.off_z = take((size_t)chunk_rows * d.H * 4);
+        p.off_dz32 = take((size_t)chunk_rows * d.H * 4);
+        p.off_kept_max = o;
     } else {
         p.off_dh = p.off_z = p.off_kept_max = o;
     }
@@ -86,7 +91,7 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     p.off_stage_pred = take((size_t)stage_samples * (d.U_max + 1) * d.H * 4);
     p.stage_samples = stage_samples;
     p.group_rows_cap = lat_cap;
-    p.chunk_rows = p.bf16 ? chunk_rows : 0;
+    p.chunk_rows = (p.bf16 || p.f32_gemm) ? chunk_rows : 0;
     p.total_bytes = o;
     return o;
 }
@@ -101,6 +106,8 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     p.keep = p.bf16 && d.keep_scores;
     p.fused = p.bf16 && fused_backward_shape(d.H, d.V);
     p.stage = p.bf16 && d.input_grads_bf16;
+    p.f32_gemm = !p.bf16 && f32_gemm_shape(d.H, d.V);
+    const bool chunked = p.bf16 || p.f32_gemm;
     const size_t stage_per_sample = ((size_t)d.T_max + d.U_max + 1) * d.H * 4;
     p.tile_off.assign(B + 1, 0);
     p.row_off.assign(B + 1, 0);
@@ -115,22 +122,24 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     }
     p.rows_total = p.row_off[B];
     p.tiles_total = p.tile_off[B];
+    // the most rows a chunk can hold: tile rows (bf16), lattice nodes (fp32 GEMM form)
     const long long all_tile_rows =
-        (long long)align_up((size_t)p.tiles_total * TILE_ROWS, GEMM_TILE);
-    const size_t crb = !p.bf16 ? 0
-                               : (size_t)2 * chunk_pitch(d.V) + (size_t)2 * chunk_pitch(d.H) +
-                                     (p.keep ? (size_t)(d.V / 64) * 4 : 0);
+        (long long)align_up((size_t)(p.bf16 ? p.tiles_total * TILE_ROWS : p.rows_total), GEMM_TILE);
+    const size_t crb = p.f32_gemm ? (size_t)4 * d.V + (size_t)8 * d.H
+                       : !p.bf16  ? 0
+                                  : (size_t)2 * chunk_pitch(d.V) + (size_t)2 * chunk_pitch(d.H) +
+                                        (p.keep ? (size_t)(d.V / 64) * 4 : 0);
     // With kept scores a group's backward pass is one chunk: the chunk buffers hold whole samples.
     const long long chunk_floor = p.keep ? max_tile_rows : GEMM_TILE;
 
     // smallest workable plan: one (largest) sample per group, one GEMM tile of rows per chunk
     Plan tmp = p;
-    p.min_bytes = lay_out(d, tmp, max_rows, p.bf16 ? chunk_floor : 0, p.stage ? 1 : 0);
+    p.min_bytes = lay_out(d, tmp, max_rows, chunked ? chunk_floor : 0, p.stage ? 1 : 0);
 
     // the default plan; a caller that passes exactly the size it was told gets exactly this plan back
     const long long lat_default = std::min(p.rows_total, std::max(max_rows, (256LL << 20) / 20));
     long long chunk_default = 0;
-    if (p.bf16) {
+    if (chunked) {
         // 832 MiB: 768 MiB of rows at H = 512, V = 1024 plus the padding of their row pitch
         // kept scores: 8 GiB, so that a group still fills the GPU when a row takes 10 KB
         const unsigned long long budget = p.keep ? (8ULL << 30) : (832ULL << 20);
@@ -150,7 +159,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         stage_samples = stage_default;
     } else if (workspace_bytes < p.min_bytes) {
         lat_cap = max_rows;
-        chunk_rows = p.bf16 ? chunk_floor : 0;
+        chunk_rows = chunked ? chunk_floor : 0;
         stage_samples = p.stage ? 1 : 0;
     } else {
         // the fixed part and the alignment slack come off first
@@ -163,7 +172,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
                                                        std::max<long long>(1, (long long)(avail / 8 / stage_per_sample)));
         const size_t stage_bytes = (size_t)stage_samples * stage_per_sample;
         avail = avail > stage_bytes ? avail - stage_bytes : 0;
-        if (!p.bf16) {
+        if (!chunked) {
             lat_cap = std::min<long long>(p.rows_total, std::max<long long>(max_rows, (long long)(avail / 20)));
             chunk_rows = 0;
         } else {

@@ -36,6 +36,7 @@ struct Plan {
     int B = 0;
     bool bf16 = false;
     bool fused = false;                 // bf16 only: backward runs in the fused kernel
+    bool f32_gemm = false;              // fp32 only: H, V multiples of 128, the steps run as fp32 MFMA GEMMs over chunks
     bool keep = false;                  // bf16 only: forward keeps the scores, one backward chunk per group
     bool stage = false;                 // bf16 only: d_enc, d_pred leave as bf16; fp32 sums of one group in the workspace
     long long stage_samples = 0;        // samples a group may hold then
@@ -45,13 +46,14 @@ struct Plan {
     std::vector<Chunk> chunks;
     long long rows_total = 0, tiles_total = 0;
     long long group_rows_cap = 0;       // lattice nodes a group may hold
-    long long chunk_rows = 0;           // rows (multiple of GEMM_TILE) of the chunk buffers
+    long long chunk_rows = 0;           // rows (multiple of GEMM_TILE) of the chunk buffers (fp32 GEMM form: lattice nodes)
     // workspace layout (byte offsets)
     size_t off_T = 0, off_U = 0, off_weight = 0, off_tile_off = 0, off_row_off = 0, off_lnP = 0, off_shift = 0, off_tile_sample = 0;
     size_t off_tile_esum = 0;          // bf16: per-tile emission sums (float per tile)
     size_t off_wpack = 0, off_wq = 0;
     size_t off_lse = 0, off_lpb = 0, off_lpy = 0, off_alpha = 0, off_beta = 0;
     size_t off_dh = 0, off_z = 0, off_kept_max = 0;
+    size_t off_dz32 = 0;                // fp32 GEMM form: dZ [chunk_rows, H]; off_dh, off_z hold S and Z as fp32
     size_t off_stage_enc = 0, off_stage_pred = 0;   // fp32 [stage_samples, T_max, H], [stage_samples, U_max+1, H]
     size_t off_dwslots = 0;             // bf16: per-workgroup partial sums of the dW GEMM
     int dw_splits = 0;                  // bf16: K splits of the dW GEMM (a multiple of 8)
@@ -61,6 +63,9 @@ struct Plan {
 
 // Shapes the fused backward kernel covers (its dz accumulators must fit the register file).
 inline bool fused_backward_shape(int H, int V) { return H % 128 == 0 && H <= 640 && V % 256 == 0; }
+
+// Shapes the fp32 GEMM form covers (its tiles have no edge handling).
+inline bool f32_gemm_shape(int H, int V) { return H % 128 == 0 && V % 128 == 0; }
 
 // dW GEMM geometry: 256x256 output tiles, and as many K splits (a multiple of 8, one set per XCD) as
 // give about one workgroup per compute unit.  Every (split, tile) workgroup owns a 256 KiB slot of

@@ -6,8 +6,10 @@ paper's zero-padding scheme (padding grows linearly over the batch: acoustic 0 -
     python -m paper_2211_16270_amd.sweep batch    # speed and peak memory over the batch size
     python -m paper_2211_16270_amd.sweep keep     # scores kept (keep_scores = 1) against computed twice
     python -m paper_2211_16270_amd.sweep keep16   # the same at B = 16 only, with the time of each kernel
+    python -m paper_2211_16270_amd.sweep fp32     # the grid and three batch sizes with fp32 inputs and arithmetic
 
-Timing only (inputs are seeded random tensors made on the GPU, as in the paper's benchmark); bf16 inputs.
+Timing only (inputs are seeded random tensors made on the GPU, as in the paper's benchmark); bf16 inputs unless
+stated.
 Ways of running a batch:
   packed      one call, true lengths: this library's default (padding removed, samples share launches)
   padded      one call, every length set to the maximum: what a computation on the padded batch costs
@@ -31,16 +33,18 @@ def paper_lengths(B: int, T: int, U: int):
     return T_len, U_len
 
 
-def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211):
+def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211, dtype="bf16"):
     import torch
     from . import binding as Bd
 
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     g = torch.Generator(device="cuda").manual_seed(seed)
-    enc = torch.randn(B, T, H, generator=g, device="cuda").to(torch.bfloat16)
-    pred = torch.randn(B, U + 1, H, generator=g, device="cuda").to(torch.bfloat16)
-    W = (torch.randn(H, V, generator=g, device="cuda") / H ** 0.5).to(torch.bfloat16)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rdt = Bd.RNNT_BF16 if dtype == "bf16" else Bd.RNNT_F32
+    enc = torch.randn(B, T, H, generator=g, device="cuda").to(tdt)
+    pred = torch.randn(B, U + 1, H, generator=g, device="cuda").to(tdt)
+    W = (torch.randn(H, V, generator=g, device="cuda") / H ** 0.5).to(tdt)
     b_out = torch.zeros(V, dtype=torch.float32, device="cuda")
     labels = torch.randint(1, V, (B, max(U, 1)), generator=g, device="cuda", dtype=torch.int32)
     torch.cuda.synchronize()
@@ -55,7 +59,7 @@ def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211):
     dW, db = torch.empty(H, V, **f32), torch.empty(V, **f32)
     stream = torch.cuda.current_stream()
     if mode == "one_by_one":
-        desc1 = Bd.make_desc(1, T, U, H, V, 0, Bd.RNNT_BF16, accumulate_params=1)
+        desc1 = Bd.make_desc(1, T, U, H, V, 0, rdt, accumulate_params=1)
         nb = max(Bd.rnnt_joint_loss_workspace_bytes(desc1, T_len[b:b + 1], U_len[b:b + 1]) for b in range(B))
         ws = Bd.Workspace(nb)
 
@@ -68,7 +72,7 @@ def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211):
                                                d_pred[b:b + 1], dW, db, ws.buf, stream)
                 assert s == 0, s
     else:
-        desc = Bd.make_desc(B, T, U, H, V, 0, Bd.RNNT_BF16, keep_scores=1 if mode == "kept" else 0)
+        desc = Bd.make_desc(B, T, U, H, V, 0, rdt, keep_scores=1 if mode == "kept" else 0)
         nb = Bd.rnnt_joint_loss_workspace_bytes(desc, T_len, U_len)
         ws = Bd.Workspace(nb)
 
@@ -135,8 +139,17 @@ def main(argv):
             for k, (c, ms) in prof.items():
                 if c:
                     print(f"    {k:24s} launches per step {c // 4:3d}   {ms / 4:8.3f} ms per step")
+    elif which == "fp32":
+        print(f"H = {H}, V = {V}, fp32 inputs and arithmetic (fp32 MFMA GEMMs over chunks of lattice nodes), packed\n")
+        print("| B | T x U | ms per step | samples/s | executed TFLOP/s | workspace GB | peak GB (inputs + outputs + workspace) |")
+        print("|---|---|---|---|---|---|---|")
+        cases = [(16, T, U) for T, U in [(50, 10), (100, 20), (139, 27), (232, 46), (300, 60), (400, 80), (500, 100)]]
+        for B, T, U in cases + [(1, 500, 100), (64, 500, 100)]:
+            r = run_case(B, T, U, H, V, "packed", steps=2, warmup=1, dtype="f32")
+            print(f"| {B} | {T} x {U} | {r['ms']:.1f} | {r['samples_per_s']:.1f} | {r['pflops_exec'] * 1e3:.1f} | "
+                  f"{r['workspace_gb']:.2f} | {r['peak_gb']:.2f} |", flush=True)
     else:
-        raise SystemExit("usage: python -m paper_2211_16270_amd.sweep grid|batch|keep|keep16")
+        raise SystemExit("usage: python -m paper_2211_16270_amd.sweep grid|batch|keep|keep16|fp32")
 
 
 if __name__ == "__main__":

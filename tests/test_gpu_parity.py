@@ -63,6 +63,73 @@ def test_f32_moderate_shape_and_group_splitting():
     assert_parity(got2, ref, "f32", "mid32 min workspace")
 
 
+# ------------------------------------------------------------------ fp32 MFMA GEMM form (H, V multiples of 128)
+@pytest.mark.parametrize("H,V", [(128, 128), (256, 384), (384, 128)])
+def test_f32_gemm_form_against_the_checker(H, V):
+    wl = synth.custom_workload("g32", B=5, T_max=37, U_max=11, H=H, V=V, dtype="f32", index=131,
+                               t_rule="uniform", t_lo=5, u_rule="uniform", u_lo=0)
+    batch = synth.make_batch(wl)
+    _say("fp32 GEMM form", H, V, batch.T_len, batch.U_len)
+    ref = run_oracle(batch)
+    got = run_gpu(batch)
+    st, info, _ = Bd.rnnt_joint_loss_plan(got["desc"], batch.T_len, batch.U_len, 0)
+    assert st == 0 and info["chunk_rows"] >= 128              # this shape runs as GEMMs over chunk buffers
+    e, errs = assert_parity(got, ref, "f32", "fp32 GEMM form")
+    _say("fp32 GEMM form errs", e, errs)
+    assert_padding_zero(got, batch)
+    # smallest workspace: one sample per group, chunks of 128 lattice nodes (several per sample)
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(got["desc"], batch.T_len, batch.U_len, 1)
+    st, info, _ = Bd.rnnt_joint_loss_plan(got["desc"], batch.T_len, batch.U_len, nmin)
+    assert st == 0 and info["chunk_rows"] == 128 and info["n_groups"] >= 2
+    small = run_gpu(batch, budget_bytes=nmin)
+    assert_parity(small, ref, "f32", "fp32 GEMM form, smallest workspace")
+    assert_padding_zero(small, batch)
+    # weighted sum of the losses, one sample left out
+    w = np.array([0.5, 0.0, 2.0, 1.0 / 3.0, 1.0], dtype=np.float32)
+    gw, rw = run_gpu(batch, sample_weight=w), run_oracle(batch, sample_weight=w.astype(np.float64))
+    assert_parity(gw, rw, "f32", "fp32 GEMM form, weighted")
+    assert np.all(gw["d_enc"][1] == 0.0) and np.all(gw["d_pred"][1] == 0.0)
+
+
+@pytest.mark.parametrize("T_len,U_len,blank", [
+    ([1, 1], [0, 0], 0),
+    ([9, 4], [0, 0], 2),
+    ([1, 1], [5, 3], 0),
+    ([11, 7], [6, 2], 127),
+    ([13, 2], [1, 6], 64),
+])
+def test_f32_gemm_form_edge_lattices(T_len, U_len, blank):
+    wl = synth.custom_workload("edge32g", B=2, T_max=13, U_max=6, H=128, V=128, dtype="f32", index=132)
+    batch = synth.with_lengths(synth.make_batch(wl), T_len, U_len)
+    batch.labels[0, :1] = blank if U_len[0] > 0 else batch.labels[0, :1]
+    _say("edge fp32 GEMM form", T_len, U_len, blank)
+    got, ref = run_gpu(batch, blank=blank), run_oracle(batch, blank=blank)
+    assert_parity(got, ref, "f32", f"edge {T_len} {U_len}")
+    assert_padding_zero(got, batch)
+
+
+def test_f32_gemm_form_several_chunks_and_accumulate():
+    import torch
+    wl = synth.custom_workload("g32b", B=6, T_max=90, U_max=20, H=256, V=512, dtype="f32", index=133,
+                               t_rule="uniform", t_lo=40, u_rule="uniform", u_lo=5)
+    batch = synth.make_batch(wl)
+    ref = run_oracle(batch)
+    got = run_gpu(batch)
+    assert_parity(got, ref, "f32", "g32b")
+    # a budget that cuts the call into several groups and chunks
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(got["desc"], batch.T_len, batch.U_len, 1)
+    budget = nmin + (6 << 20)
+    st, info, _ = Bd.rnnt_joint_loss_plan(got["desc"], batch.T_len, batch.U_len, budget)
+    assert st == 0 and 128 < info["chunk_rows"] < info["rows_total"]
+    mid = run_gpu(batch, budget_bytes=budget)
+    assert_parity(mid, ref, "f32", "g32b with a budget")
+    # accumulate_params: dW_out, db_out are added to what the arrays hold
+    acc = (torch.full((wl.H, wl.V), 0.25, device="cuda"), torch.full((wl.V,), -0.5, device="cuda"))
+    got2 = run_gpu(batch, accumulate_into=acc)
+    assert rel_grad_err(got2["dW_out"] - 0.25, ref["dW_out"]) <= 2e-4
+    assert rel_grad_err(got2["db_out"] + 0.5, ref["db_out"]) <= 2e-4
+
+
 # ------------------------------------------------------------------ bf16 MFMA path
 def _mid_bf16(index=110, **kw):
     args = dict(B=4, T_max=37, U_max=19, H=128, V=256, dtype="bf16", index=index,

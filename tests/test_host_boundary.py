@@ -162,6 +162,24 @@ def test_backward_chunks_are_whole_rounds_of_256_tiles_when_a_group_needs_severa
         assert info["n_chunks"] == want, name
 
 
+def test_fp32_shapes_with_gemm_tiles_get_chunk_buffers():
+    T = np.array([30, 17, 25], dtype=np.int32); U = np.array([7, 0, 11], dtype=np.int32)
+    rows = int((T.astype(np.int64) * (U + 1)).sum())
+    for H, V, gemm in [(128, 256, True), (256, 128, True), (128, 200, False), (96, 256, False)]:
+        desc = Bd.make_desc(3, 30, 11, H, V, 0, Bd.RNNT_F32)
+        st, info, _ = Bd.rnnt_joint_loss_plan(desc, T, U, 0)
+        assert st == 0
+        if gemm:
+            # S [rows, V], Z and dZ [rows, H] in fp32, rows = the call's lattice nodes rounded up to 128
+            assert info["chunk_rows"] == -(-rows // 128) * 128
+            assert info["chunk_bytes"] >= info["chunk_rows"] * (4 * V + 8 * H)
+            nmin = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 1)
+            st, small, _ = Bd.rnnt_joint_loss_plan(desc, T, U, nmin)
+            assert st == 0 and small["chunk_rows"] == 128 and small["n_groups"] == 2
+        else:
+            assert info["chunk_rows"] == 0 and info["chunk_bytes"] == 0
+
+
 def test_workspace_does_not_grow_with_batch_size_once_capped():
     # memory "almost independent of batch size" (Section 5.2): doubling B leaves the default plan's size
     wl = synth.WORKLOADS["C4"]
