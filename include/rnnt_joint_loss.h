@@ -43,7 +43,8 @@ typedef enum {
 } rnnt_status;
 
 typedef enum {
-    RNNT_F32 = 0, /* enc, pred, W_out are float; everything is computed in fp32 (plain FMA)   */
+    RNNT_F32 = 0, /* enc, pred, W_out are float; everything is computed in fp32: the three      */
+                  /* GEMMs on fp32 MFMA where H and V are multiples of 128, else plain FMA    */
     RNNT_BF16 = 1 /* enc, pred, W_out are bfloat16; the three GEMMs run on bf16 MFMA with     */
                   /* fp32 accumulation, tanh/softmax/lattice in fp32                          */
 } rnnt_dtype;
@@ -99,6 +100,8 @@ const char* rnnt_last_hip_error(void);
  *   hold up to 8 GiB, never more than the call's tile rows need, and the smallest plan holds the largest
  *   sample's rows: 2 (V + 64) + 2 (H + 64) + V / 16 bytes per row of its 64-node lattice tiles; with
  *   desc->input_grads_bf16 up to 256 MiB more, for the float sums of d_enc and d_pred of one group).
+ *   RNNT_F32 with H and V multiples of 128 has chunk buffers too: 4 V + 8 H bytes per lattice node of a
+ *   chunk (scores, joint activations and their gradients as float), 128 nodes in the smallest plan.
  *   Otherwise the largest plan not exceeding budget_bytes; if
  *   even the smallest workable plan (one sample per group, one tile row per chunk) exceeds it,
  *   that smallest size is returned, so a result > budget_bytes means "budget too small".

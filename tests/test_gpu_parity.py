@@ -130,6 +130,50 @@ def test_f32_gemm_form_several_chunks_and_accumulate():
     assert rel_grad_err(got2["db_out"] + 0.5, ref["db_out"]) <= 2e-4
 
 
+def test_f32_gemm_form_at_the_paper_joint_and_vocabulary_size():
+    # H = 1024, V = 4096 (Section 5.1) in fp32, lengths with the paper's padding scheme scaled down; a budget that
+    # cuts the backward pass into several chunks
+    wl = synth.custom_workload("p32", B=4, T_max=96, U_max=20, H=1024, V=4096, dtype="f32", index=134,
+                               t_rule="uniform", t_lo=80, u_rule="uniform", u_lo=10)
+    batch = synth.make_batch(wl)
+    _say("fp32 GEMM form 1024 x 4096", batch.T_len, batch.U_len)
+    ref = run_oracle(batch)
+    got = run_gpu(batch)
+    e, errs = assert_parity(got, ref, "f32", "p32")
+    _say("p32 errs", e, errs)
+    assert_padding_zero(got, batch)
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(got["desc"], batch.T_len, batch.U_len, 1)
+    budget = nmin + (40 << 20)
+    st, info, _ = Bd.rnnt_joint_loss_plan(got["desc"], batch.T_len, batch.U_len, budget)
+    assert st == 0 and 128 < info["chunk_rows"] < info["rows_total"]
+    assert_parity(run_gpu(batch, budget_bytes=budget), ref, "f32", "p32 with a budget")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_f32_gemm_form_random_shapes(seed):
+    rng = np.random.default_rng(9500 + seed)
+    H, V = int(rng.choice([128, 256, 384])), int(rng.choice([128, 256, 640]))
+    B, T_max, U_max = int(rng.integers(1, 6)), int(rng.integers(1, 41)), int(rng.integers(0, 21))
+    blank = int(rng.integers(0, V))
+    wl = synth.custom_workload(f"rg{seed}", B=B, T_max=T_max, U_max=U_max, H=H, V=V, dtype="f32", index=340 + seed)
+    T_len, U_len = rng.integers(1, T_max + 1, size=B), rng.integers(0, U_max + 1, size=B)
+    batch = synth.with_lengths(synth.make_batch(wl), T_len, U_len)
+    labels = rng.integers(0, V, size=batch.labels.shape).astype(np.int32)        # blank included on purpose
+    for b in range(B):
+        labels[b, U_len[b]:] = -1
+    import dataclasses
+    batch = dataclasses.replace(batch, labels=labels)
+    smallest = bool(rng.integers(0, 2))
+    _say("random fp32 GEMM form", seed, dict(B=B, T_max=T_max, U_max=U_max, H=H, V=V, blank=blank), T_len.tolist(),
+         U_len.tolist(), "smallest workspace" if smallest else "")
+    budget = 0
+    if smallest:
+        budget = Bd.rnnt_joint_loss_workspace_bytes(Bd.make_desc(B, T_max, U_max, H, V, blank, Bd.RNNT_F32), T_len, U_len, 1)
+    got = run_gpu(batch, blank=blank, budget_bytes=budget)
+    assert_parity(got, run_oracle(batch, blank=blank), "f32", f"random fp32 GEMM form {seed}")
+    assert_padding_zero(got, batch)
+
+
 # ------------------------------------------------------------------ bf16 MFMA path
 def _mid_bf16(index=110, **kw):
     args = dict(B=4, T_max=37, U_max=19, H=128, V=256, dtype="bf16", index=index,
