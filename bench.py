@@ -5,7 +5,7 @@ A step is one call of rnnt_joint_loss_fwd_bwd over one synthetic batch (the whol
 joint tiles, score GEMM, softmax statistics, lattice, score gradients, backward GEMMs), with
 all inputs already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2|C3|C4|C5|C1] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2|C3|C4|C5|C1|P16|P16F32] [--no-cpu-baseline]
 
 `value` is samples/s over K timed steps (whole job, one GPU).  `roofline` describes the kernel
 that takes the most time: its algorithmic flops per launch divided by its average launch
@@ -26,7 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_FLOPS = 2.5e15     # MI355X dense bf16 MFMA
-PEAK_F32_FLOPS = 157.3e12    # MI355X fp32 vector
+PEAK_F32_FLOPS = 157.3e12    # MI355X fp32, vector and MFMA alike
 CPU_SAMPLE = {"C1": 2, "C2": 32, "C3": 12, "C4": 12, "C5": 8}  # samples the checker is timed on (10-30 s)
 COPY_BYTES = 256 << 20
 
@@ -61,10 +61,12 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    if args.config == "P16":
+    if args.config in ("P16", "P16F32"):
         # shaped like the paper's benchmark (Section 5.1): 16 samples of up to 500 x 100, joint size 1024,
         # 4096 word pieces; lengths drawn uniformly down to the paper's largest padding (9.3 % / 45.8 %)
-        wl = synth.custom_workload("P16", B=16, T_max=500, U_max=100, H=1024, V=4096, dtype="bf16", index=5,
+        # P16F32: the same in fp32 (the paper's own precision), on the fp32 MFMA GEMM form of the path
+        wl = synth.custom_workload(args.config, B=16, T_max=500, U_max=100, H=1024, V=4096,
+                                   dtype="bf16" if args.config == "P16" else "f32", index=5,
                                    t_rule="uniform", t_lo=454, u_rule="uniform", u_lo=54)
     else:
         wl = synth.WORKLOADS[args.config]
@@ -178,7 +180,9 @@ def main():
     from paper_2211_16270_amd.pmc_summary import read_traffic
     tname = f"hbm_traffic_{wl.name}" + ("_keep_scores" if args.keep_scores else "") + ".txt"
     traffic = read_traffic(os.path.join(ROOT, "profiles", tname)) if not args.batch else {}
-    roofline = {"bound": "mfma" if wl.dtype == "bf16" else "alu", "kernel": dom,
+    # fp32: GEMMs on the fp32 MFMA instruction where the plan has chunk buffers (H, V multiples of 128; `kernel` is
+    # then the group of launches of one chunk: three GEMMs and the row kernels between them), else plain FMA
+    roofline = {"bound": "mfma" if (wl.dtype == "bf16" or info["chunk_rows"] > 0) else "alu", "kernel": dom,
                 "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
                 "traffic": traffic.get(dom), "alg_flops_per_launch": flops_per_launch,
                 "avg_launch_us": kernels[dom]["avg_launch_us"]}

@@ -292,11 +292,18 @@ __global__ __launch_bounds__(256) void k_rows_stats_f32(Problem pr, SampleTable 
     const NodePos p = locate_node(st, ls.row_base, s0, s1, r0 + i);
     const float* row = S + i * V;
     const int label = (p.u < p.U) ? pr.labels[(size_t)p.s * pr.U_max + p.u] : -1;
+    const f32x4* row4 = reinterpret_cast<const f32x4*>(row);      // V is a multiple of 128, rows are 16-byte aligned
     float m = RNNT_NEG_INF;
-    for (int v = lane; v < V; v += 64) m = fmaxf(m, row[v]);
+    for (int v = lane; v < V / 4; v += 64) {
+        const f32x4 x = row4[v];
+        m = fmaxf(fmaxf(m, fmaxf(x[0], x[1])), fmaxf(x[2], x[3]));
+    }
     const float M = wave_max(m);
     float ssum = 0.0f;
-    for (int v = lane; v < V; v += 64) ssum += expf(row[v] - M);
+    for (int v = lane; v < V / 4; v += 64) {
+        const f32x4 x = row4[v];
+        ssum += (expf(x[0] - M) + expf(x[1] - M)) + (expf(x[2] - M) + expf(x[3] - M));
+    }
     const float lse = M + logf(wave_sum(ssum));
     if (lane == 0) {
         ls.lse[p.idx] = lse;
@@ -321,11 +328,17 @@ __global__ __launch_bounds__(256) void k_rows_dh_f32(Problem pr, SampleTable st,
     const int label = (p.u < p.U) ? pr.labels[(size_t)p.s * pr.U_max + p.u] : -1;
     const RowPost rp = row_posteriors(ls, p.idx, p.t, p.u, p.T, p.U, p.s);
     const float off = rp.log_gamma - ls.lse[p.idx];
-    for (int v = lane; v < V; v += 64) {
-        float d = expf(row[v] + off);
-        if (v == pr.blank) d -= rp.Bk;
-        if (v == label) d -= rp.Yk;
-        row[v] = d;
+    f32x4* row4 = reinterpret_cast<f32x4*>(row);
+    for (int v = lane; v < V / 4; v += 64) {
+        f32x4 x = row4[v];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float d = expf(x[j] + off);
+            if (4 * v + j == pr.blank) d -= rp.Bk;
+            if (4 * v + j == label) d -= rp.Yk;
+            x[j] = d;
+        }
+        row4[v] = x;
     }
 }
 

@@ -20,6 +20,10 @@ KERNEL_ALIASES = [
     ("k_joint_scores<2", "joint_scores_fwd_keep"), ("k_kept_to_dh", "kept_scores_to_dh"),
     ("k_lattice", "lattice"), ("k_copy_f32", "copy_f32"), ("k_prepare", "prepare"),
     ("k_fwd_f32", "fwd_f32"), ("k_bwd_f32", "bwd_f32"),
+    ("k_gemm_f32<false, true>", "gemm_f32 scores = Z W"), ("k_gemm_f32<true, true>", "gemm_f32 dW = Z^T dh"),
+    ("k_gemm_f32<false, false>", "gemm_f32 dZ = dh W^T"), ("k_rows_z_f32", "rows_z_f32"),
+    ("k_rows_stats_f32", "rows_stats_f32"), ("k_rows_dh_f32", "rows_dh_f32"), ("k_rows_dz_f32", "rows_dz_f32"),
+    ("k_col_sum", "col_sum"),
 ]
 
 
