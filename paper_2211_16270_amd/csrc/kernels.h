@@ -167,6 +167,17 @@ hipError_t launch_proj_backward_input(int bf16, const float* d_out, long long ro
 // dW += h^T d_out over the real rows   (dW fp32 [D,H])
 hipError_t launch_proj_backward_weight(int bf16, const void* h, long long rows, int D, const RowMask& mask,
                                        const float* d_out, int H, float* dW, hipStream_t stream);
+// C[m,n] (+)= sum_k A(m,k) B(k,n) (+ bias[n]) in fp32 on the fp32 MFMA instruction, any M, N, K.  An operand
+// is k-slow (element (i,k) at p[k*ld + i]) or k-contiguous (at p[i*ld + k]); combinations: A contiguous with
+// either B, or both slow.  Rows of an operand's source array outside its mask read as zero.  atomic: C is
+// added to with float atomics (required for splits > 1).  gemm_f32_edge_fits: the 16-byte alignment the
+// kernel's loads need (extents along the contiguous index: K resp. M for A, K resp. N for B).
+bool gemm_f32_edge_fits(const void* A, long long lda, const void* B, long long ldb, long long a_contig_extent,
+                        long long b_contig_extent);
+hipError_t launch_gemm_f32_masked(int a_kslow, int b_kslow, const float* A, long long lda, const RowMask& ma,
+                                  const float* B, long long ldb, const RowMask& mb, float* C, long long ldc,
+                                  const float* bias, int atomic, long long M, long long N, long long K, int splits,
+                                  hipStream_t stream);
 // out[c] += sum_r x[r,c]   (x fp32 [rows,cols])
 hipError_t launch_col_sum(const float* x, long long rows, int cols, float* out, hipStream_t stream);
 

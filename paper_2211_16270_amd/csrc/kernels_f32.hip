@@ -11,6 +11,8 @@
 //      d_enc, d_pred += dZ (1 - Z^2)                             k_rows_dz_f32
 //    The chunk buffers S [rows, V], Z and dZ [rows, H] live in the workspace; rows beyond the chunk's
 //    last node (up to the next multiple of 128) are zero.  The throughput path is the bf16 one.
+#include <cstdint>
+
 #include "device_common.h"
 
 namespace rnnt {
@@ -187,14 +189,43 @@ struct OperandF32 {
     }
 };
 
+// The same operand with edges: elements with i >= n_i or k >= n_k, and those of a padded source row (the
+// row index is i if !KSLOW, k if KSLOW; see RowMask), read as zero.  The extent along the contiguous index
+// is a multiple of 4, so a 16-byte piece is inside or outside as a whole.  Branch-free: a piece outside is
+// loaded from the operand's first element and cleared.
+template <bool KSLOW>
+struct OperandF32Edge : OperandF32<KSLOW> {
+    long long n_i, n_k;
+    RowMask mask;
+    __device__ __forceinline__ void fetch(f32x4 (&v)[2], long long i0, long long k0, int tid) const {
+        typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int e = tid + 256 * q;
+            const long long i = !KSLOW ? i0 + (e >> 2) : i0 + (e & 31) * 4;
+            const long long k = !KSLOW ? k0 + (e & 3) * 4 : k0 + (e >> 5);
+            const long long off = !KSLOW ? i * this->ld + k : k * this->ld + i;
+            const bool ok = i < n_i && k < n_k;
+            bool keep = ok;
+            if (mask.len != nullptr) {
+                const long long src = ok ? (!KSLOW ? i : k) : 0, b = src / mask.period;
+                keep = ok && (int)(src - b * mask.period) < mask.len[b] + mask.extra;
+            }
+            u32x4_t w = __builtin_bit_cast(u32x4_t, *reinterpret_cast<const f32x4*>(this->p + (ok ? off : 0)));
+            w &= keep ? ~0u : 0u;
+            v[q] = __builtin_bit_cast(f32x4, w);
+        }
+    }
+};
+
 // C[m, n] (+)= sum_k A(m, k) B(k, n) (+ bias[n]) in fp32.  128x128 output tile per workgroup, 4 waves x
 // (64x64 = 2x2 MFMA 32x32x2 tiles), K-step 16, global loads one K-step ahead in registers.
 // grid (M/128, N/128, splits); a split covers k_per_split (a multiple of 16) of K.  atomic != 0: the tile
 // is added to C with float atomics (split over K, or C accumulates over calls).
-template <bool AK, bool BK>
-__global__ __launch_bounds__(256) void k_gemm_f32(OperandF32<AK> A, OperandF32<BK> B, float* __restrict__ C,
-                                                  long long ldc, const float* __restrict__ bias, int atomic,
-                                                  long long K, long long k_per_split) {
+template <class OpA, class OpB>
+__global__ __launch_bounds__(256) void k_gemm_f32(OpA A, OpB B, float* __restrict__ C, long long ldc,
+                                                  const float* __restrict__ bias, int atomic, long long M,
+                                                  long long N, long long K, long long k_per_split) {
     __shared__ __align__(16) float As[FK * FP];
     __shared__ __align__(16) float Bs[FK * FP];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
@@ -240,10 +271,12 @@ __global__ __launch_bounds__(256) void k_gemm_f32(OperandF32<AK> A, OperandF32<B
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const long long n = n0 + wn * 64 + j * 32 + l32;
+            if (n >= N) continue;
             const float bv = (bias != nullptr && blockIdx.z == 0) ? bias[n] : 0.0f;
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
                 const long long m = m0 + wm * 64 + i * 32 + 8 * (q >> 2) + 4 * hb + (q & 3);
+                if (m >= M) continue;
                 const float v = acc[i][j][q] + bv;
                 if (atomic) atomicAdd(C + m * ldc + n, v);
                 else C[m * ldc + n] = v;
@@ -261,8 +294,30 @@ hipError_t launch_gemm_f32(const float* A, long long lda, const float* B, long l
     per = (per + FK - 1) / FK * FK;
     const long long nz = (K + per - 1) / per;
     if (M / FT > 0x7fffffffLL || N / FT > 65535 || nz > 65535) return hipErrorInvalidValue;
-    k_gemm_f32<AK, BK><<<dim3((unsigned)(M / FT), (unsigned)(N / FT), (unsigned)nz), dim3(256), 0, stream>>>(
-        OperandF32<AK>{A, lda}, OperandF32<BK>{B, ldb}, C, ldc, bias, atomic, K, per);
+    k_gemm_f32<<<dim3((unsigned)(M / FT), (unsigned)(N / FT), (unsigned)nz), dim3(256), 0, stream>>>(
+        OperandF32<AK>{A, lda}, OperandF32<BK>{B, ldb}, C, ldc, bias, atomic, M, N, K, per);
+    return hipGetLastError();
+}
+
+template <bool AK, bool BK>
+hipError_t launch_gemm_f32_edge(const float* A, long long lda, const RowMask& ma, const float* B, long long ldb,
+                                const RowMask& mb, float* C, long long ldc, const float* bias, int atomic,
+                                long long M, long long N, long long K, int splits, hipStream_t stream) {
+    if (M <= 0 || N <= 0 || K <= 0) return hipSuccess;
+    // 16-byte pieces along each operand's contiguous index
+    const bool fits = lda % 4 == 0 && ldb % 4 == 0 && (AK ? M : K) % 4 == 0 && (BK ? N : K) % 4 == 0 &&
+                      (uintptr_t)A % 16 == 0 && (uintptr_t)B % 16 == 0;
+    if (!fits || splits < 1 || (splits > 1 && !atomic)) return hipErrorInvalidValue;
+    long long per = (K + splits - 1) / splits;
+    per = (per + FK - 1) / FK * FK;
+    const long long nz = (K + per - 1) / per, gm = (M + FT - 1) / FT, gn = (N + FT - 1) / FT;
+    if (gm > 0x7fffffffLL || gn > 65535 || nz > 65535) return hipErrorInvalidValue;
+    OperandF32Edge<AK> a;
+    a.p = A; a.ld = lda; a.n_i = M; a.n_k = K; a.mask = ma;
+    OperandF32Edge<BK> b;
+    b.p = B; b.ld = ldb; b.n_i = N; b.n_k = K; b.mask = mb;
+    k_gemm_f32<<<dim3((unsigned)gm, (unsigned)gn, (unsigned)nz), dim3(256), 0, stream>>>(a, b, C, ldc, bias, atomic, M,
+                                                                                        N, K, per);
     return hipGetLastError();
 }
 
@@ -361,6 +416,25 @@ __global__ __launch_bounds__(256) void k_rows_dz_f32(Problem pr, SampleTable st,
 }
 
 }  // namespace
+
+bool gemm_f32_edge_fits(const void* A, long long lda, const void* B, long long ldb, long long a_contig_extent,
+                        long long b_contig_extent) {
+    return lda % 4 == 0 && ldb % 4 == 0 && a_contig_extent % 4 == 0 && b_contig_extent % 4 == 0 &&
+           (uintptr_t)A % 16 == 0 && (uintptr_t)B % 16 == 0;
+}
+
+hipError_t launch_gemm_f32_masked(int a_kslow, int b_kslow, const float* A, long long lda, const RowMask& ma,
+                                  const float* B, long long ldb, const RowMask& mb, float* C, long long ldc,
+                                  const float* bias, int atomic, long long M, long long N, long long K, int splits,
+                                  hipStream_t stream) {
+    if (!a_kslow && b_kslow)
+        return launch_gemm_f32_edge<false, true>(A, lda, ma, B, ldb, mb, C, ldc, bias, atomic, M, N, K, splits, stream);
+    if (!a_kslow && !b_kslow)
+        return launch_gemm_f32_edge<false, false>(A, lda, ma, B, ldb, mb, C, ldc, bias, atomic, M, N, K, splits, stream);
+    if (a_kslow && b_kslow)
+        return launch_gemm_f32_edge<true, true>(A, lda, ma, B, ldb, mb, C, ldc, bias, atomic, M, N, K, splits, stream);
+    return hipErrorInvalidValue;
+}
 
 hipError_t launch_fwd_f32_gemm(const Problem& pr, const SampleTable& st, const LatticeState& ls, int s0, int s1,
                                long long r0, long long n, float* S, float* Z, hipStream_t stream) {

@@ -13,7 +13,8 @@
 // A k-contiguous operand lies in LDS as [row][k] and gives fragments by plain 16-byte reads; a k-slow
 // operand lies there as in memory ([k][row], 16-byte chunks XOR-swizzled) and gives fragments by the
 // transposing LDS read.  Global loads run one K-step ahead in registers.  These GEMMs are about 1 % of the path's flops.
-// fp32 path (any sizes): one thread per output element.
+// fp32 path: the fp32 MFMA tile GEMM of the fp32 joint path where rows are 16-byte aligned (D, H multiples of 4);
+// else one thread per output element.
 #include "device_common.h"
 #include "kernels.h"
 
@@ -280,6 +281,9 @@ hipError_t launch_proj_forward(int bf16, const void* h, long long rows, int D, c
         return launch_tile_gemm<bf16_t, false, bf16_t, true>(h, D, mask, W, H, RowMask{nullptr, 1, 0}, ep, rows, H, D, 1,
                                                              stream);
     }
+    if (gemm_f32_edge_fits(h, D, W, H, D, H))
+        return launch_gemm_f32_masked(0, 1, (const float*)h, D, mask, (const float*)W, H, RowMask{nullptr, 1, 0},
+                                      (float*)out, H, bias, 0, rows, H, D, 1, stream);
     const long long total = rows * H;
     k_proj_gemm_f32<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(
         (const float*)h, D, 1, (const float*)W, H, 1, (float*)out, H, bias, rows, H, D, mask, 1, 0);
@@ -294,6 +298,9 @@ hipError_t launch_proj_backward_input(int bf16, const float* d_out, long long ro
         Epilogue ep{d_in, D, nullptr, 0, 0};
         return launch_tile_gemm<float, false, bf16_t, false>(d_out, H, none, W, H, none, ep, rows, D, H, 1, stream);
     }
+    if (gemm_f32_edge_fits(d_out, H, W, H, H, H))
+        return launch_gemm_f32_masked(0, 0, d_out, H, none, (const float*)W, H, none, d_in, D, nullptr, 0, rows, D, H, 1,
+                                      stream);
     const long long total = rows * D;
     k_proj_gemm_f32<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(
         d_out, H, 1, (const float*)W, 1, H, d_in, D, nullptr, rows, D, H, none, 0, 0);
@@ -311,6 +318,16 @@ hipError_t launch_proj_backward_weight(int bf16, const void* h, long long rows, 
         if (splits < 1) splits = 1;
         Epilogue ep{dW, H, nullptr, 0, 1};
         return launch_tile_gemm<bf16_t, true, float, true>(h, D, mask, d_out, H, mask, ep, D, H, rows, (int)splits, stream);
+    }
+    if (gemm_f32_edge_fits(h, D, d_out, H, D, H)) {
+        // split over the rows as on the bf16 path; dW is added to with float atomics
+        const long long tiles = (long long)((D + PT - 1) / PT) * ((H + PT - 1) / PT);
+        long long splits = (512 + tiles - 1) / tiles;
+        const long long max_splits = (rows + 255) / 256;
+        if (splits > max_splits) splits = max_splits;
+        if (splits < 1) splits = 1;
+        return launch_gemm_f32_masked(1, 1, (const float*)h, D, mask, d_out, H, mask, dW, H, nullptr, 1, D, H, rows,
+                                      (int)splits, stream);
     }
     const long long total = (long long)D * H;
     k_proj_gemm_f32<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(

@@ -20,14 +20,18 @@ KERNEL_ALIASES = [
     ("k_joint_scores<2", "joint_scores_fwd_keep"), ("k_kept_to_dh", "kept_scores_to_dh"),
     ("k_lattice", "lattice"), ("k_copy_f32", "copy_f32"), ("k_prepare", "prepare"),
     ("k_fwd_f32", "fwd_f32"), ("k_bwd_f32", "bwd_f32"),
-    ("k_gemm_f32<false, true>", "gemm_f32 scores = Z W"), ("k_gemm_f32<true, true>", "gemm_f32 dW = Z^T dh"),
-    ("k_gemm_f32<false, false>", "gemm_f32 dZ = dh W^T"), ("k_rows_z_f32", "rows_z_f32"),
+    ("k_rows_z_f32", "rows_z_f32"),
     ("k_rows_stats_f32", "rows_stats_f32"), ("k_rows_dh_f32", "rows_dh_f32"), ("k_rows_dz_f32", "rows_dz_f32"),
     ("k_col_sum", "col_sum"),
 ]
 
 
 def alias(name: str):
+    if "k_gemm_f32<" in name:
+        # operand classes OperandF32<k-slow?> / OperandF32Edge<k-slow?> of A and B
+        slow = [name[i + 1:].startswith("true") for i in range(len(name)) if name[i] == "<" and name[:i].endswith(("OperandF32", "OperandF32Edge"))]
+        kind = {(False, True): "scores = Z W", (True, True): "dW = Z^T dh", (False, False): "dZ = dh W^T"}.get(tuple(slow[:2]), "")
+        return "gemm_f32 " + ("(edges) " if "OperandF32Edge" in name else "") + kind
     for key, short in KERNEL_ALIASES:
         if key in name:
             return short

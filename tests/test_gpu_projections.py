@@ -57,6 +57,17 @@ def test_f32_projected_path_ragged_lengths():
     check(run_gpu_proj(batch, proj), run_oracle_proj(batch, proj), "f32", batch, "f32 ragged")
 
 
+@pytest.mark.parametrize("H,V,H_A,H_L", [(256, 128, 132, 200), (24, 11, 10, 7), (128, 256, 516, 4)])
+def test_f32_projected_path_tile_gemms_with_edges_and_the_fallback(H, V, H_A, H_L):
+    # widths that are multiples of 4 run the projections as fp32 MFMA tile GEMMs (ragged tiles, masked padded rows),
+    # others as one thread per output element; (256, 128) and (128, 256) also take the GEMM form of the joint path
+    wl = synth.custom_workload("pf32b", B=4, T_max=37, U_max=11, H=H, V=V, dtype="f32", index=133,
+                               t_rule="uniform", t_lo=5, u_rule="uniform", u_lo=0)
+    batch = synth.make_batch(wl)
+    proj = synth.make_proj_inputs(batch, H_A=H_A, H_L=H_L)
+    check(run_gpu_proj(batch, proj), run_oracle_proj(batch, proj), "f32", batch, f"f32 {H},{V},{H_A},{H_L}")
+
+
 def test_f32_identity_projection_equals_the_unprojected_entry_point():
     import torch
     batch = synth.make_batch("C1")
