@@ -44,7 +44,7 @@ typedef enum {
 
 typedef enum {
     RNNT_F32 = 0, /* enc, pred, W_out are float; everything is computed in fp32: the three      */
-                  /* GEMMs on fp32 MFMA where H and V are multiples of 128, else plain FMA    */
+                  /* GEMMs on fp32 MFMA where H, V are multiples of 4 from 64 on, else plain FMA */
     RNNT_BF16 = 1 /* enc, pred, W_out are bfloat16; the three GEMMs run on bf16 MFMA with     */
                   /* fp32 accumulation, tanh/softmax/lattice in fp32                          */
 } rnnt_dtype;
@@ -100,7 +100,7 @@ const char* rnnt_last_hip_error(void);
  *   hold up to 8 GiB, never more than the call's tile rows need, and the smallest plan holds the largest
  *   sample's rows: 2 (V + 64) + 2 (H + 64) + V / 16 bytes per row of its 64-node lattice tiles; with
  *   desc->input_grads_bf16 up to 256 MiB more, for the float sums of d_enc and d_pred of one group).
- *   RNNT_F32 with H and V multiples of 128 has chunk buffers too: 4 V + 8 H bytes per lattice node of a
+ *   RNNT_F32 with H and V multiples of 4, both >= 64, has chunk buffers too: 4 V + 8 H bytes per lattice node of a
  *   chunk (scores, joint activations and their gradients as float), 128 nodes in the smallest plan.
  *   Otherwise the largest plan not exceeding budget_bytes; if
  *   even the smallest workable plan (one sample per group, one tile row per chunk) exceeds it,
@@ -153,6 +153,8 @@ rnnt_status rnnt_validate_labels_host(const rnnt_desc* desc, const int32_t* labe
  * d_pred   dev  [B, U_max+1, H]    the same type, out, fully overwritten (zeros in padded rows)
  * dW_out   dev  [H, V]             float, out (overwritten or accumulated, see desc)
  * db_out   dev  [V]                float, out (same)
+ * enc, pred, W_out, b_out, d_enc, d_pred, dW_out, db_out are 16-byte aligned (RNNT_ERR_UNSUPPORTED otherwise;
+ * not required for RNNT_F32 shapes that take the plain FMA kernels).
  * workspace dev, 256-byte aligned, workspace_bytes >= rnnt_joint_loss_workspace_bytes(...);
  *          a larger workspace lets more samples share a launch
  * hip_stream  a hipStream_t (NULL = the default stream)

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <initializer_list>
 #include <vector>
 
 #include "../../include/rnnt_joint_loss.h"
@@ -196,6 +197,11 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     if (!enc || !pred || !W_out || !b_out || !loss || !T_len || !U_len) return RNNT_ERR_NULL;
     if (desc->U_max > 0 && !labels) return RNNT_ERR_NULL;
     if (grads && (!d_enc_out || !d_pred_out || !dW_out || !db_out)) return RNNT_ERR_NULL;
+    // the MFMA kernels read and write these arrays in 16-byte pieces
+    if (desc->dtype == RNNT_BF16 || f32_gemm_shape(desc->H, desc->V))
+        for (const void* q : {enc, pred, W_out, (const void*)b_out, (const void*)d_enc_out, (const void*)d_pred_out,
+                              (const void*)dW_out, (const void*)db_out})
+            if ((uintptr_t)q % 16 != 0) return RNNT_ERR_UNSUPPORTED;
     stt = check_lengths(desc, T_len, U_len);
     if (stt != RNNT_OK) return stt;
     if (sample_weight)

@@ -78,7 +78,7 @@ hipError_t launch_fwd_f32(const Problem& pr, const SampleTable& st, const Lattic
 hipError_t launch_bwd_f32(const Problem& pr, const SampleTable& st, const LatticeState& ls,
                           const GradOut& go, int s0, int s1, long long rows, hipStream_t stream);
 
-// fp32 MFMA GEMM form of the same two steps for H, V multiples of 128, over lattice nodes [r0, r0 + n) of the
+// fp32 MFMA GEMM form of the same two steps for H, V multiples of 4, over lattice nodes [r0, r0 + n) of the
 // group (node index relative to the group's first).  S [rows, V], Z and dZ [rows, H] are chunk buffers of
 // n rounded up to a multiple of 128 rows.
 hipError_t launch_fwd_f32_gemm(const Problem& pr, const SampleTable& st, const LatticeState& ls, int s0, int s1,

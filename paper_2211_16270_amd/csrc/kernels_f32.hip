@@ -1,6 +1,6 @@
 // fp32 path.  Two forms:
 //  * plain FMA kernels, one wavefront per lattice node, for any H, V (the small fp32 workloads);
-//  * for H and V multiples of 128, the same steps over chunks of lattice nodes as fp32 MFMA GEMMs
+//  * for H and V multiples of 4 from 64 on, the same steps over chunks of lattice nodes as fp32 MFMA GEMMs
 //    (v_mfma_f32_32x32x2_f32, full fp32 products and sums) with row kernels between them:
 //      Z = tanh(enc_t + pred_u)              (Eq. 4)            k_rows_z_f32
 //      S = Z W + b                            (Eq. 6)            k_gemm_f32 <A k-contiguous, B k-slow>
@@ -347,7 +347,7 @@ __global__ __launch_bounds__(256) void k_rows_stats_f32(Problem pr, SampleTable 
     const NodePos p = locate_node(st, ls.row_base, s0, s1, r0 + i);
     const float* row = S + i * V;
     const int label = (p.u < p.U) ? pr.labels[(size_t)p.s * pr.U_max + p.u] : -1;
-    const f32x4* row4 = reinterpret_cast<const f32x4*>(row);      // V is a multiple of 128, rows are 16-byte aligned
+    const f32x4* row4 = reinterpret_cast<const f32x4*>(row);      // V is a multiple of 4, rows are 16-byte aligned
     float m = RNNT_NEG_INF;
     for (int v = lane; v < V / 4; v += 64) {
         const f32x4 x = row4[v];
@@ -436,6 +436,19 @@ hipError_t launch_gemm_f32_masked(int a_kslow, int b_kslow, const float* A, long
     return hipErrorInvalidValue;
 }
 
+namespace {
+// The GEMM of the joint path: without edge handling where H and V are multiples of the tile, else with it.
+template <bool AK, bool BK>
+hipError_t joint_gemm_f32(const float* A, long long lda, const float* B, long long ldb, float* C, long long ldc,
+                          const float* bias, int atomic, long long M, long long N, long long K, int splits,
+                          hipStream_t stream) {
+    if (M % FT == 0 && N % FT == 0 && K % FK == 0)
+        return launch_gemm_f32<AK, BK>(A, lda, B, ldb, C, ldc, bias, atomic, M, N, K, splits, stream);
+    const RowMask none{nullptr, 1, 0};
+    return launch_gemm_f32_edge<AK, BK>(A, lda, none, B, ldb, none, C, ldc, bias, atomic, M, N, K, splits, stream);
+}
+}  // namespace
+
 hipError_t launch_fwd_f32_gemm(const Problem& pr, const SampleTable& st, const LatticeState& ls, int s0, int s1,
                                long long r0, long long n, float* S, float* Z, hipStream_t stream) {
     if (n <= 0) return hipSuccess;
@@ -443,7 +456,7 @@ hipError_t launch_fwd_f32_gemm(const Problem& pr, const SampleTable& st, const L
     k_rows_z_f32<<<dim3((unsigned)np), dim3(256), 0, stream>>>(pr, st, ls, s0, s1, r0, n, Z);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = launch_gemm_f32<false, true>(Z, pr.H, (const float*)pr.W, pr.V, S, pr.V, pr.b_out, 0, np, pr.V, pr.H, 1, stream);
+    e = joint_gemm_f32<false, true>(Z, pr.H, (const float*)pr.W, pr.V, S, pr.V, pr.b_out, 0, np, pr.V, pr.H, 1, stream);
     if (e != hipSuccess) return e;
     k_rows_stats_f32<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, stream>>>(pr, st, ls, s0, s1, r0, n, S);
     return hipGetLastError();
@@ -459,7 +472,7 @@ hipError_t launch_bwd_f32_gemm(const Problem& pr, const SampleTable& st, const L
     k_rows_z_f32<<<dim3((unsigned)np), dim3(256), 0, stream>>>(pr, st, ls, s0, s1, r0, n, Z);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = launch_gemm_f32<false, true>(Z, H, W, V, S, V, pr.b_out, 0, np, V, H, 1, stream);
+    e = joint_gemm_f32<false, true>(Z, H, W, V, S, V, pr.b_out, 0, np, V, H, 1, stream);
     if (e != hipSuccess) return e;
     k_rows_dh_f32<<<dim3((unsigned)(np / 4)), dim3(256), 0, stream>>>(pr, st, ls, s0, s1, r0, n, np, S);
     e = hipGetLastError();
@@ -467,13 +480,13 @@ hipError_t launch_bwd_f32_gemm(const Problem& pr, const SampleTable& st, const L
     e = launch_col_sum(S, np, V, go.db, stream);
     if (e != hipSuccess) return e;
     // dW += Z^T dh: about 512 workgroups in all, at least 128 rows per split
-    const long long tiles = (long long)(H / FT) * (V / FT);
+    const long long tiles = (long long)((H + FT - 1) / FT) * ((V + FT - 1) / FT);
     long long splits = (512 + tiles - 1) / tiles;
     if (splits > np / FT) splits = np / FT;
-    e = launch_gemm_f32<true, true>(Z, H, S, V, go.dW, V, nullptr, 1, H, V, np, (int)splits, stream);
+    e = joint_gemm_f32<true, true>(Z, H, S, V, go.dW, V, nullptr, 1, H, V, np, (int)splits, stream);
     if (e != hipSuccess) return e;
     // dZ = dh W^T   (B(k = v, n = h) = W[h, v]: k-contiguous)
-    e = launch_gemm_f32<false, false>(S, V, W, V, dZ, H, nullptr, 0, np, H, V, 1, stream);
+    e = joint_gemm_f32<false, false>(S, V, W, V, dZ, H, nullptr, 0, np, H, V, 1, stream);
     if (e != hipSuccess) return e;
     k_rows_dz_f32<<<dim3((unsigned)n), dim3(256), 0, stream>>>(pr, st, ls, s0, s1, r0, Z, dZ, go.d_enc, go.d_pred);
     return hipGetLastError();

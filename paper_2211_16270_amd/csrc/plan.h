@@ -36,7 +36,7 @@ struct Plan {
     int B = 0;
     bool bf16 = false;
     bool fused = false;                 // bf16 only: backward runs in the fused kernel
-    bool f32_gemm = false;              // fp32 only: H, V multiples of 128, the steps run as fp32 MFMA GEMMs over chunks
+    bool f32_gemm = false;              // fp32 only: H, V multiples of 4 from 64 on, the steps run as fp32 MFMA GEMMs over chunks
     bool keep = false;                  // bf16 only: forward keeps the scores, one backward chunk per group
     bool stage = false;                 // bf16 only: d_enc, d_pred leave as bf16; fp32 sums of one group in the workspace
     long long stage_samples = 0;        // samples a group may hold then
@@ -64,8 +64,8 @@ struct Plan {
 // Shapes the fused backward kernel covers (its dz accumulators must fit the register file).
 inline bool fused_backward_shape(int H, int V) { return H % 128 == 0 && H <= 640 && V % 256 == 0; }
 
-// Shapes the fp32 GEMM form covers (its tiles have no edge handling).
-inline bool f32_gemm_shape(int H, int V) { return H % 128 == 0 && V % 128 == 0; }
+// Shapes the fp32 GEMM form covers: rows of 16-byte pieces, and wide enough for 128 x 128 tiles to pay.
+inline bool f32_gemm_shape(int H, int V) { return H % 4 == 0 && V % 4 == 0 && H >= 64 && V >= 64; }
 
 // dW GEMM geometry: 256x256 output tiles, and as many K splits (a multiple of 8, one set per XCD) as
 // give about one workgroup per compute unit.  Every (split, tile) workgroup owns a 256 KiB slot of

@@ -63,8 +63,8 @@ def test_f32_moderate_shape_and_group_splitting():
     assert_parity(got2, ref, "f32", "mid32 min workspace")
 
 
-# ------------------------------------------------------------------ fp32 MFMA GEMM form (H, V multiples of 128)
-@pytest.mark.parametrize("H,V", [(128, 128), (256, 384), (384, 128)])
+# ------------------------------------------------------------------ fp32 MFMA GEMM form (H, V multiples of 4, >= 64)
+@pytest.mark.parametrize("H,V", [(128, 128), (256, 384), (384, 128), (64, 64), (68, 100), (320, 1000), (132, 72)])
 def test_f32_gemm_form_against_the_checker(H, V):
     wl = synth.custom_workload("g32", B=5, T_max=37, U_max=11, H=H, V=V, dtype="f32", index=131,
                                t_rule="uniform", t_lo=5, u_rule="uniform", u_lo=0)

@@ -79,6 +79,7 @@ def test_argument_checks_happen_on_the_host():
     assert call(desc, T, U, ws_bytes=4096) == 5                  # too small
     odd = Bd.make_desc(wl.B, wl.T_max, wl.U_max, 500, wl.V, 0, Bd.RNNT_BF16)
     assert call(odd, T, U) == 6                                  # H not supported by the MFMA path
+    assert call(desc, T, U, enc=ctypes.c_void_p(0x1004)) == 6    # the kernels need 16-byte aligned arrays
     assert Bd.rnnt_joint_loss_workspace_bytes(bad, T, U) == 0
 
 
@@ -165,7 +166,7 @@ def test_backward_chunks_are_whole_rounds_of_256_tiles_when_a_group_needs_severa
 def test_fp32_shapes_with_gemm_tiles_get_chunk_buffers():
     T = np.array([30, 17, 25], dtype=np.int32); U = np.array([7, 0, 11], dtype=np.int32)
     rows = int((T.astype(np.int64) * (U + 1)).sum())
-    for H, V, gemm in [(128, 256, True), (256, 128, True), (128, 200, False), (96, 256, False)]:
+    for H, V, gemm in [(128, 256, True), (256, 128, True), (96, 200, True), (128, 202, False), (60, 256, False)]:
         desc = Bd.make_desc(3, 30, 11, H, V, 0, Bd.RNNT_F32)
         st, info, _ = Bd.rnnt_joint_loss_plan(desc, T, U, 0)
         assert st == 0
