@@ -304,7 +304,7 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                            [&] { return launch_fwd_f32(pr, wv.st, ls, g.s0, g.s1, g.rows, stream); }));
         // f^W_2, f^W_3
         RNNT_HIP(timed(KC_LATTICE, stream,
-                       [&] { return launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, loss, stream); }));
+                       [&] { return launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, bf16 ? 0 : 1, loss, stream); }));
         // f^W_4 and Algorithm 1 lines 8, 10, 11
         for (; ci < plan.chunks.size() && plan.chunks[ci].group == (int)gi; ++ci) {
             if (!grads) continue;

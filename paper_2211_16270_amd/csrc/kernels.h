@@ -88,7 +88,8 @@ hipError_t launch_bwd_f32_gemm(const Problem& pr, const SampleTable& st, const L
                                hipStream_t stream);
 
 // ---- lattice (alpha, beta, loss) ------------------------------------------------------------
-hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0, int s1, int u_max,
+// wide != 0: the sweep accumulates in fp64 (alpha, beta, ln P still stored as fp32); used by the fp32 path
+hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0, int s1, int u_max, int wide,
                           float* loss, hipStream_t stream);
 
 // ---- bf16 MFMA path -------------------------------------------------------------------------

@@ -63,9 +63,19 @@ __device__ __forceinline__ float log_add_exp_fast(float a, float b) {
 
 constexpr int LAT_MAX_T = 1024; // threads per workgroup (label positions 0..U <= 1023)
 
+// R = float: the sweep in fp32 (bf16 path).  R = double: the recursion accumulates in fp64 and alpha, beta are
+// rounded to fp32 once, when stored (fp32 path: a sweep of T+U dependent fp32 log-add-exps loses about
+// sqrt(T+U) half-ulps of values of the order of 100, 2e-4 relative in the posteriors of a 500 x 100 lattice).
+__device__ __forceinline__ float lattice_lae(float a, float b) { return log_add_exp_fast(a, b); }
+__device__ __forceinline__ double lattice_lae(double a, double b) {
+    const double m = fmax(a, b);
+    return m + log1p(exp(-fabs(a - b)));      // one of the two may be -inf
+}
+
+template <typename R>
 __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeState ls, int s0,
                                                        float* __restrict__ loss) {
-    __shared__ float xch[2][LAT_MAX_T + 2];
+    __shared__ R xch[2][LAT_MAX_T + 2];
     __shared__ float red[LAT_MAX_T / 64];
     __shared__ float shift_sh;
 
@@ -92,11 +102,11 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
             for (int w = 0; w < (int)(blockDim.x >> 6); ++w) tot += red[w];
             shift_sh = -tot / (float)n;
         }
-        xch[0][tid + 1] = RNNT_NEG_INF;
-        xch[1][tid + 1] = RNNT_NEG_INF;
+        xch[0][tid + 1] = (R)RNNT_NEG_INF;
+        xch[1][tid + 1] = (R)RNNT_NEG_INF;
         if (tid == 0) {
-            xch[0][0] = xch[1][0] = RNNT_NEG_INF;
-            xch[0][blockDim.x + 1] = xch[1][blockDim.x + 1] = RNNT_NEG_INF;
+            xch[0][0] = xch[1][0] = (R)RNNT_NEG_INF;
+            xch[0][blockDim.x + 1] = xch[1][blockDim.x + 1] = (R)RNNT_NEG_INF;
         }
         __syncthreads();
     }
@@ -104,7 +114,7 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
     const int u = tid;
     const bool col = (u <= U);
     const int nsteps = T + U;   // anti-diagonals 0 .. T+U-1
-    float own = RNNT_NEG_INF;
+    R own = RNNT_NEG_INF;
     int par = 0;
     float pb[LAT_PF], py[LAT_PF];
 
@@ -129,19 +139,19 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
                 if (k < nsteps) {
                     const int t = k - u;
                     const bool act = col && t >= 0 && t < T;
-                    const float left = xch[par][u];          // column u-1, previous step
-                    float val = own;
+                    const R left = xch[par][u];          // column u-1, previous step
+                    R val = own;
                     if (act) {
                         if (k == 0) {
-                            val = 0.0f;
+                            val = (R)0;
                         } else {
                             // the offset and the boundary conditions go into the emission values, which do not
                             // depend on the step before: the dependent chain is own -> add -> log-add-exp
-                            const float eb = (t > 0) ? pb[i] + c : RNNT_NEG_INF;
-                            const float ey = (u > 0) ? py[i] + c : RNNT_NEG_INF;
-                            val = log_add_exp_fast(own + eb, left + ey);
+                            const R eb = (t > 0) ? (R)pb[i] + (R)c : (R)RNNT_NEG_INF;
+                            const R ey = (u > 0) ? (R)py[i] + (R)c : (R)RNNT_NEG_INF;
+                            val = lattice_lae(own + eb, left + ey);
                         }
-                        alpha[t * W1 + u] = val;
+                        alpha[t * W1 + u] = (float)val;
                         own = val;
                     }
                     xch[par ^ 1][u + 1] = val;
@@ -153,10 +163,10 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
         }
         if (u == U) {
             // own = alpha[T-1,U]; ln P (offset) = alpha + final blank
-            const float lnP_off = own + (lpb[(T - 1) * W1 + U] + c);
-            ls.lnP[s] = lnP_off;
+            const R lnP_off = own + ((R)lpb[(T - 1) * W1 + U] + (R)c);
+            ls.lnP[s] = (float)lnP_off;
             ls.shift[s] = c;
-            loss[s] = -(lnP_off - c * (float)(T + U));
+            loss[s] = (float)-(lnP_off - (R)c * (R)(T + U));
         }
     } else {
         float* __restrict__ beta = ls.beta + base;
@@ -179,17 +189,17 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
                 if (k < nsteps) {
                     const int t = T - 1 - (k - (U - u));
                     const bool act = col && t >= 0 && t < T;
-                    const float right = xch[par][u + 2];     // column u+1, previous step
-                    float val = own;
+                    const R right = xch[par][u + 2];     // column u+1, previous step
+                    R val = own;
                     if (act) {
                         if (k == 0) {
-                            val = pb[i] + c;                 // beta[T-1,U] = final blank
+                            val = (R)pb[i] + (R)c;           // beta[T-1,U] = final blank
                         } else {
-                            const float eb = (t < T - 1) ? pb[i] + c : RNNT_NEG_INF;
-                            const float ey = (u < U) ? py[i] + c : RNNT_NEG_INF;
-                            val = log_add_exp_fast(own + eb, right + ey);
+                            const R eb = (t < T - 1) ? (R)pb[i] + (R)c : (R)RNNT_NEG_INF;
+                            const R ey = (u < U) ? (R)py[i] + (R)c : (R)RNNT_NEG_INF;
+                            val = lattice_lae(own + eb, right + ey);
                         }
-                        beta[t * W1 + u] = val;
+                        beta[t * W1 + u] = (float)val;
                         own = val;
                     }
                     xch[par ^ 1][u + 1] = val;
@@ -374,9 +384,15 @@ __global__ __launch_bounds__(64) void k_lattice_wave(SampleTable st, LatticeStat
     }
 }
 
-hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0, int s1, int u_max, float* loss,
-                          hipStream_t stream) {
+hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0, int s1, int u_max, int wide,
+                          float* loss, hipStream_t stream) {
     if (s1 <= s0) return hipSuccess;
+    if (wide) {
+        const int threads = ((u_max + 1) + 63) / 64 * 64;
+        if (threads > LAT_MAX_T) return hipErrorInvalidValue;
+        k_lattice<double><<<dim3((unsigned)(s1 - s0), 2), dim3(threads), 0, stream>>>(st, ls, s0, loss);
+        return hipGetLastError();
+    }
     if (u_max + 1 <= 64) {
         k_lattice_wave<<<dim3((unsigned)(s1 - s0), 2), dim3(64), 2 * LW_RING * sizeof(float), stream>>>(
             st, ls, s0, loss);
@@ -384,7 +400,7 @@ hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0,
     }
     int threads = ((u_max + 1) + 63) / 64 * 64;
     if (threads > LAT_MAX_T) return hipErrorInvalidValue;
-    k_lattice<<<dim3((unsigned)(s1 - s0), 2), dim3(threads), 0, stream>>>(st, ls, s0, loss);
+    k_lattice<float><<<dim3((unsigned)(s1 - s0), 2), dim3(threads), 0, stream>>>(st, ls, s0, loss);
     return hipGetLastError();
 }
 

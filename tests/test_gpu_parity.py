@@ -586,6 +586,32 @@ def test_bf16_paper_shaped_workload_sampled_default_and_kept_scores():
         assert rel_grad_err(kept[k], plain[k]) <= tol["grad"], k
 
 
+def test_f32_paper_shaped_bench_workload_sampled():
+    # the workload of `bench.py --config P16F32` (16 samples up to 500 x 100, joint size 1024, 4096 word pieces, fp32)
+    # in the default plan that the benchmark times; the checker recomputes the sample with the fewest lattice nodes
+    wl = synth.custom_workload("P16F32", B=16, T_max=500, U_max=100, H=1024, V=4096, dtype="f32", index=5,
+                               t_rule="uniform", t_lo=454, u_rule="uniform", u_lo=54)
+    batch = synth.make_batch(wl)
+    rows = batch.T_len.astype(np.int64) * (batch.U_len + 1)
+    b = int(np.argmin(rows))
+    T, U = int(batch.T_len[b]), int(batch.U_len[b])
+    _say("paper-shaped fp32 sample", b, T, U)
+    r = O.sample_loss_and_grads(batch.enc[b, :T], batch.pred[b, :U + 1], batch.W_out, batch.b_out,
+                                batch.labels[b, :U], 0)
+    got = run_gpu(batch)
+    st, info, _ = Bd.rnnt_joint_loss_plan(got["desc"], batch.T_len, batch.U_len, 0)
+    assert st == 0 and 128 <= info["chunk_rows"] < info["rows_total"]       # several chunks of lattice nodes
+    assert np.all(np.isfinite(got["loss"]))
+    assert_padding_zero(got, batch)
+    tol = TOL["f32"]
+    el = abs(got["loss"][b] - r["loss"]) / abs(r["loss"])
+    ee = rel_grad_err(got["d_enc"][b, :T], r["d_enc"])
+    ep = rel_grad_err(got["d_pred"][b, :U + 1], r["d_pred"])
+    _say("paper-shaped fp32 errs", el, ee, ep)
+    assert el <= tol["loss"] and ee <= tol["grad"] and ep <= tol["grad"]
+    assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-4 * float(np.abs(got["db_out"]).sum())
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_small_shapes_against_the_checker(seed):
     # seeded random shapes, lengths and blank positions, both precisions; labels may equal the blank
