@@ -56,6 +56,8 @@ typedef struct {
     int32_t U_max;  /* label slots per sample, >= 0; pred has U_max + 1 rows, U_max <= 1023  */
     int32_t H;      /* joint size.  RNNT_BF16: multiple of 128, <= 1024.  RNNT_F32: 1..4096   */
     int32_t V;      /* vocabulary incl. blank.  RNNT_BF16: multiple of 256.  RNNT_F32: 2..16384 */
+                    /* (another size: pad W_out with zero columns and b_out with -1e4 there; the  */
+                    /* padding then has probability 0 and zero gradients)                         */
     int32_t blank;  /* index of the blank symbol, in [0,V)                                   */
     int32_t dtype;  /* rnnt_dtype                                                            */
     int32_t accumulate_params; /* 0: dW_out, db_out are overwritten; 1: added to (Alg. 1, line 3 / 8) */

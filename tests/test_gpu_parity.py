@@ -612,6 +612,29 @@ def test_f32_paper_shaped_bench_workload_sampled():
     assert abs(float(got["db_out"].astype(np.float64).sum())) < 1e-4 * float(np.abs(got["db_out"]).sum())
 
 
+@pytest.mark.parametrize("opts", [{}, dict(keep_scores=1)])
+def test_bf16_vocabulary_padded_to_the_tile_with_a_large_negative_bias(opts):
+    # a vocabulary that is not a multiple of 256 (here 300) is padded by the caller: zero columns in W_out and a
+    # bias of -1e4 there, so that the padding has probability exp(-1e4) = 0; the checker sees the 300 real entries
+    import dataclasses
+    V_real, V_pad = 300, 512
+    wl = synth.custom_workload("vpad", B=3, T_max=29, U_max=9, H=128, V=V_pad, dtype="bf16", index=140,
+                               t_rule="uniform", t_lo=8, u_rule="uniform", u_lo=1)
+    batch = synth.make_batch(wl)
+    labels = np.where(batch.labels >= 0, batch.labels % (V_real - 1) + 1, batch.labels).astype(np.int32)
+    W = batch.W_out.copy(); W[:, V_real:] = 0.0
+    b = np.zeros(V_pad, dtype=np.float32); b[V_real:] = -1e4
+    padded = dataclasses.replace(batch, W_out=W, b_out=b, labels=labels)
+    got = run_gpu(padded, **opts)
+    real = dataclasses.replace(padded, wl=dataclasses.replace(wl, V=V_real), W_out=W[:, :V_real].copy(),
+                               b_out=b[:V_real].copy())
+    ref = run_oracle(real)
+    assert np.all(got["dW_out"][:, V_real:] == 0.0) and np.all(got["db_out"][V_real:] == 0.0)
+    cut = dict(got, dW_out=got["dW_out"][:, :V_real], db_out=got["db_out"][:V_real])
+    assert_parity(cut, ref, "bf16", f"padded vocabulary {opts}")
+    assert_padding_zero(got, padded)
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_small_shapes_against_the_checker(seed):
     # seeded random shapes, lengths and blank positions, both precisions; labels may equal the blank
