@@ -154,7 +154,8 @@ hipError_t launch_bwd_f32(const Problem& pr, const SampleTable& st, const Lattic
 namespace {
 
 constexpr int FT = 128;       // output tile edge
-constexpr int FK = 16;        // K-step
+constexpr int FK = 16;        // K-step (32: 2.7 % slower at H = 1024, V = 4096)
+constexpr int FQ = FT * FK / 4 / 256;  // 16-byte pieces per thread, operand and step
 constexpr int FP = FT + 4;    // LDS row pitch (floats) of the [k][i] tile images
 
 // One operand of the tile product.  KSLOW = false: element (i, k) at p[i*ld + k]; true: at p[k*ld + i].
@@ -165,21 +166,21 @@ template <bool KSLOW>
 struct OperandF32 {
     const float* p;
     long long ld;
-    __device__ __forceinline__ void fetch(f32x4 (&v)[2], long long i0, long long k0, int tid) const {
+    __device__ __forceinline__ void fetch(f32x4 (&v)[FQ], long long i0, long long k0, int tid) const {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < FQ; ++q) {
             const int e = tid + 256 * q;
-            const long long off = !KSLOW ? (i0 + (e >> 2)) * ld + k0 + (e & 3) * 4
+            const long long off = !KSLOW ? (i0 + e / (FK / 4)) * ld + k0 + (e % (FK / 4)) * 4
                                          : (k0 + (e >> 5)) * ld + i0 + (e & 31) * 4;
             v[q] = *reinterpret_cast<const f32x4*>(p + off);
         }
     }
-    __device__ __forceinline__ void stage(const f32x4 (&v)[2], float* tile, int tid) const {
+    __device__ __forceinline__ void stage(const f32x4 (&v)[FQ], float* tile, int tid) const {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < FQ; ++q) {
             const int e = tid + 256 * q;
             if (!KSLOW) {
-                const int i = e >> 2, k = (e & 3) * 4;
+                const int i = e / (FK / 4), k = (e % (FK / 4)) * 4;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) tile[(k + j) * FP + i] = v[q][j];
             } else {
@@ -197,13 +198,13 @@ template <bool KSLOW>
 struct OperandF32Edge : OperandF32<KSLOW> {
     long long n_i, n_k;
     RowMask mask;
-    __device__ __forceinline__ void fetch(f32x4 (&v)[2], long long i0, long long k0, int tid) const {
+    __device__ __forceinline__ void fetch(f32x4 (&v)[FQ], long long i0, long long k0, int tid) const {
         typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < FQ; ++q) {
             const int e = tid + 256 * q;
-            const long long i = !KSLOW ? i0 + (e >> 2) : i0 + (e & 31) * 4;
-            const long long k = !KSLOW ? k0 + (e & 3) * 4 : k0 + (e >> 5);
+            const long long i = !KSLOW ? i0 + e / (FK / 4) : i0 + (e & 31) * 4;
+            const long long k = !KSLOW ? k0 + (e % (FK / 4)) * 4 : k0 + (e >> 5);
             const long long off = !KSLOW ? i * this->ld + k : k * this->ld + i;
             const bool ok = i < n_i && k < n_k;
             bool keep = ok;
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(OpA A, OpB B, float* __restric
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{0};
-    f32x4 va[2], vb[2];
+    f32x4 va[FQ], vb[FQ];
     A.fetch(va, m0, ks, tid);
     B.fetch(vb, n0, ks, tid);
     for (long long k0 = ks; k0 < ke; k0 += FK) {
