@@ -275,6 +275,11 @@ rnnt_status rnnt_debug_copy_f32(const float* src, float* dst, size_t n, void* hi
  */
 rnnt_status rnnt_debug_mfma_loop(const void* frags, float* out, int32_t workgroups, int32_t iters,
                                  void* hip_stream);
+/* The same loop on the fp8 MFMA (e4m3 operands, 32x32x64, unit block scales, fp32 accumulation): frags holds 32
+ * fragments of 64 lanes x 32 bytes (64 KiB); 2 * 32*32*64 * 16 * iters * 4 * workgroups flop per launch.  The path
+ * itself has no fp8 kernel; this tells what one could gain. */
+rnnt_status rnnt_debug_mfma_loop_fp8(const void* frags, float* out, int32_t workgroups, int32_t iters,
+                                     void* hip_stream);
 
 /*
  * Per-kernel timing for the benchmark (not a paper operation; measurement support for the

@@ -564,6 +564,14 @@ extern "C" rnnt_status rnnt_debug_mfma_loop(const void* frags, float* out, int32
     return RNNT_OK;
 }
 
+extern "C" rnnt_status rnnt_debug_mfma_loop_fp8(const void* frags, float* out, int32_t workgroups, int32_t iters,
+                                                void* hip_stream) {
+    if (!frags || !out) return RNNT_ERR_NULL;
+    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > 1000000) return RNNT_ERR_SHAPE;
+    RNNT_HIP(launch_mfma_loop_fp8(frags, out, workgroups, iters, (hipStream_t)hip_stream));
+    return RNNT_OK;
+}
+
 extern "C" const char* rnnt_last_hip_error(void) {
     static char text[160];
     if (g_last_hip_error == hipSuccess) return "";

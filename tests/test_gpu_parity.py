@@ -335,6 +335,16 @@ def test_mfma_loop_of_the_measurement_entry_point_multiplies():
     assert bool((out == 16 * 2 * 16.0 * 5).all())
 
 
+def test_fp8_mfma_loop_of_the_measurement_entry_point_multiplies():
+    # e4m3 ones (0x38) times ones: every 32x32x64 MFMA adds 64 to each accumulator element
+    import torch
+    frags = torch.full((32 * 64 * 32,), 0x38, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(2 * 256, dtype=torch.float32, device="cuda")
+    assert Bd.rnnt_debug_mfma_loop_fp8(frags, out, 2, 3) == 0
+    torch.cuda.synchronize()
+    assert bool((out == 16 * 2 * 64.0 * 3).all()), out[:4]
+
+
 # ------------------------------------------------------------------ scores kept instead of computed twice
 @pytest.mark.parametrize("H,V", [(128, 256), (640, 1024), (896, 256), (1024, 512), (256, 768), (1024, 4096)])
 def test_bf16_kept_scores_match_the_checker_and_the_default_path(H, V):

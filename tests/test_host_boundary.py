@@ -33,6 +33,8 @@ def test_no_hip_error_is_reported_before_one_happened():
     assert Bd.lib().rnnt_debug_mfma_loop(None, None, 1, 1, None) == 1   # null pointers are refused on the host
     assert Bd.lib().rnnt_debug_mfma_loop(ctypes.c_void_p(256), ctypes.c_void_p(256), 0, 1, None) == 2
     assert Bd.lib().rnnt_debug_mfma_loop(ctypes.c_void_p(256), ctypes.c_void_p(256), 1, 2000000, None) == 2
+    assert Bd.lib().rnnt_debug_mfma_loop_fp8(None, None, 1, 1, None) == 1
+    assert Bd.lib().rnnt_debug_mfma_loop_fp8(ctypes.c_void_p(256), ctypes.c_void_p(256), 1, 0, None) == 2
 
 
 def test_struct_layouts_match_the_header():
