@@ -263,6 +263,9 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         RNNT_HIP(timed(KC_PREPARE, stream, [&] { return launch_prepare(pa, stream); }));
     }
 
+    // fp32 path: sweeps of 128 steps or more accumulate in fp64 (the rounding of a dependent chain of fp32
+    // log-add-exps grows with its length; short lattices stay inside the fp32 tolerance without it)
+    const int wide_lattice = (!bf16 && desc->T_max + desc->U_max >= 128) ? 1 : 0;
     size_t ci = 0;
     int dw_first = 1;
     for (size_t gi = 0; gi < plan.groups.size(); ++gi) {
@@ -304,7 +307,7 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                            [&] { return launch_fwd_f32(pr, wv.st, ls, g.s0, g.s1, g.rows, stream); }));
         // f^W_2, f^W_3
         RNNT_HIP(timed(KC_LATTICE, stream,
-                       [&] { return launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, bf16 ? 0 : 1, loss, stream); }));
+                       [&] { return launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, wide_lattice, loss, stream); }));
         // f^W_4 and Algorithm 1 lines 8, 10, 11
         for (; ci < plan.chunks.size() && plan.chunks[ci].group == (int)gi; ++ci) {
             if (!grads) continue;
