@@ -128,6 +128,14 @@ def test_f32_gemm_form_several_chunks_and_accumulate():
     got2 = run_gpu(batch, accumulate_into=acc)
     assert rel_grad_err(got2["dW_out"] - 0.25, ref["dW_out"]) <= 2e-4
     assert rel_grad_err(got2["db_out"] + 0.5, ref["db_out"]) <= 2e-4
+    # the loss-only entry point runs the forward chunks and the lattice alone
+    dev = got["dev"]
+    loss = torch.zeros(batch.B, dtype=torch.float32, device="cuda:0")
+    st = Bd.rnnt_joint_loss_fwd(got["desc"], dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                dev["T_len"], dev["U_len"], loss, got["workspace"].buf)
+    torch.cuda.synchronize()
+    assert st == 0
+    np.testing.assert_array_equal(loss.cpu().numpy(), got["loss"])
 
 
 def test_f32_gemm_form_at_the_paper_joint_and_vocabulary_size():
