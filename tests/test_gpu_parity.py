@@ -500,6 +500,29 @@ def test_autograd_front_end_returns_the_library_gradients():
         assert rel_grad_err(x.grad.float().cpu().numpy(), ref[k]) <= 2e-2, k
 
 
+def test_autograd_front_end_with_float32_leaves():
+    # fp32 tensors go through the fp32 path (here its MFMA GEMM form): gradients against the checker at the
+    # fp32 tolerance, for a plain sum and for a masked mean
+    import torch
+    from paper_2211_16270_amd.autograd import rnnt_joint_loss
+    wl = synth.custom_workload("ag32", B=3, T_max=21, U_max=7, H=128, V=192, dtype="f32", index=124,
+                               t_rule="uniform", t_lo=5, u_rule="uniform", u_lo=1)
+    batch = synth.make_batch(wl, pad="zero")
+    dev = Bd.to_device(batch)
+    leaves = [dev[k].clone().requires_grad_(True) for k in ("enc", "pred", "W_out", "b_out")]
+    for w in (None, np.array([0.5, 0.0, 0.5], dtype=np.float32)):
+        for x in leaves:
+            x.grad = None
+        loss = rnnt_joint_loss(*leaves, dev["labels"], batch.T_len, batch.U_len, 0)
+        (loss.sum() if w is None else (loss * torch.tensor(w, device=loss.device)).sum()).backward()
+        torch.cuda.synchronize()
+        ref = run_oracle(batch, sample_weight=None if w is None else w.astype(np.float64))
+        for x, k in zip(leaves, GRADS):
+            assert x.grad.dtype == torch.float32
+            assert rel_grad_err(x.grad.cpu().numpy(), ref[k]) <= TOL["f32"]["grad"], (k, w)
+        assert rel_loss_err(loss.detach().cpu().numpy().astype(np.float64), run_oracle(batch)["loss"]) <= TOL["f32"]["loss"]
+
+
 # ------------------------------------------------------------------ the benchmarked workload
 def test_bf16_bench_workload_subbatch_parity():
     ids = [0, 17]
