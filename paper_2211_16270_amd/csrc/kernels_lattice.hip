@@ -110,10 +110,46 @@ __global__ __launch_bounds__(LAT_MAX_T) void k_lattice(SampleTable st, LatticeSt
         }
         __syncthreads();
     }
-    const float c = shift_sh;
+    float c = shift_sh;
     const int u = tid;
     const bool col = (u <= U);
     const int nsteps = T + U;   // anti-diagonals 0 .. T+U-1
+    if constexpr (sizeof(R) == 8) {
+        // fp64 sweep (fp32 path): alpha and beta are still stored as fp32, so their magnitude where the posteriors
+        // are not negligible decides the accuracy.  With c = -ln P / (T+U) the offset ln P is zero and alpha, beta
+        // stay near zero along the alignments that carry the probability, whatever the emissions look like (flat
+        // scores, where the number of alignments adds hundreds to ln P, or peaked ones).  ln P is not known
+        // beforehand: both workgroups of the sample first run the alpha sweep without storing anything (the same
+        // arithmetic in both, hence the same c), then the sweep proper.
+        __shared__ double c_better;
+        R o = (R)RNNT_NEG_INF;
+        int pr = 0;
+        for (int k = 0; k < nsteps; ++k) {
+            const int t = k - u;
+            const bool act = col && t >= 0 && t < T;
+            const R left = xch[pr][u];
+            R val = o;
+            if (act) {
+                if (k == 0) {
+                    val = (R)0;
+                } else {
+                    const R eb = (t > 0) ? (R)lpb[(t - 1) * W1 + u] + (R)c : (R)RNNT_NEG_INF;
+                    const R ey = (u > 0) ? (R)lpy[t * W1 + u - 1] + (R)c : (R)RNNT_NEG_INF;
+                    val = lattice_lae(o + eb, left + ey);
+                }
+                o = val;
+            }
+            xch[pr ^ 1][u + 1] = val;
+            __syncthreads();
+            pr ^= 1;
+        }
+        if (u == U) c_better = (double)c - (o + ((R)lpb[(T - 1) * W1 + U] + (R)c)) / (double)(T + U);
+        __syncthreads();
+        c = (float)c_better;
+        xch[0][tid + 1] = (R)RNNT_NEG_INF;
+        xch[1][tid + 1] = (R)RNNT_NEG_INF;
+        __syncthreads();
+    }
     R own = RNNT_NEG_INF;
     int par = 0;
     float pb[LAT_PF], py[LAT_PF];

@@ -138,6 +138,19 @@ def test_f32_gemm_form_several_chunks_and_accumulate():
     np.testing.assert_array_equal(loss.cpu().numpy(), got["loss"])
 
 
+def test_f32_long_lattices_keep_the_gradient_tolerance():
+    # lattices near the largest of the named workloads (1000 x 200): the fp32 path's sweep accumulates in fp64, so
+    # that the posteriors of a chain of 1100 dependent log-add-exps stay inside the fp32 gradient tolerance
+    wl = synth.custom_workload("long32", B=2, T_max=1000, U_max=200, H=64, V=64, dtype="f32", index=135,
+                               t_rule="uniform", t_lo=900, u_rule="uniform", u_lo=150)
+    batch = synth.make_batch(wl)
+    _say("long fp32 lattices", batch.T_len, batch.U_len)
+    got, ref = run_gpu(batch), run_oracle(batch)
+    e, errs = assert_parity(got, ref, "f32", "long32")
+    _say("long32 errs", e, errs)
+    assert_padding_zero(got, batch)
+
+
 def test_f32_gemm_form_at_the_paper_joint_and_vocabulary_size():
     # H = 1024, V = 4096 (Section 5.1) in fp32, lengths with the paper's padding scheme scaled down; a budget that
     # cuts the backward pass into several chunks
