@@ -10,7 +10,8 @@
 // log-probability shifts ln P by c*(T+U) and leaves all posteriors unchanged.  c is chosen per
 // sample (minus the mean of the larger of the two emission log-probabilities over the lattice)
 // so that alpha and beta stay near zero instead of growing to thousands, which keeps fp32
-// resolution for the posteriors of long utterances.
+// resolution for the posteriors of long utterances.  The fp32 path's instantiation (k_lattice<double>)
+// accumulates in fp64 and takes c = -ln P / (T+U) from a first sweep.
 #include "device_common.h"
 
 namespace rnnt {
