@@ -352,12 +352,10 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                 }));
                 dw_first = 0;
             } else if (plan.f32_gemm) {
-                for (long long r0 = 0; r0 < g.rows; r0 += plan.chunk_rows)
-                    RNNT_HIP(timed(KC_BWD_F32, stream, [&] {
-                        return launch_bwd_f32_gemm(pr, wv.st, ls, go, g.s0, g.s1, r0,
-                                                   std::min(plan.chunk_rows, g.rows - r0), (float*)wv.dH, (float*)wv.Z,
-                                                   wv.dZ32, stream);
-                    }));
+                RNNT_HIP(timed(KC_BWD_F32, stream, [&] {
+                    return launch_bwd_f32_gemm(pr, wv.st, ls, go, g.s0, g.s1, c.row0, c.rows, (float*)wv.dH,
+                                               (float*)wv.Z, wv.dZ32, stream);
+                }));
             } else {
                 RNNT_HIP(timed(KC_BWD_F32, stream,
                                [&] { return launch_bwd_f32(pr, wv.st, ls, go, g.s0, g.s1, g.rows, stream); }));

@@ -244,6 +244,17 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
                 p.chunks.push_back(c);
             }
         }
+    } else if (p.f32_gemm) {
+        // fp32 GEMM form: ranges of lattice nodes that fit the chunk buffers
+        for (int gi = 0; gi < (int)p.groups.size(); ++gi) {
+            const Group& g = p.groups[gi];
+            for (long long r0 = 0; r0 < g.rows; r0 += chunk_rows) {
+                Chunk c{gi, g.tile0, g.tile1};
+                c.row0 = r0;
+                c.rows = std::min(chunk_rows, g.rows - r0);
+                p.chunks.push_back(c);
+            }
+        }
     } else {
         for (int gi = 0; gi < (int)p.groups.size(); ++gi)
             p.chunks.push_back(Chunk{gi, p.groups[gi].tile0, p.groups[gi].tile1});

@@ -30,6 +30,7 @@ struct Group {
 struct Chunk {
     int group;
     int tile0, tile1;    // global tile range, inside the group's range
+    long long row0 = 0, rows = 0;   // fp32 GEMM form: lattice nodes [row0, row0 + rows) of the group instead
 };
 
 struct Plan {

@@ -177,8 +177,12 @@ def test_fp32_shapes_with_gemm_tiles_get_chunk_buffers():
             assert info["chunk_rows"] == -(-rows // 128) * 128
             assert info["chunk_bytes"] >= info["chunk_rows"] * (4 * V + 8 * H)
             nmin = Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 1)
-            st, small, _ = Bd.rnnt_joint_loss_plan(desc, T, U, nmin)
+            st, small, groups = Bd.rnnt_joint_loss_plan(desc, T, U, nmin)
             assert st == 0 and small["chunk_rows"] == 128 and small["n_groups"] == 2
+            # chunks are ranges of 128 lattice nodes of a group
+            per_sample = T.astype(np.int64) * (U + 1)
+            assert small["n_chunks"] == sum(-(-int(per_sample[groups == g].sum()) // 128) for g in range(2))
+            assert info["n_chunks"] == info["n_groups"] == 1
         else:
             assert info["chunk_rows"] == 0 and info["chunk_bytes"] == 0
 
