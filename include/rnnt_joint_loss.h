@@ -82,7 +82,8 @@ typedef struct {
     int32_t n_groups;         /* launches of the forward/lattice stage; samples of a group run together */
     int32_t n_chunks;         /* launches of the backward stage (row ranges of <= chunk_rows)  */
     int64_t group_rows_cap;   /* lattice rows that fit one group                               */
-    int64_t chunk_rows;       /* tile-padded rows per backward chunk                           */
+    int64_t chunk_rows;       /* rows per backward chunk: tile-padded (bf16), lattice nodes    */
+                              /* (fp32 GEMM form), 0 for the plain fp32 kernels                */
     size_t  workspace_bytes;  /* bytes the plan uses                                           */
     size_t  lattice_bytes;    /* part of it: lse, lpb, lpy, alpha, beta of one group           */
     size_t  chunk_bytes;      /* part of it: bf16 score-gradient / joint chunk buffers         */
