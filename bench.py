@@ -5,13 +5,18 @@ A step is one call of rnnt_joint_loss_fwd_bwd over one synthetic batch (the whol
 joint tiles, score GEMM, softmax statistics, lattice, score gradients, backward GEMMs), with
 all inputs already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2|C3|C4|C5|C1|P16|P16F32] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4|C2|C3|C5|C1|P16|P16F32] [--no-cpu-baseline]
 
-`value` is samples/s over K timed steps (whole job, one GPU).  `roofline` describes the kernel
-that takes the most time: its algorithmic flops per launch divided by its average launch
-duration, measured with HIP events recorded on the call's stream in a second pass over the
-same K steps (the events are kept out of the pass that yields `value`).  `cpu_baseline` is
-the float64 checker timed on the host cores on a few samples of the same workload.
+The default workload is C4, the largest one a single GPU holds and the one the target is stated on
+(B = 1024, T <= 1000, U <= 200, H = 512, V = 1024, bf16).  `value` is samples/s over K timed steps (whole
+job, one GPU).  `roofline` describes the kernel that takes the most time: its ALGORITHMIC flops per launch
+(2 H V per lattice node and contraction the method asks for: the scores once, dW_out, dz; scores that a
+backward kernel computes a second time count as executed work only) divided by its average launch duration,
+measured with HIP events recorded on the call's stream in a second pass over the same K steps (the events
+are kept out of the pass that yields `value`); `exec_flops_per_launch` / `frac_exec` count what the kernel
+really multiplies.  `roofline.traffic` is read from the committed rocprofv3 counter summary of this workload
+under profiles/ (it is not measured in this run).  `cpu_baseline` is the float64 checker timed on the host
+cores on a few samples of the same workload.
 """
 import argparse
 import json
@@ -36,7 +41,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="C2")
+    ap.add_argument("--config", default="C4")
     ap.add_argument("--budget-mib", type=int, default=0, help="workspace budget (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="use only the first N samples (profiling aid)")
@@ -158,11 +163,15 @@ def main():
 
     R = int(info["rows_total"])
     HV = wl.H * wl.V
-    # algorithmic flops per launch of each MFMA kernel: 2*H*V per lattice node it covers
-    alg_flops_per_step = {"joint_scores_fwd": 2.0 * R * HV, "joint_scores_bwd": 2.0 * R * HV,
+    # flops per step of each MFMA kernel, 2*H*V per lattice node and contraction.  Algorithmic: the three
+    # contractions the method asks for (scores, dW_out, dz), each counted once, where it is first computed;
+    # executed: what the kernel multiplies, i.e. also the scores a backward kernel computes a second time.
+    alg_flops_per_step = {"joint_scores_fwd": 2.0 * R * HV, "joint_scores_bwd": 0.0,
                           "joint_scores_fwd_keep": 2.0 * R * HV,
-                          "gemm_dz": 2.0 * R * HV, "gemm_dw_db": 2.0 * R * HV, "joint_bwd_fused": 4.0 * R * HV,
-                          "fwd_f32": 2.0 * R * HV, "bwd_f32": 6.0 * R * HV}
+                          "gemm_dz": 2.0 * R * HV, "gemm_dw_db": 2.0 * R * HV, "joint_bwd_fused": 2.0 * R * HV,
+                          "fwd_f32": 2.0 * R * HV, "bwd_f32": 4.0 * R * HV}
+    exec_flops_per_step = dict(alg_flops_per_step, joint_scores_bwd=2.0 * R * HV, bwd_f32=6.0 * R * HV,
+                               joint_bwd_fused=(2.0 if args.keep_scores else 4.0) * R * HV)
     kernels = {}
     for name, (cnt, ms) in prof.items():
         if cnt:
@@ -174,8 +183,13 @@ def main():
     launches = kernels[dom]["launches_per_step"]
     avg_s = kernels[dom]["avg_launch_us"] * 1e-6
     flops_per_launch = alg_flops_per_step[dom] / launches
+    exec_per_launch = exec_flops_per_step[dom] / launches
     peak = PEAK_BF16_FLOPS if wl.dtype == "bf16" else PEAK_F32_FLOPS
     achieved = flops_per_launch / avg_s
+    for name, k in kernels.items():
+        if name in alg_flops_per_step:
+            k["frac_alg"] = alg_flops_per_step[name] / (k["ms_per_step"] * 1e-3) / peak
+            k["frac_exec"] = exec_flops_per_step[name] / (k["ms_per_step"] * 1e-3) / peak
     # HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if any
     from paper_2211_16270_amd.pmc_summary import read_traffic
     tname = f"hbm_traffic_{wl.name}" + ("_keep_scores" if args.keep_scores else "") + ".txt"
@@ -184,13 +198,18 @@ def main():
     # then the group of launches of one chunk: three GEMMs and the row kernels between them), else plain FMA
     roofline = {"bound": "mfma" if (wl.dtype == "bf16" or info["chunk_rows"] > 0) else "alu", "kernel": dom,
                 "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
-                "traffic": traffic.get(dom), "alg_flops_per_launch": flops_per_launch,
-                "avg_launch_us": kernels[dom]["avg_launch_us"]}
+                "traffic": traffic.get(dom), "traffic_source": ("profiles/" + tname) if traffic.get(dom) else None,
+                "alg_flops_per_launch": flops_per_launch, "exec_flops_per_launch": exec_per_launch,
+                "frac_exec": exec_per_launch / avg_s / peak, "avg_launch_us": kernels[dom]["avg_launch_us"]}
     step_s = elapsed / steps
     util_alg = 6.0 * R * HV / step_s / peak
     util_exec = (6.0 if args.keep_scores else 8.0) * R * HV / step_s / peak
     lat = kernels.get("lattice")
-    lattice_gbs = (24.0 * R / (lat["ms_per_step"] * 1e-3) / 1e9) if lat else None
+    # lattice pass: bytes per launch from the committed FETCH_SIZE / WRITE_SIZE summary where there is one,
+    # next to the figure from the 24 bytes per node the sweep has to move (emissions read twice, alpha, beta written)
+    lattice_alg_gbs = (24.0 * R / (lat["ms_per_step"] * 1e-3) / 1e9) if lat else None
+    lattice_gbs = (traffic["lattice"] * lat["launches_per_step"] / (lat["ms_per_step"] * 1e-3) / 1e9) \
+        if lat and traffic.get("lattice") else None
 
     out = {
         "metric": "samples/s fused joint+RNN-T loss+grads" + (" incl. input projections" if args.projections else ""),
@@ -207,7 +226,7 @@ def main():
                    "workspace_bytes": int(nbytes)},
         "mfma_util_alg": util_alg, "mfma_util_exec": util_exec,
         "peak_hbm_gb": peak_bytes / 1e9,
-        "lattice_gb_per_s": lattice_gbs,
+        "lattice_gb_per_s": lattice_gbs, "lattice_gb_per_s_from_24B_per_node": lattice_alg_gbs,
         "ms_per_step_with_events": elapsed_prof / steps * 1e3,
         "gpu_kernel_ms_per_step": gpu_ms,
         "roofline": roofline,

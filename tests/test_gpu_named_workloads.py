@@ -1,0 +1,159 @@
+"""GPU parity on the named workloads at their real shapes: sub-batches the float64 checker finishes in
+seconds, every one of the five outputs compared element by element (loss, d_enc, d_pred, dW_out, db_out),
+in the default plan that bench.py times and in plans a small workspace cuts into several groups of samples
+and several backward chunks (run with -m gpu on an MI355X)."""
+import numpy as np
+import pytest
+
+from paper_2211_16270_amd import binding as Bd
+from paper_2211_16270_amd import synth
+from tests.gpu_util import assert_padding_zero, assert_parity, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _rows(wl):
+    T, U, _ = synth.draw_lengths_labels(wl)
+    return T.astype(np.int64) * (U.astype(np.int64) + 1), T, U
+
+
+def _ids_spanning(wl, n, max_rows=None):
+    """n sample ids of a workload: the one with the fewest lattice nodes, the one with the most (at most
+    max_rows, if given) and the first others."""
+    rows, _, _ = _rows(wl)
+    ok = np.arange(wl.B) if max_rows is None else np.nonzero(rows <= max_rows)[0]
+    lo = int(ok[np.argmin(rows[ok])])
+    hi = int(ok[np.argmax(rows[ok])])
+    ids = [lo, hi]
+    for b in ok:
+        if len(ids) >= n:
+            break
+        if int(b) not in ids:
+            ids.append(int(b))
+    return ids
+
+
+def _budget_with_several_groups_and_chunks(batch, desc_opts, frac=0.5):
+    """A workspace size between the smallest plan and the default one that cuts the sub-batch into at
+    least two groups of samples and more backward chunks than groups."""
+    wl = batch.wl
+    desc = Bd.make_desc(batch.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, Bd.RNNT_BF16, 0, **desc_opts)
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(desc, batch.T_len, batch.U_len, 1)
+    ndef = Bd.rnnt_joint_loss_workspace_bytes(desc, batch.T_len, batch.U_len, 0)
+    for f in (frac, 0.25, 0.1, 0.03, 0.0):
+        budget = int(nmin + f * (ndef - nmin))
+        st, info, _ = Bd.rnnt_joint_loss_plan(desc, batch.T_len, batch.U_len, budget)
+        assert st == 0
+        if info["n_groups"] >= 2 and info["n_chunks"] > info["n_groups"]:
+            return budget, info
+    raise AssertionError("no budget cuts this sub-batch into several groups and chunks")
+
+
+def test_c2_full_batch_all_outputs():
+    # the whole B = 32 batch (the checker takes a few seconds): default plan = one group, one chunk
+    batch = synth.make_batch("C2")
+    ref = run_oracle(batch)
+    got = run_gpu(batch)
+    e, errs = assert_parity(got, ref, "bf16", "C2 full")
+    _say("C2 full errs", e, errs)
+    assert_padding_zero(got, batch)
+    kept = run_gpu(batch, keep_scores=1)
+    e, errs = assert_parity(kept, ref, "bf16", "C2 full, kept scores")
+    _say("C2 full kept errs", e, errs)
+
+
+def test_c4_subbatch_all_outputs_default_and_small_workspace():
+    # memory-headline workload (B = 1024, T <= 1000, U <= 200, H = 512, V = 1024): 12 of its samples, among them
+    # the one with the fewest and the one with the most lattice nodes (multi-wave lattice kernel, U + 1 > 64)
+    wl = synth.WORKLOADS["C4"]
+    ids = _ids_spanning(wl, 12)
+    batch = synth.make_batch(wl, sample_ids=ids)
+    _say("C4 ids", ids, batch.T_len.tolist(), batch.U_len.tolist())
+    ref = run_oracle(batch)
+    _say("C4 checker done")
+    got = run_gpu(batch)
+    e, errs = assert_parity(got, ref, "bf16", "C4 sub-batch")
+    _say("C4 sub-batch errs", e, errs)
+    assert_padding_zero(got, batch)
+    budget, info = _budget_with_several_groups_and_chunks(batch, {})
+    _say("C4 small plan", info)
+    small = run_gpu(batch, budget_bytes=budget)
+    e, errs = assert_parity(small, ref, "bf16", "C4 sub-batch, several groups and chunks")
+    _say("C4 small-workspace errs", e, errs)
+    assert_padding_zero(small, batch)
+
+
+def test_c3_subbatch_all_outputs_default_small_workspace_and_kept_scores():
+    # H = 640 (the widest joint the fused backward kernel takes), V = 4096: 8 samples incl. fewest / most nodes
+    wl = synth.WORKLOADS["C3"]
+    ids = _ids_spanning(wl, 8)
+    batch = synth.make_batch(wl, sample_ids=ids)
+    _say("C3 ids", ids, batch.T_len.tolist(), batch.U_len.tolist())
+    ref = run_oracle(batch)
+    _say("C3 checker done")
+    got = run_gpu(batch)
+    e, errs = assert_parity(got, ref, "bf16", "C3 sub-batch")
+    _say("C3 sub-batch errs", e, errs)
+    assert_padding_zero(got, batch)
+    budget, info = _budget_with_several_groups_and_chunks(batch, {})
+    _say("C3 small plan", info)
+    small = run_gpu(batch, budget_bytes=budget)
+    e, errs = assert_parity(small, ref, "bf16", "C3 sub-batch, several groups and chunks")
+    _say("C3 small-workspace errs", e, errs)
+    kept = run_gpu(batch, keep_scores=1)
+    e, errs = assert_parity(kept, ref, "bf16", "C3 sub-batch, kept scores")
+    _say("C3 kept errs", e, errs)
+    assert_padding_zero(kept, batch)
+
+
+def test_c5_subbatch_all_outputs_short_and_long_samples_together():
+    # V = 8192, Zipf labels, log-uniform lengths: the shortest sample (50 x 16: single-wave lattice kernel, 16 x 4
+    # tiles) next to long ones (U + 1 > 64: multi-wave lattice kernel, 8 x 8 tiles) in one launch.  The checker
+    # forms a sample's [T, U+1, V] scores in float64 several times over, so the long ones are capped at 60 000
+    # lattice nodes (4 GB per such array); the longest sample of the workload (800 x 241, 12.6 GB per array) is
+    # left to the invariants of the full-size run below.
+    wl = synth.WORKLOADS["C5"]
+    ids = _ids_spanning(wl, 8, max_rows=60_000)
+    batch = synth.make_batch(wl, sample_ids=ids)
+    _say("C5 ids", ids, batch.T_len.tolist(), batch.U_len.tolist())
+    assert batch.U_len.min() + 1 <= 64 < batch.U_len.max() + 1
+    ref = run_oracle(batch)
+    _say("C5 checker done")
+    got = run_gpu(batch)
+    e, errs = assert_parity(got, ref, "bf16", "C5 sub-batch")
+    _say("C5 sub-batch errs", e, errs)
+    assert_padding_zero(got, batch)
+    kept = run_gpu(batch, keep_scores=1)
+    e, errs = assert_parity(kept, ref, "bf16", "C5 sub-batch, kept scores")
+    _say("C5 kept errs", e, errs)
+    budget, info = _budget_with_several_groups_and_chunks(batch, {})
+    _say("C5 small plan", info)
+    small = run_gpu(batch, budget_bytes=budget)
+    e, errs = assert_parity(small, ref, "bf16", "C5 sub-batch, several groups and chunks")
+    _say("C5 small-workspace errs", e, errs)
+
+
+def test_c5_longest_and_shortest_sample_packing_invariance():
+    # the longest (800 x 241) and the shortest sample of C5 in one call against each of them alone: per-sample
+    # outputs do not depend on what else shares the launch; the parameter gradients add up
+    wl = synth.WORKLOADS["C5"]
+    rows, _, _ = _rows(wl)
+    lo, hi = int(np.argmin(rows)), int(np.argmax(rows))
+    both = run_gpu(synth.make_batch(wl, sample_ids=[lo, hi]))
+    a = run_gpu(synth.make_batch(wl, sample_ids=[lo]))
+    b = run_gpu(synth.make_batch(wl, sample_ids=[hi]))
+    assert np.all(np.isfinite(both["loss"]))
+    np.testing.assert_allclose(both["loss"], np.concatenate([a["loss"], b["loss"]]), rtol=1e-6)
+    for k in ("d_enc", "d_pred"):
+        for i, single in enumerate((a, b)):
+            d = np.abs(both[k][i] - single[k][0]).max() / np.abs(single[k][0]).max()
+            assert d < 1e-3, (k, i, d)
+    for k in ("dW_out", "db_out"):
+        s = a[k].astype(np.float64) + b[k].astype(np.float64)
+        d = np.abs(both[k] - s).max() / np.abs(s).max()
+        assert d < 2e-3, (k, d)
+    assert abs(float(both["db_out"].astype(np.float64).sum())) < 1e-2 * float(np.abs(both["db_out"]).sum())
