@@ -196,6 +196,31 @@ rnnt_status rnnt_joint_loss_fwd_bwd_weighted(const rnnt_desc* desc,
                                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * rnnt_joint_loss_fwd_bwd for callers that cannot allocate device memory or provide a workspace (code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the workspace is an array of
+ * RNNT_STATIC_SCRATCH_BYTES that is part of the library's device code, one copy per GPU the library runs on, held
+ * until the process ends.  The call allocates nothing, on the device or through the runtime: no hipMalloc /
+ * hipFree, and the length tables reach the GPU as kernel arguments instead of through a host-to-device copy.
+ * Same inputs, outputs, layouts and results as rnnt_joint_loss_fwd_bwd with a workspace of that size (the same
+ * schedule, so dW_out is bit-identical and the other sums agree up to the order of their atomic additions).
+ *   RNNT_ERR_WORKSPACE  the call's smallest plan does not fit the array (the packed copies of W_out, 4 H V bytes,
+ *                       the dW partial sums, about 64 MiB while H V <= 2^21, 20 bytes per lattice node of the
+ *                       largest sample and one 128-row backward chunk must fit), or B > RNNT_STATIC_MAX_B
+ *   other errors as rnnt_joint_loss_fwd_bwd
+ * Nothing in the array has to be cleared between calls (every part is written before it is read within a call);
+ * it keeps the last call's contents.  All calls on one GPU share the one array: calls that overlap on a GPU
+ * (different streams or threads) race; order them on one stream.
+ */
+#define RNNT_STATIC_SCRATCH_BYTES (128u << 20)
+#define RNNT_STATIC_MAX_B 8192
+rnnt_status rnnt_joint_loss_fwd_bwd_static(const rnnt_desc* desc,
+                                           const void* enc, const void* pred, const void* W_out,
+                                           const float* b_out, const int32_t* labels,
+                                           const int32_t* T_len_host, const int32_t* U_len_host,
+                                           float* loss, void* d_enc, void* d_pred,
+                                           float* dW_out, float* db_out, void* hip_stream);
+
+/*
  * Loss only (Eqs. 4, 6, 7-9): same inputs, no gradient outputs, same workspace rule
  * (the chunk buffers stay unused).
  */

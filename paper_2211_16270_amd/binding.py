@@ -22,7 +22,9 @@ EXPORTS = ["rnnt_status_string", "rnnt_last_hip_error", "rnnt_joint_loss_workspa
            "rnnt_parallel_iterations", "rnnt_validate_labels_host", "rnnt_joint_loss_fwd_bwd",
            "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice", "rnnt_profile_enable",
            "rnnt_debug_copy_f32", "rnnt_debug_mfma_loop", "rnnt_debug_mfma_loop_fp8", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
-           "rnnt_joint_proj_workspace_bytes", "rnnt_joint_proj_loss_fwd_bwd", "rnnt_joint_loss_fwd_bwd_weighted"]
+           "rnnt_joint_proj_workspace_bytes", "rnnt_joint_proj_loss_fwd_bwd", "rnnt_joint_loss_fwd_bwd_weighted",
+           "rnnt_joint_loss_fwd_bwd_static"]
+RNNT_STATIC_SCRATCH_BYTES = 128 << 20
 
 
 class RnntDesc(ctypes.Structure):
@@ -86,6 +88,8 @@ def lib() -> ctypes.CDLL:
     L.rnnt_joint_loss_fwd_bwd.restype = ctypes.c_int
     L.rnnt_joint_loss_fwd_bwd.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, f32p, f32p, f32p, f32p,
                                           vp, ctypes.c_size_t, vp]
+    L.rnnt_joint_loss_fwd_bwd_static.restype = ctypes.c_int
+    L.rnnt_joint_loss_fwd_bwd_static.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, f32p, f32p, f32p, f32p, vp]
     L.rnnt_joint_loss_fwd_bwd_weighted.restype = ctypes.c_int
     L.rnnt_joint_loss_fwd_bwd_weighted.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, f32p, f32p, f32p, f32p,
                                                     f32p, vp, ctypes.c_size_t, vp]
@@ -177,6 +181,15 @@ def rnnt_joint_loss_fwd_bwd(desc: RnntDesc, enc, pred, W_out, b_out, labels, T_l
         _ptr(loss), _ptr(d_enc), _ptr(d_pred), _ptr(dW_out), _ptr(db_out), _ptr(workspace),
         int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
         _stream_handle(stream)))
+
+
+def rnnt_joint_loss_fwd_bwd_static(desc: RnntDesc, enc, pred, W_out, b_out, labels, T_len, U_len,
+                                   loss, d_enc, d_pred, dW_out, db_out, stream=None) -> int:
+    """Raw call of the entry point whose workspace is the library's own static device array."""
+    T, U = _i32(T_len), _i32(U_len)
+    return int(lib().rnnt_joint_loss_fwd_bwd_static(
+        ctypes.byref(desc), _ptr(enc), _ptr(pred), _ptr(W_out), _ptr(b_out), _ptr(labels), _ip(T), _ip(U),
+        _ptr(loss), _ptr(d_enc), _ptr(d_pred), _ptr(dW_out), _ptr(db_out), _stream_handle(stream)))
 
 
 def rnnt_joint_loss_fwd_bwd_weighted(desc: RnntDesc, enc, pred, W_out, b_out, labels, T_len, U_len, sample_weight,

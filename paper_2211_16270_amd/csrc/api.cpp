@@ -145,6 +145,33 @@ int g_last_hip_line = 0;
         }                                        \
     } while (0)
 
+// Host tables -> device without a copy engine and without touching host memory after the call returns: the
+// values travel as kernel arguments (at most 960 ints per launch), which the runtime captures at launch.
+struct TableChunk {
+    int n;
+    int v[960];
+};
+__global__ void k_put_table(TableChunk c, int* __restrict__ dst) {
+    for (int i = threadIdx.x; i < c.n; i += blockDim.x) dst[i] = c.v[i];
+}
+hipError_t put_table(const unsigned char* src, size_t bytes, void* dst, hipStream_t stream) {
+    // bytes is a multiple of 4 (all tables are int32 / int64 / float)
+    const size_t n = bytes / 4;
+    const int* s = reinterpret_cast<const int*>(src);
+    for (size_t at = 0; at < n; at += 960) {
+        TableChunk c;
+        c.n = (int)std::min<size_t>(960, n - at);
+        std::memcpy(c.v, s + at, (size_t)c.n * 4);
+        k_put_table<<<dim3(1), dim3(256), 0, stream>>>(c, reinterpret_cast<int*>(dst) + at);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+// tables of at most this many bytes always travel that way (a pageable host-to-device copy makes the host wait
+// for the stream; a few small launches do not)
+constexpr size_t TABLE_BY_KERNEL_MAX = 8 * 960 * 4;
+
 struct WsView {
     SampleTable st;
     LatticeState ls;   // row_base filled per group
@@ -191,7 +218,7 @@ WsView view_workspace(const Plan& p, void* ws) {
 rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const void* W_out, const float* b_out,
                 const int32_t* labels, const int32_t* T_len, const int32_t* U_len, float* loss, void* d_enc_out,
                 void* d_pred_out, float* dW_out, float* db_out, void* workspace, size_t workspace_bytes,
-                void* hip_stream, bool grads, const float* sample_weight = nullptr) {
+                void* hip_stream, bool grads, const float* sample_weight = nullptr, bool no_copy_engine = false) {
     rnnt_status stt = check_desc(desc);
     if (stt != RNNT_OK) return stt;
     if (!enc || !pred || !W_out || !b_out || !loss || !T_len || !U_len) return RNNT_ERR_NULL;
@@ -225,7 +252,10 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         if (sample_weight) std::memcpy(tab.data() + (plan.off_weight - plan.off_T), sample_weight, B * 4);
         std::memcpy(tab.data() + (plan.off_tile_off - plan.off_T), plan.tile_off.data(), (B + 1) * 4);
         std::memcpy(tab.data() + (plan.off_row_off - plan.off_T), plan.row_off.data(), (B + 1) * 8);
-        RNNT_HIP(hipMemcpyAsync(w + plan.off_T, tab.data(), tab_bytes, hipMemcpyHostToDevice, stream));
+        if (no_copy_engine || tab_bytes <= TABLE_BY_KERNEL_MAX)
+            RNNT_HIP(put_table(tab.data(), tab_bytes, w + plan.off_T, stream));
+        else
+            RNNT_HIP(hipMemcpyAsync(w + plan.off_T, tab.data(), tab_bytes, hipMemcpyHostToDevice, stream));
     }
 
     Problem pr{desc->B, desc->T_max, desc->U_max, desc->H, desc->V, desc->blank, enc, pred, W_out, b_out, labels};
@@ -401,6 +431,46 @@ extern "C" rnnt_status rnnt_joint_loss_fwd_bwd_weighted(const rnnt_desc* desc, c
                                                         void* hip_stream) {
     return run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW_out, db_out,
                workspace, workspace_bytes, hip_stream, true, sample_weight);
+}
+
+// ---- the entry point that allocates nothing --------------------------------------------------------------
+// Its workspace is this array: every GPU the library runs on holds one copy until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the address a kernel can use is looked up
+// once per device and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[RNNT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+}  // namespace
+
+extern "C" rnnt_status rnnt_joint_loss_fwd_bwd_static(const rnnt_desc* desc, const void* enc, const void* pred,
+                                                      const void* W_out, const float* b_out, const int32_t* labels,
+                                                      const int32_t* T_len, const int32_t* U_len, float* loss,
+                                                      void* d_enc, void* d_pred, float* dW_out, float* db_out,
+                                                      void* hip_stream) {
+    rnnt_status stt = check_desc(desc);
+    if (stt != RNNT_OK) return stt;
+    stt = check_lengths(desc, T_len, U_len);
+    if (stt != RNNT_OK) return stt;
+    if (desc->B > RNNT_STATIC_MAX_B) return RNNT_ERR_WORKSPACE;
+    {
+        // the smallest plan of this call must fit the array (host arithmetic only)
+        Plan p;
+        build_plan(*desc, T_len, U_len, RNNT_STATIC_SCRATCH_BYTES, p);
+        if (p.total_bytes > (size_t)RNNT_STATIC_SCRATCH_BYTES) return RNNT_ERR_WORKSPACE;
+    }
+    int dev = -1;
+    RNNT_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return RNNT_ERR_UNSUPPORTED;
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        RNNT_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return RNNT_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return run(desc, enc, pred, W_out, b_out, labels, T_len, U_len, loss, d_enc, d_pred, dW_out, db_out,
+               g_scratch_ptr[dev], (size_t)RNNT_STATIC_SCRATCH_BYTES, hip_stream, true, nullptr, true);
 }
 
 namespace {
