@@ -36,6 +36,73 @@ CPU_SAMPLE = {"C1": 2, "C2": 32, "C3": 12, "C4": 12, "C5": 8}  # samples the che
 COPY_BYTES = 256 << 20
 
 
+def read_traffic(path):
+    """{kernel: HBM bytes per launch} from a counter summary under profiles/ (lines of
+    `kernel launches fetch_KiB write_KiB fetch_bytes write_bytes hbm_bytes_per_launch`)."""
+    res = {}
+    if not os.path.exists(path):
+        return res
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        parts = line.split()
+        res[parts[0]] = float(parts[-1])
+    return res
+
+
+def mfma_operand_patterns():
+    """Operand fragments (bit patterns) for the MFMA-only loop: bf16 32 x 64 lanes x 8, e4m3 32 x 64 lanes x 32."""
+    rng = np.random.Generator(np.random.PCG64(2211))
+    n = 32 * 64 * 8
+    sign = rng.integers(0, 2, n, dtype=np.uint16) << 15
+    expo = (118 + rng.integers(0, 8, n, dtype=np.uint16)) << 7          # magnitudes 2^-9 .. 2^-2
+    mant = rng.integers(0, 128, n, dtype=np.uint16)
+    bf16 = [("zeros", np.zeros(n, dtype=np.uint16)), ("ones", np.full(n, 0x3F80, dtype=np.uint16)),
+            ("random, 3 mantissa bits", sign | np.uint16(122 << 7) | (mant & 0x70)), ("random bf16", sign | expo | mant)]
+    rng = np.random.Generator(np.random.PCG64(2212))
+    n = 32 * 64 * 32
+    rnd = rng.integers(0, 256, n, dtype=np.uint8)
+    rnd = np.where((rnd & 0x7F) == 0x7F, rnd & 0xF0, rnd).astype(np.uint8)          # no NaN encodings
+    mid = ((rng.integers(0, 2, n, dtype=np.uint8) << 7) | ((4 + rng.integers(0, 6, n, dtype=np.uint8)) << 3)
+           | rng.integers(0, 8, n, dtype=np.uint8)).astype(np.uint8)                 # magnitudes 2^-3 .. 2^2
+    fp8 = [("zeros", np.zeros(n, dtype=np.uint8)), ("ones", np.full(n, 0x38, dtype=np.uint8)),
+           ("random e4m3, exponents 4..9", mid), ("random bytes", rnd)]
+    return bf16, fp8
+
+
+def mfma_loop_tflops(Bd, torch, bits, fp8, workgroups, iters):
+    """Best of three launches of the library's MFMA-only loop (no memory access inside) on these operand bits."""
+    frags = torch.from_numpy(bits.copy()).cuda() if fp8 else \
+        torch.from_numpy(bits.view(np.int16).copy()).cuda().view(torch.bfloat16)
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    best = None
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        st = (Bd.rnnt_debug_mfma_loop_fp8 if fp8 else Bd.rnnt_debug_mfma_loop)(frags, out, workgroups, iters)
+        e1.record()
+        assert st == 0, st
+        e1.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    k = 64 if fp8 else 16
+    return 2.0 * 32 * 32 * k * 16 * iters * 4 * workgroups / (best * 1e-3) / 1e12, best
+
+
+def mfma_table(Bd, torch):
+    """What the matrix units sustain on chosen operand values, next to the published peaks (the text kept as
+    profiles/mfma_rate_by_operand_values.txt)."""
+    bf16, fp8 = mfma_operand_patterns()
+    for title, pats, is8, iters, peak in (("v_mfma_f32_32x32x16_bf16", bf16, False, 20000, 2500.0),
+                                         ("v_mfma_f32_32x32x64_f8f6f4 (e4m3)", fp8, True, 10000, 5000.0)):
+        print(f"# MFMA-only loop, {title}, {iters} iterations of 16 MFMAs per wave, 256 compute units")
+        print(f"# operand values, waves per SIMD, ms per launch, TFLOP/s, fraction of the published {peak / 1e3:.1f} PFLOP/s")
+        for name, bits in pats:
+            for wgs in (256, 512):
+                tf, ms = mfma_loop_tflops(Bd, torch, bits, is8, wgs, iters)
+                print(f"{name}, {wgs // 256}, {ms:.2f}, {tf:.0f}, {tf / peak:.3f}", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +119,8 @@ def main():
     ap.add_argument("--projections", type=int, default=0, metavar="D",
                     help="time the entry point with the joint network's input projections inside "
                          "(Eq. 4 complete), encoder / prediction width D (0 = the north-star entry point)")
+    ap.add_argument("--mfma-table", action="store_true",
+                    help="only print what the MFMA-only loop sustains on chosen operand values (bf16 and fp8) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the 256 MiB plain copy kernel 5 times (HBM counter calibration under rocprofv3)")
     args = ap.parse_args()
@@ -66,6 +135,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.mfma_table:
+        mfma_table(Bd, torch)
+        return
     if args.config in ("P16", "P16F32"):
         # shaped like the paper's benchmark (Section 5.1): 16 samples of up to 500 x 100, joint size 1024,
         # 4096 word pieces; lengths drawn uniformly down to the paper's largest padding (9.3 % / 45.8 %)
@@ -191,7 +263,6 @@ def main():
             k["frac_alg"] = alg_flops_per_step[name] / (k["ms_per_step"] * 1e-3) / peak
             k["frac_exec"] = exec_flops_per_step[name] / (k["ms_per_step"] * 1e-3) / peak
     # HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if any
-    from paper_2211_16270_amd.pmc_summary import read_traffic
     tname = f"hbm_traffic_{wl.name}" + ("_keep_scores" if args.keep_scores else "") + ".txt"
     traffic = read_traffic(os.path.join(ROOT, "profiles", tname)) if not args.batch else {}
     # fp32: GEMMs on the fp32 MFMA instruction where the plan has chunk buffers (H, V multiples of 128; `kernel` is
@@ -201,6 +272,11 @@ def main():
                 "traffic": traffic.get(dom), "traffic_source": ("profiles/" + tname) if traffic.get(dom) else None,
                 "alg_flops_per_launch": flops_per_launch, "exec_flops_per_launch": exec_per_launch,
                 "frac_exec": exec_per_launch / avg_s / peak, "avg_launch_us": kernels[dom]["avg_launch_us"]}
+    # what the matrix units sustain on operands like this path's (random bf16 values): an MFMA-only loop, no
+    # memory access; the chip lowers its clock under its power limit, so this is below the published peak
+    pats, _ = mfma_operand_patterns()
+    measured_peak = {name: mfma_loop_tflops(Bd, torch, bits, False, 512, 4000)[0]
+                     for name, bits in pats if name in ("zeros", "random bf16")} if wl.dtype == "bf16" else None
     step_s = elapsed / steps
     util_alg = 6.0 * R * HV / step_s / peak
     util_exec = (6.0 if args.keep_scores else 8.0) * R * HV / step_s / peak
@@ -230,6 +306,9 @@ def main():
         "ms_per_step_with_events": elapsed_prof / steps * 1e3,
         "gpu_kernel_ms_per_step": gpu_ms,
         "roofline": roofline,
+        "measured_mfma_peak": None if measured_peak is None else
+        {"unit": "TFLOP/s", "what": "MFMA-only loop, 32x32x16 bf16, two waves per SIMD, no memory access",
+         "zeros": measured_peak["zeros"], "random_bf16": measured_peak["random bf16"]},
         "kernels": kernels,
     }
 

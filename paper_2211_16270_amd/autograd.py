@@ -9,7 +9,9 @@ output layer are accumulated while the samples are walked, nothing is kept for a
 forward of the autograd function already holds the gradients of sum_b w_b loss_b for the weights w it was
 given (default: ones).  backward() hands them out if the incoming gradient of the loss vector equals those
 weights, and otherwise calls the library once more with the incoming gradient as the weights.  Pass
-`sample_weight` (e.g. 1/B for a mean) to make the first call the only one.
+`sample_weight` (e.g. 1/B for a mean) to make the first call the only one.  The weights of the library are
+non-negative, so the gradient that reaches the loss vector must be >= 0 for every sample (backward raises
+otherwise).  The forward call's outputs and workspace stay alive until backward has run.
 """
 from __future__ import annotations
 
@@ -44,6 +46,10 @@ class _RnntJointLoss(torch.autograd.Function):
     @staticmethod
     def backward(ctx, grad_loss):
         g = grad_loss.detach().float().cpu().numpy()          # B numbers; also orders this after the forward
+        if not (np.all(np.isfinite(g)) and np.all(g >= 0.0)):
+            # the library takes one weight >= 0 per sample (they scale posterior probabilities in log space)
+            raise ValueError("rnnt_joint_loss: the gradient reaching the loss vector must be finite and >= 0 for "
+                             "every sample (sum, mean, masks and positive scalings are; a negated loss is not)")
         out = ctx.out
         if not np.array_equal(g, ctx.w_host):
             out = Bd.run_fwd_bwd(ctx.dev, *ctx.shape, workspace=ctx.out["workspace"], sample_weight=g, **ctx.opts)

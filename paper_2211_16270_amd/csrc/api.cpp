@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "../../include/rnnt_joint_loss.h"
+#include "../../include/rnnt_joint_loss_debug.h"
 #include "kernels.h"
 #include "plan.h"
 

@@ -198,6 +198,8 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
             else break;
         }
     }
+    // the kernels index a group's lattice state with 32-bit integers (a sample alone has at most 2^30 nodes)
+    lat_cap = std::min<long long>(lat_cap, 2147483647LL);
     lay_out(d, p, lat_cap, chunk_rows, stage_samples);
     if (workspace_bytes != 0 && workspace_bytes < p.min_bytes) p.total_bytes = p.min_bytes;
 
@@ -226,7 +228,9 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         g.tile1 = p.tile_off[g.s1];
         p.groups.push_back(g);
     }
-    // backward chunks: balanced tile ranges of at most chunk_rows rows, even tile counts (fused kernel: whole rounds)
+    // backward chunks of at most chunk_rows rows: a group that fits one chunk is one chunk; a larger one is cut
+    // into chunks of whole rounds of 256 tiles where the chunk buffers hold at least four rounds (the last chunk
+    // takes the rest), else into equal parts of an even number of tiles
     if (p.bf16 && !p.keep) {
         const long long cap_tiles = chunk_rows / TILE_ROWS;
         for (int gi = 0; gi < (int)p.groups.size(); ++gi) {

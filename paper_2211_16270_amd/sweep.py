@@ -8,8 +8,9 @@ paper's zero-padding scheme (padding grows linearly over the batch: acoustic 0 -
     python -m paper_2211_16270_amd.sweep keep16   # the same at B = 16 only, with the time of each kernel
     python -m paper_2211_16270_amd.sweep fp32     # the grid and three batch sizes with fp32 inputs and arithmetic
 
-Timing only (inputs are seeded random tensors made on the GPU, as in the paper's benchmark); bf16 inputs unless
-stated.
+Inputs are seeded random tensors made on the GPU, as in the paper's benchmark; bf16 inputs unless stated.
+`run_case(..., return_tensors=True)` also hands back the inputs, lengths and outputs of the last step, which is
+how the GPU tests check every way of running a batch against the float64 checker on the same tensors.
 Ways of running a batch:
   packed      one call, true lengths: this library's default (padding removed, samples share launches)
   padded      one call, every length set to the maximum: what a computation on the padded batch costs
@@ -33,7 +34,7 @@ def paper_lengths(B: int, T: int, U: int):
     return T_len, U_len
 
 
-def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211, dtype="bf16"):
+def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211, dtype="bf16", return_tensors=False):
     import torch
     from . import binding as Bd
 
@@ -91,9 +92,13 @@ def run_case(B, T, U, H, V, mode, steps=3, warmup=1, seed=2211, dtype="bf16"):
     dt = (time.perf_counter() - t0) / steps
     assert bool(torch.isfinite(loss).all())
     rows = int(np.sum(T_len.astype(np.int64) * (U_len + 1)))
-    return dict(ms=dt * 1e3, samples_per_s=B / dt, peak_gb=torch.cuda.max_memory_allocated() / 1e9,
-                workspace_gb=nb / 1e9, rows=rows,
-                pflops_exec=(6.0 if mode == "kept" else 8.0) * rows * H * V / dt / 1e15)
+    res = dict(ms=dt * 1e3, samples_per_s=B / dt, peak_gb=torch.cuda.max_memory_allocated() / 1e9,
+               workspace_gb=nb / 1e9, rows=rows,
+               pflops_exec=(6.0 if mode == "kept" else 8.0) * rows * H * V / dt / 1e15)
+    if return_tensors:
+        res["tensors"] = dict(enc=enc, pred=pred, W_out=W, b_out=b_out, labels=labels, T_len=T_len, U_len=U_len,
+                              loss=loss, d_enc=d_enc, d_pred=d_pred, dW_out=dW, db_out=db)
+    return res
 
 
 def main(argv):

@@ -157,3 +157,31 @@ def test_c5_longest_and_shortest_sample_packing_invariance():
         d = np.abs(both[k] - s).max() / np.abs(s).max()
         assert d < 2e-3, (k, d)
     assert abs(float(both["db_out"].astype(np.float64).sum())) < 1e-2 * float(np.abs(both["db_out"]).sum())
+
+
+@pytest.mark.parametrize("mode,dtype", [("packed", "bf16"), ("padded", "bf16"), ("one_by_one", "bf16"), ("kept", "bf16"),
+                                        ("packed", "f32"), ("one_by_one", "f32")])
+def test_paper_shaped_sweep_modes_against_the_checker(mode, dtype):
+    # one small point of the paper-shaped sweeps (Section 5.1's padding scheme: lengths fall linearly over the
+    # batch) in every way the sweep runs a batch; the checker gets the very tensors the sweep made on the GPU
+    # and the lengths that way of running used (all at the maximum for "padded")
+    from oracle import rnnt_oracle as O
+    from paper_2211_16270_amd import sweep
+    from tests.gpu_util import GRADS, TOL, rel_grad_err, rel_loss_err
+    B, T, U, H, V = 4, 50, 10, 256, 512
+    r = sweep.run_case(B, T, U, H, V, mode, steps=2, warmup=1, dtype=dtype, return_tensors=True)
+    t = r["tensors"]
+    if mode != "padded":
+        Tp, Up = sweep.paper_lengths(B, T, U)
+        assert np.array_equal(t["T_len"], Tp) and np.array_equal(t["U_len"], Up) and Tp.min() < T and Up.min() < U
+    f64 = lambda x: x.float().cpu().numpy().astype(np.float64)
+    ref = O.rnnt_joint_loss(f64(t["enc"]), f64(t["pred"]), f64(t["W_out"]), f64(t["b_out"]),
+                            t["labels"].cpu().numpy(), t["T_len"], t["U_len"], 0)
+    tol = TOL[dtype]
+    e = rel_loss_err(f64(t["loss"]), ref["loss"])
+    assert e <= tol["loss"], (mode, dtype, e)
+    for k in GRADS:
+        eg = rel_grad_err(f64(t[k]), ref[k])
+        _say("sweep", mode, dtype, k, eg)
+        assert eg <= tol["grad"], (mode, dtype, k, eg)
+    assert r["rows"] == int(np.sum(t["T_len"].astype(np.int64) * (t["U_len"] + 1)))
