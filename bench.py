@@ -119,6 +119,10 @@ def main():
     ap.add_argument("--projections", type=int, default=0, metavar="D",
                     help="time the entry point with the joint network's input projections inside "
                          "(Eq. 4 complete), encoder / prediction width D (0 = the north-star entry point)")
+    ap.add_argument("--planned", action="store_true",
+                    help="call through a plan handle (rnnt_plan_create once, rnnt_joint_loss_fwd_bwd_planned per step)")
+    ap.add_argument("--lattice-stream", action="store_true",
+                    help="with --planned: the lattice sweeps run on a second stream beside the previous group's backward pass")
     ap.add_argument("--mfma-table", action="store_true",
                     help="only print what the MFMA-only loop sustains on chosen operand values (bf16 and fp8) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -161,9 +165,15 @@ def main():
     dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
     desc = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, dt, keep_scores=int(args.keep_scores),
                         input_grads_bf16=int(args.bf16_grads))
-    nbytes = Bd.rnnt_joint_loss_workspace_bytes(desc, dev["T_len"], dev["U_len"], args.budget_mib << 20)
-    st, info, _ = Bd.rnnt_joint_loss_plan(desc, dev["T_len"], dev["U_len"], nbytes)
-    assert st == 0, st
+    plan = side = None
+    if args.planned or args.lattice_stream:
+        plan = Bd.PlanHandle(desc, dev["T_len"], dev["U_len"], args.budget_mib << 20, overlap_lattice=args.lattice_stream)
+        nbytes, info = plan.workspace_bytes, plan.describe()
+        side = torch.cuda.Stream() if args.lattice_stream else None
+    else:
+        nbytes = Bd.rnnt_joint_loss_workspace_bytes(desc, dev["T_len"], dev["U_len"], args.budget_mib << 20)
+        st, info, _ = Bd.rnnt_joint_loss_plan(desc, dev["T_len"], dev["U_len"], nbytes)
+        assert st == 0, st
     torch.cuda.reset_peak_memory_stats()
     ws = Bd.Workspace(nbytes)
     loss = torch.empty(wl.B, dtype=torch.float32, device="cuda")
@@ -193,8 +203,12 @@ def main():
             if s != 0:
                 raise Bd.RnntError(s, "rnnt_joint_proj_loss_fwd_bwd")
             return
-        s = Bd.rnnt_joint_loss_fwd_bwd(desc, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
-                                       dev["T_len"], dev["U_len"], loss, d_enc, d_pred, dW, db, ws.buf, stream)
+        if plan is not None:
+            s = Bd.rnnt_joint_loss_fwd_bwd_planned(plan, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                                   None, loss, d_enc, d_pred, dW, db, ws.buf, stream, side)
+        else:
+            s = Bd.rnnt_joint_loss_fwd_bwd(desc, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                           dev["T_len"], dev["U_len"], loss, d_enc, d_pred, dW, db, ws.buf, stream)
         if s != 0:
             raise Bd.RnntError(s, "rnnt_joint_loss_fwd_bwd")
 
@@ -296,7 +310,9 @@ def main():
         "config": {"workload": f"{wl.name}: B={wl.B} T_max={wl.T_max} U_max={wl.U_max} H={wl.H} V={wl.V} "
                                f"{wl.dtype}, ragged lengths, {R} lattice nodes ({100.0 * R / info['rows_padded']:.1f}% of padded)",
                    "entry_point": "rnnt_joint_proj_loss_fwd_bwd, H_A = H_L = %d" % args.projections
-                   if args.projections else "rnnt_joint_loss_fwd_bwd",
+                   if args.projections else ("rnnt_joint_loss_fwd_bwd_planned" + (", lattice sweeps on a second stream"
+                                                                                   if side is not None else "")
+                                             if plan is not None else "rnnt_joint_loss_fwd_bwd"),
                    "keep_scores": int(args.keep_scores), "input_grads_bf16": int(args.bf16_grads),
                    "groups": info["n_groups"], "chunks": info["n_chunks"],
                    "workspace_bytes": int(nbytes)},

@@ -226,6 +226,47 @@ rnnt_status rnnt_joint_loss_fwd_bwd_static(const rnnt_desc* desc,
                                            float* dW_out, float* db_out, void* hip_stream);
 
 /*
+ * The same call for a training loop that repeats one batch geometry (Algorithm 1's loop body is run once per
+ * training step): the schedule of Section 4.1.2's analogue is worked out once and kept in a handle, so a call
+ * neither rebuilds it nor touches pageable host memory.
+ *
+ * rnnt_plan_create      checks desc and the lengths, builds the schedule for budget_bytes (meaning as in
+ *                       rnnt_joint_loss_workspace_bytes; 0 = default) and stores the length tables in pinned host
+ *                       memory (ordinary memory if no GPU is present or pinning fails).  overlap_lattice = 1 lays
+ *                       the workspace out with room for the lattice state of two groups of samples (each then
+ *                       half as large by default), which lets a call run every group's lattice sweep (f^W_2,
+ *                       depth T + U, a few workgroups per sample) on a second stream beside the previous group's
+ *                       backward pass.  The handle is host memory owned by the caller; HIP events are added to it
+ *                       by the first call that uses a second stream.  Not thread-safe per handle.
+ * rnnt_plan_workspace_bytes   workspace size calls with this handle need (0 for NULL)
+ * rnnt_plan_describe    the schedule, as rnnt_joint_loss_plan reports it
+ * rnnt_plan_destroy     frees the handle (NULL is allowed); the caller makes sure no call using it is still
+ *                       running on the GPU
+ * rnnt_joint_loss_fwd_bwd_planned   rnnt_joint_loss_fwd_bwd_weighted for the handle's desc and lengths
+ *                       (sample_weight_host NULL = all ones).  hip_stream_lattice: NULL, or a second stream of
+ *                       the same priority on the same device; used only if the handle was created with
+ *                       overlap_lattice = 1, the call has more than one group and desc->keep_scores = 0.  The
+ *                       lattice sweeps then run there, ordered against hip_stream by events (no host wait);
+ *                       when the call returns, everything the second stream was given is ordered before the
+ *                       end of the work on hip_stream, so the caller synchronises hip_stream only.  Results are
+ *                       those of the one-stream call with the same schedule.
+ */
+typedef struct rnnt_plan_handle rnnt_plan_handle;
+rnnt_status rnnt_plan_create(const rnnt_desc* desc, const int32_t* T_len_host, const int32_t* U_len_host,
+                             size_t budget_bytes, int32_t overlap_lattice, rnnt_plan_handle** plan);
+size_t rnnt_plan_workspace_bytes(const rnnt_plan_handle* plan);
+rnnt_status rnnt_plan_describe(const rnnt_plan_handle* plan, rnnt_plan_info* info);
+void rnnt_plan_destroy(rnnt_plan_handle* plan);
+rnnt_status rnnt_joint_loss_fwd_bwd_planned(rnnt_plan_handle* plan,
+                                            const void* enc, const void* pred, const void* W_out,
+                                            const float* b_out, const int32_t* labels,
+                                            const float* sample_weight_host,
+                                            float* loss, void* d_enc, void* d_pred,
+                                            float* dW_out, float* db_out,
+                                            void* workspace, size_t workspace_bytes,
+                                            void* hip_stream, void* hip_stream_lattice);
+
+/*
  * Loss only (Eqs. 4, 6, 7-9): same inputs, no gradient outputs, same workspace rule
  * (the chunk buffers stay unused).
  */

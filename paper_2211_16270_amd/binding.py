@@ -23,7 +23,8 @@ EXPORTS = ["rnnt_status_string", "rnnt_last_hip_error", "rnnt_joint_loss_workspa
            "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice", "rnnt_profile_enable",
            "rnnt_debug_copy_f32", "rnnt_debug_mfma_loop", "rnnt_debug_mfma_loop_fp8", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
            "rnnt_joint_proj_workspace_bytes", "rnnt_joint_proj_loss_fwd_bwd", "rnnt_joint_loss_fwd_bwd_weighted",
-           "rnnt_joint_loss_fwd_bwd_static"]
+           "rnnt_joint_loss_fwd_bwd_static", "rnnt_plan_create", "rnnt_plan_workspace_bytes", "rnnt_plan_describe",
+           "rnnt_plan_destroy", "rnnt_joint_loss_fwd_bwd_planned"]
 RNNT_STATIC_SCRATCH_BYTES = 128 << 20
 
 
@@ -90,6 +91,17 @@ def lib() -> ctypes.CDLL:
                                           vp, ctypes.c_size_t, vp]
     L.rnnt_joint_loss_fwd_bwd_static.restype = ctypes.c_int
     L.rnnt_joint_loss_fwd_bwd_static.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, f32p, f32p, f32p, f32p, vp]
+    L.rnnt_plan_create.restype = ctypes.c_int
+    L.rnnt_plan_create.argtypes = [dp, i32p, i32p, ctypes.c_size_t, ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p)]
+    L.rnnt_plan_workspace_bytes.restype = ctypes.c_size_t
+    L.rnnt_plan_workspace_bytes.argtypes = [vp]
+    L.rnnt_plan_describe.restype = ctypes.c_int
+    L.rnnt_plan_describe.argtypes = [vp, ctypes.POINTER(RnntPlanInfo)]
+    L.rnnt_plan_destroy.restype = None
+    L.rnnt_plan_destroy.argtypes = [vp]
+    L.rnnt_joint_loss_fwd_bwd_planned.restype = ctypes.c_int
+    L.rnnt_joint_loss_fwd_bwd_planned.argtypes = [vp, vp, vp, vp, f32p, vp, f32p, f32p, f32p, f32p, f32p, f32p, vp,
+                                                   ctypes.c_size_t, vp, vp]
     L.rnnt_joint_loss_fwd_bwd_weighted.restype = ctypes.c_int
     L.rnnt_joint_loss_fwd_bwd_weighted.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, f32p, f32p, f32p, f32p,
                                                     f32p, vp, ctypes.c_size_t, vp]
@@ -190,6 +202,56 @@ def rnnt_joint_loss_fwd_bwd_static(desc: RnntDesc, enc, pred, W_out, b_out, labe
     return int(lib().rnnt_joint_loss_fwd_bwd_static(
         ctypes.byref(desc), _ptr(enc), _ptr(pred), _ptr(W_out), _ptr(b_out), _ptr(labels), _ip(T), _ip(U),
         _ptr(loss), _ptr(d_enc), _ptr(d_pred), _ptr(dW_out), _ptr(db_out), _stream_handle(stream)))
+
+
+class PlanHandle:
+    """rnnt_plan_create / rnnt_plan_destroy as an object: the schedule and the pinned length tables of one batch
+    geometry, kept between calls."""
+
+    def __init__(self, desc: RnntDesc, T_len, U_len, budget_bytes: int = 0, overlap_lattice: bool = False):
+        T, U = _i32(T_len), _i32(U_len)
+        h = ctypes.c_void_p()
+        st = lib().rnnt_plan_create(ctypes.byref(desc), _ip(T), _ip(U), int(budget_bytes), int(bool(overlap_lattice)),
+                                    ctypes.byref(h))
+        if st != 0:
+            raise RnntError(int(st), "rnnt_plan_create")
+        self.handle, self.desc = h, desc
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib().rnnt_plan_workspace_bytes(self.handle))
+
+    def describe(self) -> dict:
+        info = RnntPlanInfo()
+        st = lib().rnnt_plan_describe(self.handle, ctypes.byref(info))
+        if st != 0:
+            raise RnntError(int(st), "rnnt_plan_describe")
+        return {name: getattr(info, name) for name, _ in RnntPlanInfo._fields_}
+
+    def close(self):
+        if self.handle:
+            lib().rnnt_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def rnnt_joint_loss_fwd_bwd_planned(plan: PlanHandle, enc, pred, W_out, b_out, labels, sample_weight,
+                                    loss, d_enc, d_pred, dW_out, db_out, workspace, stream=None,
+                                    lattice_stream=None) -> int:
+    """Raw call with a plan handle; lattice_stream: a torch stream for the lattice sweeps, or None."""
+    w = None if sample_weight is None else np.ascontiguousarray(sample_weight, dtype=np.float32)
+    wp = None if w is None else w.ctypes.data
+    ls = None if lattice_stream is None else int(lattice_stream.cuda_stream)
+    return int(lib().rnnt_joint_loss_fwd_bwd_planned(
+        plan.handle, _ptr(enc), _ptr(pred), _ptr(W_out), _ptr(b_out), _ptr(labels), wp,
+        _ptr(loss), _ptr(d_enc), _ptr(d_pred), _ptr(dW_out), _ptr(db_out), _ptr(workspace),
+        int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
+        _stream_handle(stream), ls))
 
 
 def rnnt_joint_loss_fwd_bwd_weighted(desc: RnntDesc, enc, pred, W_out, b_out, labels, T_len, U_len, sample_weight,

@@ -5,7 +5,9 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
+#include <new>
 #include <initializer_list>
 #include <vector>
 
@@ -31,6 +33,19 @@ extern "C" const char* rnnt_status_string(rnnt_status s) {
     return "unknown status";
 }
 
+static void fill_info(const rnnt_desc& d, const Plan& p, rnnt_plan_info* info) {
+    info->rows_total = p.rows_total;
+    info->rows_padded = (int64_t)d.B * d.T_max * (d.U_max + 1);
+    info->tiles_total = p.tiles_total;
+    info->n_groups = (int32_t)p.groups.size();
+    info->n_chunks = (int32_t)p.chunks.size();
+    info->group_rows_cap = p.group_rows_cap;
+    info->chunk_rows = p.chunk_rows;
+    info->workspace_bytes = p.total_bytes;
+    info->lattice_bytes = p.lattice_bytes;
+    info->chunk_bytes = p.chunk_bytes;
+}
+
 extern "C" size_t rnnt_joint_loss_workspace_bytes(const rnnt_desc* desc, const int32_t* T_len,
                                                   const int32_t* U_len, size_t budget_bytes) {
     if (check_desc(desc) != RNNT_OK || check_lengths(desc, T_len, U_len) != RNNT_OK) return 0;
@@ -49,16 +64,7 @@ extern "C" rnnt_status rnnt_joint_loss_plan(const rnnt_desc* desc, const int32_t
     Plan p;
     build_plan(*desc, T_len, U_len, workspace_bytes, p);
     if (workspace_bytes != 0 && p.total_bytes > workspace_bytes) return RNNT_ERR_WORKSPACE;
-    info->rows_total = p.rows_total;
-    info->rows_padded = (int64_t)desc->B * desc->T_max * (desc->U_max + 1);
-    info->tiles_total = p.tiles_total;
-    info->n_groups = (int32_t)p.groups.size();
-    info->n_chunks = (int32_t)p.chunks.size();
-    info->group_rows_cap = p.group_rows_cap;
-    info->chunk_rows = p.chunk_rows;
-    info->workspace_bytes = p.total_bytes;
-    info->lattice_bytes = p.lattice_bytes;
-    info->chunk_bytes = p.chunk_bytes;
+    fill_info(*desc, p, info);
     if (sample_group)
         for (int g = 0; g < (int)p.groups.size(); ++g)
             for (int s = p.groups[g].s0; s < p.groups[g].s1; ++s) sample_group[s] = g;
@@ -216,13 +222,33 @@ WsView view_workspace(const Plan& p, void* ws) {
     return v;
 }
 
-rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const void* W_out, const float* b_out,
-                const int32_t* labels, const int32_t* T_len, const int32_t* U_len, float* loss, void* d_enc_out,
-                void* d_pred_out, float* dW_out, float* db_out, void* workspace, size_t workspace_bytes,
-                void* hip_stream, bool grads, const float* sample_weight = nullptr, bool no_copy_engine = false) {
-    rnnt_status stt = check_desc(desc);
-    if (stt != RNNT_OK) return stt;
-    if (!enc || !pred || !W_out || !b_out || !loss || !T_len || !U_len) return RNNT_ERR_NULL;
+// How the host tables reach the workspace.
+struct TableSource {
+    const unsigned char* staged = nullptr;   // tables laid out as in the workspace (from plan.off_T on), or null
+    bool staged_pinned = false;              // `staged` is pinned host memory that outlives the call
+    bool no_copy_engine = false;             // kernel arguments only
+};
+// Second stream for the lattice sweeps, with the events that order it against the main stream.
+struct Overlap {
+    hipStream_t lattice_stream = nullptr;
+    hipEvent_t* fwd_done = nullptr;          // [groups]
+    hipEvent_t* lat_done = nullptr;          // [groups]
+};
+
+size_t table_bytes(const Plan& plan, size_t B) { return plan.off_row_off + (B + 1) * 8 - plan.off_T; }
+
+void fill_tables(const Plan& plan, size_t B, const int32_t* T_len, const int32_t* U_len, unsigned char* tab) {
+    std::memset(tab, 0, table_bytes(plan, B));
+    std::memcpy(tab, T_len, B * 4);
+    std::memcpy(tab + (plan.off_U - plan.off_T), U_len, B * 4);
+    std::memcpy(tab + (plan.off_tile_off - plan.off_T), plan.tile_off.data(), (B + 1) * 4);
+    std::memcpy(tab + (plan.off_row_off - plan.off_T), plan.row_off.data(), (B + 1) * 8);
+}
+
+rnnt_status check_call(const rnnt_desc* desc, const void* enc, const void* pred, const void* W_out,
+                       const float* b_out, const int32_t* labels, float* loss, void* d_enc_out, void* d_pred_out,
+                       float* dW_out, float* db_out, bool grads, const float* sample_weight) {
+    if (!enc || !pred || !W_out || !b_out || !loss) return RNNT_ERR_NULL;
     if (desc->U_max > 0 && !labels) return RNNT_ERR_NULL;
     if (grads && (!d_enc_out || !d_pred_out || !dW_out || !db_out)) return RNNT_ERR_NULL;
     // the MFMA kernels read and write these arrays in 16-byte pieces
@@ -230,33 +256,44 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         for (const void* q : {enc, pred, W_out, (const void*)b_out, (const void*)d_enc_out, (const void*)d_pred_out,
                               (const void*)dW_out, (const void*)db_out})
             if ((uintptr_t)q % 16 != 0) return RNNT_ERR_UNSUPPORTED;
-    stt = check_lengths(desc, T_len, U_len);
-    if (stt != RNNT_OK) return stt;
     if (sample_weight)
         for (int b = 0; b < desc->B; ++b)
             if (!(sample_weight[b] >= 0.0f) || !std::isfinite(sample_weight[b])) return RNNT_ERR_WEIGHT;
-    if (!workspace || ((uintptr_t)workspace % WS_ALIGN) != 0 || workspace_bytes == 0) return RNNT_ERR_WORKSPACE;
-    Plan plan;
-    build_plan(*desc, T_len, U_len, workspace_bytes, plan);
-    if (plan.total_bytes > workspace_bytes) return RNNT_ERR_WORKSPACE;
+    return RNNT_OK;
+}
 
+// The launch sequence of one call for a plan that fits the workspace.
+rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_len, const int32_t* U_len,
+                    const TableSource& ts, const Overlap& ov, const void* enc, const void* pred, const void* W_out,
+                    const float* b_out, const int32_t* labels, float* loss, void* d_enc_out, void* d_pred_out,
+                    float* dW_out, float* db_out, void* workspace, void* hip_stream, bool grads,
+                    const float* sample_weight) {
     hipStream_t stream = (hipStream_t)hip_stream;
     const WsView wv = view_workspace(plan, workspace);
     unsigned char* w = (unsigned char*)workspace;
     const size_t B = (size_t)desc->B;
-    // host tables -> workspace in one copy (pageable source: consumed before the call returns)
     {
-        const size_t tab_bytes = plan.off_row_off + (B + 1) * 8 - plan.off_T;
-        std::vector<unsigned char> tab(tab_bytes, 0);
-        std::memcpy(tab.data(), T_len, B * 4);
-        std::memcpy(tab.data() + (plan.off_U - plan.off_T), U_len, B * 4);
-        if (sample_weight) std::memcpy(tab.data() + (plan.off_weight - plan.off_T), sample_weight, B * 4);
-        std::memcpy(tab.data() + (plan.off_tile_off - plan.off_T), plan.tile_off.data(), (B + 1) * 4);
-        std::memcpy(tab.data() + (plan.off_row_off - plan.off_T), plan.row_off.data(), (B + 1) * 8);
-        if (no_copy_engine || tab_bytes <= TABLE_BY_KERNEL_MAX)
-            RNNT_HIP(put_table(tab.data(), tab_bytes, w + plan.off_T, stream));
-        else
-            RNNT_HIP(hipMemcpyAsync(w + plan.off_T, tab.data(), tab_bytes, hipMemcpyHostToDevice, stream));
+        const size_t tab_bytes = table_bytes(plan, B);
+        if (ts.staged && ts.staged_pinned && !ts.no_copy_engine) {
+            // pinned source owned by the plan handle: a truly asynchronous copy
+            RNNT_HIP(hipMemcpyAsync(w + plan.off_T, ts.staged, tab_bytes, hipMemcpyHostToDevice, stream));
+        } else {
+            std::vector<unsigned char> tab;
+            const unsigned char* src = ts.staged;
+            if (!src) {
+                tab.resize(tab_bytes);
+                fill_tables(plan, B, T_len, U_len, tab.data());
+                src = tab.data();
+            }
+            // small tables travel as kernel arguments (a pageable host-to-device copy makes the host wait for
+            // the stream; a few small launches do not); large ones by one copy, consumed before the call returns
+            if (ts.no_copy_engine || tab_bytes <= TABLE_BY_KERNEL_MAX)
+                RNNT_HIP(put_table(src, tab_bytes, w + plan.off_T, stream));
+            else
+                RNNT_HIP(hipMemcpyAsync(w + plan.off_T, src, tab_bytes, hipMemcpyHostToDevice, stream));
+        }
+        if (sample_weight)
+            RNNT_HIP(put_table(reinterpret_cast<const unsigned char*>(sample_weight), B * 4, w + plan.off_weight, stream));
     }
 
     Problem pr{desc->B, desc->T_max, desc->U_max, desc->H, desc->V, desc->blank, enc, pred, W_out, b_out, labels};
@@ -299,25 +336,21 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     const int wide_lattice = (!bf16 && desc->T_max + desc->U_max >= 128) ? 1 : 0;
     size_t ci = 0;
     int dw_first = 1;
-    for (size_t gi = 0; gi < plan.groups.size(); ++gi) {
+    const bool keep = plan.keep && grads;
+    // lattice state of group gi: with two buffers consecutive groups alternate between the halves of each array
+    auto group_state = [&](size_t gi) {
         const Group& g = plan.groups[gi];
         LatticeState ls = wv.ls;
+        const size_t half = (plan.lat_buffers == 2 && (gi & 1)) ? (size_t)plan.group_rows_cap : 0;
+        ls.lse += half; ls.lpb += half; ls.lpy += half; ls.alpha += half; ls.beta += half;
         ls.row_base = plan.row_off[g.s0];
         ls.weight = sample_weight ? (const float*)(w + plan.off_weight) : nullptr;
-        if (stage) {
-            // the kernels index d_enc, d_pred by the sample's number in the call: base pointers such that
-            // sample g.s0 is the first one of the (cleared) workspace arrays
-            PrepArgs pz{};
-            pz.zero_ptr[0] = wv.stage_enc;
-            pz.zero_n[0] = (size_t)(g.s1 - g.s0) * enc_per_sample;
-            pz.zero_ptr[1] = wv.stage_pred;
-            pz.zero_n[1] = (size_t)(g.s1 - g.s0) * pred_per_sample;
-            RNNT_HIP(timed(KC_PREPARE, stream, [&] { return launch_prepare(pz, stream); }));
-            d_enc = (float*)((uintptr_t)wv.stage_enc - (uintptr_t)g.s0 * enc_per_sample * 4);
-            d_pred = (float*)((uintptr_t)wv.stage_pred - (uintptr_t)g.s0 * pred_per_sample * 4);
-        }
-        // Eq. 4, Eq. 6, f^W_1
-        const bool keep = plan.keep && grads;
+        return ls;
+    };
+    // Eq. 4, Eq. 6, f^W_1 for one group
+    auto forward = [&](size_t gi) -> rnnt_status {
+        const Group& g = plan.groups[gi];
+        const LatticeState ls = group_state(gi);
         if (keep)
             RNNT_HIP(timed(KC_FWD_KEEP, stream, [&] {
                 return launch_fwd_keep_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, g.tile0, g.tile1, wv.dH, wv.Z,
@@ -336,10 +369,32 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
         else
             RNNT_HIP(timed(KC_FWD_F32, stream,
                            [&] { return launch_fwd_f32(pr, wv.st, ls, g.s0, g.s1, g.rows, stream); }));
-        // f^W_2, f^W_3
-        RNNT_HIP(timed(KC_LATTICE, stream,
-                       [&] { return launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, wide_lattice, loss, stream); }));
-        // f^W_4 and Algorithm 1 lines 8, 10, 11
+        return RNNT_OK;
+    };
+    // f^W_2, f^W_3 for one group, on the given stream
+    auto lattice = [&](size_t gi, hipStream_t on) -> rnnt_status {
+        const Group& g = plan.groups[gi];
+        const LatticeState ls = group_state(gi);
+        RNNT_HIP(timed(KC_LATTICE, on,
+                       [&] { return launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, wide_lattice, loss, on); }));
+        return RNNT_OK;
+    };
+    // f^W_4 and Algorithm 1 lines 8, 10, 11 for one group
+    auto backward = [&](size_t gi) -> rnnt_status {
+        const Group& g = plan.groups[gi];
+        const LatticeState ls = group_state(gi);
+        if (stage) {
+            // the kernels index d_enc, d_pred by the sample's number in the call: base pointers such that
+            // sample g.s0 is the first one of the (cleared) workspace arrays
+            PrepArgs pz{};
+            pz.zero_ptr[0] = wv.stage_enc;
+            pz.zero_n[0] = (size_t)(g.s1 - g.s0) * enc_per_sample;
+            pz.zero_ptr[1] = wv.stage_pred;
+            pz.zero_n[1] = (size_t)(g.s1 - g.s0) * pred_per_sample;
+            RNNT_HIP(timed(KC_PREPARE, stream, [&] { return launch_prepare(pz, stream); }));
+            d_enc = (float*)((uintptr_t)wv.stage_enc - (uintptr_t)g.s0 * enc_per_sample * 4);
+            d_pred = (float*)((uintptr_t)wv.stage_pred - (uintptr_t)g.s0 * pred_per_sample * 4);
+        }
         for (; ci < plan.chunks.size() && plan.chunks[ci].group == (int)gi; ++ci) {
             if (!grads) continue;
             const Chunk& c = plan.chunks[ci];
@@ -403,6 +458,37 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
                                           (size_t)(g.s1 - g.s0) * pred_per_sample, stream);
             }));
         }
+        return RNNT_OK;
+    };
+    const size_t ng = plan.groups.size();
+    rnnt_status stt = RNNT_OK;
+    // The second stream takes the lattice sweeps.  Order on the main stream: forward(0), forward(1), backward(0),
+    // forward(2), backward(1), ...: the sweep of group g+1 (latency-bound, a few workgroups per sample) runs beside
+    // the backward pass of group g, whose lattice state lies in the other half of the lattice arrays.  Kept scores
+    // occupy the chunk buffers from a group's forward to its backward pass, so that mode stays on one stream.
+    const bool overlap = ov.lattice_stream && plan.lat_buffers == 2 && !keep && ng > 1;
+    if (!overlap) {
+        for (size_t gi = 0; gi < ng; ++gi) {
+            if ((stt = forward(gi)) != RNNT_OK) return stt;
+            if ((stt = lattice(gi, stream)) != RNNT_OK) return stt;
+            if ((stt = backward(gi)) != RNNT_OK) return stt;
+        }
+    } else {
+        auto forward_then_sweep = [&](size_t gi) -> rnnt_status {
+            rnnt_status s2 = forward(gi);
+            if (s2 != RNNT_OK) return s2;
+            RNNT_HIP(hipEventRecord(ov.fwd_done[gi], stream));
+            RNNT_HIP(hipStreamWaitEvent(ov.lattice_stream, ov.fwd_done[gi], 0));
+            if ((s2 = lattice(gi, ov.lattice_stream)) != RNNT_OK) return s2;
+            RNNT_HIP(hipEventRecord(ov.lat_done[gi], ov.lattice_stream));
+            return RNNT_OK;
+        };
+        if ((stt = forward_then_sweep(0)) != RNNT_OK) return stt;
+        for (size_t gi = 0; gi < ng; ++gi) {
+            if (gi + 1 < ng && (stt = forward_then_sweep(gi + 1)) != RNNT_OK) return stt;
+            RNNT_HIP(hipStreamWaitEvent(stream, ov.lat_done[gi], 0));
+            if ((stt = backward(gi)) != RNNT_OK) return stt;
+        }
     }
     if (bf16 && grads && !dw_first)
         RNNT_HIP(timed(KC_DW_REDUCE, stream, [&] {
@@ -412,7 +498,120 @@ rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const 
     return RNNT_OK;
 }
 
+rnnt_status run(const rnnt_desc* desc, const void* enc, const void* pred, const void* W_out, const float* b_out,
+                const int32_t* labels, const int32_t* T_len, const int32_t* U_len, float* loss, void* d_enc_out,
+                void* d_pred_out, float* dW_out, float* db_out, void* workspace, size_t workspace_bytes,
+                void* hip_stream, bool grads, const float* sample_weight = nullptr, bool no_copy_engine = false) {
+    rnnt_status stt = check_desc(desc);
+    if (stt != RNNT_OK) return stt;
+    if (!T_len || !U_len) return RNNT_ERR_NULL;
+    stt = check_call(desc, enc, pred, W_out, b_out, labels, loss, d_enc_out, d_pred_out, dW_out, db_out, grads, nullptr);
+    if (stt != RNNT_OK) return stt;
+    stt = check_lengths(desc, T_len, U_len);
+    if (stt != RNNT_OK) return stt;
+    stt = check_call(desc, enc, pred, W_out, b_out, labels, loss, d_enc_out, d_pred_out, dW_out, db_out, grads,
+                     sample_weight);
+    if (stt != RNNT_OK) return stt;
+    if (!workspace || ((uintptr_t)workspace % WS_ALIGN) != 0 || workspace_bytes == 0) return RNNT_ERR_WORKSPACE;
+    Plan plan;
+    build_plan(*desc, T_len, U_len, workspace_bytes, plan);
+    if (plan.total_bytes > workspace_bytes) return RNNT_ERR_WORKSPACE;
+    TableSource ts;
+    ts.no_copy_engine = no_copy_engine;
+    return execute(desc, plan, T_len, U_len, ts, Overlap{}, enc, pred, W_out, b_out, labels, loss, d_enc_out,
+                   d_pred_out, dW_out, db_out, workspace, hip_stream, grads, sample_weight);
+}
+
 }  // namespace
+
+// ---- a plan kept between calls ----------------------------------------------------------------------------
+struct rnnt_plan_handle {
+    rnnt_desc desc;
+    std::vector<int32_t> T_len, U_len;
+    Plan plan;
+    unsigned char* tables = nullptr;     // the host tables as they lie in the workspace
+    bool tables_pinned = false;
+    std::vector<hipEvent_t> events;      // 2 per group once a call has used a second stream
+};
+
+extern "C" rnnt_status rnnt_plan_create(const rnnt_desc* desc, const int32_t* T_len, const int32_t* U_len,
+                                        size_t budget_bytes, int32_t overlap_lattice, rnnt_plan_handle** out) {
+    if (!out) return RNNT_ERR_NULL;
+    *out = nullptr;
+    rnnt_status stt = check_desc(desc);
+    if (stt != RNNT_OK) return stt;
+    stt = check_lengths(desc, T_len, U_len);
+    if (stt != RNNT_OK) return stt;
+    if (overlap_lattice != 0 && overlap_lattice != 1) return RNNT_ERR_SHAPE;
+    rnnt_plan_handle* h = new (std::nothrow) rnnt_plan_handle();
+    if (!h) return RNNT_ERR_NULL;
+    h->desc = *desc;
+    h->T_len.assign(T_len, T_len + desc->B);
+    h->U_len.assign(U_len, U_len + desc->B);
+    build_plan(*desc, T_len, U_len, budget_bytes, h->plan, overlap_lattice != 0);
+    const size_t tb = table_bytes(h->plan, (size_t)desc->B);
+    // pinned, so that the copy of a call never makes the host wait; ordinary memory where no GPU is present
+    // (the plan can then still be inspected) or pinning fails
+    void* pinned = nullptr;
+    if (hipHostMalloc(&pinned, tb, hipHostMallocDefault) == hipSuccess && pinned) {
+        h->tables = (unsigned char*)pinned;
+        h->tables_pinned = true;
+    } else {
+        (void)hipGetLastError();
+        h->tables = (unsigned char*)std::malloc(tb);
+        if (!h->tables) { delete h; return RNNT_ERR_NULL; }
+    }
+    fill_tables(h->plan, (size_t)desc->B, T_len, U_len, h->tables);
+    *out = h;
+    return RNNT_OK;
+}
+
+extern "C" void rnnt_plan_destroy(rnnt_plan_handle* h) {
+    if (!h) return;
+    for (hipEvent_t e : h->events) (void)hipEventDestroy(e);
+    if (h->tables_pinned) (void)hipHostFree(h->tables);
+    else std::free(h->tables);
+    delete h;
+}
+
+extern "C" size_t rnnt_plan_workspace_bytes(const rnnt_plan_handle* h) { return h ? h->plan.total_bytes : 0; }
+
+extern "C" rnnt_status rnnt_plan_describe(const rnnt_plan_handle* h, rnnt_plan_info* info) {
+    if (!h || !info) return RNNT_ERR_NULL;
+    fill_info(h->desc, h->plan, info);
+    return RNNT_OK;
+}
+
+extern "C" rnnt_status rnnt_joint_loss_fwd_bwd_planned(rnnt_plan_handle* h, const void* enc, const void* pred,
+                                                       const void* W_out, const float* b_out, const int32_t* labels,
+                                                       const float* sample_weight, float* loss, void* d_enc,
+                                                       void* d_pred, float* dW_out, float* db_out, void* workspace,
+                                                       size_t workspace_bytes, void* hip_stream,
+                                                       void* hip_stream_lattice) {
+    if (!h) return RNNT_ERR_NULL;
+    rnnt_status stt = check_call(&h->desc, enc, pred, W_out, b_out, labels, loss, d_enc, d_pred, dW_out, db_out, true,
+                                 sample_weight);
+    if (stt != RNNT_OK) return stt;
+    if (!workspace || ((uintptr_t)workspace % WS_ALIGN) != 0 || workspace_bytes < h->plan.total_bytes)
+        return RNNT_ERR_WORKSPACE;
+    Overlap ov;
+    const size_t ng = h->plan.groups.size();
+    if (hip_stream_lattice && hip_stream_lattice != hip_stream && h->plan.lat_buffers == 2 && ng > 1) {
+        while (h->events.size() < 2 * ng) {
+            hipEvent_t e = nullptr;
+            RNNT_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            h->events.push_back(e);
+        }
+        ov.lattice_stream = (hipStream_t)hip_stream_lattice;
+        ov.fwd_done = h->events.data();
+        ov.lat_done = h->events.data() + ng;
+    }
+    TableSource ts;
+    ts.staged = h->tables;
+    ts.staged_pinned = h->tables_pinned;
+    return execute(&h->desc, h->plan, h->T_len.data(), h->U_len.data(), ts, ov, enc, pred, W_out, b_out, labels, loss,
+                   d_enc, d_pred, dW_out, db_out, workspace, hip_stream, true, sample_weight);
+}
 
 extern "C" rnnt_status rnnt_joint_loss_fwd_bwd(const rnnt_desc* desc, const void* enc, const void* pred,
                                                const void* W_out, const float* b_out, const int32_t* labels,

@@ -66,11 +66,14 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     p.dw_splits = p.bf16 ? dw_split_count(d.H, d.V) : 0;
     p.off_dwslots = take(p.bf16 ? dw_slot_bytes(d.H, d.V) : 0);
     size_t lat0 = o;
-    p.off_lse = take((size_t)lat_cap * 4);
-    p.off_lpb = take((size_t)lat_cap * 4);
-    p.off_lpy = take((size_t)lat_cap * 4);
-    p.off_alpha = take((size_t)lat_cap * 4);
-    p.off_beta = take((size_t)lat_cap * 4);
+    // lat_buffers = 2: consecutive groups alternate between two halves of each array, so that one group's
+    // lattice sweep can run while its neighbour's state is still in use
+    const size_t lat_elems = (size_t)lat_cap * (size_t)p.lat_buffers;
+    p.off_lse = take(lat_elems * 4);
+    p.off_lpb = take(lat_elems * 4);
+    p.off_lpy = take(lat_elems * 4);
+    p.off_alpha = take(lat_elems * 4);
+    p.off_beta = take(lat_elems * 4);
     p.lattice_bytes = o - lat0;
     size_t ch0 = o;
     if (p.bf16) {
@@ -99,9 +102,11 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
 }  // namespace
 
 void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
-                size_t workspace_bytes, Plan& p) {
+                size_t workspace_bytes, Plan& p, bool two_lattice_buffers) {
     const int B = d.B;
     p.B = B;
+    p.lat_buffers = two_lattice_buffers ? 2 : 1;
+    const long long lat_row_bytes = 20LL * p.lat_buffers;    // workspace bytes per lattice node a group may hold
     p.bf16 = (d.dtype == RNNT_BF16);
     p.keep = p.bf16 && d.keep_scores;
     p.fused = p.bf16 && fused_backward_shape(d.H, d.V);
@@ -137,7 +142,7 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     p.min_bytes = lay_out(d, tmp, max_rows, chunked ? chunk_floor : 0, p.stage ? 1 : 0);
 
     // the default plan; a caller that passes exactly the size it was told gets exactly this plan back
-    const long long lat_default = std::min(p.rows_total, std::max(max_rows, (256LL << 20) / 20));
+    const long long lat_default = std::min(p.rows_total, std::max(max_rows, (256LL << 20) / lat_row_bytes));
     long long chunk_default = 0;
     if (chunked) {
         // 832 MiB: 768 MiB of rows at H = 512, V = 1024 plus the padding of their row pitch
@@ -173,19 +178,19 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
         const size_t stage_bytes = (size_t)stage_samples * stage_per_sample;
         avail = avail > stage_bytes ? avail - stage_bytes : 0;
         if (!chunked) {
-            lat_cap = std::min<long long>(p.rows_total, std::max<long long>(max_rows, (long long)(avail / 20)));
+            lat_cap = std::min<long long>(p.rows_total, std::max<long long>(max_rows, (long long)(avail / lat_row_bytes)));
             chunk_rows = 0;
         } else {
-            long long lat_quarter = (long long)(avail / 4 / 20);
+            long long lat_quarter = (long long)(avail / 4 / lat_row_bytes);
             lat_cap = std::min(p.rows_total, std::max(max_rows, lat_quarter));
-            size_t lat_bytes = (size_t)lat_cap * 20;
+            size_t lat_bytes = (size_t)lat_cap * lat_row_bytes;
             size_t rest = avail > lat_bytes ? avail - lat_bytes : 0;
             chunk_rows = (long long)(rest / crb) / GEMM_TILE * GEMM_TILE;
             chunk_rows = std::min(all_tile_rows, std::max<long long>(chunk_floor, chunk_rows));
             // what the chunk buffers do not need goes to the lattice
             size_t chunk_bytes = (size_t)chunk_rows * crb;
             if (avail > chunk_bytes) {
-                long long more = (long long)((avail - chunk_bytes) / 20);
+                long long more = (long long)((avail - chunk_bytes) / lat_row_bytes);
                 lat_cap = std::min(p.rows_total, std::max(lat_cap, more));
             }
         }

@@ -47,6 +47,7 @@ struct Plan {
     std::vector<Chunk> chunks;
     long long rows_total = 0, tiles_total = 0;
     long long group_rows_cap = 0;       // lattice nodes a group may hold
+    int lat_buffers = 1;                // 2: the lattice arrays hold two groups (group g uses half g % 2)
     long long chunk_rows = 0;           // rows (multiple of GEMM_TILE) of the chunk buffers (fp32 GEMM form: lattice nodes)
     // workspace layout (byte offsets)
     size_t off_T = 0, off_U = 0, off_weight = 0, off_tile_off = 0, off_row_off = 0, off_lnP = 0, off_shift = 0, off_tile_sample = 0;
@@ -88,7 +89,9 @@ rnnt_status check_lengths(const rnnt_desc* d, const int32_t* T_len, const int32_
 // Builds the plan for a workspace of `workspace_bytes` (0 = default trade-off).  If the size
 // is below the smallest workable one, plan.total_bytes = plan.min_bytes > workspace_bytes and
 // the group/chunk lists are those of the smallest plan.
+// two_lattice_buffers: room for the lattice state of two groups at a time (for calls that run a group's lattice
+// sweep on a second stream while the previous group's backward pass is still reading its own state).
 void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
-                size_t workspace_bytes, Plan& plan);
+                size_t workspace_bytes, Plan& plan, bool two_lattice_buffers = false);
 
 }  // namespace rnnt

@@ -185,3 +185,70 @@ def test_paper_shaped_sweep_modes_against_the_checker(mode, dtype):
         _say("sweep", mode, dtype, k, eg)
         assert eg <= tol["grad"], (mode, dtype, k, eg)
     assert r["rows"] == int(np.sum(t["T_len"].astype(np.int64) * (t["U_len"] + 1)))
+
+
+def _run_planned(batch, plan, lattice_stream=None, sample_weight=None, workspace=None):
+    import torch
+    wl = batch.wl
+    dev = Bd.to_device(batch)
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    out = dict(loss=torch.empty(batch.B, **f32), d_enc=torch.empty(batch.B, wl.T_max, wl.H, **f32),
+               d_pred=torch.empty(batch.B, wl.U_max + 1, wl.H, **f32), dW_out=torch.empty(wl.H, wl.V, **f32),
+               db_out=torch.empty(wl.V, **f32))
+    ws = workspace or Bd.Workspace(plan.workspace_bytes)
+    st = Bd.rnnt_joint_loss_fwd_bwd_planned(plan, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                            sample_weight, out["loss"], out["d_enc"], out["d_pred"], out["dW_out"],
+                                            out["db_out"], ws.buf, lattice_stream=lattice_stream)
+    assert st == 0, Bd.STATUS_NAMES[st]
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in out.items()}, ws
+
+
+def test_plan_handle_one_stream_equals_the_plain_call():
+    batch = synth.make_batch("C2")
+    desc = Bd.make_desc(batch.B, 250, 50, 512, 1024, 0, Bd.RNNT_BF16)
+    plan = Bd.PlanHandle(desc, batch.T_len, batch.U_len)
+    plain = run_gpu(batch)
+    got, ws = _run_planned(batch, plan)
+    np.testing.assert_array_equal(got["loss"], plain["loss"])
+    np.testing.assert_array_equal(got["dW_out"], plain["dW_out"])          # same schedule, fixed summation order
+    for k in ("d_enc", "d_pred", "db_out"):
+        assert np.abs(got[k] - plain[k]).max() <= 1e-5 * np.abs(plain[k]).max(), k
+    again, _ = _run_planned(batch, plan, workspace=ws)                      # the handle and workspace are reusable
+    np.testing.assert_array_equal(again["loss"], got["loss"])
+    np.testing.assert_array_equal(again["dW_out"], got["dW_out"])
+    plan.close()
+
+
+@pytest.mark.parametrize("name,n,frac", [("C2", 32, 0.005), ("C4", 12, 0.05)])
+def test_lattice_sweeps_on_a_second_stream_against_the_checker(name, n, frac):
+    # several groups of samples; every group's lattice sweep runs on a second stream beside the previous group's
+    # backward pass (two lattice buffers).  Checked against the float64 checker, against the one-stream call with
+    # the same handle, three calls in a row, and with per-sample weights.
+    import torch
+    wl = synth.WORKLOADS[name]
+    ids = list(range(n)) if name == "C2" else _ids_spanning(wl, n)
+    batch = synth.make_batch(wl, sample_ids=ids)
+    desc = Bd.make_desc(batch.B, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16)
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(desc, batch.T_len, batch.U_len, 1)
+    ndef = Bd.rnnt_joint_loss_workspace_bytes(desc, batch.T_len, batch.U_len, 0)
+    plan = Bd.PlanHandle(desc, batch.T_len, batch.U_len, budget_bytes=int(nmin + frac * (ndef - nmin)), overlap_lattice=True)
+    info = plan.describe()
+    _say("two-stream plan", name, info)
+    assert info["n_groups"] >= 3
+    ref = run_oracle(batch)
+    side = torch.cuda.Stream()
+    one, ws = _run_planned(batch, plan)
+    assert_parity(one, ref, "bf16", f"{name} planned, one stream")
+    for rep in range(3):
+        two, _ = _run_planned(batch, plan, lattice_stream=side, workspace=ws)
+        e, errs = assert_parity(two, ref, "bf16", f"{name} planned, lattice on a second stream, call {rep}")
+        np.testing.assert_array_equal(two["loss"], one["loss"])
+        np.testing.assert_array_equal(two["dW_out"], one["dW_out"])
+    _say("two-stream errs", e, errs)
+    assert_padding_zero(two, batch)
+    w = np.linspace(0.0, 2.0, batch.B).astype(np.float32)
+    refw = run_oracle(batch, sample_weight=w.astype(np.float64))
+    tw, _ = _run_planned(batch, plan, lattice_stream=side, sample_weight=w, workspace=ws)
+    assert_parity(tw, refw, "bf16", f"{name} planned, second stream, weighted")
+    plan.close()

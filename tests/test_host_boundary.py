@@ -366,3 +366,31 @@ def test_group_of_samples_never_exceeds_32_bit_lattice_indices():
     assert info["group_rows_cap"] <= 2 ** 31 - 1 and info["n_groups"] >= 2
     counts = np.bincount(groups)
     assert counts.max() * 1000 * 1024 <= 2 ** 31 - 1
+
+
+def test_plan_handle_holds_the_schedule_of_the_plan_query():
+    # no GPU needed: the handle falls back to ordinary host memory for its tables
+    wl = synth.WORKLOADS["C4"]
+    T, U, _ = synth.draw_lengths_labels(wl)
+    desc = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, 0, Bd.RNNT_BF16)
+    st, info, _ = Bd.rnnt_joint_loss_plan(desc, T, U, 0)
+    assert st == 0
+    h = Bd.PlanHandle(desc, T, U)
+    assert h.workspace_bytes == info["workspace_bytes"] == Bd.rnnt_joint_loss_workspace_bytes(desc, T, U, 0)
+    assert h.describe() == info
+    h.close()
+    # room for the lattice state of two groups: each group at most half as large, same lattice bytes
+    h2 = Bd.PlanHandle(desc, T, U, overlap_lattice=True)
+    d2 = h2.describe()
+    assert d2["lattice_bytes"] <= info["lattice_bytes"] + 4096
+    assert d2["group_rows_cap"] * 2 <= info["group_rows_cap"] + 2
+    assert d2["n_groups"] >= 2 * info["n_groups"] - 1 and d2["rows_total"] == info["rows_total"]
+    h2.close()
+    # bad arguments are refused when the handle is made
+    bad = Bd.make_desc(wl.B, wl.T_max, wl.U_max, 500, wl.V, 0, Bd.RNNT_BF16)
+    with pytest.raises(Bd.RnntError):
+        Bd.PlanHandle(bad, T, U)
+    with pytest.raises(Bd.RnntError):
+        Bd.PlanHandle(desc, T + 1000, U)
+    assert Bd.lib().rnnt_plan_workspace_bytes(None) == 0
+    Bd.lib().rnnt_plan_destroy(None)
