@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--projections", type=int, default=0, metavar="D",
                     help="time the entry point with the joint network's input projections inside "
                          "(Eq. 4 complete), encoder / prediction width D (0 = the north-star entry point)")
+    ap.add_argument("--skip-below", type=int, default=0, metavar="K",
+                    help="skip_below_log2 = K in the descriptor: lattice tiles whose posteriors all lie below 2^-K "
+                         "stay out of the backward pass (0 = every tile, the default and the headline)")
     ap.add_argument("--planned", action="store_true",
                     help="call through a plan handle (rnnt_plan_create once, rnnt_joint_loss_fwd_bwd_planned per step)")
     ap.add_argument("--lattice-stream", action="store_true",
@@ -164,7 +167,7 @@ def main():
     dev = Bd.to_device(batch)
     dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
     desc = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, dt, keep_scores=int(args.keep_scores),
-                        input_grads_bf16=int(args.bf16_grads))
+                        input_grads_bf16=int(args.bf16_grads), skip_below_log2=args.skip_below)
     plan = side = None
     if args.planned or args.lattice_stream:
         plan = Bd.PlanHandle(desc, dev["T_len"], dev["U_len"], args.budget_mib << 20, overlap_lattice=args.lattice_stream)
@@ -249,6 +252,12 @@ def main():
 
     R = int(info["rows_total"])
     HV = wl.H * wl.V
+    # share of the lattice tiles the backward pass worked on (1 unless --skip-below)
+    bwd_share = 1.0
+    if args.skip_below and plan is None:
+        st, act, tot = Bd.rnnt_debug_read_active_tiles(desc, dev["T_len"], dev["U_len"], ws.buf)
+        assert st == 0, st
+        bwd_share = act / tot
     # flops per step of each MFMA kernel, 2*H*V per lattice node and contraction.  Algorithmic: the three
     # contractions the method asks for (scores, dW_out, dz), each counted once, where it is first computed;
     # executed: what the kernel multiplies, i.e. also the scores a backward kernel computes a second time.
@@ -258,6 +267,11 @@ def main():
                           "fwd_f32": 2.0 * R * HV, "bwd_f32": 4.0 * R * HV}
     exec_flops_per_step = dict(alg_flops_per_step, joint_scores_bwd=2.0 * R * HV, bwd_f32=6.0 * R * HV,
                                joint_bwd_fused=(2.0 if args.keep_scores else 4.0) * R * HV)
+    if bwd_share < 1.0:
+        # tiles of negligible posterior are left out: both counts cover only the rows the kernels worked on
+        for name in ("joint_bwd_fused", "gemm_dw_db"):
+            alg_flops_per_step[name] *= bwd_share
+            exec_flops_per_step[name] *= bwd_share
     kernels = {}
     for name, (cnt, ms) in prof.items():
         if cnt:
@@ -292,8 +306,8 @@ def main():
     measured_peak = {name: mfma_loop_tflops(Bd, torch, bits, False, 512, 4000)[0]
                      for name, bits in pats if name in ("zeros", "random bf16")} if wl.dtype == "bf16" else None
     step_s = elapsed / steps
-    util_alg = 6.0 * R * HV / step_s / peak
-    util_exec = (6.0 if args.keep_scores else 8.0) * R * HV / step_s / peak
+    util_alg = (2.0 + 4.0 * bwd_share) * R * HV / step_s / peak
+    util_exec = (2.0 + (4.0 if args.keep_scores else 6.0) * bwd_share) * R * HV / step_s / peak
     lat = kernels.get("lattice")
     # lattice pass: bytes per launch from the committed FETCH_SIZE / WRITE_SIZE summary where there is one,
     # next to the figure from the 24 bytes per node the sweep has to move (emissions read twice, alpha, beta written)
@@ -314,6 +328,7 @@ def main():
                                                                                    if side is not None else "")
                                              if plan is not None else "rnnt_joint_loss_fwd_bwd"),
                    "keep_scores": int(args.keep_scores), "input_grads_bf16": int(args.bf16_grads),
+                   "skip_below_log2": args.skip_below, "backward_tile_share": bwd_share,
                    "groups": info["n_groups"], "chunks": info["n_chunks"],
                    "workspace_bytes": int(nbytes)},
         "mfma_util_alg": util_alg, "mfma_util_exec": util_exec,

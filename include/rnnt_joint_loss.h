@@ -77,6 +77,15 @@ typedef struct {
                                   the same shape (half the bytes of the two largest outputs): the sums are
                                   formed in float for one group of samples at a time in the workspace and
                                   rounded once (nearest even) on their way out (mixed precision, Section 6) */
+    int32_t skip_below_log2;   /* 0: every lattice node goes through the backward pass.  k = 1..126 (RNNT_BF16 with
+                                  H <= 640 and keep_scores = 0 only): after the lattice pass (f^W_2), 64-node
+                                  lattice tiles in which every node has a posterior gamma = exp(alpha + beta - ln P)
+                                  below 2^-k are left out of the backward pass (f^W_4 and Algorithm 1 lines 8, 10,
+                                  11).  Every entry of such a node's score gradient is at most gamma in magnitude,
+                                  so each gradient entry changes by less than 2^-k times the number of lattice nodes
+                                  that add to it.  The loss is not affected.  The alignments that carry the
+                                  probability pass through a narrow band of a long lattice; with k = 30 four fifths
+                                  of the tiles of a 750 x 140 lattice drop out.                               */
 } rnnt_desc;
 
 /* What the host scheduler decided for a call (Section 4.1.2 analogue; see rnnt_joint_loss_plan). */

@@ -28,6 +28,15 @@ rnnt_status rnnt_debug_read_lattice(const rnnt_desc* desc, const int32_t* T_len_
                                     float* alpha_host, float* beta_host);
 
 /*
+ * Test and measurement hook: after a call with desc->skip_below_log2 > 0 on this workspace (same desc, lengths
+ * and workspace size; stream synchronised by this function), the number of lattice tiles that went through the
+ * backward pass and the number of all tiles.  With skip_below_log2 = 0 both are the number of all tiles.
+ */
+rnnt_status rnnt_debug_read_active_tiles(const rnnt_desc* desc, const int32_t* T_len_host,
+                                         const int32_t* U_len_host, const void* workspace,
+                                         size_t workspace_bytes, int64_t* active_tiles, int64_t* all_tiles);
+
+/*
  * Measurement support, not a paper operation: copies n floats (n a multiple of 4, both dev, 16-byte
  * aligned) with a plain grid-stride kernel.  Its known size calibrates the HBM byte counters that
  * the per-kernel traffic figures are read from.  Enqueues on hip_stream, does not wait.

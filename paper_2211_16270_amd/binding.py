@@ -24,7 +24,7 @@ EXPORTS = ["rnnt_status_string", "rnnt_last_hip_error", "rnnt_joint_loss_workspa
            "rnnt_debug_copy_f32", "rnnt_debug_mfma_loop", "rnnt_debug_mfma_loop_fp8", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
            "rnnt_joint_proj_workspace_bytes", "rnnt_joint_proj_loss_fwd_bwd", "rnnt_joint_loss_fwd_bwd_weighted",
            "rnnt_joint_loss_fwd_bwd_static", "rnnt_plan_create", "rnnt_plan_workspace_bytes", "rnnt_plan_describe",
-           "rnnt_plan_destroy", "rnnt_joint_loss_fwd_bwd_planned"]
+           "rnnt_plan_destroy", "rnnt_joint_loss_fwd_bwd_planned", "rnnt_debug_read_active_tiles"]
 RNNT_STATIC_SCRATCH_BYTES = 128 << 20
 
 
@@ -32,7 +32,8 @@ class RnntDesc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32), ("U_max", ctypes.c_int32),
                 ("H", ctypes.c_int32), ("V", ctypes.c_int32), ("blank", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("accumulate_params", ctypes.c_int32),
-                ("keep_scores", ctypes.c_int32), ("input_grads_bf16", ctypes.c_int32)]
+                ("keep_scores", ctypes.c_int32), ("input_grads_bf16", ctypes.c_int32),
+                ("skip_below_log2", ctypes.c_int32)]
 
 
 class RnntPlanInfo(ctypes.Structure):
@@ -114,6 +115,9 @@ def lib() -> ctypes.CDLL:
     L.rnnt_joint_loss_fwd.argtypes = [dp, vp, vp, vp, f32p, vp, i32p, i32p, f32p, vp, ctypes.c_size_t, vp]
     L.rnnt_debug_read_lattice.restype = ctypes.c_int
     L.rnnt_debug_read_lattice.argtypes = [dp, i32p, i32p, vp, ctypes.c_size_t, ctypes.c_int32, vp, vp]
+    L.rnnt_debug_read_active_tiles.restype = ctypes.c_int
+    L.rnnt_debug_read_active_tiles.argtypes = [dp, i32p, i32p, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int64),
+                                               ctypes.POINTER(ctypes.c_int64)]
     L.rnnt_debug_copy_f32.restype = ctypes.c_int
     L.rnnt_debug_copy_f32.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.rnnt_debug_mfma_loop.restype = ctypes.c_int
@@ -133,9 +137,9 @@ def lib() -> ctypes.CDLL:
 
 
 def make_desc(B, T_max, U_max, H, V, blank=0, dtype=RNNT_BF16, accumulate_params=0, keep_scores=0,
-              input_grads_bf16=0) -> RnntDesc:
+              input_grads_bf16=0, skip_below_log2=0) -> RnntDesc:
     return RnntDesc(int(B), int(T_max), int(U_max), int(H), int(V), int(blank), int(dtype),
-                    int(accumulate_params), int(keep_scores), int(input_grads_bf16))
+                    int(accumulate_params), int(keep_scores), int(input_grads_bf16), int(skip_below_log2))
 
 
 def _i32(a) -> np.ndarray:
@@ -309,6 +313,16 @@ def rnnt_debug_read_lattice(desc: RnntDesc, T_len, U_len, workspace, b: int):
     return int(st), al.reshape(shape), be.reshape(shape)
 
 
+def rnnt_debug_read_active_tiles(desc: RnntDesc, T_len, U_len, workspace):
+    """(status, tiles that went through the backward pass, all tiles) after a call on this workspace."""
+    T, U = _i32(T_len), _i32(U_len)
+    a, n = ctypes.c_int64(0), ctypes.c_int64(0)
+    st = lib().rnnt_debug_read_active_tiles(ctypes.byref(desc), _ip(T), _ip(U), _ptr(workspace),
+                                            int(workspace.numel() * workspace.element_size()),
+                                            ctypes.byref(a), ctypes.byref(n))
+    return int(st), int(a.value), int(n.value)
+
+
 def rnnt_debug_copy_f32(src, dst, stream=None) -> int:
     """Copies the float32 tensor src into dst (same size, multiple of 4 elements) with the library's
     plain copy kernel."""
@@ -377,7 +391,7 @@ def to_device(batch, device="cuda:0"):
 
 def run_fwd_bwd(dev: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optional[Workspace] = None,
                 budget_bytes: int = 0, accumulate_into=None, stream=None, sample_weight=None, keep_scores=0,
-                input_grads_bf16=0):
+                input_grads_bf16=0, skip_below_log2=0):
     """Allocates outputs (and a workspace unless given), calls rnnt_joint_loss_fwd_bwd (its weighted form if
     sample_weight is given), raises on a non-zero status.  keep_scores, input_grads_bf16: the descriptor's fields of
     those names (with the latter d_enc and d_pred are bfloat16 tensors).  Returns dict(loss, d_enc, d_pred, dW_out, db_out,
@@ -385,7 +399,7 @@ def run_fwd_bwd(dev: dict, B, T_max, U_max, H, V, blank, dtype, workspace: Optio
     import torch
     device = dev["enc"].device
     desc = make_desc(B, T_max, U_max, H, V, blank, dtype, 0 if accumulate_into is None else 1, keep_scores,
-                     input_grads_bf16)
+                     input_grads_bf16, skip_below_log2)
     if workspace is None:
         n = rnnt_joint_loss_workspace_bytes(desc, dev["T_len"], dev["U_len"], budget_bytes)
         if n == 0:

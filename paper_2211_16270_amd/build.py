@@ -12,7 +12,7 @@ LIB_DIR = os.path.join(PKG_DIR, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "librnnt_joint_loss.so")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 
-SOURCES = ["api.cpp", "plan.cpp", "kernels_prep.hip", "kernels_f32.hip", "kernels_lattice.hip", "kernels_bf16.hip", "kernels_bf16_fused.hip", "kernels_bf16_dz.hip", "kernels_proj.hip", "kernels_probe.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "kernels_prep.hip", "kernels_f32.hip", "kernels_lattice.hip", "kernels_select.hip", "kernels_bf16.hip", "kernels_bf16_fused.hip", "kernels_bf16_dz.hip", "kernels_proj.hip", "kernels_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 DEVICE_FLAGS = [

@@ -100,11 +100,12 @@ namespace {
 // Optional per-kernel timing with HIP events on the caller's stream (off by default).
 enum KernelClass { KC_PREPARE = 0, KC_FWD_SCORES, KC_LATTICE, KC_BWD_SCORES, KC_GEMM_DZ, KC_GEMM_DW,
                    KC_BWD_FUSED, KC_FWD_F32, KC_BWD_F32, KC_DW_REDUCE, KC_PROJ, KC_FWD_KEEP, KC_KEPT_TO_DH,
-                   KC_GRADS_TO_BF16, KC_COUNT };
+                   KC_GRADS_TO_BF16, KC_SELECT, KC_COUNT };
 const char* const kKernelNames[KC_COUNT] = {"prepare", "joint_scores_fwd", "lattice",
                                             "joint_scores_bwd", "gemm_dz", "gemm_dw_db", "joint_bwd_fused",
                                             "fwd_f32", "bwd_f32", "dw_reduce", "projections",
-                                            "joint_scores_fwd_keep", "kept_scores_to_dh", "input_grads_to_bf16"};
+                                            "joint_scores_fwd_keep", "kept_scores_to_dh", "input_grads_to_bf16",
+                                            "select_tiles"};
 struct Profiler {
     bool enabled = false;
     struct Rec { int cls; hipEvent_t e0, e1; };
@@ -337,6 +338,8 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
     size_t ci = 0;
     int dw_first = 1;
     const bool keep = plan.keep && grads;
+    const bool skip = plan.skip_log2 > 0 && grads;
+    const float skip_log_floor = -(float)plan.skip_log2 * 0.6931471805599453f;
     // lattice state of group gi: with two buffers consecutive groups alternate between the halves of each array
     auto group_state = [&](size_t gi) {
         const Group& g = plan.groups[gi];
@@ -377,6 +380,13 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
         const LatticeState ls = group_state(gi);
         RNNT_HIP(timed(KC_LATTICE, on,
                        [&] { return launch_lattice(wv.st, ls, g.s0, g.s1, g.u_max, wide_lattice, loss, on); }));
+        if (skip)
+            // tiles whose posteriors all lie below the floor are left out of this group's backward pass
+            RNNT_HIP(timed(KC_SELECT, on, [&] {
+                return launch_select_tiles(wv.st, ls, g.s0, g.s1, g.tile0, g.tile1, skip_log_floor,
+                                           (int*)(w + plan.off_tile_flags), (int*)(w + plan.off_tile_active),
+                                           (int*)(w + plan.off_n_active) + gi, on);
+            }));
         return RNNT_OK;
     };
     // f^W_4 and Algorithm 1 lines 8, 10, 11 for one group
@@ -400,6 +410,10 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
             const Chunk& c = plan.chunks[ci];
             if (bf16) {
                 const long long rows = (long long)(c.tile1 - c.tile0) * TILE_ROWS;
+                // with a tile list the chunk takes entries [c.tile0 - g.tile0, c.tile1 - g.tile0) of the group's list
+                const ActiveTiles at{skip ? (const int*)(w + plan.off_tile_active) : nullptr,
+                                     skip ? (const int*)(w + plan.off_n_active) + gi : nullptr, g.tile0,
+                                     c.tile0 - g.tile0};
                 if (keep && plan.fused) {
                     // the group's scores are in the chunk buffers already: the fused kernel turns them into dh
                     // on their way into the dz GEMM and writes dh back for the dW GEMM
@@ -420,7 +434,7 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
                 } else if (plan.fused) {
                     RNNT_HIP(timed(KC_BWD_FUSED, stream, [&] {
                         return launch_bwd_fused_bf16(pr, wv.wpack, wv.wq, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1,
-                                                     wv.dH, wv.Z, d_enc, d_pred, stream);
+                                                     wv.dH, wv.Z, d_enc, d_pred, at, stream);
                     }));
                 } else {
                     RNNT_HIP(timed(KC_BWD_SCORES, stream, [&] {
@@ -434,7 +448,7 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
                 }
                 RNNT_HIP(timed(KC_GEMM_DW, stream, [&] {
                     return launch_gemm_dw_bf16(desc->H, desc->V, rows, plan.dw_splits, dw_first, wv.Z, wv.dH,
-                                               wv.dw_slots, db_out, stream);
+                                               wv.dw_slots, db_out, at, stream);
                 }));
                 dw_first = 0;
             } else if (plan.f32_gemm) {
@@ -817,6 +831,28 @@ extern "C" rnnt_status rnnt_debug_read_lattice(const rnnt_desc* desc, const int3
             alpha_host[i] -= shift * (float)(t + u);
             beta_host[i] -= shift * (float)((T - t) + (U - u));
         }
+    return RNNT_OK;
+}
+
+extern "C" rnnt_status rnnt_debug_read_active_tiles(const rnnt_desc* desc, const int32_t* T_len, const int32_t* U_len,
+                                                    const void* workspace, size_t workspace_bytes,
+                                                    int64_t* active_tiles, int64_t* all_tiles) {
+    rnnt_status stt = check_desc(desc);
+    if (stt != RNNT_OK) return stt;
+    stt = check_lengths(desc, T_len, U_len);
+    if (stt != RNNT_OK) return stt;
+    if (!workspace || !active_tiles || !all_tiles) return RNNT_ERR_NULL;
+    Plan plan;
+    build_plan(*desc, T_len, U_len, workspace_bytes, plan);
+    if (plan.total_bytes > workspace_bytes) return RNNT_ERR_WORKSPACE;
+    *all_tiles = plan.tiles_total;
+    *active_tiles = plan.tiles_total;
+    if (plan.skip_log2 == 0) return RNNT_OK;
+    std::vector<int> n(plan.groups.size());
+    RNNT_HIP(hipDeviceSynchronize());
+    RNNT_HIP(hipMemcpy(n.data(), (const unsigned char*)workspace + plan.off_n_active, n.size() * 4, hipMemcpyDeviceToHost));
+    *active_tiles = 0;
+    for (int v : n) *active_tiles += v;
     return RNNT_OK;
 }
 

@@ -94,6 +94,20 @@ hipError_t launch_bwd_f32_gemm(const Problem& pr, const SampleTable& st, const L
 hipError_t launch_lattice(const SampleTable& st, const LatticeState& ls, int s0, int s1, int u_max, int wide,
                           float* loss, hipStream_t stream);
 
+// After the lattice pass of a group: flags[tile] = 1 for tiles [tile0, tile1) with a node whose posterior
+// ln gamma = alpha + beta - ln P is at least log_floor, their ids in ascending order in active[tile0 ...] and their
+// number in *n_active.
+hipError_t launch_select_tiles(const SampleTable& st, const LatticeState& ls, int s0, int s1, int tile0, int tile1,
+                               float log_floor, int* flags, int* active, int* n_active, hipStream_t stream);
+// The tiles a backward launch works on: null active = tiles [tile0, tile1) one by one; else entry cbase + i of the
+// group's list active[group_tile0 ...], for i below *n_active - cbase (workgroups beyond that return at once).
+struct ActiveTiles {
+    const int* active;
+    const int* n_active;
+    int group_tile0;
+    int cbase;
+};
+
 // ---- bf16 MFMA path -------------------------------------------------------------------------
 // joint tile in LDS -> scores on MFMA -> online log-softmax -> lse, lpb, lpy   (tiles [tile0,tile1))
 hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
@@ -138,7 +152,7 @@ __host__ __device__ inline int chunk_pitch(int n) { return n + 64; }
 // fragment-major copy of W_out.
 hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const void* Wq, const SampleTable& st,
                                  const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
-                                 void* Z, float* d_enc, float* d_pred, hipStream_t stream);
+                                 void* Z, float* d_enc, float* d_pred, const ActiveTiles& at, hipStream_t stream);
 // The same for scores the forward pass has kept (launch_fwd_keep_bf16): `kept` holds them and leaves as dH; Z is
 // not touched.
 hipError_t launch_bwd_fused_kept_bf16(const Problem& pr, const void* Wq, const SampleTable& st, const LatticeState& ls,
@@ -147,8 +161,9 @@ hipError_t launch_bwd_fused_kept_bf16(const Problem& pr, const void* Wq, const S
 // Split-K GEMM Z^T dH over one chunk's rows: every (split, tile) workgroup adds its 256x256 partial
 // product to its own slot (`first` != 0: overwrites it), db += column sums of dH.  `splits` and the
 // slot buffer size follow dw_split_count / dw_slot_bytes (plan.h).
+// With at.active set the chunk holds only min(rows, 64 * (*at.n_active - at.cbase)) rows (read on the device).
 hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, int splits, int first, const void* Z,
-                               const void* dH, float* slots, float* db, hipStream_t stream);
+                               const void* dH, float* slots, float* db, const ActiveTiles& at, hipStream_t stream);
 // dW = (accumulate ? dW : 0) + sum of the slots over the splits
 hipError_t launch_dw_reduce(int H, int V, int splits, const float* slots, float* dW, int accumulate,
                             hipStream_t stream);

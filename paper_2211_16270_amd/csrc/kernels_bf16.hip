@@ -518,6 +518,8 @@ struct DwArgs {
     int first;       // overwrite the slot instead of adding to it
     int H, V;
     int mt, nt;      // output tiles along H and V
+    int splits;
+    ActiveTiles at;  // at.active set: the chunk holds 64 * (*at.n_active - at.cbase) rows if that is less than K
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -545,8 +547,18 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
     const int tile = q % ntile, split = xcd + 8 * (q / ntile);
     const int bm = tile % g.mt, bn = tile / g.mt;
     const long long m0 = (long long)bm * WT, n0 = (long long)bn * WT;
-    const long long ks = (long long)split * g.k_per_split;
-    const long long ke = ks + g.k_per_split < g.K ? ks + g.k_per_split : g.K;
+    long long K = g.K, k_per_split = g.k_per_split;
+    if (g.at.active) {
+        long long act = (long long)*g.at.n_active - g.at.cbase;
+        act = act < 0 ? 0 : act * JT_ROWS;
+        if (act < K) {
+            K = act;
+            const long long per = (K + g.splits - 1) / g.splits;
+            k_per_split = (per + WK - 1) / WK * WK;
+        }
+    }
+    const long long ks = (long long)split * k_per_split;
+    const long long ke = ks + k_per_split < K ? ks + k_per_split : K;
     const bool do_db = (bm == 0) && (wm == 0);
     constexpr unsigned STAGE_BYTES = 2u * WK * WT * 2u;
     constexpr unsigned OPER_BYTES = (unsigned)WK * WT * 2u;
@@ -602,6 +614,7 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
     const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 
     const long long nsteps = ke > ks ? (ke - ks) / WK : 0;   // a split beyond the chunk still writes its slot
+    if (nsteps == 0 && !g.first) return;                     // ... unless the slot already holds a sum: nothing to add
     static_assert(WK == 32, "the loop below is written for two k16-steps per stage");
     bf16x8 fa[2][4], fb[2][4];
     auto read_frags = [&](int set, long long stage, int kk) {
@@ -698,10 +711,10 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
 }
 
 hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, int splits, int first, const void* Z, const void* dH,
-                               float* slots, float* db, hipStream_t stream) {
+                               float* slots, float* db, const ActiveTiles& at, hipStream_t stream) {
     if (rows <= 0 || splits <= 0 || (splits & 7) != 0 || rows % WK != 0) return hipErrorInvalidValue;
     const long long mt = (H + WT - 1) / WT, nt = V / WT;
-    DwArgs g{(const bf16_t*)Z, (const bf16_t*)dH, rows, 0, slots, db, first, H, V, (int)mt, (int)nt};
+    DwArgs g{(const bf16_t*)Z, (const bf16_t*)dH, rows, 0, slots, db, first, H, V, (int)mt, (int)nt, splits, at};
     // split s runs on XCD s % 8; a split past the end of a short chunk only touches its slot
     long long per = (rows + splits - 1) / splits;
     g.k_per_split = (per + WK - 1) / WK * WK;

@@ -40,6 +40,7 @@ struct FusedArgs {
     float* d_enc;
     float* d_pred;
     const float* kept_max;   // KEPT: running maxima of the kept scores, [chunk tiles][V/64][64 rows]
+    ActiveTiles at;          // which tiles this launch works on (see kernels.h)
 };
 
 // HT = hidden 32-tiles per dz wave = ceil(H / 128); FB_PF = fragment prefetch distance of the score loop in
@@ -62,7 +63,13 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
-    const int tile = a.tile0 + blockIdx.x;
+    int tile = a.tile0 + blockIdx.x;
+    if (a.at.active) {
+        // listed tiles only: entry cbase + blockIdx.x of the group's list, if there is one (uniform per workgroup)
+        const int ci = a.at.cbase + (int)blockIdx.x;
+        if (ci >= *a.at.n_active) return;
+        tile = a.at.active[a.at.group_tile0 + ci];
+    }
     const TilePos tp = locate_tile(a.st, a.s0, a.s1, tile);
     const int b = tp.s;
     const long long chunk_row0 = (long long)blockIdx.x * FB_ROWS;
@@ -465,10 +472,10 @@ static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t stream) {
 
 hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const void* Wq, const SampleTable& st,
                                  const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH, void* Z,
-                                 float* d_enc, float* d_pred, hipStream_t stream) {
+                                 float* d_enc, float* d_pred, const ActiveTiles& at, hipStream_t stream) {
     if (tile1 <= tile0) return hipSuccess;
     FusedArgs a{pr, st, ls, (const bf16_t*)Wpack, (const bf16_t*)Wq, s0, s1, tile0, tile1,
-                (bf16_t*)dH, (bf16_t*)Z, d_enc, d_pred, nullptr};
+                (bf16_t*)dH, (bf16_t*)Z, d_enc, d_pred, nullptr, at};
     const int ht = (pr.H / 32 + 3) / 4;
     // H = 128 ... 640 in steps of 128: H/16 = 8, 16, 24, 32, 40 k16-steps
     if (ht <= 1) return launch_fused_t<1, 4, 4, false>(a, stream);
@@ -484,7 +491,7 @@ hipError_t launch_bwd_fused_kept_bf16(const Problem& pr, const void* Wq, const S
                                       float* d_enc, float* d_pred, hipStream_t stream) {
     if (tile1 <= tile0) return hipSuccess;
     FusedArgs a{pr, st, ls, nullptr, (const bf16_t*)Wq, s0, s1, tile0, tile1,
-                (bf16_t*)kept, nullptr, d_enc, d_pred, kept_max};
+                (bf16_t*)kept, nullptr, d_enc, d_pred, kept_max, ActiveTiles{nullptr, nullptr, 0, 0}};
     const int ht = (pr.H / 32 + 3) / 4;
     if (ht <= 1) return launch_fused_t<1, 4, 4, true>(a, stream);
     if (ht == 2) return launch_fused_t<2, 8, 4, true>(a, stream);

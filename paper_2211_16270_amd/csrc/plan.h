@@ -52,6 +52,9 @@ struct Plan {
     // workspace layout (byte offsets)
     size_t off_T = 0, off_U = 0, off_weight = 0, off_tile_off = 0, off_row_off = 0, off_lnP = 0, off_shift = 0, off_tile_sample = 0;
     size_t off_tile_esum = 0;          // bf16: per-tile emission sums (float per tile)
+    int skip_log2 = 0;                 // descriptor's skip_below_log2
+    size_t off_tile_flags = 0, off_tile_active = 0, off_n_active = 0;   // skip_log2 > 0: per tile keep flag, per group
+                                                                        // the list of kept tiles, per group their number
     size_t off_wpack = 0, off_wq = 0;
     size_t off_lse = 0, off_lpb = 0, off_lpy = 0, off_alpha = 0, off_beta = 0;
     size_t off_dh = 0, off_z = 0, off_kept_max = 0;

@@ -11,14 +11,15 @@ GRADS = ("d_enc", "d_pred", "dW_out", "db_out")
 
 
 def run_gpu(batch, budget_bytes=0, blank=None, workspace=None, accumulate_into=None, sample_weight=None,
-            keep_scores=0, input_grads_bf16=0):
+            keep_scores=0, input_grads_bf16=0, skip_below_log2=0):
     import torch
     wl = batch.wl
     dev = Bd.to_device(batch)
     dt = Bd.RNNT_BF16 if wl.dtype == "bf16" else Bd.RNNT_F32
     out = Bd.run_fwd_bwd(dev, batch.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank if blank is None else blank, dt,
                          workspace=workspace, budget_bytes=budget_bytes, accumulate_into=accumulate_into,
-                         sample_weight=sample_weight, keep_scores=keep_scores, input_grads_bf16=input_grads_bf16)
+                         sample_weight=sample_weight, keep_scores=keep_scores, input_grads_bf16=input_grads_bf16,
+                         skip_below_log2=skip_below_log2)
     torch.cuda.synchronize()
     res = {k: out[k].float().cpu().numpy() for k in ("loss",) + GRADS}
     res["workspace"] = out["workspace"]

@@ -252,3 +252,55 @@ def test_lattice_sweeps_on_a_second_stream_against_the_checker(name, n, frac):
     tw, _ = _run_planned(batch, plan, lattice_stream=side, sample_weight=w, workspace=ws)
     assert_parity(tw, refw, "bf16", f"{name} planned, second stream, weighted")
     plan.close()
+
+
+@pytest.mark.parametrize("name,n,k", [("C2", 32, 30), ("C4", 12, 30), ("C4", 12, 20), ("C3", 8, 30)])
+def test_backward_pass_without_the_tiles_of_negligible_posterior(name, n, k):
+    # skip_below_log2 = k: lattice tiles whose nodes all have a posterior below 2^-k stay out of the backward pass.
+    # All five outputs against the checker at the usual tolerance, the loss bit-identical to the full call, the
+    # gradients within 2^-k * (nodes that add to an entry) of it, and a real share of the tiles left out.
+    wl = synth.WORKLOADS[name]
+    ids = list(range(n)) if name == "C2" else _ids_spanning(wl, n)
+    batch = synth.make_batch(wl, sample_ids=ids)
+    ref = run_oracle(batch)
+    full = run_gpu(batch)
+    got = run_gpu(batch, skip_below_log2=k)
+    e, errs = assert_parity(got, ref, "bf16", f"{name} without negligible tiles, k = {k}")
+    assert_padding_zero(got, batch)
+    np.testing.assert_array_equal(got["loss"], full["loss"])
+    st, active, total = Bd.rnnt_debug_read_active_tiles(got["desc"], batch.T_len, batch.U_len, got["workspace"].buf)
+    assert st == 0 and 0 < active <= total
+    _say("negligible tiles", name, k, "active", active, "of", total, "errs", e, errs)
+    for key in ("d_enc", "d_pred", "dW_out", "db_out"):
+        d = np.abs(got[key].astype(np.float64) - full[key]).max() / np.abs(full[key]).max()
+        assert d < 1e-4, (key, d)          # far inside the tolerance: what was left out is below 2^-20 per node
+    if name != "C2":
+        assert active < 0.6 * total        # long lattices: most tiles carry no posterior mass
+    # a small workspace: several groups, several chunks per group, the list cut across chunks
+    budget, info = _budget_with_several_groups_and_chunks(batch, {})
+    small = run_gpu(batch, budget_bytes=budget, skip_below_log2=k)
+    assert_parity(small, ref, "bf16", f"{name} without negligible tiles, small workspace")
+    st, active2, total2 = Bd.rnnt_debug_read_active_tiles(small["desc"], batch.T_len, batch.U_len, small["workspace"].buf)
+    assert st == 0 and (active2, total2) == (active, total)
+
+
+def test_negligible_tile_option_edge_cases():
+    # tiny lattices (every tile holds posterior mass: nothing is left out), a weight of zero (all of that sample's
+    # tiles drop out), and shapes the option does not cover
+    wl = synth.custom_workload("skipedge", B=4, T_max=37, U_max=19, H=128, V=256, dtype="bf16", index=170,
+                               t_rule="uniform", t_lo=3, u_rule="uniform", u_lo=0)
+    batch = synth.make_batch(wl)
+    ref = run_oracle(batch)
+    got = run_gpu(batch, skip_below_log2=30)
+    assert_parity(got, ref, "bf16", "small lattices, k = 30")
+    w = np.array([1.0, 0.0, 0.5, 2.0], dtype=np.float32)
+    gw = run_gpu(batch, skip_below_log2=30, sample_weight=w)
+    assert_parity(gw, run_oracle(batch, sample_weight=w.astype(np.float64)), "bf16", "weights, k = 30")
+    assert np.all(gw["d_enc"][1] == 0.0) and np.all(gw["d_pred"][1] == 0.0)
+    one = run_gpu(batch, skip_below_log2=1)            # gamma < 1/2 dropped: a coarse result, but a finite one
+    assert all(np.all(np.isfinite(one[k2])) for k2 in ("loss", "d_enc", "d_pred", "dW_out", "db_out"))
+    np.testing.assert_array_equal(one["loss"], got["loss"])
+    for bad in (dict(keep_scores=1), dict(H=1024), dict(dtype=Bd.RNNT_F32), dict(skip=127), dict(skip=-1)):
+        d = Bd.make_desc(2, 8, 4, bad.get("H", 128), 256, 0, bad.get("dtype", Bd.RNNT_BF16),
+                         keep_scores=bad.get("keep_scores", 0), skip_below_log2=bad.get("skip", 30))
+        assert Bd.rnnt_joint_loss_workspace_bytes(d, [8, 8], [4, 4]) == 0, bad

@@ -39,7 +39,7 @@ def test_no_hip_error_is_reported_before_one_happened():
 
 
 def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(Bd.RnntDesc) == 40
+    assert ctypes.sizeof(Bd.RnntDesc) == 44
     assert ctypes.sizeof(Bd.RnntPlanInfo) == 8 * 3 + 4 * 2 + 8 * 2 + 8 * 3
 
 
