@@ -189,28 +189,36 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         };
         auto wp_load = [&](size_t off, int j) { return *reinterpret_cast<const bf16x8*>(wpb + off + j * 1024 + lane_b); };
 
+        // The first fragment block and the bias of a step are fetched while the step before is still busy with
+        // its exponentials and its copy-out (at the start of a step nothing else would hide their way from the L2).
+        bf16x8 ringA[2][2][FB_PF];
+        f32x4 bias_next[2][4];
+        auto load_bias = [&](int vs_) {
+#pragma unroll
+            for (int vt = 0; vt < 2; ++vt) {
+                const float* bp = a.pr.b_out + vs_ * FB_VSTEP + w4 * 64 + vt * 32 + 4 * hb;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bias_next[vt][j] = *reinterpret_cast<const f32x4*>(bp + 8 * j);
+            }
+        };
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+            for (int j = 0; j < FB_PF; ++j) ringA[0][vt][j] = wp_load(wp_off(0, vt, 0), j);
+        load_bias(0);
         for (int vs = 0; vs < nvs; ++vs) {
             bf16_t* buf = dhs + (vs & 1) * (FB_ROWS * FB_DP);
             // -------- scores of 64 entries x 64 rows; accumulators start from the bias
             f32x16 acc[2][2];
 #pragma unroll
-            for (int vt = 0; vt < 2; ++vt) {
-                const float* bp = a.pr.b_out + vs * FB_VSTEP + w4 * 64 + vt * 32 + 4 * hb;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const f32x4 t4 = *reinterpret_cast<const f32x4*>(bp + 8 * j);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        acc[vt][0][4 * j + i] = t4[i];
-                        acc[vt][1][4 * j + i] = t4[i];
-                    }
-                }
-            }
-            bf16x8 ringA[2][2][FB_PF];
-#pragma unroll
             for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-                for (int j = 0; j < FB_PF; ++j) ringA[0][vt][j] = wp_load(wp_off(vs, vt, 0), j);
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        acc[vt][0][4 * j + i] = bias_next[vt][j][i];
+                        acc[vt][1][4 * j + i] = bias_next[vt][j][i];
+                    }
             bf16x8 bc[2] = {*reinterpret_cast<const bf16x8*>(zrow0), *reinterpret_cast<const bf16x8*>(zrow1)};
             const bf16_t* zc0 = zrow0;
             const bf16_t* zc1 = zrow1;
@@ -220,8 +228,10 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
                 for (int half = 0; half < 2; ++half) {
                     const int kb = kb2 + half;
                     const int cs = half, ns = half ^ 1;
-                    const int nkb_ = (kb + 1 < nkb) ? kb + 1 : kb;
-                    const size_t noff0 = wp_off(vs, 0, nkb_), noff1 = wp_off(vs, 1, nkb_);
+                    // next block of this step, else the first block of the next step (of this one again at the end)
+                    int nvs_ = vs, nkb_ = kb + 1;
+                    if (nkb_ == nkb) { nkb_ = 0; nvs_ = (vs + 1 < nvs) ? vs + 1 : vs; }
+                    const size_t noff0 = wp_off(nvs_, 0, nkb_), noff1 = wp_off(nvs_, 1, nkb_);
                     const int knext = (kb + 1 == nkb) ? 0 : (kb + 1) * FB_PF * 16;
                     const bf16_t* zn0 = zrow0 + knext;
                     const bf16_t* zn1 = zrow1 + knext;
@@ -251,6 +261,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
                 }
             }
             __builtin_amdgcn_s_setprio(0);
+            load_bias(vs + 1 < nvs ? vs + 1 : vs);
             // -------- f^W_4: dh = gamma * softmax - posteriors, to bf16, into this step's LDS buffer (row-major).
             //          The dz waves read the other buffer meanwhile; they left this one before the last barrier.
 #pragma unroll
