@@ -122,6 +122,9 @@ def main():
     ap.add_argument("--skip-below", type=int, default=0, metavar="K",
                     help="skip_below_log2 = K in the descriptor: lattice tiles whose posteriors all lie below 2^-K "
                          "stay out of the backward pass (0 = every tile, the default and the headline)")
+    ap.add_argument("--no-skip-variant", action="store_true",
+                    help="leave out the second measurement (the same steps with skip_below_log2 = 30) that the default "
+                         "bf16 line carries; for profiler runs that should hold the default path only")
     ap.add_argument("--planned", action="store_true",
                     help="call through a plan handle (rnnt_plan_create once, rnnt_joint_loss_fwd_bwd_planned per step)")
     ap.add_argument("--lattice-stream", action="store_true",
@@ -254,7 +257,8 @@ def main():
     # skip_below_log2 = 30; not the headline: `value` above is the full computation)
     skip_variant = None
     if (wl.dtype == "bf16" and wl.H <= 640 and not (args.skip_below or args.keep_scores or args.projections
-                                                     or args.bf16_grads or plan is not None)):
+                                                     or args.bf16_grads or args.no_skip_variant or args.batch
+                                                     or plan is not None)):
         desc2 = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, dt, skip_below_log2=30)
         n2 = Bd.rnnt_joint_loss_workspace_bytes(desc2, dev["T_len"], dev["U_len"], args.budget_mib << 20)
         del ws
