@@ -120,11 +120,12 @@ def main():
                     help="time the entry point with the joint network's input projections inside "
                          "(Eq. 4 complete), encoder / prediction width D (0 = the north-star entry point)")
     ap.add_argument("--skip-below", type=int, default=0, metavar="K",
-                    help="skip_below_log2 = K in the descriptor: lattice tiles whose posteriors all lie below 2^-K "
-                         "stay out of the backward pass (0 = every tile, the default and the headline)")
+                    help="skip_below_log2 = K in the descriptor: lattice tiles whose posteriors all lie below 2^-K stay "
+                         "out of the backward pass.  0 = the library's default and the headline (only tiles whose score "
+                         "gradients are exactly zero as bf16 operands are left out), -1 = every tile is multiplied")
     ap.add_argument("--no-skip-variant", action="store_true",
-                    help="leave out the second measurement (the same steps with skip_below_log2 = 30) that the default "
-                         "bf16 line carries; for profiler runs that should hold the default path only")
+                    help="leave out the two further measurements (the same steps with skip_below_log2 = -1 and 30) that "
+                         "the default bf16 line carries; for profiler runs that should hold the default path only")
     ap.add_argument("--planned", action="store_true",
                     help="call through a plan handle (rnnt_plan_create once, rnnt_joint_loss_fwd_bwd_planned per step)")
     ap.add_argument("--lattice-stream", action="store_true",
@@ -235,6 +236,13 @@ def main():
     assert bool(torch.isfinite(loss).all()), "non-finite loss"
     peak_bytes = torch.cuda.max_memory_allocated()
 
+    # share of the lattice tiles the backward pass worked on (tiles whose bf16 score gradients are all zero are left out)
+    share_main = 1.0
+    if plan is None and not args.projections:
+        st, act, tot = Bd.rnnt_debug_read_active_tiles(desc, dev["T_len"], dev["U_len"], ws.buf)
+        assert st == 0, st
+        share_main = act / tot
+
     # second pass: the same K steps with every launch bracketed by HIP events on the same stream
     Bd.rnnt_profile_enable(True)
     t0 = time.perf_counter()
@@ -253,46 +261,47 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # the same steps with the backward pass restricted to the lattice tiles that hold posterior mass (descriptor option
-    # skip_below_log2 = 30; not the headline: `value` above is the full computation)
-    skip_variant = None
+    # the same steps with other values of skip_below_log2 (not the headline): -1 = every lattice tile goes through the
+    # backward pass, also those whose score gradients are exactly zero as bf16 operands; 30 = only tiles with a node of
+    # posterior >= 2^-30
+    variants = None
     if (wl.dtype == "bf16" and wl.H <= 640 and not (args.skip_below or args.keep_scores or args.projections
                                                      or args.bf16_grads or args.no_skip_variant or args.batch
                                                      or plan is not None)):
-        desc2 = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, dt, skip_below_log2=30)
-        n2 = Bd.rnnt_joint_loss_workspace_bytes(desc2, dev["T_len"], dev["U_len"], args.budget_mib << 20)
-        del ws
-        ws = Bd.Workspace(n2)
-        loss_full = loss.clone()
+        loss_default = loss.clone()
+        variants = {}
+        for key, k_skip, what in (("every_tile", -1, "skip_below_log2 = -1: every lattice tile goes through the backward "
+                                   "pass, also those whose score gradients are all zero as bf16 operands"),
+                                  ("negligible_tiles_skipped", 30, "skip_below_log2 = 30: backward pass only over lattice "
+                                   "tiles with a node of posterior >= 2^-30; same loss, gradients within rounding of the "
+                                   "full computation (tests)")):
+            desc2 = Bd.make_desc(wl.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, dt, skip_below_log2=k_skip)
+            n2 = Bd.rnnt_joint_loss_workspace_bytes(desc2, dev["T_len"], dev["U_len"], args.budget_mib << 20)
+            del ws
+            ws = Bd.Workspace(n2)
 
-        def step2():
-            s = Bd.rnnt_joint_loss_fwd_bwd(desc2, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
-                                           dev["T_len"], dev["U_len"], loss, d_enc, d_pred, dW, db, ws.buf, stream)
-            if s != 0:
-                raise Bd.RnntError(s, "rnnt_joint_loss_fwd_bwd")
-        k2 = max(2, min(steps, 6))
-        step2()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(k2):
+            def step2():
+                s = Bd.rnnt_joint_loss_fwd_bwd(desc2, dev["enc"], dev["pred"], dev["W_out"], dev["b_out"], dev["labels"],
+                                               dev["T_len"], dev["U_len"], loss, d_enc, d_pred, dW, db, ws.buf, stream)
+                if s != 0:
+                    raise Bd.RnntError(s, "rnnt_joint_loss_fwd_bwd")
+            k2 = max(2, min(steps, 6))
             step2()
-        torch.cuda.synchronize()
-        dt2 = (time.perf_counter() - t0) / k2
-        st, act, tot = Bd.rnnt_debug_read_active_tiles(desc2, dev["T_len"], dev["U_len"], ws.buf)
-        assert st == 0 and bool(torch.equal(loss, loss_full))
-        skip_variant = {"skip_below_log2": 30, "value": wl.B / dt2, "unit": "samples/s", "ms_per_step": dt2 * 1e3,
-                        "steps": k2, "backward_tile_share": act / tot,
-                        "what": "backward pass only over lattice tiles with a node of posterior >= 2^-30; same loss, "
-                                "gradients within rounding of the full computation (tests)"}
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(k2):
+                step2()
+            torch.cuda.synchronize()
+            dt2 = (time.perf_counter() - t0) / k2
+            st, act, tot = Bd.rnnt_debug_read_active_tiles(desc2, dev["T_len"], dev["U_len"], ws.buf)
+            assert st == 0 and bool(torch.equal(loss, loss_default))
+            variants[key] = {"skip_below_log2": k_skip, "value": wl.B / dt2, "unit": "samples/s",
+                             "ms_per_step": dt2 * 1e3, "steps": k2, "backward_tile_share": act / tot, "what": what}
 
     R = int(info["rows_total"])
     HV = wl.H * wl.V
-    # share of the lattice tiles the backward pass worked on (1 unless --skip-below)
-    bwd_share = 1.0
-    if args.skip_below and plan is None:
-        st, act, tot = Bd.rnnt_debug_read_active_tiles(desc, dev["T_len"], dev["U_len"], ws.buf)
-        assert st == 0, st
-        bwd_share = act / tot
+    # share of the lattice tiles the backward pass worked on
+    bwd_share = share_main
     # flops per step of each MFMA kernel, 2*H*V per lattice node and contraction.  Algorithmic: the three
     # contractions the method asks for (scores, dW_out, dz), each counted once, where it is first computed;
     # executed: what the kernel multiplies, i.e. also the scores a backward kernel computes a second time.
@@ -367,12 +376,15 @@ def main():
                    "groups": info["n_groups"], "chunks": info["n_chunks"],
                    "workspace_bytes": int(nbytes)},
         "mfma_util_alg": util_alg, "mfma_util_exec": util_exec,
+        # 6 R H V over the step time: what an implementation that multiplies every lattice node would have to sustain
+        # for this step time (equal to mfma_util_alg when backward_tile_share is 1)
+        "mfma_util_dense_equivalent": 6.0 * R * HV / step_s / peak,
         "peak_hbm_gb": peak_bytes / 1e9,
         "lattice_gb_per_s": lattice_gbs, "lattice_gb_per_s_from_24B_per_node": lattice_alg_gbs,
         "ms_per_step_with_events": elapsed_prof / steps * 1e3,
         "gpu_kernel_ms_per_step": gpu_ms,
         "roofline": roofline,
-        "with_negligible_tiles_skipped": skip_variant,
+        "other_tile_selections": variants,
         "measured_mfma_peak": None if measured_peak is None else
         {"unit": "TFLOP/s", "what": "MFMA-only loop, 32x32x16 bf16, two waves per SIMD, no memory access",
          "zeros": measured_peak["zeros"], "random_bf16": measured_peak["random bf16"]},

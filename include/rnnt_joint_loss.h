@@ -77,15 +77,21 @@ typedef struct {
                                   the same shape (half the bytes of the two largest outputs): the sums are
                                   formed in float for one group of samples at a time in the workspace and
                                   rounded once (nearest even) on their way out (mixed precision, Section 6) */
-    int32_t skip_below_log2;   /* 0: every lattice node goes through the backward pass.  k = 1..126 (RNNT_BF16 with
-                                  H <= 640 and keep_scores = 0 only): after the lattice pass (f^W_2), 64-node
-                                  lattice tiles in which every node has a posterior gamma = exp(alpha + beta - ln P)
-                                  below 2^-k are left out of the backward pass (f^W_4 and Algorithm 1 lines 8, 10,
-                                  11).  Every entry of such a node's score gradient is at most gamma in magnitude,
-                                  so each gradient entry changes by less than 2^-k times the number of lattice nodes
-                                  that add to it.  The loss is not affected.  The alignments that carry the
-                                  probability pass through a narrow band of a long lattice; with k = 30 four fifths
-                                  of the tiles of a 750 x 140 lattice drop out.                               */
+    int32_t skip_below_log2;   /* Which 64-node lattice tiles take part in the backward pass (f^W_4 and Algorithm 1
+                                  lines 8, 10, 11).  Every entry of a node's score gradient is at most the node's
+                                  posterior gamma = exp(alpha + beta - ln P) in magnitude, and the alignments that
+                                  carry the probability pass through a narrow band of a long lattice.
+                                  0 (default): where the fused backward kernel runs (RNNT_BF16, H <= 640,
+                                     keep_scores = 0), tiles in which every node has gamma < 2^-135 are left out:
+                                     as bfloat16 MFMA operands their score gradients are all exactly zero (a
+                                     magnitude below 2^-134 rounds to zero), so no term of any sum changes; only
+                                     the order of the floating-point additions can.  Elsewhere no tile is left out.
+                                  -1: no tile is left out, anywhere.
+                                  k = 1..126 (fused backward kernel only, else RNNT_ERR_UNSUPPORTED): tiles in
+                                     which every node has gamma < 2^-k are left out; each gradient entry changes
+                                     by less than 2^-k times the number of lattice nodes that add to it (with
+                                     k = 30 four fifths of the tiles of a 750 x 140 lattice drop out).
+                                  The loss is never affected.                                                  */
 } rnnt_desc;
 
 /* What the host scheduler decided for a call (Section 4.1.2 analogue; see rnnt_joint_loss_plan). */

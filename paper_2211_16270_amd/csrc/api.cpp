@@ -384,7 +384,7 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
             // tiles whose posteriors all lie below the floor are left out of this group's backward pass
             RNNT_HIP(timed(KC_SELECT, on, [&] {
                 return launch_select_tiles(wv.st, ls, g.s0, g.s1, g.tile0, g.tile1, skip_log_floor,
-                                           (int*)(w + plan.off_tile_flags), (int*)(w + plan.off_tile_active),
+                                           (int*)(w + plan.off_tile_esum), (int*)(w + plan.off_tile_esum),
                                            (int*)(w + plan.off_n_active) + gi, on);
             }));
         return RNNT_OK;
@@ -411,7 +411,7 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
             if (bf16) {
                 const long long rows = (long long)(c.tile1 - c.tile0) * TILE_ROWS;
                 // with a tile list the chunk takes entries [c.tile0 - g.tile0, c.tile1 - g.tile0) of the group's list
-                const ActiveTiles at{skip ? (const int*)(w + plan.off_tile_active) : nullptr,
+                const ActiveTiles at{skip ? (const int*)(w + plan.off_tile_esum) : nullptr,
                                      skip ? (const int*)(w + plan.off_n_active) + gi : nullptr, g.tile0,
                                      c.tile0 - g.tile0};
                 if (keep && plan.fused) {

@@ -1,12 +1,13 @@
-// Which lattice tiles of a group take part in the backward pass (descriptor field skip_below_log2 > 0).
+// Which lattice tiles of a group take part in the backward pass.
 //
 // Every entry of a lattice node's score gradient dh = gamma * softmax - posteriors (f^W_4) is at most the
 // node's posterior gamma = exp(alpha + beta - ln P) in magnitude (the blank and label occupations are parts
 // of gamma).  On long utterances gamma is far below the resolution of the sums the gradients are
 // accumulated in for most of the lattice: the alignments that carry the probability pass through a narrow
 // band.  A tile whose 64 nodes all have gamma < 2^-k contributes less than 2^-k per gradient entry and node
-// and is left out.  k_tile_flags marks the tiles that stay, k_compact_tiles lists them in their original
-// order (so that every sum that is formed in a fixed order still is).
+// and is left out; with k = 135 (the default where the fused backward kernel runs) everything such a tile would
+// feed into the backward GEMMs is exactly zero as a bfloat16 value.  k_tile_flags marks the tiles that stay,
+// k_compact_tiles lists them in their original order (so that every sum that is formed in a fixed order still is).
 #include "device_common.h"
 
 namespace rnnt {
@@ -19,7 +20,9 @@ struct SelectArgs {
     int s0, s1, tile0, tile1;
     float log_floor;     // ln of the smallest posterior that keeps a tile
     int* flags;          // [tiles of the call] 1 = the tile stays
-    int* active;         // [tiles of the call] the group's entries, from tile0 on: tile ids that stay, ascending
+    int* active;         // [tiles of the call] the group's entries, from tile0 on: tile ids that stay, ascending.
+                         // May be the same array as flags: a round's flags are all read (barrier) before its list
+                         // entries are written, and those land at or below the positions the round has read.
     int* n_active;       // one counter (this group's)
 };
 

@@ -20,8 +20,8 @@ rnnt_status check_desc(const rnnt_desc* d) {
     if (d->input_grads_bf16 != 0 && d->input_grads_bf16 != 1) return RNNT_ERR_SHAPE;
     if (d->input_grads_bf16 && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
     if (d->dtype != RNNT_F32 && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
-    if (d->skip_below_log2 < 0 || d->skip_below_log2 > 126) return RNNT_ERR_SHAPE;
-    if (d->skip_below_log2 &&
+    if (d->skip_below_log2 < -1 || d->skip_below_log2 > 126) return RNNT_ERR_SHAPE;
+    if (d->skip_below_log2 > 0 &&
         (d->dtype != RNNT_BF16 || d->keep_scores || !fused_backward_shape(d->H, d->V)))
         return RNNT_ERR_UNSUPPORTED;                            // the fused backward kernel is the one that takes a tile list
     if (d->U_max > 1023) return RNNT_ERR_UNSUPPORTED;           // one lattice thread per label position
@@ -65,8 +65,8 @@ size_t lay_out(const rnnt_desc& d, Plan& p, long long lat_cap, long long chunk_r
     p.off_shift = take(B * 4);
     p.off_tile_sample = take((size_t)p.tiles_total * 4);
     p.off_tile_esum = take(p.bf16 ? (size_t)p.tiles_total * 4 : 0);
-    p.off_tile_flags = take(p.skip_log2 ? (size_t)p.tiles_total * 4 : 0);
-    p.off_tile_active = take(p.skip_log2 ? (size_t)p.tiles_total * 4 : 0);
+    // the list of tiles that take part in the backward pass is written over the emission sums of the same tiles
+    // (the lattice pass has consumed them by then): only the per-group counts need room of their own
     p.off_n_active = take(p.skip_log2 ? B * 4 : 0);
     p.off_wpack = take(p.bf16 ? (size_t)d.H * d.V * 2 : 0);
     p.off_wq = take(p.fused ? (size_t)d.H * d.V * 2 : 0);
@@ -118,7 +118,10 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     p.keep = p.bf16 && d.keep_scores;
     p.fused = p.bf16 && fused_backward_shape(d.H, d.V);
     p.stage = p.bf16 && d.input_grads_bf16;
-    p.skip_log2 = d.skip_below_log2;
+    // 0: where the fused backward kernel runs, tiles whose score gradients are all zero as bf16 values are left
+    // out (ZERO_IN_BF16_LOG2); -1: no tile is ever left out
+    p.skip_log2 = d.skip_below_log2 > 0 ? d.skip_below_log2
+                  : (d.skip_below_log2 == 0 && p.fused && !p.keep) ? ZERO_IN_BF16_LOG2 : 0;
     p.f32_gemm = !p.bf16 && f32_gemm_shape(d.H, d.V);
     const bool chunked = p.bf16 || p.f32_gemm;
     const size_t stage_per_sample = ((size_t)d.T_max + d.U_max + 1) * d.H * 4;

@@ -52,9 +52,9 @@ struct Plan {
     // workspace layout (byte offsets)
     size_t off_T = 0, off_U = 0, off_weight = 0, off_tile_off = 0, off_row_off = 0, off_lnP = 0, off_shift = 0, off_tile_sample = 0;
     size_t off_tile_esum = 0;          // bf16: per-tile emission sums (float per tile)
-    int skip_log2 = 0;                 // descriptor's skip_below_log2
-    size_t off_tile_flags = 0, off_tile_active = 0, off_n_active = 0;   // skip_log2 > 0: per tile keep flag, per group
-                                                                        // the list of kept tiles, per group their number
+    int skip_log2 = 0;                 // > 0: tiles whose posteriors all lie below 2^-skip_log2 stay out of the backward pass
+    size_t off_n_active = 0;           // skip_log2 > 0: per group the number of tiles that stay (their list lies in the
+                                       // tile_esum array, over the entries of the same tiles)
     size_t off_wpack = 0, off_wq = 0;
     size_t off_lse = 0, off_lpb = 0, off_lpy = 0, off_alpha = 0, off_beta = 0;
     size_t off_dh = 0, off_z = 0, off_kept_max = 0;
@@ -65,6 +65,11 @@ struct Plan {
     size_t lattice_bytes = 0, chunk_bytes = 0, total_bytes = 0;
     size_t min_bytes = 0;               // smallest workable workspace
 };
+
+// A score gradient dh = gamma * softmax - posteriors is at most the node's posterior gamma in magnitude, and a
+// magnitude below 2^-134 (half the smallest bfloat16 denormal) rounds to zero as bf16: with gamma < 2^-135 at every
+// node of a tile, every operand the tile would feed into the backward GEMMs is exactly zero.
+constexpr int ZERO_IN_BF16_LOG2 = 135;
 
 // Shapes the fused backward kernel covers (its dz accumulators must fit the register file).
 inline bool fused_backward_shape(int H, int V) { return H % 128 == 0 && H <= 640 && V % 256 == 0; }

@@ -263,7 +263,7 @@ def test_backward_pass_without_the_tiles_of_negligible_posterior(name, n, k):
     ids = list(range(n)) if name == "C2" else _ids_spanning(wl, n)
     batch = synth.make_batch(wl, sample_ids=ids)
     ref = run_oracle(batch)
-    full = run_gpu(batch)
+    full = run_gpu(batch, skip_below_log2=-1)               # every tile
     got = run_gpu(batch, skip_below_log2=k)
     e, errs = assert_parity(got, ref, "bf16", f"{name} without negligible tiles, k = {k}")
     assert_padding_zero(got, batch)
@@ -300,7 +300,28 @@ def test_negligible_tile_option_edge_cases():
     one = run_gpu(batch, skip_below_log2=1)            # gamma < 1/2 dropped: a coarse result, but a finite one
     assert all(np.all(np.isfinite(one[k2])) for k2 in ("loss", "d_enc", "d_pred", "dW_out", "db_out"))
     np.testing.assert_array_equal(one["loss"], got["loss"])
-    for bad in (dict(keep_scores=1), dict(H=1024), dict(dtype=Bd.RNNT_F32), dict(skip=127), dict(skip=-1)):
+    for bad in (dict(keep_scores=1), dict(H=1024), dict(dtype=Bd.RNNT_F32), dict(skip=127), dict(skip=-2)):
         d = Bd.make_desc(2, 8, 4, bad.get("H", 128), 256, 0, bad.get("dtype", Bd.RNNT_BF16),
                          keep_scores=bad.get("keep_scores", 0), skip_below_log2=bad.get("skip", 30))
         assert Bd.rnnt_joint_loss_workspace_bytes(d, [8, 8], [4, 4]) == 0, bad
+
+
+@pytest.mark.parametrize("name,n", [("C4", 12), ("C3", 8), ("C5", 8)])
+def test_default_leaves_out_only_tiles_whose_score_gradients_are_zero_in_bf16(name, n):
+    # skip_below_log2 = 0 (default): tiles whose posteriors all lie below 2^-135 stay out of the backward pass; as bf16
+    # operands their score gradients are exactly zero, so against the pass over every tile (-1) only the order of the
+    # floating-point additions differs: loss identical, gradients equal to a few units of fp32 rounding of the sums
+    wl = synth.WORKLOADS[name]
+    ids = _ids_spanning(wl, n, max_rows=60_000 if name == "C5" else None)
+    batch = synth.make_batch(wl, sample_ids=ids)
+    dflt = run_gpu(batch)
+    every = run_gpu(batch, skip_below_log2=-1)
+    np.testing.assert_array_equal(dflt["loss"], every["loss"])
+    for key in ("d_enc", "d_pred", "dW_out", "db_out"):
+        d = np.abs(dflt[key].astype(np.float64) - every[key]).max() / np.abs(every[key]).max()
+        _say("default vs every tile", name, key, d)
+        assert d < 2e-6, (key, d)
+    st, active, total = Bd.rnnt_debug_read_active_tiles(dflt["desc"], batch.T_len, batch.U_len, dflt["workspace"].buf)
+    st2, a2, t2 = Bd.rnnt_debug_read_active_tiles(every["desc"], batch.T_len, batch.U_len, every["workspace"].buf)
+    _say("default keeps", active, "of", total, "tiles")
+    assert st == 0 and st2 == 0 and a2 == t2 == total and 0 < active < total
