@@ -429,7 +429,7 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
                     }));
                     RNNT_HIP(timed(KC_GEMM_DZ, stream, [&] {
                         return launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred,
-                                                   stream);
+                                                   ActiveTiles{nullptr, nullptr, 0, 0}, stream);
                     }));
                 } else if (plan.fused) {
                     RNNT_HIP(timed(KC_BWD_FUSED, stream, [&] {
@@ -439,11 +439,11 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
                 } else {
                     RNNT_HIP(timed(KC_BWD_SCORES, stream, [&] {
                         return launch_bwd_scores_bf16(pr, wv.wpack, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
-                                                      wv.Z, stream);
+                                                      wv.Z, at, stream);
                     }));
                     RNNT_HIP(timed(KC_GEMM_DZ, stream, [&] {
                         return launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred,
-                                                   stream);
+                                                   at, stream);
                     }));
                 }
                 RNNT_HIP(timed(KC_GEMM_DW, stream, [&] {

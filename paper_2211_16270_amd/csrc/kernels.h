@@ -116,7 +116,7 @@ hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTab
 // joint tile -> scores recomputed -> dh (bf16) into the chunk buffers dH [rows,V], Z [rows,H]
 hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                                   const LatticeState& ls, int s0, int s1, int tile0, int tile1,
-                                  void* dH, void* Z, hipStream_t stream);
+                                  void* dH, void* Z, const ActiveTiles& at, hipStream_t stream);
 // The forward launch that also keeps the joint tiles (Z [rows,H]) and the scores (kept [rows,V]: fp16
 // differences to the running maxima kept_max [tiles][V/64][64]) of tiles [tile0,tile1), and the launch that
 // turns the kept scores into dh (bf16, in place) once alpha and beta are known.
@@ -128,7 +128,7 @@ hipError_t launch_kept_to_dh_bf16(const Problem& pr, const SampleTable& st, cons
                                   hipStream_t stream);
 // dz = dH W^T, times the tanh derivative, reduced over the tile's u resp. t, added to d_enc, d_pred
 hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0,
-                               int tile1, const void* dH, float* d_enc, float* d_pred,
+                               int tile1, const void* dH, float* d_enc, float* d_pred, const ActiveTiles& at,
                                hipStream_t stream);
 // Shape of a sample's lattice tiles (64 rows each): 8 frames x 8 label positions, or 16 x 4 where that covers the
 // sample's T x (U + 1) lattice with at least 3 % fewer tiles (the padding rows of partly filled tiles cost as

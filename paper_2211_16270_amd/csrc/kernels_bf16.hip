@@ -42,6 +42,7 @@ struct JointArgs {
     bf16_t* dH;     // [chunk rows, V]   (MODE 2: fp16 score differences)
     bf16_t* Z;      // [chunk rows, H]
     float* kept_max;  // MODE 2: [chunk tiles][V/64][64 rows] running maxima
+    ActiveTiles at;   // MODE 1: which tiles the launch works on (see kernels.h); unused (null) otherwise
 };
 
 
@@ -67,7 +68,13 @@ __global__ __launch_bounds__(64 * NW, 2) void k_joint_scores(JointArgs a) {
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hb = lane >> 5;
-    const int tile = a.tile0 + blockIdx.x;
+    int tile = a.tile0 + blockIdx.x;
+    if (MODE == 1 && a.at.active) {
+        // listed tiles only: entry cbase + blockIdx.x of the group's list, if there is one (uniform per workgroup)
+        const int ci = a.at.cbase + (int)blockIdx.x;
+        if (ci >= *a.at.n_active) return;
+        tile = a.at.active[a.at.group_tile0 + ci];
+    }
     const TilePos tp = locate_tile(a.st, a.s0, a.s1, tile);
     const int b = tp.s;
     const long long chunk_row0 = (long long)blockIdx.x * JT_ROWS;
@@ -387,7 +394,8 @@ static hipError_t launch_joint(const JointArgs& a, hipStream_t stream) {
 
 hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st, const LatticeState& ls,
                            int s0, int s1, int tile0, int tile1, hipStream_t stream) {
-    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr, nullptr};
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr, nullptr,
+                ActiveTiles{nullptr, nullptr, 0, 0}};
     // a longer prefetch distance where the hidden size allows it (the forward kernel has the registers)
     if (pr.H % 256 == 0) return launch_joint<0, 4, 2, 8>(a, stream);
     return launch_joint<0, 4, 2, 4>(a, stream);
@@ -395,15 +403,16 @@ hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTab
 
 hipError_t launch_bwd_scores_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                                   const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* dH,
-                                  void* Z, hipStream_t stream) {
-    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)dH, (bf16_t*)Z, nullptr};
+                                  void* Z, const ActiveTiles& at, hipStream_t stream) {
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)dH, (bf16_t*)Z, nullptr, at};
     return launch_joint<1, 4, 2, 4>(a, stream);
 }
 
 hipError_t launch_fwd_keep_bf16(const Problem& pr, const void* Wpack, const SampleTable& st,
                                 const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* kept,
                                 void* Z, float* kept_max, hipStream_t stream) {
-    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)kept, (bf16_t*)Z, kept_max};
+    JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)kept, (bf16_t*)Z, kept_max,
+                ActiveTiles{nullptr, nullptr, 0, 0}};
     if (pr.H % 256 == 0) return launch_joint<2, 4, 2, 8>(a, stream);
     return launch_joint<2, 4, 2, 4>(a, stream);
 }
@@ -486,7 +495,8 @@ hipError_t launch_kept_to_dh_bf16(const Problem& pr, const SampleTable& st, cons
                                   hipStream_t stream) {
     const int n = tile1 - tile0;
     if (n <= 0) return hipSuccess;
-    JointArgs a{pr, st, ls, nullptr, s0, s1, tile0, tile1, (bf16_t*)kept, nullptr, const_cast<float*>(kept_max)};
+    JointArgs a{pr, st, ls, nullptr, s0, s1, tile0, tile1, (bf16_t*)kept, nullptr, const_cast<float*>(kept_max),
+                ActiveTiles{nullptr, nullptr, 0, 0}};
     k_kept_to_dh<<<dim3((unsigned)n), dim3(256), 0, stream>>>(a);
     return hipGetLastError();
 }

@@ -36,6 +36,7 @@ struct DzArgs {
     float* d_pred;
     int m_tiles, n_tiles;
     long long rows;           // rows of the dH chunk buffer that were written (a multiple of 64)
+    ActiveTiles at;           // which tiles the chunk's 64-row slots hold (see kernels.h)
 };
 
 __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
@@ -47,7 +48,13 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
     // neighbours on one XCD, so the rows of dH are fetched from HBM once.
     const int L = blockIdx.x, xcd = L & 7, q = L >> 3;
     const int by = q % g.n_tiles, bx = xcd + 8 * (q / g.n_tiles);
-    if (bx >= g.m_tiles) return;
+    // slots of the chunk that hold a tile: all of the launch's, or what is left of the group's list
+    int n_slots = g.tile1 - g.tile0;
+    if (g.at.active) {
+        const int left = *g.at.n_active - g.at.cbase;
+        n_slots = left < n_slots ? left : n_slots;
+    }
+    if (bx * 4 >= n_slots) return;          // also covers bx >= m_tiles (uniform per workgroup)
     const int H = g.pr.H, V = g.pr.V;
     const long long m0 = (long long)bx * ZT;
     const int n0 = by * ZT;
@@ -169,10 +176,12 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
     // per tile 20 row slots, the tile's frames first, its label positions behind them.
     __shared__ TilePos tpos[4];      // where the workgroup's four lattice tiles lie (s < 0: past the last tile)
     if (tid < 4) {
-        const int tile = g.tile0 + bx * 4 + tid;
+        const int slot = bx * 4 + tid;
         TilePos t{};
         t.s = -1;
-        if (tile < g.tile1) t = locate_tile(g.st, g.s0, g.s1, tile);
+        if (slot < n_slots)
+            t = locate_tile(g.st, g.s0, g.s1,
+                            g.at.active ? g.at.active[g.at.group_tile0 + g.at.cbase + slot] : g.tile0 + slot);
         tpos[tid] = t;
     }
     __syncthreads();
@@ -271,12 +280,13 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
 }  // namespace
 
 hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0, int tile1,
-                               const void* dH, float* d_enc, float* d_pred, hipStream_t stream) {
+                               const void* dH, float* d_enc, float* d_pred, const ActiveTiles& at,
+                               hipStream_t stream) {
     const int n = tile1 - tile0;
     if (n <= 0) return hipSuccess;
     if (pr.V % ZK != 0) return hipErrorInvalidValue;
     DzArgs g{(const bf16_t*)dH, (const bf16_t*)pr.W, pr, st, s0, s1, tile0, tile1, d_enc, d_pred,
-             (n + 3) / 4, (pr.H + ZT - 1) / ZT, (long long)n * 64};
+             (n + 3) / 4, (pr.H + ZT - 1) / ZT, (long long)n * 64, at};
     const size_t smem = (size_t)ZST * Z_STAGE;
     static bool configured = false;
     if (!configured) {

@@ -300,19 +300,25 @@ def test_negligible_tile_option_edge_cases():
     one = run_gpu(batch, skip_below_log2=1)            # gamma < 1/2 dropped: a coarse result, but a finite one
     assert all(np.all(np.isfinite(one[k2])) for k2 in ("loss", "d_enc", "d_pred", "dW_out", "db_out"))
     np.testing.assert_array_equal(one["loss"], got["loss"])
-    for bad in (dict(keep_scores=1), dict(H=1024), dict(dtype=Bd.RNNT_F32), dict(skip=127), dict(skip=-2)):
+    for bad in (dict(keep_scores=1), dict(dtype=Bd.RNNT_F32), dict(skip=127), dict(skip=-2)):
         d = Bd.make_desc(2, 8, 4, bad.get("H", 128), 256, 0, bad.get("dtype", Bd.RNNT_BF16),
                          keep_scores=bad.get("keep_scores", 0), skip_below_log2=bad.get("skip", 30))
         assert Bd.rnnt_joint_loss_workspace_bytes(d, [8, 8], [4, 4]) == 0, bad
 
 
-@pytest.mark.parametrize("name,n", [("C4", 12), ("C3", 8), ("C5", 8)])
+@pytest.mark.parametrize("name,n", [("C4", 12), ("C3", 8), ("C5", 8), ("P1024", 4)])
 def test_default_leaves_out_only_tiles_whose_score_gradients_are_zero_in_bf16(name, n):
     # skip_below_log2 = 0 (default): tiles whose posteriors all lie below 2^-135 stay out of the backward pass; as bf16
     # operands their score gradients are exactly zero, so against the pass over every tile (-1) only the order of the
     # floating-point additions differs: loss identical, gradients equal to a few units of fp32 rounding of the sums
-    wl = synth.WORKLOADS[name]
-    ids = _ids_spanning(wl, n, max_rows=60_000 if name == "C5" else None)
+    if name == "P1024":
+        # the paper's own shape (joint size 1024, 4096 word pieces, 500 x 100): the unfused backward kernels
+        wl = synth.custom_workload("P4", B=4, T_max=500, U_max=100, H=1024, V=4096, dtype="bf16", index=5,
+                                   t_rule="uniform", t_lo=454, u_rule="uniform", u_lo=54)
+        ids = list(range(n))
+    else:
+        wl = synth.WORKLOADS[name]
+        ids = _ids_spanning(wl, n, max_rows=60_000 if name == "C5" else None)
     batch = synth.make_batch(wl, sample_ids=ids)
     dflt = run_gpu(batch)
     every = run_gpu(batch, skip_below_log2=-1)
