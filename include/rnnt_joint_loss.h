@@ -81,13 +81,13 @@ typedef struct {
                                   lines 8, 10, 11).  Every entry of a node's score gradient is at most the node's
                                   posterior gamma = exp(alpha + beta - ln P) in magnitude, and the alignments that
                                   carry the probability pass through a narrow band of a long lattice.
-                                  0 (default): on the bf16 path that computes the scores twice (RNNT_BF16,
-                                     keep_scores = 0), tiles in which every node has gamma < 2^-135 are left out:
-                                     as bfloat16 MFMA operands their score gradients are all exactly zero (a
-                                     magnitude below 2^-134 rounds to zero), so no term of any sum changes; only
-                                     the order of the floating-point additions can.  Elsewhere no tile is left out.
+                                  0 (default): with RNNT_BF16, tiles in which every node has gamma < 2^-135 are
+                                     left out: as bfloat16 MFMA operands their score gradients are all exactly zero
+                                     (a magnitude below 2^-134 rounds to zero), so no term of any sum changes; only
+                                     the order of the floating-point additions can.  With RNNT_F32 no tile is left
+                                     out.
                                   -1: no tile is left out, anywhere.
-                                  k = 1..126 (RNNT_BF16 with keep_scores = 0, else RNNT_ERR_UNSUPPORTED): tiles in
+                                  k = 1..126 (RNNT_BF16, else RNNT_ERR_UNSUPPORTED): tiles in
                                      which every node has gamma < 2^-k are left out; each gradient entry changes
                                      by less than 2^-k times the number of lattice nodes that add to it (with
                                      k = 30 four fifths of the tiles of a 750 x 140 lattice drop out).

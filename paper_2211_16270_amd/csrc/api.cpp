@@ -411,25 +411,26 @@ rnnt_status execute(const rnnt_desc* desc, const Plan& plan, const int32_t* T_le
             if (bf16) {
                 const long long rows = (long long)(c.tile1 - c.tile0) * TILE_ROWS;
                 // with a tile list the chunk takes entries [c.tile0 - g.tile0, c.tile1 - g.tile0) of the group's list
+                // (kept scores: one chunk per group, filled tile by tile by the forward pass)
                 const ActiveTiles at{skip ? (const int*)(w + plan.off_tile_esum) : nullptr,
                                      skip ? (const int*)(w + plan.off_n_active) + gi : nullptr, g.tile0,
-                                     c.tile0 - g.tile0};
+                                     c.tile0 - g.tile0, keep ? c.tile0 : -1};
                 if (keep && plan.fused) {
                     // the group's scores are in the chunk buffers already: the fused kernel turns them into dh
                     // on their way into the dz GEMM and writes dh back for the dW GEMM
                     RNNT_HIP(timed(KC_BWD_FUSED, stream, [&] {
                         return launch_bwd_fused_kept_bf16(pr, wv.wq, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
-                                                          wv.kept_max, d_enc, d_pred, stream);
+                                                          wv.kept_max, d_enc, d_pred, at, stream);
                     }));
                 } else if (keep) {
                     // ... or, for joint sizes the fused kernel does not cover, one pass turns them into dh
                     RNNT_HIP(timed(KC_KEPT_TO_DH, stream, [&] {
                         return launch_kept_to_dh_bf16(pr, wv.st, ls, g.s0, g.s1, c.tile0, c.tile1, wv.dH,
-                                                      wv.kept_max, stream);
+                                                      wv.kept_max, at, stream);
                     }));
                     RNNT_HIP(timed(KC_GEMM_DZ, stream, [&] {
                         return launch_gemm_dz_bf16(pr, wv.st, g.s0, g.s1, c.tile0, c.tile1, wv.dH, d_enc, d_pred,
-                                                   ActiveTiles{nullptr, nullptr, 0, 0}, stream);
+                                                   at, stream);
                     }));
                 } else if (plan.fused) {
                     RNNT_HIP(timed(KC_BWD_FUSED, stream, [&] {

@@ -101,12 +101,17 @@ hipError_t launch_select_tiles(const SampleTable& st, const LatticeState& ls, in
                                float log_floor, int* flags, int* active, int* n_active, hipStream_t stream);
 // The tiles a backward launch works on: null active = tiles [tile0, tile1) one by one; else entry cbase + i of the
 // group's list active[group_tile0 ...], for i below *n_active - cbase (workgroups beyond that return at once).
+// Where a listed tile's 64 rows lie in the chunk buffers: in slot i (slot_tile0 < 0: the backward pass fills the
+// buffers itself, densely), or in slot tile - slot_tile0 (kept scores: the forward pass has filled the buffers
+// tile by tile before the list existed).
 struct ActiveTiles {
     const int* active;
     const int* n_active;
     int group_tile0;
     int cbase;
+    int slot_tile0;
 };
+constexpr ActiveTiles EVERY_TILE{nullptr, nullptr, 0, 0, -1};
 
 // ---- bf16 MFMA path -------------------------------------------------------------------------
 // joint tile in LDS -> scores on MFMA -> online log-softmax -> lse, lpb, lpy   (tiles [tile0,tile1))
@@ -125,7 +130,7 @@ hipError_t launch_fwd_keep_bf16(const Problem& pr, const void* Wpack, const Samp
                                 void* Z, float* kept_max, hipStream_t stream);
 hipError_t launch_kept_to_dh_bf16(const Problem& pr, const SampleTable& st, const LatticeState& ls, int s0,
                                   int s1, int tile0, int tile1, void* kept, const float* kept_max,
-                                  hipStream_t stream);
+                                  const ActiveTiles& at, hipStream_t stream);
 // dz = dH W^T, times the tanh derivative, reduced over the tile's u resp. t, added to d_enc, d_pred
 hipError_t launch_gemm_dz_bf16(const Problem& pr, const SampleTable& st, int s0, int s1, int tile0,
                                int tile1, const void* dH, float* d_enc, float* d_pred, const ActiveTiles& at,
@@ -157,7 +162,7 @@ hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const voi
 // not touched.
 hipError_t launch_bwd_fused_kept_bf16(const Problem& pr, const void* Wq, const SampleTable& st, const LatticeState& ls,
                                       int s0, int s1, int tile0, int tile1, void* kept, const float* kept_max,
-                                      float* d_enc, float* d_pred, hipStream_t stream);
+                                      float* d_enc, float* d_pred, const ActiveTiles& at, hipStream_t stream);
 // Split-K GEMM Z^T dH over one chunk's rows: every (split, tile) workgroup adds its 256x256 partial
 // product to its own slot (`first` != 0: overwrites it), db += column sums of dH.  `splits` and the
 // slot buffer size follow dw_split_count / dw_slot_bytes (plan.h).

@@ -395,7 +395,7 @@ static hipError_t launch_joint(const JointArgs& a, hipStream_t stream) {
 hipError_t launch_fwd_bf16(const Problem& pr, const void* Wpack, const SampleTable& st, const LatticeState& ls,
                            int s0, int s1, int tile0, int tile1, hipStream_t stream) {
     JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, nullptr, nullptr, nullptr,
-                ActiveTiles{nullptr, nullptr, 0, 0}};
+                EVERY_TILE};
     // a longer prefetch distance where the hidden size allows it (the forward kernel has the registers)
     if (pr.H % 256 == 0) return launch_joint<0, 4, 2, 8>(a, stream);
     return launch_joint<0, 4, 2, 4>(a, stream);
@@ -412,7 +412,7 @@ hipError_t launch_fwd_keep_bf16(const Problem& pr, const void* Wpack, const Samp
                                 const LatticeState& ls, int s0, int s1, int tile0, int tile1, void* kept,
                                 void* Z, float* kept_max, hipStream_t stream) {
     JointArgs a{pr, st, ls, (const bf16_t*)Wpack, s0, s1, tile0, tile1, (bf16_t*)kept, (bf16_t*)Z, kept_max,
-                ActiveTiles{nullptr, nullptr, 0, 0}};
+                EVERY_TILE};
     if (pr.H % 256 == 0) return launch_joint<2, 4, 2, 8>(a, stream);
     return launch_joint<2, 4, 2, 4>(a, stream);
 }
@@ -429,7 +429,14 @@ __global__ __launch_bounds__(256) void k_kept_to_dh(JointArgs a) {
     typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
     const int V = a.pr.V;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int tile = a.tile0 + blockIdx.x;
+    int tile = a.tile0 + blockIdx.x;
+    if (a.at.active) {
+        // listed tiles only (uniform per workgroup); the kept scores of a tile lie at its position in the launch
+        const int ci = a.at.cbase + (int)blockIdx.x;
+        if (ci >= *a.at.n_active) return;
+        tile = a.at.active[a.at.group_tile0 + ci];
+    }
+    const int slot = tile - a.tile0;
     const TilePos tp = locate_tile(a.st, a.s0, a.s1, tile);
     const int b = tp.s;
     if (tid < 64) {
@@ -451,9 +458,9 @@ __global__ __launch_bounds__(256) void k_kept_to_dh(JointArgs a) {
     }
     __syncthreads();
     const int cpr = V >> 3;                      // 16-byte pieces per row
-    const float* mx = a.kept_max + (size_t)blockIdx.x * (V / 64) * 64;
+    const float* mx = a.kept_max + (size_t)slot * (V / 64) * 64;
     for (int row = wave; row < 64; row += 4) {
-        bf16_t* rowp = a.dH + (size_t)((long long)blockIdx.x * JT_ROWS + row) * chunk_pitch(V);
+        bf16_t* rowp = a.dH + (size_t)((long long)slot * JT_ROWS + row) * chunk_pitch(V);
         const float g = row_g[row], bk = row_b[row], yk = row_y[row];
         const int lab = row_lab[row];
         for (int c0 = lane; c0 < cpr; c0 += 256) {
@@ -492,11 +499,11 @@ __global__ __launch_bounds__(256) void k_kept_to_dh(JointArgs a) {
 
 hipError_t launch_kept_to_dh_bf16(const Problem& pr, const SampleTable& st, const LatticeState& ls, int s0,
                                   int s1, int tile0, int tile1, void* kept, const float* kept_max,
-                                  hipStream_t stream) {
+                                  const ActiveTiles& at, hipStream_t stream) {
     const int n = tile1 - tile0;
     if (n <= 0) return hipSuccess;
     JointArgs a{pr, st, ls, nullptr, s0, s1, tile0, tile1, (bf16_t*)kept, nullptr, const_cast<float*>(kept_max),
-                ActiveTiles{nullptr, nullptr, 0, 0}};
+                at};
     k_kept_to_dh<<<dim3((unsigned)n), dim3(256), 0, stream>>>(a);
     return hipGetLastError();
 }
@@ -531,6 +538,9 @@ struct DwArgs {
     int splits;
     ActiveTiles at;  // at.active set: the chunk holds 64 * (*at.n_active - at.cbase) rows if that is less than K
 };
+// BY_TILE (at.slot_tile0 >= 0): the 64 rows of the list's entry i lie in slot (tile - at.slot_tile0) of both chunk
+// buffers instead of slot i.  A stage of 32 rows lies inside one slot, so only the first row of a stage changes;
+// the list entry of a stage is read (a scalar load) one loop iteration before the stage's copies are issued.
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -544,6 +554,7 @@ __device__ __forceinline__ bf16x8 lds_read_tr_frag(const bf16_t* p) {
     return __builtin_bit_cast(bf16x8, v);
 }
 
+template <bool BY_TILE>
 __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
     extern __shared__ __align__(16) unsigned char dw_smem[];   // [WST] x { A [WK][256], B [WK][256] } bf16
     const int tid = threadIdx.x;
@@ -592,11 +603,22 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
     const char* Zs = reinterpret_cast<const char*>(g.Z) + (ks + 2 * wv) * ZL * 2;
     const char* Ds = reinterpret_cast<const char*>(g.dH) + (ks + 2 * wv) * DL * 2;
     const unsigned dst0 = smem_base + (unsigned)(2 * wv) * (WT * 2u);
-    // DMA j (0..7) of the stage that takes rows [gstep*WK, +WK) of the split into LDS buffer buf
-    auto issue_one = [&](long long gstep, unsigned buf, int j) {
+    // First buffer row of stage gstep (rows [gstep*WK, +WK) of the split), relative to row ks; `entry` is the list
+    // entry of the stage's slot (BY_TILE only).
+    // (read through the constant address space: the list was written before this launch, and only such a load
+    // becomes a scalar load that stays clear of the vector-memory counter the copies below are tracked with)
+    typedef const int __attribute__((address_space(4))) * list_ptr;
+    const list_ptr lst = BY_TILE ? (list_ptr)(g.at.active + g.at.group_tile0 + g.at.cbase) : nullptr;
+    auto stage_entry = [&](long long gstep) { return BY_TILE ? lst[(ks + gstep * WK) >> 6] : 0; };
+    auto stage_row = [&](long long gstep, int entry) -> long long {
+        if (!BY_TILE) return gstep * WK;
+        return ((long long)(entry - g.at.slot_tile0) << 6) + ((ks + gstep * WK) & 63) - ks;
+    };
+    // DMA j (0..7) of the stage whose first row is row0 into LDS buffer buf
+    auto issue_one = [&](long long row0, unsigned buf, int j) {
         const int i = j >> 1;
         const unsigned sb = dst0 + buf * STAGE_BYTES + (unsigned)(8 * i) * (WT * 2u);
-        const long long krow = gstep * WK + 8 * i;
+        const long long krow = row0 + 8 * i;
         if (j & 1) lds_dma16_s(Ds + krow * DL * 2, offB, sb + OPER_BYTES);
         else lds_dma16_s(Zs + krow * ZL * 2, offA, sb);
     };
@@ -640,7 +662,7 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
     // the issue port only briefly: the reads go out in its shadow, and the last of them is 8 MFMAs old when
     // the step ends.
     // Behind each of the last eight goes one DMA of a later stage (dma_g >= 0).
-    auto multiply = [&](int set, long long next_stage, int next_kk, long long dma_g, unsigned dma_buf) {
+    auto multiply = [&](int set, long long next_stage, int next_kk, long long dma_row0, unsigned dma_buf) {
         const bf16_t* st = reinterpret_cast<const bf16_t*>(dw_smem + (size_t)(next_stage & (WST - 1)) * STAGE_BYTES) +
                            next_kk * 16 * WT;
 #pragma unroll
@@ -651,7 +673,7 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
                 const int idx = mt * 4 + nt;
                 if (idx < 4) fa[set ^ 1][idx] = lds_read_tr_frag(st + aoff[idx]);
                 else if (idx < 8) fb[set ^ 1][idx - 4] = lds_read_tr_frag(st + boff[idx - 4]);
-                else if (set == 1) issue_one(dma_g, dma_buf, idx - 8);
+                else if (set == 1) issue_one(dma_row0, dma_buf, idx - 8);
                 __builtin_amdgcn_sched_barrier(0);
             }
         if (do_db) {
@@ -673,15 +695,21 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
     if (nsteps > 0) {
         const long long last = nsteps - 1;
 #pragma unroll
-        for (int st3 = 0; st3 < 3; ++st3)
+        for (int st3 = 0; st3 < 3; ++st3) {
+            const long long gs = st3 < last ? st3 : last;
+            const long long row0 = stage_row(gs, stage_entry(gs));
 #pragma unroll
-            for (int j = 0; j < 8; ++j) issue_one(st3 < last ? st3 : last, (unsigned)st3, j);
+            for (int j = 0; j < 8; ++j) issue_one(row0, (unsigned)st3, j);
+        }
+        int entry_ahead = stage_entry(3 < last ? 3 : last);
         asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
         __syncthreads();
         read_frags(0, 0, 0);
         for (long long it = 0; it < nsteps; ++it) {
             __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);     // set 0 landed (read behind the first MFMAs of the step before)
             __builtin_amdgcn_sched_barrier(0);
+            const long long dma_row0 = stage_row(it + 3 < last ? it + 3 : last, entry_ahead);
+            entry_ahead = stage_entry(it + 4 < last ? it + 4 : last);      // arrives during this iteration
             multiply(0, it, 1, 0, 0);
             __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);     // set 1 landed
             // stage it+1 landed (stage it+2 stays in flight); every wave is past stage it-1, whose buffer
@@ -689,7 +717,7 @@ __global__ __launch_bounds__(256) void k_gemm_dw256(DwArgs g) {
             asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
-            multiply(1, it + 1, 0, it + 3 < last ? it + 3 : last, (unsigned)((it + 3) & (WST - 1)));
+            multiply(1, it + 1, 0, dma_row0, (unsigned)((it + 3) & (WST - 1)));
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // no copy may land after the workgroup has ended
     }
@@ -731,12 +759,17 @@ hipError_t launch_gemm_dw_bf16(int H, int V, long long rows, int splits, int fir
     const size_t smem = (size_t)WST * 2 * WK * WT * 2;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_dw256),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_dw256<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_dw256<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    k_gemm_dw256<<<dim3((unsigned)(mt * nt * splits)), dim3(256), smem, stream>>>(g);
+    const dim3 grid((unsigned)(mt * nt * splits));
+    if (at.active && at.slot_tile0 >= 0) k_gemm_dw256<true><<<grid, dim3(256), smem, stream>>>(g);
+    else k_gemm_dw256<false><<<grid, dim3(256), smem, stream>>>(g);
     return hipGetLastError();
 }
 

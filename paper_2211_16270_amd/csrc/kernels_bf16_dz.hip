@@ -74,7 +74,18 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
     const int lseg = ((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) * 8;
     const unsigned lane_offA = (unsigned)(((long long)(lane >> 3) * DL + lseg) * 2);
     const unsigned lane_offB = (unsigned)(((long long)(lane >> 3) * V + lseg) * 2);
-    const char* As = reinterpret_cast<const char*>(g.dH) + (m0 + 8 * wv) * DL * 2;
+    // the workgroup's four 64-row slots of the dH buffer: consecutive, or (kept scores) wherever the forward pass
+    // has put the listed tiles; entries past the list's end read the last listed tile again
+    const char* As[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        long long row = m0 + 64 * k;
+        if (g.at.active && g.at.slot_tile0 >= 0) {
+            const int e = bx * 4 + k < n_slots ? bx * 4 + k : n_slots - 1;
+            row = (long long)(g.at.active[g.at.group_tile0 + g.at.cbase + e] - g.at.slot_tile0) * 64;
+        }
+        As[k] = reinterpret_cast<const char*>(g.dH) + (row + 8 * wv) * DL * 2;
+    }
     const char* Bs = reinterpret_cast<const char*>(g.W) + (long long)(n0 + 8 * wv) * V * 2;
     const bool half_tile = (n0 + 128 >= H);
     const unsigned dst0 = smem_base + (unsigned)(8 * wv) * 128u;
@@ -86,7 +97,7 @@ __global__ __launch_bounds__(256) void k_gemm_dz256(DzArgs g) {
             const int ib = (half_tile && i >= 4) ? i - 4 : i;
             lds_dma16_s(Bs + ((long long)(32 * ib) * V + (long long)gstep * ZK) * 2, lane_offB, sb + Z_OPER);
         } else {
-            lds_dma16_s(As + ((long long)(32 * i) * DL + (long long)gstep * ZK) * 2, lane_offA, sb);
+            lds_dma16_s(As[i >> 1] + ((long long)(32 * (i & 1)) * DL + (long long)gstep * ZK) * 2, lane_offA, sb);
         }
     };
     // fragment of 32 rows, k16-step kk of a stage: lane holds row l32, segment 2*kk + hb at position

@@ -72,7 +72,9 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
     }
     const TilePos tp = locate_tile(a.st, a.s0, a.s1, tile);
     const int b = tp.s;
-    const long long chunk_row0 = (long long)blockIdx.x * FB_ROWS;
+    // the tile's 64 rows in the chunk buffers: dense, or by tile position where the forward pass has filled them
+    const int slot = (a.at.active && a.at.slot_tile0 >= 0) ? tile - a.at.slot_tile0 : (int)blockIdx.x;
+    const long long chunk_row0 = (long long)slot * FB_ROWS;
 
     // ---- joint tile (Eq. 4)
     build_joint_tile<512, 2>(zs, ZP, reinterpret_cast<const bf16_t*>(a.pr.enc) + (size_t)b * a.pr.T_max * H,
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(512) void k_joint_bwd_fused(FusedArgs a) {
         const int seg = lane & 7, r0 = lane >> 3;          // rows r0 + 8 i, eight entries at 64 w4 + 8 seg
         const size_t DL = chunk_pitch(V);
         bf16_t* piece = a.dH + (size_t)chunk_row0 * DL + w4 * 64 + seg * 8;
-        const float* mx = a.kept_max + ((size_t)blockIdx.x * (V / 64) + w4) * 64;
+        const float* mx = a.kept_max + ((size_t)slot * (V / 64) + w4) * 64;
         float g[8], vB[8], vY[8];
         int lb[8];
 #pragma unroll
@@ -499,10 +501,10 @@ hipError_t launch_bwd_fused_bf16(const Problem& pr, const void* Wpack, const voi
 
 hipError_t launch_bwd_fused_kept_bf16(const Problem& pr, const void* Wq, const SampleTable& st, const LatticeState& ls,
                                       int s0, int s1, int tile0, int tile1, void* kept, const float* kept_max,
-                                      float* d_enc, float* d_pred, hipStream_t stream) {
+                                      float* d_enc, float* d_pred, const ActiveTiles& at, hipStream_t stream) {
     if (tile1 <= tile0) return hipSuccess;
     FusedArgs a{pr, st, ls, nullptr, (const bf16_t*)Wq, s0, s1, tile0, tile1,
-                (bf16_t*)kept, nullptr, d_enc, d_pred, kept_max, ActiveTiles{nullptr, nullptr, 0, 0}};
+                (bf16_t*)kept, nullptr, d_enc, d_pred, kept_max, at};
     const int ht = (pr.H / 32 + 3) / 4;
     if (ht <= 1) return launch_fused_t<1, 4, 4, true>(a, stream);
     if (ht == 2) return launch_fused_t<2, 8, 4, true>(a, stream);

@@ -21,8 +21,8 @@ rnnt_status check_desc(const rnnt_desc* d) {
     if (d->input_grads_bf16 && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
     if (d->dtype != RNNT_F32 && d->dtype != RNNT_BF16) return RNNT_ERR_UNSUPPORTED;
     if (d->skip_below_log2 < -1 || d->skip_below_log2 > 126) return RNNT_ERR_SHAPE;
-    if (d->skip_below_log2 > 0 && (d->dtype != RNNT_BF16 || d->keep_scores))
-        return RNNT_ERR_UNSUPPORTED;                            // the recomputing bf16 backward kernels take a tile list
+    if (d->skip_below_log2 > 0 && d->dtype != RNNT_BF16)
+        return RNNT_ERR_UNSUPPORTED;                            // the bf16 backward kernels take a tile list
     if (d->U_max > 1023) return RNNT_ERR_UNSUPPORTED;           // one lattice thread per label position
     if ((long long)d->T_max * (d->U_max + 1) > (1LL << 30)) return RNNT_ERR_UNSUPPORTED;
     if (d->dtype == RNNT_BF16) {
@@ -117,10 +117,10 @@ void build_plan(const rnnt_desc& d, const int32_t* T_len, const int32_t* U_len,
     p.keep = p.bf16 && d.keep_scores;
     p.fused = p.bf16 && fused_backward_shape(d.H, d.V);
     p.stage = p.bf16 && d.input_grads_bf16;
-    // 0: on the bf16 path that computes the scores twice, tiles whose score gradients are all zero as bf16 values
-    // are left out (ZERO_IN_BF16_LOG2); -1: no tile is ever left out
+    // 0: on the bf16 paths, tiles whose score gradients are all zero as bf16 values are left out
+    // (ZERO_IN_BF16_LOG2); -1: no tile is ever left out
     p.skip_log2 = d.skip_below_log2 > 0 ? d.skip_below_log2
-                  : (d.skip_below_log2 == 0 && p.bf16 && !p.keep) ? ZERO_IN_BF16_LOG2 : 0;
+                  : (d.skip_below_log2 == 0 && p.bf16) ? ZERO_IN_BF16_LOG2 : 0;
     p.f32_gemm = !p.bf16 && f32_gemm_shape(d.H, d.V);
     const bool chunked = p.bf16 || p.f32_gemm;
     const size_t stage_per_sample = ((size_t)d.T_max + d.U_max + 1) * d.H * 4;

@@ -300,7 +300,7 @@ def test_negligible_tile_option_edge_cases():
     one = run_gpu(batch, skip_below_log2=1)            # gamma < 1/2 dropped: a coarse result, but a finite one
     assert all(np.all(np.isfinite(one[k2])) for k2 in ("loss", "d_enc", "d_pred", "dW_out", "db_out"))
     np.testing.assert_array_equal(one["loss"], got["loss"])
-    for bad in (dict(keep_scores=1), dict(dtype=Bd.RNNT_F32), dict(skip=127), dict(skip=-2)):
+    for bad in (dict(dtype=Bd.RNNT_F32), dict(skip=127), dict(skip=-2)):
         d = Bd.make_desc(2, 8, 4, bad.get("H", 128), 256, 0, bad.get("dtype", Bd.RNNT_BF16),
                          keep_scores=bad.get("keep_scores", 0), skip_below_log2=bad.get("skip", 30))
         assert Bd.rnnt_joint_loss_workspace_bytes(d, [8, 8], [4, 4]) == 0, bad
@@ -331,3 +331,47 @@ def test_default_leaves_out_only_tiles_whose_score_gradients_are_zero_in_bf16(na
     st2, a2, t2 = Bd.rnnt_debug_read_active_tiles(every["desc"], batch.T_len, batch.U_len, every["workspace"].buf)
     _say("default keeps", active, "of", total, "tiles")
     assert st == 0 and st2 == 0 and a2 == t2 == total and 0 < active < total
+
+
+@pytest.mark.parametrize("name,n", [("C4", 12), ("C3", 8), ("P1024", 4)])
+def test_kept_scores_with_the_tile_selection(name, n):
+    # keep_scores = 1: the forward pass has written every tile's scores and joint rows into the chunk buffers before
+    # the list exists, so the backward kernels and the dW_out GEMM pick the listed tiles' rows where they lie (fused
+    # kernel for H <= 640, conversion pass + dz GEMM above).  Default against the checker and against the pass over
+    # every tile (loss identical, gradients equal to rounding of the sums); k = 30 against the checker; a small
+    # workspace (several groups) the same.
+    if name == "P1024":
+        wl = synth.custom_workload("P4", B=4, T_max=500, U_max=100, H=1024, V=4096, dtype="bf16", index=5,
+                                   t_rule="uniform", t_lo=454, u_rule="uniform", u_lo=54)
+        ids = list(range(n))
+    else:
+        wl = synth.WORKLOADS[name]
+        ids = _ids_spanning(wl, n)
+    batch = synth.make_batch(wl, sample_ids=ids)
+    ref = run_oracle(batch)
+    dflt = run_gpu(batch, keep_scores=1)
+    e, errs = assert_parity(dflt, ref, "bf16", f"{name} kept scores, default tile selection")
+    assert_padding_zero(dflt, batch)
+    every = run_gpu(batch, keep_scores=1, skip_below_log2=-1)
+    np.testing.assert_array_equal(dflt["loss"], every["loss"])
+    for key in ("d_enc", "d_pred", "dW_out", "db_out"):
+        d = np.abs(dflt[key].astype(np.float64) - every[key]).max() / np.abs(every[key]).max()
+        _say("kept scores, default vs every tile", name, key, d)
+        assert d < 2e-6, (key, d)
+    st, active, total = Bd.rnnt_debug_read_active_tiles(dflt["desc"], batch.T_len, batch.U_len, dflt["workspace"].buf)
+    _say("kept scores: default keeps", active, "of", total, "tiles; errs", e, errs)
+    assert st == 0 and 0 < active < total
+    k30 = run_gpu(batch, keep_scores=1, skip_below_log2=30)
+    assert_parity(k30, ref, "bf16", f"{name} kept scores, k = 30")
+    st, a30, _ = Bd.rnnt_debug_read_active_tiles(k30["desc"], batch.T_len, batch.U_len, k30["workspace"].buf)
+    assert st == 0 and 0 < a30 < active
+    # a workspace that cuts the sub-batch into several groups (with kept scores a group is one chunk)
+    desc = Bd.make_desc(batch.B, wl.T_max, wl.U_max, wl.H, wl.V, wl.blank, Bd.RNNT_BF16, 0, keep_scores=1)
+    nmin = Bd.rnnt_joint_loss_workspace_bytes(desc, batch.T_len, batch.U_len, 1)
+    ndef = Bd.rnnt_joint_loss_workspace_bytes(desc, batch.T_len, batch.U_len, 0)
+    budget = nmin + (ndef - nmin) // 3
+    st, info, _ = Bd.rnnt_joint_loss_plan(desc, batch.T_len, batch.U_len, budget)
+    assert st == 0 and info["n_groups"] >= 2, info
+    small = run_gpu(batch, keep_scores=1, budget_bytes=budget)
+    assert_parity(small, ref, "bf16", f"{name} kept scores, small workspace")
+    np.testing.assert_array_equal(small["loss"], dflt["loss"])
