@@ -103,6 +103,33 @@ def mfma_table(Bd, torch):
                 print(f"{name}, {wgs // 256}, {ms:.2f}, {tf:.0f}, {tf / peak:.3f}", flush=True)
 
 
+def stream_table(Bd, torch):
+    """What the compute units get when all of them read one shared array the way the score kernels stream their
+    W_out fragments (the text kept as profiles/shared_array_read_rate.txt)."""
+    print("# every workgroup (256 threads) reads the same array, 16 bytes per lane, eight loads in flight per wave; 256 compute units")
+    print("# array MiB, workgroups per compute unit, ms per launch, TB/s into the compute units, bytes per clock and "
+          "compute unit at 2.4 GHz")
+    for mib in (1, 2, 16, 128, 1024):
+        src = torch.randint(0, 2 ** 31 - 1, (mib << 18,), dtype=torch.int32, device="cuda")
+        for wpc in (1, 2, 4, 8):
+            wgs = 256 * wpc
+            iters = max(1, (128 if mib <= 16 else 8) * 16 // mib // wpc * 2)
+            out = torch.empty(wgs * 1024, dtype=torch.int32, device="cuda")
+            best = None
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                st = Bd.rnnt_debug_stream_read(src, out, wgs, iters)
+                e1.record()
+                assert st == 0, st
+                e1.synchronize()
+                ms = e0.elapsed_time(e1)
+                best = ms if best is None else min(best, ms)
+            tb = float(mib << 20) * iters * wgs / (best * 1e-3) / 1e12
+            print(f"{mib}, {wpc}, {best:.2f}, {tb:.2f}, {tb * 1e12 / 256 / 2.4e9:.1f}", flush=True)
+        del src
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -132,6 +159,9 @@ def main():
                     help="with --planned: the lattice sweeps run on a second stream beside the previous group's backward pass")
     ap.add_argument("--mfma-table", action="store_true",
                     help="only print what the MFMA-only loop sustains on chosen operand values (bf16 and fp8) and exit")
+    ap.add_argument("--stream-table", action="store_true",
+                    help="print what the compute units get when all of them read one shared array (L2, last-level "
+                         "cache, HBM) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the 256 MiB plain copy kernel 5 times (HBM counter calibration under rocprofv3)")
     args = ap.parse_args()
@@ -148,6 +178,9 @@ def main():
     torch.cuda.set_device(0)
     if args.mfma_table:
         mfma_table(Bd, torch)
+        return
+    if args.stream_table:
+        stream_table(Bd, torch)
         return
     if args.config in ("P16", "P16F32"):
         # shaped like the paper's benchmark (Section 5.1): 16 samples of up to 500 x 100, joint size 1024,

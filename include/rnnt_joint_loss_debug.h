@@ -63,6 +63,20 @@ rnnt_status rnnt_debug_mfma_loop_fp8(const void* frags, float* out, int32_t work
                                      void* hip_stream);
 
 /*
+ * Measurement support (not a paper operation): every workgroup (256 threads) reads the same array, 16 bytes per
+ * lane and 1 KB per wave instruction, as the score kernels stream their W_out fragments.  With an array that stays
+ * in the L2 this tells what the path from the L2 to the compute units delivers when all of them pull at once, the
+ * other resource (besides the matrix units) those kernels depend on.
+ *   src    dev  bytes to read: a multiple of 32 KiB, at most 4 GiB, 16-byte aligned
+ *   out    dev  workgroups * 4096 bytes, overwritten (a checksum that keeps the loads alive)
+ *   workgroups 1..65536; iters 1..1000000 passes over the array per workgroup:
+ *               bytes * iters * workgroups bytes reach the compute units per launch
+ * Enqueues on hip_stream, does not wait.  RNNT_ERR_NULL / RNNT_ERR_SHAPE on bad arguments.
+ */
+rnnt_status rnnt_debug_stream_read(const void* src, size_t bytes, void* out, int32_t workgroups, int32_t iters,
+                                   void* hip_stream);
+
+/*
  * Per-kernel timing for the benchmark (not a paper operation; measurement support for the
  * throughput figures reported against Table 1's cost terms).  While enabled, every launch made
  * by the entry points of rnnt_joint_loss.h is bracketed by HIP events recorded on the caller's stream

@@ -21,7 +21,7 @@ STATUS_NAMES = ["RNNT_OK", "RNNT_ERR_NULL", "RNNT_ERR_SHAPE", "RNNT_ERR_LENGTH",
 EXPORTS = ["rnnt_status_string", "rnnt_last_hip_error", "rnnt_joint_loss_workspace_bytes", "rnnt_joint_loss_plan",
            "rnnt_parallel_iterations", "rnnt_validate_labels_host", "rnnt_joint_loss_fwd_bwd",
            "rnnt_joint_loss_fwd", "rnnt_debug_read_lattice", "rnnt_profile_enable",
-           "rnnt_debug_copy_f32", "rnnt_debug_mfma_loop", "rnnt_debug_mfma_loop_fp8", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
+           "rnnt_debug_copy_f32", "rnnt_debug_stream_read", "rnnt_debug_mfma_loop", "rnnt_debug_mfma_loop_fp8", "rnnt_profile_kernel_count", "rnnt_profile_kernel_name", "rnnt_profile_read",
            "rnnt_joint_proj_workspace_bytes", "rnnt_joint_proj_loss_fwd_bwd", "rnnt_joint_loss_fwd_bwd_weighted",
            "rnnt_joint_loss_fwd_bwd_static", "rnnt_plan_create", "rnnt_plan_workspace_bytes", "rnnt_plan_describe",
            "rnnt_plan_destroy", "rnnt_joint_loss_fwd_bwd_planned", "rnnt_debug_read_active_tiles"]
@@ -120,6 +120,8 @@ def lib() -> ctypes.CDLL:
                                                ctypes.POINTER(ctypes.c_int64)]
     L.rnnt_debug_copy_f32.restype = ctypes.c_int
     L.rnnt_debug_copy_f32.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.rnnt_debug_stream_read.restype = ctypes.c_int
+    L.rnnt_debug_stream_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, ctypes.c_int32, vp]
     L.rnnt_debug_mfma_loop.restype = ctypes.c_int
     L.rnnt_debug_mfma_loop.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp]
     L.rnnt_debug_mfma_loop_fp8.restype = ctypes.c_int
@@ -327,6 +329,12 @@ def rnnt_debug_copy_f32(src, dst, stream=None) -> int:
     """Copies the float32 tensor src into dst (same size, multiple of 4 elements) with the library's
     plain copy kernel."""
     return int(lib().rnnt_debug_copy_f32(_ptr(src), _ptr(dst), int(src.numel()), _stream_handle(stream)))
+
+
+def rnnt_debug_stream_read(src, out, workgroups: int, iters: int, stream=None) -> int:
+    """Every workgroup reads all of `src` (a torch tensor) `iters` times; out: a tensor of workgroups * 4096 bytes."""
+    return int(lib().rnnt_debug_stream_read(_ptr(src), int(src.numel() * src.element_size()), _ptr(out),
+                                            int(workgroups), int(iters), _stream_handle(stream)))
 
 
 def rnnt_debug_mfma_loop_fp8(frags, out, workgroups: int, iters: int, stream=None) -> int:

@@ -872,6 +872,16 @@ extern "C" rnnt_status rnnt_debug_mfma_loop(const void* frags, float* out, int32
     return RNNT_OK;
 }
 
+extern "C" rnnt_status rnnt_debug_stream_read(const void* src, size_t bytes, void* out, int32_t workgroups,
+                                              int32_t iters, void* hip_stream) {
+    if (!src || !out) return RNNT_ERR_NULL;
+    if (bytes < 32768 || bytes % 32768 != 0 || bytes > ((size_t)1 << 32) || workgroups < 1 || workgroups > 65536 ||
+        iters < 1 || iters > 1000000 || ((uintptr_t)src % 16) != 0 || ((uintptr_t)out % 16) != 0)
+        return RNNT_ERR_SHAPE;
+    RNNT_HIP(launch_stream_read(src, bytes, out, workgroups, iters, (hipStream_t)hip_stream));
+    return RNNT_OK;
+}
+
 extern "C" rnnt_status rnnt_debug_mfma_loop_fp8(const void* frags, float* out, int32_t workgroups, int32_t iters,
                                                 void* hip_stream) {
     if (!frags || !out) return RNNT_ERR_NULL;

@@ -70,6 +70,8 @@ hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s
 
 // loop of workgroups x 4 waves x iters x 16 MFMAs (32x32x16 bf16) on the 32 x 1 KiB fragments at `frags`;
 // writes workgroups x 256 floats to `out` (measurement support)
+// every workgroup (256 threads) reads the same `bytes` (a multiple of 32 KiB) `iters` times; out: 4096 bytes per workgroup
+hipError_t launch_stream_read(const void* src, size_t bytes, void* out, int workgroups, int iters, hipStream_t stream);
 hipError_t launch_mfma_loop(const void* frags, float* out, int workgroups, int iters, hipStream_t stream);
 // the same with the fp8 (e4m3) MFMA 32x32x64, unit scales: fragments of 64 lanes x 32 bytes (64 KiB in all)
 hipError_t launch_mfma_loop_fp8(const void* frags, float* out, int workgroups, int iters, hipStream_t stream);

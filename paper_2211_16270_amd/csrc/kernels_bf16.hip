@@ -512,8 +512,8 @@ hipError_t launch_kept_to_dh_bf16(const Problem& pr, const SampleTable& st, cons
 // dW += Z^T dH and db += column sums of dH (Alg. 1 line 8) as one split-K GEMM with 256x256 tiles.
 // 256 threads = 4 waves in 2 (hidden) x 2 (vocabulary), one per SIMD; each wave owns 128 x 128 = 4 x 4
 // accumulator tiles (256 accumulator registers), so that a k16-step reads 8 fragments from LDS for 16
-// MFMAs: the transposing LDS read delivers about 70 bytes per clock and CU, a quarter of the plain
-// 16-byte read, and sets the ratio of fragments to MFMAs this kernel can afford.  Both operands are row-major with the contraction index (the chunk's rows) as the slow one:
+// MFMAs and every byte of a stage feeds 128 flops.  Both operands are row-major with the contraction index (the
+// chunk's rows) as the slow one:
 // Z [rows,H], dH [rows,V].  Stages of 32 rows travel global -> LDS asynchronously (global_load_lds, no
 // registers), four stages deep, and lie in LDS as in memory ([row][column], 16-byte chunks
 // XOR-swizzled by 4*(row%4), which spreads the four rows a transposing read touches per 32 lanes over all 64 banks); MFMA fragments, which need 8 consecutive rows of one column per lane,

@@ -61,7 +61,34 @@ __global__ __launch_bounds__(256) void k_mfma_loop_fp8(const i32x8* __restrict__
     out[(size_t)blockIdx.x * 256 + threadIdx.x] = r;
 }
 
+// Every workgroup reads the same n16 16-byte pieces `iters` times, 16 bytes per lane and 1 KB per wave instruction,
+// eight instructions in flight per wave (the way the score kernels stream their W_out fragments, which all
+// workgroups share): what the path from the L2 (or, for a larger array, from the last-level cache or HBM) to the
+// compute units delivers when every compute unit pulls at once.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void k_stream_read(const u32x4* __restrict__ src, size_t n16, int iters,
+                                                     u32x4* __restrict__ out) {
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (int it = 0; it < iters; ++it) {
+        const u32x4* p = src + threadIdx.x;
+        asm volatile("" : "+v"(p));              // a new pointer as far as the compiler knows: the loads stay in the loop
+        for (size_t i = 0; i < n16; i += 8 * 256) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = p[i + j * 256];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc ^= v[j];
+        }
+    }
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = acc;
+}
+
 }  // namespace
+
+hipError_t launch_stream_read(const void* src, size_t bytes, void* out, int workgroups, int iters, hipStream_t stream) {
+    k_stream_read<<<dim3((unsigned)workgroups), dim3(256), 0, stream>>>((const u32x4*)src, bytes / 16, iters, (u32x4*)out);
+    return hipGetLastError();
+}
 
 hipError_t launch_mfma_loop_fp8(const void* frags, float* out, int workgroups, int iters, hipStream_t stream) {
     k_mfma_loop_fp8<<<dim3((unsigned)workgroups), dim3(256), 0, stream>>>((const i32x8*)frags, out, iters);
